@@ -1,0 +1,158 @@
+"""Benchmark of the TopLoc hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic activations
+already resident in HBM: toploc_build_proofs over every chunk, then
+toploc_verify_proofs of those proofs against the same tensor.  The workload is
+the Llama-3.1-70B-shaped configuration (128 sequences x 4096 tokens x hidden
+8192 bf16 = 16384 chunks of 32 tokens, 8 GiB), k = 128.
+
+Prints ONE JSON line.  `value` is activation bytes consumed by build and verify
+together per second (each step streams the tensor twice).  `roofline` is for
+the kernel with the longest average launch, timed with HIP events on the
+launch stream inside the timed region.  `cpu_baseline` is the CPU oracle timed
+on a bounded sample of the same chunks on the host cores.
+"""
+import argparse
+import json
+import sys
+import time
+
+HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="config3", choices=["config3", "config2"])
+    ap.add_argument("--k", type=int, default=128)
+    ap.add_argument("--cpu-sample-chunks", type=int, default=512)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (chunks are independent; a multi-GPU run would "
+                 "shard sequences with no exchange step). Use --gpus 1.")
+
+    import numpy as np
+    import torch
+    from paper_2501_16007_amd import binding as tl
+    from paper_2501_16007_amd import synth
+
+    dev = "cuda:0"
+    k = args.k
+    if args.workload == "config3":
+        x = synth.config3(dev)
+        name = "llama-3.1-70b-shaped: 128 seq x 4096 tok x hidden 8192 bf16, 32-token chunks, k=%d" % k
+    else:
+        x = synth.config2(dev)
+        name = "llama-3.1-8b-shaped: 64 seq x 2048 tok x hidden 4096 bf16, 32-token chunks, k=%d" % k
+    chunks = synth.as_chunks(x)
+    n_chunks, n = chunks.shape
+    act_bytes = n_chunks * n * 2
+    pb = 2 + 2 * k
+
+    proofs = torch.empty((n_chunks, pb), dtype=torch.uint8, device=dev)
+    status = torch.empty(n_chunks, dtype=torch.uint8, device=dev)
+    results = torch.empty((n_chunks, 20), dtype=torch.uint8, device=dev)
+    ws = tl.new_workspace(k, 1, n, n_chunks, dev)
+
+    def step():
+        tl.toploc_build_proofs(chunks, k=k, chunk_tokens=1, workspace=ws, out=(proofs, status))
+        tl.toploc_verify_proofs(chunks, proofs, k=k, chunk_tokens=1, out=results)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+
+    # sanity of what was timed: every chunk built and accepted
+    resn = tl.results_numpy(results)
+    assert int(status.max()) == 0 and bool((resn["accept"] == 1).all()), "timed run produced wrong verdicts"
+
+    # per-kernel launch durations, HIP events on the launch stream, same loop
+    tl.toploc_profile_enable(True)
+    tl.toploc_profile_read()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    prof = tl.toploc_profile_read()
+    tl.toploc_profile_enable(False)
+    kernels = {}
+    alg_bytes = {   # algorithmic HBM bytes per chunk: what the method itself must move
+        "select_kernel": 2 * n + 6 * k,          # read the chunk, hand k (index, value) pairs on
+        "interp_kernel": 6 * k + pb + 1,         # read the pairs, write the proof and status
+        "verify_kernel": 2 * n + pb + 20,        # read the chunk and the proof, write the record
+    }
+    for kn, (launches, total_ms) in prof.items():
+        if launches:
+            avg_ms = total_ms / launches
+            kernels[kn] = {"launches": launches, "avg_ms": avg_ms,
+                           "GBps": alg_bytes[kn] * n_chunks / (avg_ms * 1e-3) / 1e9}
+    dom = max(kernels, key=lambda kn: kernels[kn]["avg_ms"])
+    roofline = {
+        "bound": "hbm",
+        "kernel": dom,
+        "achieved": kernels[dom]["GBps"],
+        "peak": HBM_PEAK_GBPS,
+        "unit": "GB/s",
+        "frac": kernels[dom]["GBps"] / HBM_PEAK_GBPS,
+        "traffic": None,
+        "avg_launch_ms": kernels[dom]["avg_ms"],
+        "algorithmic_bytes_per_launch": alg_bytes[dom] * n_chunks,
+    }
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle as orc
+        ns = min(args.cpu_sample_chunks, n_chunks)
+        sel = torch.arange(0, n_chunks, max(1, n_chunks // ns), device=dev)[:ns]
+        sample = synth.bits_numpy(chunks[sel])
+        cores = orc.max_threads()
+        t0 = time.perf_counter()
+        o_proofs, o_status = orc.build(sample, k)
+        o_res = orc.verify(sample, o_proofs, k)
+        cdt = time.perf_counter() - t0
+        assert np.array_equal(proofs[sel].cpu().numpy(), o_proofs), "GPU proofs differ from the oracle on the sample"
+        assert bool((o_res["accept"] == 1).all())
+        cpu = {
+            "value": 2 * sample.size * 2 / cdt / 1e9,
+            "unit": "GB/s",
+            "cores": cores,
+            "kind": "oracle",
+            "sample": "%d of %d chunks (every %d-th), build + verify, %.1f s wall" % (
+                ns, n_chunks, max(1, n_chunks // ns), cdt),
+            "chunks_per_s": ns / cdt,
+        }
+
+    out = {
+        "metric": "proof build + verify throughput (activation GB/s consumed by build and verify)",
+        "value": 2 * act_bytes / (ms_per_step * 1e-3) / 1e9,
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u16",
+        "data": "synthetic",
+        "config": {"workload": name, "n_chunks": n_chunks, "chunk_values": n, "k": k,
+                   "activation_bytes": act_bytes},
+        "chunks_per_s": n_chunks / (ms_per_step * 1e-3),
+        "frac_hbm_peak": 2 * act_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "kernels": kernels,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,161 @@
+/*
+ * toploc.h -- C ABI of the MI355X (gfx950) TopLoc proof build / verify library.
+ *
+ * The paper states the problem as two functions applied once per chunk of 32
+ * new tokens (Section 4; Section 5.5 and 5.8 for the 32-token sampling):
+ *   Algorithm 1:  (hidden state tensor h, k)      -> encoded proof p
+ *   Algorithm 2:  (hidden state tensor h, proof p) -> accept / reject
+ * with the three thresholds of Section 5.2 as fixed parameters.  The entry
+ * points below are those two functions over a batch of independent chunks.
+ *
+ * Conventions common to every entry point
+ *  - Pointers named d_* are DEVICE pointers (HIP global memory of the current
+ *    device); everything else is a host pointer read during the call only.
+ *  - The caller owns every buffer.  The library allocates no device memory and
+ *    keeps no reference after the work it enqueued has finished.
+ *  - All work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL is
+ *    the default stream).  No entry point synchronises; results are valid once
+ *    the stream has reached the end of the enqueued work.
+ *  - bf16 values are read and written as their 16-bit patterns.  No floating
+ *    point arithmetic happens anywhere on the path.
+ *  - Return value: TOPLOC_OK (0) when the work was enqueued, a negative
+ *    TOPLOC_E* code when the call was rejected (nothing was enqueued then).
+ *    Data-dependent per-chunk conditions never fail the call; they are reported
+ *    per chunk in `d_status` / `toploc_verify_result.status`.
+ *
+ * Layout of a chunk: `chunk_tokens` consecutive token rows of `hidden` bf16
+ * values, row major, so the flat index of (token t, channel c) is t*hidden + c
+ * and chunk j starts at element j*chunk_tokens*hidden.  The chunk length
+ * N = chunk_tokens*hidden must be a multiple of 8 and `d_hidden_bf16` 16-byte
+ * aligned (the kernels read 16 bytes per lane).
+ *
+ * Layout of a proof (2 + 2k bytes; 258 for k = 128 as in the paper's abstract):
+ *   bytes 0..1     m mod 65536, little endian (0 stands for m = 65536), where m
+ *                  is the injective modulus of Algorithm 6
+ *   bytes 2+2j..   coefficient c_j of x^j of the interpolated polynomial over
+ *                  GF(65497) (Algorithm 3's output), little endian, j = 0..k-1
+ */
+#ifndef TOPLOC_H
+#define TOPLOC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TOPLOC_PRIME 65497u     /* the field modulus M of Algorithms 3 and 5            */
+#define TOPLOC_MAX_K 512u       /* largest supported top-k parameter                    */
+
+/* call-level return codes */
+#define TOPLOC_OK 0
+#define TOPLOC_EINVAL (-1)      /* null / misaligned pointer, k = 0, k > N, k > MAX_K,   */
+                                /* N not a multiple of 8, N >= 2^32, prime != 65497      */
+#define TOPLOC_EWORKSPACE (-2)  /* workspace smaller than toploc_workspace_bytes()       */
+#define TOPLOC_EHIP (-3)        /* a HIP runtime call failed; see toploc_last_hip_error  */
+
+/* per-chunk status codes */
+#define TOPLOC_CHUNK_OK 0
+#define TOPLOC_CHUNK_NO_MODULUS 1   /* Algorithm 6 exhausted [2^15+1, 65536]             */
+#define TOPLOC_CHUNK_NO_INVERSE 2   /* Algorithm 4's error exit; unreachable once the    */
+                                    /* modulus makes the points distinct in GF(p)        */
+#define TOPLOC_CHUNK_MALFORMED 3    /* verify: decoded m < 2^15+1 or a coefficient >= p  */
+
+typedef struct {
+    uint32_t k;             /* top-k parameter of Algorithms 1 and 2 (128 in the paper) */
+    uint32_t chunk_tokens;  /* tokens per proof (32 in the paper)                       */
+    uint32_t hidden;        /* hidden size of the model                                 */
+    uint32_t prime;         /* must be TOPLOC_PRIME                                     */
+} toploc_params;
+
+/* T_exp, T_mean, T_median of Algorithm 2; Section 5.2 gives {38, 10, 8} for bf16. */
+typedef struct {
+    uint32_t t_exp, t_mean, t_median;
+} toploc_thresholds;
+
+/* What Algorithm 2 computes for one chunk. 20 bytes. */
+typedef struct {
+    uint32_t err_exp;      /* err_e: top-k entries whose exponent differs from P(x)'s     */
+    uint32_t n_match;      /* |err_m|: entries whose exponent matched                     */
+    uint32_t mant_sum;     /* sum of err_m (mean = mant_sum / n_match, kept exact)        */
+    uint32_t mant_median;  /* lower median of err_m, 0 when err_m is empty                */
+    uint8_t accept;        /* 1 unless err_e > T_exp or mean > T_mean or median > T_median */
+    uint8_t status;        /* TOPLOC_CHUNK_OK or TOPLOC_CHUNK_MALFORMED (then accept = 0) */
+    uint8_t _pad[2];
+} toploc_verify_result;
+
+/* Size of one encoded proof: 2 + 2k (Sections 4 and 5.8: two bytes per coefficient
+ * plus the modulus). Host only. */
+size_t toploc_proof_bytes(uint32_t k);
+
+/* Bytes of device scratch that build / verify / topk need for `n_chunks` chunks
+ * with these parameters (top-k pairs handed from the selection kernel to the
+ * interpolation kernel). 0 on invalid parameters. Host only. */
+size_t toploc_workspace_bytes(const toploc_params *params, uint64_t n_chunks);
+
+/* Algorithm 1 over n_chunks chunks: top-k by magnitude, injective modulus
+ * (Algorithm 6), index map, interpolation over GF(p) (Algorithm 3), encode.
+ *   d_hidden_bf16   in,  device, [n_chunks][chunk_tokens*hidden] bf16
+ *   d_proofs        out, device, n_chunks * (2+2k) bytes (zero-filled for a chunk
+ *                   whose status is not TOPLOC_CHUNK_OK)
+ *   d_status        out, device, n_chunks bytes, TOPLOC_CHUNK_*
+ *   d_topk_idx_opt  out, device, n_chunks*k uint32 flat indices in the order
+ *                   (magnitude descending, index ascending); NULL to skip
+ *   d_workspace     device scratch, 16-byte aligned, >= toploc_workspace_bytes()
+ * n_chunks = 0 is valid and enqueues nothing. */
+int toploc_build_proofs(const void *d_hidden_bf16, uint64_t n_chunks, const toploc_params *params,
+                        uint8_t *d_proofs, uint8_t *d_status, uint32_t *d_topk_idx_opt,
+                        void *d_workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Algorithm 2 over n_chunks chunks: decode, top-k of the recomputed tensor,
+ * index map, Horner evaluation (Algorithm 5) at the k mapped indices,
+ * exponent / mantissa comparison, thresholds.
+ *   d_hidden_bf16   in,  device, recomputed activations, same layout as above
+ *   d_proofs        in,  device, n_chunks * (2+2k) bytes
+ *   thresholds      in,  host
+ *   d_results       out, device, n_chunks records */
+int toploc_verify_proofs(const void *d_hidden_bf16, uint64_t n_chunks, const toploc_params *params,
+                         const uint8_t *d_proofs, const toploc_thresholds *thresholds,
+                         toploc_verify_result *d_results, void *d_workspace, size_t workspace_bytes,
+                         void *hip_stream);
+
+/* The first step of both algorithms alone (topk(h, k) of Algorithm 1 / 2):
+ *   d_topk_idx   out, device, n_chunks*k uint32, (magnitude desc, index asc)
+ *   d_topk_val   out, device, n_chunks*k uint16 bf16 patterns, same order */
+int toploc_topk(const void *d_hidden_bf16, uint64_t n_chunks, const toploc_params *params,
+                uint32_t *d_topk_idx, uint16_t *d_topk_val, void *hip_stream);
+
+/* Provider-side ring of the last chunk_tokens hidden vectors per sequence
+ * (Section 5.8, Table 6: the provider keeps the last hidden states until the
+ * proof is cut).  Copies d_step_bf16 [n_seq][hidden] into row (step mod
+ * chunk_tokens) of d_ring_bf16 [n_seq][chunk_tokens][hidden]; after every
+ * chunk_tokens-th step the ring is a valid input of toploc_build_proofs with
+ * n_chunks = n_seq.  hidden must be a multiple of 8, both pointers 16-byte
+ * aligned. */
+int toploc_ring_append(void *d_ring_bf16, const void *d_step_bf16, uint32_t n_seq, uint32_t hidden,
+                       uint32_t chunk_tokens, uint32_t step, void *hip_stream);
+
+/* Kernel timing for benchmarks.  While enabled, every kernel launch of the
+ * calling thread's device is bracketed by HIP events on the caller's stream.
+ * toploc_profile_read synchronises those events and returns, per kernel slot
+ * (TOPLOC_KERNEL_*), the number of launches and their summed duration in
+ * milliseconds since the last reset, then resets.  Not thread safe. */
+#define TOPLOC_KERNEL_SELECT 0   /* top-k selection kernel (build, topk)    */
+#define TOPLOC_KERNEL_INTERP 1   /* modulus + interpolation + encode kernel */
+#define TOPLOC_KERNEL_VERIFY 2   /* fused verify kernel                     */
+#define TOPLOC_KERNEL_RING 3     /* ring append kernel                      */
+#define TOPLOC_KERNEL_COUNT 4
+int toploc_profile_enable(int on);
+int toploc_profile_read(uint32_t *launches /*[TOPLOC_KERNEL_COUNT]*/, float *total_ms /*[TOPLOC_KERNEL_COUNT]*/);
+
+/* Text for a TOPLOC_E* code; never NULL. */
+const char *toploc_strerror(int code);
+
+/* hipError_t (as int) of the last failed HIP call in this process, 0 if none. */
+int toploc_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TOPLOC_H */

@@ -1,0 +1,212 @@
+"""Thin ctypes binding of include/toploc.h: argument marshalling only.
+
+Every step of the path runs in the HIP kernels of libtoploc_hip.so.  PyTorch
+is used for device memory and the current HIP stream, nothing else.  There is
+no fallback: if the library has not been built, loading raises.
+"""
+import ctypes
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtoploc_hip.so")
+
+PRIME = 65497
+MAX_K = 512
+OK, EINVAL, EWORKSPACE, EHIP = 0, -1, -2, -3
+CHUNK_OK, CHUNK_NO_MODULUS, CHUNK_NO_INVERSE, CHUNK_MALFORMED = 0, 1, 2, 3
+KERNEL_SELECT, KERNEL_INTERP, KERNEL_VERIFY, KERNEL_RING, KERNEL_COUNT = 0, 1, 2, 3, 4
+KERNEL_NAMES = ("select_kernel", "interp_kernel", "verify_kernel", "ring_kernel")
+BF16_THRESHOLDS = (38, 10, 8)  # T_exp, T_mean, T_median (Section 5.2 of the paper)
+
+RESULT_DTYPE = np.dtype(
+    [
+        ("err_exp", "<u4"),
+        ("n_match", "<u4"),
+        ("mant_sum", "<u4"),
+        ("mant_median", "<u4"),
+        ("accept", "u1"),
+        ("status", "u1"),
+        ("pad", "u1", (2,)),
+    ]
+)
+
+EXPORTS = (
+    "toploc_proof_bytes",
+    "toploc_workspace_bytes",
+    "toploc_build_proofs",
+    "toploc_verify_proofs",
+    "toploc_topk",
+    "toploc_ring_append",
+    "toploc_profile_enable",
+    "toploc_profile_read",
+    "toploc_strerror",
+    "toploc_last_hip_error",
+)
+
+
+class Params(ctypes.Structure):
+    _fields_ = [("k", ctypes.c_uint32), ("chunk_tokens", ctypes.c_uint32), ("hidden", ctypes.c_uint32),
+                ("prime", ctypes.c_uint32)]
+
+
+class Thresholds(ctypes.Structure):
+    _fields_ = [("t_exp", ctypes.c_uint32), ("t_mean", ctypes.c_uint32), ("t_median", ctypes.c_uint32)]
+
+
+class ToplocError(RuntimeError):
+    def __init__(self, code, what):
+        self.code = code
+        super().__init__("%s: %s (code %d, hip error %d)" % (
+            what, lib().toploc_strerror(code).decode(), code, lib().toploc_last_hip_error()))
+
+
+_lib = None
+
+
+def lib():
+    """Load libtoploc_hip.so (built by paper_2501_16007_amd.build). Raises if missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                "libtoploc_hip.so is not built: run `python -m paper_2501_16007_amd.build` (hipcc, gfx950). "
+                "There is no CPU fallback.")
+        L = ctypes.CDLL(LIB_PATH)
+        c = ctypes
+        P = c.c_void_p
+        L.toploc_proof_bytes.argtypes = [c.c_uint32]
+        L.toploc_proof_bytes.restype = c.c_size_t
+        L.toploc_workspace_bytes.argtypes = [c.POINTER(Params), c.c_uint64]
+        L.toploc_workspace_bytes.restype = c.c_size_t
+        L.toploc_build_proofs.argtypes = [P, c.c_uint64, c.POINTER(Params), P, P, P, P, c.c_size_t, P]
+        L.toploc_verify_proofs.argtypes = [P, c.c_uint64, c.POINTER(Params), P, c.POINTER(Thresholds), P, P,
+                                           c.c_size_t, P]
+        L.toploc_topk.argtypes = [P, c.c_uint64, c.POINTER(Params), P, P, P]
+        L.toploc_ring_append.argtypes = [P, P, c.c_uint32, c.c_uint32, c.c_uint32, c.c_uint32, P]
+        L.toploc_profile_enable.argtypes = [c.c_int]
+        L.toploc_profile_read.argtypes = [c.POINTER(c.c_uint32), c.POINTER(c.c_float)]
+        L.toploc_strerror.argtypes = [c.c_int]
+        L.toploc_strerror.restype = c.c_char_p
+        L.toploc_last_hip_error.restype = c.c_int
+        _lib = L
+    return _lib
+
+
+def _stream(t):
+    return ctypes.c_void_p(torch.cuda.current_stream(t.device).cuda_stream)
+
+
+def _chunks(hidden, chunk_tokens):
+    """[n_seq, n_tok, H] or [n_chunks, chunk_tokens*H] bf16 device tensor -> (n_chunks, H or None)."""
+    if hidden.dtype != torch.bfloat16 or not hidden.is_cuda or not hidden.is_contiguous():
+        raise ValueError("hidden must be a contiguous bf16 tensor on the GPU")
+    if hidden.dim() == 3:
+        n_seq, n_tok, h = hidden.shape
+        if n_tok % chunk_tokens:
+            raise ValueError("n_tok must be a multiple of chunk_tokens")
+        return n_seq * (n_tok // chunk_tokens), h
+    if hidden.dim() == 2:
+        n_chunks, n = hidden.shape
+        if n % chunk_tokens:
+            raise ValueError("chunk length must be a multiple of chunk_tokens")
+        return n_chunks, n // chunk_tokens
+    raise ValueError("hidden must be [n_seq, n_tok, H] or [n_chunks, chunk_tokens*H]")
+
+
+def toploc_proof_bytes(k):
+    return int(lib().toploc_proof_bytes(k))
+
+
+def toploc_workspace_bytes(k, chunk_tokens, hidden, n_chunks):
+    p = Params(k, chunk_tokens, hidden, PRIME)
+    return int(lib().toploc_workspace_bytes(ctypes.byref(p), n_chunks))
+
+
+def new_workspace(k, chunk_tokens, hidden, n_chunks, device):
+    nbytes = max(16, toploc_workspace_bytes(k, chunk_tokens, hidden, n_chunks))
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def toploc_build_proofs(hidden, k=128, chunk_tokens=32, want_topk=False, workspace=None, out=None):
+    """Algorithm 1 over every chunk. Returns (proofs uint8 [n_chunks, 2+2k], status uint8 [n_chunks][, idx])."""
+    n_chunks, h = _chunks(hidden, chunk_tokens)
+    dev = hidden.device
+    p = Params(k, chunk_tokens, h, PRIME)
+    pb = 2 + 2 * k
+    if out is None:
+        proofs = torch.empty((n_chunks, pb), dtype=torch.uint8, device=dev)
+        status = torch.empty(n_chunks, dtype=torch.uint8, device=dev)
+    else:
+        proofs, status = out
+    idx = torch.empty((n_chunks, k), dtype=torch.int32, device=dev) if want_topk else None
+    if workspace is None:
+        workspace = new_workspace(k, chunk_tokens, h, n_chunks, dev)
+    rc = lib().toploc_build_proofs(
+        hidden.data_ptr(), n_chunks, ctypes.byref(p), proofs.data_ptr(), status.data_ptr(),
+        idx.data_ptr() if want_topk else None, workspace.data_ptr(), workspace.numel(), _stream(hidden))
+    if rc != OK:
+        raise ToplocError(rc, "toploc_build_proofs")
+    return (proofs, status, idx) if want_topk else (proofs, status)
+
+
+def toploc_verify_proofs(hidden, proofs, k=128, chunk_tokens=32, thresholds=BF16_THRESHOLDS, out=None):
+    """Algorithm 2 over every chunk. Returns a uint8 device tensor [n_chunks, 20]; see results_numpy."""
+    n_chunks, h = _chunks(hidden, chunk_tokens)
+    if proofs.dtype != torch.uint8 or not proofs.is_cuda or not proofs.is_contiguous() or \
+            proofs.numel() != n_chunks * (2 + 2 * k):
+        raise ValueError("proofs must be a contiguous uint8 device tensor of n_chunks * (2+2k) bytes")
+    p = Params(k, chunk_tokens, h, PRIME)
+    t = Thresholds(*thresholds)
+    res = out if out is not None else torch.empty((n_chunks, RESULT_DTYPE.itemsize), dtype=torch.uint8,
+                                                  device=hidden.device)
+    rc = lib().toploc_verify_proofs(hidden.data_ptr(), n_chunks, ctypes.byref(p), proofs.data_ptr(), ctypes.byref(t),
+                                    res.data_ptr(), None, 0, _stream(hidden))
+    if rc != OK:
+        raise ToplocError(rc, "toploc_verify_proofs")
+    return res
+
+
+def results_numpy(res):
+    """Device result records -> numpy structured array (host copy, synchronises)."""
+    return res.cpu().numpy().reshape(-1).view(RESULT_DTYPE)
+
+
+def toploc_topk(hidden, k=128, chunk_tokens=32):
+    """topk(h, k) per chunk: (idx int32 [n_chunks, k], val int16 [n_chunks, k] bf16 patterns)."""
+    n_chunks, h = _chunks(hidden, chunk_tokens)
+    p = Params(k, chunk_tokens, h, PRIME)
+    idx = torch.empty((n_chunks, k), dtype=torch.int32, device=hidden.device)
+    val = torch.empty((n_chunks, k), dtype=torch.int16, device=hidden.device)
+    rc = lib().toploc_topk(hidden.data_ptr(), n_chunks, ctypes.byref(p), idx.data_ptr(), val.data_ptr(),
+                           _stream(hidden))
+    if rc != OK:
+        raise ToplocError(rc, "toploc_topk")
+    return idx, val
+
+
+def toploc_ring_append(ring, step_vec, step):
+    """ring [n_seq, chunk_tokens, H] <- step_vec [n_seq, H] at row step mod chunk_tokens."""
+    n_seq, chunk_tokens, h = ring.shape
+    if step_vec.shape != (n_seq, h) or ring.dtype != torch.bfloat16 or step_vec.dtype != torch.bfloat16 or \
+            not ring.is_contiguous() or not step_vec.is_contiguous() or not ring.is_cuda or not step_vec.is_cuda:
+        raise ValueError("ring [n_seq, T, H] and step_vec [n_seq, H] must be contiguous bf16 device tensors")
+    rc = lib().toploc_ring_append(ring.data_ptr(), step_vec.data_ptr(), n_seq, h, chunk_tokens, step, _stream(ring))
+    if rc != OK:
+        raise ToplocError(rc, "toploc_ring_append")
+
+
+def toploc_profile_enable(on):
+    lib().toploc_profile_enable(1 if on else 0)
+
+
+def toploc_profile_read():
+    """{kernel name: (launches, total ms)} since the last read; synchronises the recorded events."""
+    n = (ctypes.c_uint32 * KERNEL_COUNT)()
+    ms = (ctypes.c_float * KERNEL_COUNT)()
+    rc = lib().toploc_profile_read(n, ms)
+    if rc != OK:
+        raise ToplocError(rc, "toploc_profile_read")
+    return {KERNEL_NAMES[i]: (int(n[i]), float(ms[i])) for i in range(KERNEL_COUNT)}

@@ -1,0 +1,73 @@
+// Arithmetic in GF(p), p = 65497 = 2^16 - 39, for gfx950 integer ALUs.
+//
+// The field is the modulus M of the paper's polynomial congruence (Appendix C,
+// Algorithms 3 and 5).  Every operand is < 2^16, so products fit 32 bits and the
+// full-rate 24-bit multiplier (v_mul_u32_u24 / v_mad_u32_u24) is exact.
+// Reduction folds the high half down with 2^16 = 39 (mod p): no division, no
+// 32-bit multiply-high, no floating point.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace toploc {
+
+constexpr uint32_t kPrime = 65497u;
+constexpr uint32_t kFold16 = 39u;    // 2^16 mod p
+constexpr uint32_t kFold32 = 1521u;  // 2^32 mod p = 39^2
+
+// exact product of two operands < 2^24 whose product fits 32 bits, on the full-rate
+// 24-bit multiplier (HIP declares __umul24 as returning int: keep it unsigned)
+__device__ __forceinline__ uint32_t mul24(uint32_t a, uint32_t b)
+{
+    return (uint32_t)__umul24(a, b);
+}
+
+// any 32-bit v -> v mod p
+__device__ __forceinline__ uint32_t reduce32(uint32_t v)
+{
+    v = mul24(v >> 16, kFold16) + (v & 0xFFFFu);  // < 40 * 2^16
+    v = mul24(v >> 16, kFold16) + (v & 0xFFFFu);  // <= 39*39 + 65535 < 2p
+    return v >= kPrime ? v - kPrime : v;
+}
+
+// a, b < 2^16
+__device__ __forceinline__ uint32_t mulmod(uint32_t a, uint32_t b)
+{
+    return reduce32(mul24(a, b));
+}
+
+// a*b + c with a, b, c < p: (p-1)^2 + (p-1) < 2^32, so one reduction suffices
+// (this is one step of Horner's rule, Algorithm 5).
+__device__ __forceinline__ uint32_t muladdmod(uint32_t a, uint32_t b, uint32_t c)
+{
+    return reduce32(mul24(a, b) + c);
+}
+
+__device__ __forceinline__ uint32_t submod(uint32_t a, uint32_t b)  // a, b < p
+{
+    return a >= b ? a - b : a + kPrime - b;
+}
+
+// a sum of fewer than 2^20 products of 16-bit operands -> mod p
+__device__ __forceinline__ uint32_t reduce64(uint64_t acc)
+{
+    uint32_t lo = reduce32((uint32_t)acc);
+    uint32_t hi = (uint32_t)(acc >> 32);                 // < 2^20
+    return reduce32(lo + reduce32(hi) * kFold32);        // < p + p*1521 < 2^32
+}
+
+// a^(p-2): the inverse of a != 0 by Fermat's little theorem (replaces the
+// extended Euclid of Algorithm 4; the inverse is unique, so the result is the same).
+__device__ __forceinline__ uint32_t invmod(uint32_t a)
+{
+    // p - 2 = 65495 = 0b1111111111010111
+    uint32_t r = a;
+#pragma unroll
+    for (int bit = 14; bit >= 0; --bit) {
+        r = mulmod(r, r);
+        if ((65495u >> bit) & 1u) r = mulmod(r, a);
+    }
+    return r;
+}
+
+}  // namespace toploc

@@ -1,0 +1,528 @@
+// TopLoc proof build / verify for MI355X (gfx950): kernels and the C ABI of
+// include/toploc.h.  One workgroup per chunk everywhere; chunks are independent.
+//
+//   select_kernel   topk(h, k)                       (Algorithm 1 / 2, first step)
+//   interp_kernel   findInjectiveModulus, i mod m, InterpolateModPolynomial, encode
+//                   (Algorithm 1, remaining steps; Algorithms 3, 4, 6)
+//   verify_kernel   decode, topk, i mod m, Horner at the k points, extractBits,
+//                   err_e / err_m statistics, thresholds (Algorithm 2, Algorithm 5)
+//   ring_kernel     provider-side ring of the last chunk_tokens hidden vectors
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <vector>
+
+#include "../../include/toploc.h"
+#include "gf65497.hpp"
+#include "select.hpp"
+
+namespace toploc {
+
+constexpr int kThreads = 256;   // 4 waves per workgroup
+constexpr int kLoads = 4;       // 16-byte loads in flight per lane and round
+constexpr int kCap = 2048;      // candidate buffer entries (>= 2 * TOPLOC_MAX_K... see host check)
+constexpr uint32_t kModHigh = 65536u;
+constexpr uint32_t kModLow = 32769u;  // 2^15 + 1
+
+typedef SelectShared<kThreads, kCap> SelShared;
+
+// ---------------------------------------------------------------------------
+// topk(h, k) alone: writes the ordered (index, value) pairs of every chunk
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void select_kernel(const u32x4* __restrict__ hidden, uint32_t nvec, uint32_t k,
+                                                          uint32_t* __restrict__ out_idx, uint16_t* __restrict__ out_val,
+                                                          uint32_t* __restrict__ out_idx2)
+{
+    __shared__ SelShared s;
+    const uint64_t chunk = blockIdx.x;
+    select_topk<kThreads, kLoads, kCap>(hidden + chunk * nvec, nvec, k, s);
+    for (uint32_t t = threadIdx.x; t < k; t += kThreads) {
+        const uint32_t i = s.cand_idx[t];
+        out_idx[chunk * k + t] = i;
+        out_val[chunk * k + t] = s.cand_bits[t];
+        if (out_idx2) out_idx2[chunk * k + t] = i;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Algorithm 6 with the residues compared in the form Algorithms 3 and 5 consume
+// them, (i mod m) mod p: largest m in [2^15+1, 65536] for which the k points are
+// distinct.  xs[j] receives the mapped index.  Returns 0 when no m works.
+// bitmap: 2048 zeroed words, left zeroed.  All threads call.
+// ---------------------------------------------------------------------------
+template <int THREADS>
+__device__ uint32_t find_modulus(const uint32_t* idx, uint32_t k, uint32_t* xs, uint32_t* bitmap, uint32_t* collide)
+{
+    const uint32_t tid = threadIdx.x;
+    for (uint32_t m = kModHigh; m >= kModLow; --m) {
+        for (uint32_t j = tid; j < k; j += THREADS) {
+            uint32_t x = idx[j] % m;
+            x = x >= kPrime ? x - kPrime : x;  // x < 65536 < 2p
+            xs[j] = x;
+            const uint32_t bit = 1u << (x & 31u);
+            if (atomicOr(&bitmap[x >> 5], bit) & bit) *collide = 1u;
+        }
+        __syncthreads();
+        const uint32_t c = *collide;
+        for (uint32_t j = tid; j < k; j += THREADS) bitmap[xs[j] >> 5] = 0;
+        __syncthreads();
+        if (!c) return m;
+        if (tid == 0) *collide = 0;
+        __syncthreads();
+    }
+    return 0;
+}
+
+// ---------------------------------------------------------------------------
+// Interpolation over GF(p): the unique polynomial of degree < k through the k
+// points (x_j, y_j) -- what Algorithm 3 returns -- computed in Lagrange form so
+// that every step is k-wide parallel:
+//   W(X)  = prod_j (X - x_j)                       product tree, log2 k levels
+//   d_j   = W'(x_j)                                Horner, one lane per point
+//   a_j   = y_j / d_j                              Fermat inverse
+//   S_r   = sum_j a_j x_j^r,  r = 0..k-1           blocked Vandermonde product
+//   c_i   = sum_{r=0}^{k-1-i} W_{i+1+r} S_r        (from P = sum_j a_j W/(X - x_j))
+// ---------------------------------------------------------------------------
+template <int KMAX, int RB>
+struct InterpShared {
+    uint32_t idx[KMAX];
+    uint32_t xs[KMAX];
+    uint32_t ys[KMAX];
+    uint32_t pa[KMAX + 1];   // product tree ping
+    uint32_t pb[KMAX + 1];   // product tree pong
+    uint32_t wder[KMAX];     // coefficients of W'
+    uint32_t a[KMAX];
+    uint32_t S[KMAX];
+    union {
+        uint32_t bitmap[2048];            // modulus search
+        uint16_t V[RB * (KMAX + 2)];      // V[r][j] = x_j^(r0 + r), row pitch KMAX + 2
+    } u;
+    uint32_t collide;
+};
+
+// low coefficients f_0..f_{deg-1} of a monic polynomial of degree deg; f_deg = 1
+__device__ __forceinline__ uint32_t monic_coef(const uint32_t* f, uint32_t deg, uint32_t i)
+{
+    return i == deg ? 1u : f[i];
+}
+
+template <int THREADS, int KMAX, int RB>
+__device__ void interpolate(InterpShared<KMAX, RB>& s, uint32_t k, uint32_t* coef_out /* LDS, k entries */)
+{
+    const uint32_t tid = threadIdx.x;
+    // ---- W(X) = prod (X - x_j): pairwise products of monic polynomials ----
+    uint32_t* src = s.pa;
+    uint32_t* dst = s.pb;
+    for (uint32_t j = tid; j < k; j += THREADS) src[j] = s.xs[j] ? kPrime - s.xs[j] : 0u;
+    __syncthreads();
+    for (uint32_t d = 1; d < k; d <<= 1) {
+        for (uint32_t o = tid; o < k; o += THREADS) {
+            const uint32_t start = (o / (2 * d)) * (2 * d);
+            const uint32_t t = o - start;
+            const uint32_t df = (k - start) < d ? (k - start) : d;
+            const uint32_t rem = k - start - df;
+            const uint32_t dg = rem < d ? rem : d;
+            const uint32_t* f = src + start;
+            const uint32_t* g = src + start + df;
+            // h_t = sum_i f_i g_{t-i}, i in [max(0, t-dg), min(t, df)]
+            const uint32_t lo = t > dg ? t - dg : 0u;
+            const uint32_t hi = t < df ? t : df;
+            uint64_t acc = 0;
+            for (uint32_t i = lo; i <= hi; ++i)
+                acc += (uint64_t)mul24(monic_coef(f, df, i), monic_coef(g, dg, t - i));
+            dst[o] = reduce64(acc);
+        }
+        __syncthreads();
+        uint32_t* tmp = src; src = dst; dst = tmp;
+    }
+    const uint32_t* W = src;  // W_0..W_{k-1}; W_k = 1
+    // ---- W'(X) coefficients: wder_r = (r+1) W_{r+1} ----
+    for (uint32_t r = tid; r < k; r += THREADS) s.wder[r] = mulmod(r + 1, monic_coef(W, k, r + 1));
+    __syncthreads();
+    // ---- a_j = y_j / W'(x_j) ----
+    for (uint32_t j = tid; j < k; j += THREADS) {
+        const uint32_t x = s.xs[j];
+        uint32_t acc = s.wder[k - 1];
+        for (int r = (int)k - 2; r >= 0; --r) acc = muladdmod(acc, x, s.wder[r]);
+        s.a[j] = mulmod(s.ys[j], invmod(acc));
+        s.S[j] = 0;
+    }
+    __syncthreads();
+    // ---- S_r = sum_j a_j x_j^r, RB rows of the Vandermonde matrix at a time ----
+    constexpr uint32_t PITCH = KMAX + 2;
+    constexpr int KPT = (KMAX + THREADS - 1) / THREADS;
+    uint32_t pw[KPT];
+#pragma unroll
+    for (int i = 0; i < KPT; ++i) pw[i] = 1u;  // x_j^r0 carried from block to block
+    constexpr uint32_t SLICES = THREADS / RB;
+    const uint32_t r_local = tid % RB;
+    const uint32_t slice = tid / RB;
+    for (uint32_t r0 = 0; r0 < k; r0 += RB) {
+#pragma unroll
+        for (int i = 0; i < KPT; ++i) {
+            const uint32_t j = tid + i * THREADS;
+            if (j < k) {
+                const uint32_t x = s.xs[j];
+                uint32_t p = pw[i];
+                for (uint32_t r = 0; r < RB; ++r) {
+                    s.u.V[r * PITCH + j] = (uint16_t)p;
+                    p = mulmod(p, x);
+                }
+                pw[i] = p;
+            }
+        }
+        __syncthreads();
+        if (r0 + r_local < k) {
+            const uint32_t per = (k + SLICES - 1) / SLICES;
+            const uint32_t j0 = slice * per;
+            const uint32_t j1 = (j0 + per) < k ? (j0 + per) : k;
+            uint64_t acc = 0;
+            for (uint32_t j = j0; j < j1; ++j) acc += (uint64_t)mul24(s.a[j], (uint32_t)s.u.V[r_local * PITCH + j]);
+            if (j0 < j1) atomicAdd(&s.S[r0 + r_local], reduce64(acc));
+        }
+        __syncthreads();
+    }
+    for (uint32_t r = tid; r < k; r += THREADS) s.S[r] = reduce32(s.S[r]);  // sums of SLICES partial results
+    __syncthreads();
+    // ---- c_i = sum_{r=0}^{k-1-i} W_{i+1+r} S_r ----
+    for (uint32_t i = tid; i < k; i += THREADS) {
+        uint64_t acc = 0;
+        for (uint32_t r = 0; r + i < k; ++r)
+            acc += (uint64_t)mul24(monic_coef(W, k, i + 1 + r), s.S[r]);
+        coef_out[i] = reduce64(acc);
+    }
+    __syncthreads();
+}
+
+template <int KMAX, int RB>
+__global__ __launch_bounds__(kThreads) void interp_kernel(const uint32_t* __restrict__ topk_idx,
+                                                          const uint16_t* __restrict__ topk_val, uint32_t k,
+                                                          uint8_t* __restrict__ proofs, uint8_t* __restrict__ status)
+{
+    __shared__ InterpShared<KMAX, RB> s;
+    __shared__ uint32_t coef[KMAX];
+    const uint32_t tid = threadIdx.x;
+    const uint64_t chunk = blockIdx.x;
+    for (uint32_t j = tid; j < k; j += kThreads) {
+        s.idx[j] = topk_idx[chunk * k + j];
+        const uint32_t y = topk_val[chunk * k + j];
+        s.ys[j] = y >= kPrime ? y - kPrime : y;
+    }
+    for (uint32_t w = tid; w < 2048; w += kThreads) s.u.bitmap[w] = 0;
+    if (tid == 0) s.collide = 0;
+    __syncthreads();
+    const uint32_t m = find_modulus<kThreads>(s.idx, k, s.xs, s.u.bitmap, &s.collide);
+    uint16_t* proof = reinterpret_cast<uint16_t*>(proofs + chunk * (2 + 2 * (uint64_t)k));
+    if (m == 0) {  // uniform
+        for (uint32_t j = tid; j <= k; j += kThreads) proof[j] = 0;
+        if (tid == 0) status[chunk] = TOPLOC_CHUNK_NO_MODULUS;
+        return;
+    }
+    interpolate<kThreads, KMAX, RB>(s, k, coef);
+    if (tid == 0) { proof[0] = (uint16_t)(m & 0xFFFFu); status[chunk] = TOPLOC_CHUNK_OK; }
+    for (uint32_t j = tid; j < k; j += kThreads) proof[1 + j] = (uint16_t)coef[j];
+}
+
+// ---------------------------------------------------------------------------
+// Algorithm 2, fused: one pass over the recomputed chunk
+// ---------------------------------------------------------------------------
+template <int KMAX>
+__global__ __launch_bounds__(kThreads) void verify_kernel(const u32x4* __restrict__ hidden, uint32_t nvec, uint32_t k,
+                                                          const uint8_t* __restrict__ proofs, toploc_thresholds thr,
+                                                          toploc_verify_result* __restrict__ results)
+{
+    __shared__ SelShared s;
+    __shared__ uint32_t coef[KMAX];
+    __shared__ uint32_t hist_d[128];   // err_m as a histogram of |m_p - m_v| in [0, 127]
+    __shared__ uint32_t err_e, mant_sum, bad;
+    const uint32_t tid = threadIdx.x;
+    const uint64_t chunk = blockIdx.x;
+    // decode(p)
+    const uint16_t* proof = reinterpret_cast<const uint16_t*>(proofs + chunk * (2 + 2 * (uint64_t)k));
+    if (tid == 0) { err_e = 0; mant_sum = 0; bad = 0; }
+    for (uint32_t b = tid; b < 128; b += kThreads) hist_d[b] = 0;
+    __syncthreads();
+    const uint32_t mf = proof[0];
+    const uint32_t m = mf ? mf : kModHigh;
+    for (uint32_t j = tid; j < k; j += kThreads) {
+        const uint32_t c = proof[1 + j];
+        coef[j] = c;
+        if (c >= kPrime) bad = 1u;
+    }
+    if (tid == 0 && m < kModLow) bad = 1u;
+    __syncthreads();
+    if (bad) {  // uniform
+        if (tid == 0) {
+            toploc_verify_result r = {};
+            r.status = TOPLOC_CHUNK_MALFORMED;
+            results[chunk] = r;
+        }
+        return;
+    }
+    // topk(h, k)
+    select_topk<kThreads, kLoads, kCap>(hidden + chunk * nvec, nvec, k, s);
+    // P(i mod m) by Horner, extractBits, compare
+    for (uint32_t j = tid; j < k; j += kThreads) {
+        uint32_t x = s.cand_idx[j] % m;
+        x = x >= kPrime ? x - kPrime : x;
+        uint32_t acc = coef[k - 1];
+        for (int i = (int)k - 2; i >= 0; --i) acc = muladdmod(acc, x, coef[i]);
+        const uint32_t v = s.cand_bits[j];
+        const uint32_t e_p = (acc >> 7) & 0xFFu, m_p = acc & 0x7Fu;
+        const uint32_t e_v = (v >> 7) & 0xFFu, m_v = v & 0x7Fu;
+        if (e_p == e_v) {
+            const uint32_t d = m_p > m_v ? m_p - m_v : m_v - m_p;
+            atomicAdd(&hist_d[d], 1u);
+            atomicAdd(&mant_sum, d);
+        } else {
+            atomicAdd(&err_e, 1u);
+        }
+    }
+    __syncthreads();
+    if (tid < 64) {
+        // |err_m| and its lower median from the histogram: the smallest d whose
+        // cumulative count reaches floor((n-1)/2) + 1
+        const uint32_t h0 = hist_d[2 * tid], h1 = hist_d[2 * tid + 1];
+        uint32_t v = h0 + h1;  // inclusive prefix sum over lanes
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t o = __shfl_up(v, d);
+            if ((int)tid >= d) v += o;
+        }
+        const uint32_t n = __shfl(v, 63);
+        const uint32_t target = n ? (n - 1) / 2 + 1 : 0;
+        const uint32_t before = v - h0 - h1;
+        uint32_t med = 0xFFFFFFFFu;
+        if (n && before < target && before + h0 >= target) med = 2 * tid;
+        else if (n && before + h0 < target && v >= target) med = 2 * tid + 1;
+        const uint64_t mask = __ballot(med != 0xFFFFFFFFu);
+        const int srcl = mask ? (__ffsll((long long)mask) - 1) : 0;
+        med = __shfl(med, srcl);
+        if (tid == 0) {
+            toploc_verify_result r = {};
+            r.err_exp = err_e;
+            r.n_match = n;
+            r.mant_sum = mant_sum;
+            r.mant_median = n ? med : 0u;
+            bool reject = err_e > thr.t_exp;
+            if (n) {
+                if ((uint64_t)mant_sum > (uint64_t)thr.t_mean * n) reject = true;   // mean(err_m) > T_mean
+                if (r.mant_median > thr.t_median) reject = true;
+            }
+            r.accept = reject ? 0 : 1;
+            r.status = TOPLOC_CHUNK_OK;
+            results[chunk] = r;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// ring[s][step mod T][:] = step_vec[s][:]
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void ring_kernel(u32x4* __restrict__ ring, const u32x4* __restrict__ step_vec,
+                                                   uint32_t n_seq, uint32_t hvec, uint32_t chunk_tokens, uint32_t slot)
+{
+    const uint64_t total = (uint64_t)n_seq * hvec;
+    for (uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; i < total; i += (uint64_t)gridDim.x * blockDim.x) {
+        const uint64_t sidx = i / hvec;
+        const uint64_t v = i - sidx * hvec;
+        ring[(sidx * chunk_tokens + slot) * hvec + v] = step_vec[i];
+    }
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+static int g_last_hip_error = 0;
+static int g_profile_on = 0;
+struct ProfRec { int slot; hipEvent_t a, b; };
+static std::vector<ProfRec> g_prof;
+
+static bool hip_ok(hipError_t e)
+{
+    if (e != hipSuccess) { g_last_hip_error = (int)e; return false; }
+    return true;
+}
+
+struct ProfScope {
+    int slot; hipStream_t st; hipEvent_t a = nullptr, b = nullptr; bool on;
+    ProfScope(int slot_, hipStream_t st_) : slot(slot_), st(st_), on(g_profile_on != 0)
+    {
+        if (on) {
+            on = hip_ok(hipEventCreate(&a)) && hip_ok(hipEventCreate(&b)) && hip_ok(hipEventRecord(a, st));
+        }
+    }
+    ~ProfScope()
+    {
+        if (on && hip_ok(hipEventRecord(b, st))) g_prof.push_back({slot, a, b});
+    }
+};
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// N (values per chunk) when the parameters are usable, else 0
+static uint64_t chunk_len(const toploc_params* p)
+{
+    if (!p || p->k == 0 || p->k > TOPLOC_MAX_K || p->prime != TOPLOC_PRIME) return 0;
+    if (p->chunk_tokens == 0 || p->hidden == 0) return 0;
+    const uint64_t n = (uint64_t)p->chunk_tokens * p->hidden;
+    if (n % 8 != 0 || n >= (1ull << 32) || p->k > n) return 0;
+    return n;
+}
+
+static size_t idx_bytes(uint64_t n_chunks, uint32_t k)
+{
+    const size_t b = (size_t)n_chunks * k * sizeof(uint32_t);
+    return (b + 15) & ~(size_t)15;
+}
+
+}  // namespace toploc
+
+using namespace toploc;
+
+extern "C" {
+
+size_t toploc_proof_bytes(uint32_t k) { return 2 + 2 * (size_t)k; }
+
+size_t toploc_workspace_bytes(const toploc_params* params, uint64_t n_chunks)
+{
+    if (chunk_len(params) == 0) return 0;
+    const size_t vb = ((size_t)n_chunks * params->k * sizeof(uint16_t) + 15) & ~(size_t)15;
+    return idx_bytes(n_chunks, params->k) + vb;
+}
+
+int toploc_topk(const void* d_hidden_bf16, uint64_t n_chunks, const toploc_params* params, uint32_t* d_topk_idx,
+                uint16_t* d_topk_val, void* hip_stream)
+{
+    const uint64_t n = chunk_len(params);
+    if (n == 0 || n_chunks >= (1ull << 31)) return TOPLOC_EINVAL;
+    if (n_chunks == 0) return TOPLOC_OK;
+    if (!d_hidden_bf16 || !d_topk_idx || !d_topk_val || !aligned16(d_hidden_bf16)) return TOPLOC_EINVAL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    {
+        ProfScope ps(TOPLOC_KERNEL_SELECT, st);
+        hipLaunchKernelGGL(select_kernel, dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
+                           (const u32x4*)d_hidden_bf16, (uint32_t)(n / 8), params->k, d_topk_idx, d_topk_val,
+                           (uint32_t*)nullptr);
+    }
+    return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
+}
+
+int toploc_build_proofs(const void* d_hidden_bf16, uint64_t n_chunks, const toploc_params* params, uint8_t* d_proofs,
+                        uint8_t* d_status, uint32_t* d_topk_idx_opt, void* d_workspace, size_t workspace_bytes,
+                        void* hip_stream)
+{
+    const uint64_t n = chunk_len(params);
+    if (n == 0 || n_chunks >= (1ull << 31)) return TOPLOC_EINVAL;
+    if (n_chunks == 0) return TOPLOC_OK;
+    if (!d_hidden_bf16 || !d_proofs || !d_status || !d_workspace) return TOPLOC_EINVAL;
+    if (!aligned16(d_hidden_bf16) || !aligned16(d_workspace)) return TOPLOC_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(d_proofs) & 1u) != 0) return TOPLOC_EINVAL;
+    if (workspace_bytes < toploc_workspace_bytes(params, n_chunks)) return TOPLOC_EWORKSPACE;
+    const uint32_t k = params->k;
+    hipStream_t st = (hipStream_t)hip_stream;
+    uint32_t* ws_idx = (uint32_t*)d_workspace;
+    uint16_t* ws_val = (uint16_t*)((char*)d_workspace + idx_bytes(n_chunks, k));
+    {
+        ProfScope ps(TOPLOC_KERNEL_SELECT, st);
+        hipLaunchKernelGGL(select_kernel, dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
+                           (const u32x4*)d_hidden_bf16, (uint32_t)(n / 8), k, ws_idx, ws_val, d_topk_idx_opt);
+    }
+    if (!hip_ok(hipGetLastError())) return TOPLOC_EHIP;
+    {
+        ProfScope ps(TOPLOC_KERNEL_INTERP, st);
+        if (k <= 128)
+            hipLaunchKernelGGL((interp_kernel<128, 32>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
+                               (const uint32_t*)ws_idx, (const uint16_t*)ws_val, k, d_proofs, d_status);
+        else
+            hipLaunchKernelGGL((interp_kernel<512, 32>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
+                               (const uint32_t*)ws_idx, (const uint16_t*)ws_val, k, d_proofs, d_status);
+    }
+    return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
+}
+
+int toploc_verify_proofs(const void* d_hidden_bf16, uint64_t n_chunks, const toploc_params* params,
+                         const uint8_t* d_proofs, const toploc_thresholds* thresholds, toploc_verify_result* d_results,
+                         void* d_workspace, size_t workspace_bytes, void* hip_stream)
+{
+    (void)d_workspace; (void)workspace_bytes;  // the fused kernel keeps everything on chip
+    const uint64_t n = chunk_len(params);
+    if (n == 0 || n_chunks >= (1ull << 31) || !thresholds) return TOPLOC_EINVAL;
+    if (n_chunks == 0) return TOPLOC_OK;
+    if (!d_hidden_bf16 || !d_proofs || !d_results || !aligned16(d_hidden_bf16)) return TOPLOC_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(d_proofs) & 1u) != 0 || (reinterpret_cast<uintptr_t>(d_results) & 3u) != 0)
+        return TOPLOC_EINVAL;
+    const uint32_t k = params->k;
+    hipStream_t st = (hipStream_t)hip_stream;
+    {
+        ProfScope ps(TOPLOC_KERNEL_VERIFY, st);
+        if (k <= 128)
+            hipLaunchKernelGGL((verify_kernel<128>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
+                               (const u32x4*)d_hidden_bf16, (uint32_t)(n / 8), k, d_proofs, *thresholds, d_results);
+        else
+            hipLaunchKernelGGL((verify_kernel<512>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
+                               (const u32x4*)d_hidden_bf16, (uint32_t)(n / 8), k, d_proofs, *thresholds, d_results);
+    }
+    return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
+}
+
+int toploc_ring_append(void* d_ring_bf16, const void* d_step_bf16, uint32_t n_seq, uint32_t hidden,
+                       uint32_t chunk_tokens, uint32_t step, void* hip_stream)
+{
+    if (hidden == 0 || hidden % 8 != 0 || chunk_tokens == 0) return TOPLOC_EINVAL;
+    if (n_seq == 0) return TOPLOC_OK;
+    if (!d_ring_bf16 || !d_step_bf16 || !aligned16(d_ring_bf16) || !aligned16(d_step_bf16)) return TOPLOC_EINVAL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const uint32_t hvec = hidden / 8;
+    const uint64_t total = (uint64_t)n_seq * hvec;
+    uint64_t blocks = (total + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    {
+        ProfScope ps(TOPLOC_KERNEL_RING, st);
+        hipLaunchKernelGGL(ring_kernel, dim3((uint32_t)blocks), dim3(256), 0, st, (u32x4*)d_ring_bf16,
+                           (const u32x4*)d_step_bf16, n_seq, hvec, chunk_tokens, step % chunk_tokens);
+    }
+    return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
+}
+
+int toploc_profile_enable(int on)
+{
+    g_profile_on = on ? 1 : 0;
+    return TOPLOC_OK;
+}
+
+int toploc_profile_read(uint32_t* launches, float* total_ms)
+{
+    if (!launches || !total_ms) return TOPLOC_EINVAL;
+    for (int i = 0; i < TOPLOC_KERNEL_COUNT; ++i) { launches[i] = 0; total_ms[i] = 0.f; }
+    int rc = TOPLOC_OK;
+    for (auto& r : g_prof) {
+        float ms = 0.f;
+        if (hip_ok(hipEventSynchronize(r.b)) && hip_ok(hipEventElapsedTime(&ms, r.a, r.b))) {
+            launches[r.slot] += 1;
+            total_ms[r.slot] += ms;
+        } else {
+            rc = TOPLOC_EHIP;
+        }
+        (void)hipEventDestroy(r.a);
+        (void)hipEventDestroy(r.b);
+    }
+    g_prof.clear();
+    return rc;
+}
+
+const char* toploc_strerror(int code)
+{
+    switch (code) {
+    case TOPLOC_OK: return "ok";
+    case TOPLOC_EINVAL: return "invalid argument (null or misaligned pointer, k = 0, k > chunk length, k > TOPLOC_MAX_K, "
+                               "chunk length not a multiple of 8 or >= 2^32, prime != 65497)";
+    case TOPLOC_EWORKSPACE: return "workspace smaller than toploc_workspace_bytes()";
+    case TOPLOC_EHIP: return "a HIP runtime call failed (see toploc_last_hip_error)";
+    default: return "unknown toploc error code";
+    }
+}
+
+int toploc_last_hip_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

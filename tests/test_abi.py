@@ -1,0 +1,66 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol the
+header declares, and its host-only entry points and argument validation work
+without a GPU (no kernel is launched here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from conftest import ROOT
+
+binding = pytest.importorskip("paper_2501_16007_amd.binding")
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "toploc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(toploc_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_is_built_and_exports_every_declared_symbol():
+    assert os.path.exists(binding.LIB_PATH), "run python -m paper_2501_16007_amd.build"
+    L = binding.lib()
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_proof_size_matches_paper(golden):
+    g = {r[0]: int(r[1]) for r in golden("sizes_and_thresholds.txt")}
+    assert binding.toploc_proof_bytes(128) == g["proof_bytes_k128"]
+    assert binding.toploc_proof_bytes(32) == 66 and binding.toploc_proof_bytes(512) == 1026
+    assert binding.BF16_THRESHOLDS == (g["t_exp_bf16"], g["t_mean_bf16"], g["t_median_bf16"])
+
+
+def test_workspace_bytes_and_parameter_validation():
+    assert binding.toploc_workspace_bytes(128, 32, 4096, 10) >= 10 * 128 * 6
+    assert binding.toploc_workspace_bytes(0, 32, 4096, 10) == 0        # k = 0
+    assert binding.toploc_workspace_bytes(513, 32, 4096, 10) == 0      # k > TOPLOC_MAX_K
+    assert binding.toploc_workspace_bytes(128, 32, 3, 10) == 0         # N = 96 < k
+    assert binding.toploc_workspace_bytes(8, 3, 5, 10) == 0            # N not a multiple of 8
+    L = binding.lib()
+    bad = binding.Params(128, 32, 4096, 65521)                         # wrong prime
+    assert L.toploc_workspace_bytes(ctypes.byref(bad), 1) == 0
+
+
+def test_calls_are_rejected_before_any_launch():
+    L = binding.lib()
+    ok = binding.Params(128, 32, 4096, binding.PRIME)
+    bad = binding.Params(0, 32, 4096, binding.PRIME)
+    thr = binding.Thresholds(38, 10, 8)
+    fake = ctypes.c_void_p(0x1000)  # never dereferenced: every call below is refused or empty
+    assert L.toploc_build_proofs(fake, 1, ctypes.byref(bad), fake, fake, None, fake, 1 << 20, None) == binding.EINVAL
+    assert L.toploc_build_proofs(None, 1, ctypes.byref(ok), fake, fake, None, fake, 1 << 20, None) == binding.EINVAL
+    assert L.toploc_build_proofs(ctypes.c_void_p(0x1008), 1, ctypes.byref(ok), fake, fake, None, fake, 1 << 20,
+                                 None) == binding.EINVAL               # misaligned input
+    assert L.toploc_build_proofs(fake, 1, ctypes.byref(ok), fake, fake, None, fake, 16, None) == binding.EWORKSPACE
+    assert L.toploc_build_proofs(fake, 0, ctypes.byref(ok), fake, fake, None, fake, 0, None) == binding.OK
+    assert L.toploc_verify_proofs(fake, 1, ctypes.byref(ok), fake, None, fake, None, 0, None) == binding.EINVAL
+    assert L.toploc_verify_proofs(fake, 0, ctypes.byref(ok), fake, ctypes.byref(thr), fake, None, 0, None) == binding.OK
+    assert L.toploc_topk(fake, 1, ctypes.byref(bad), fake, fake, None) == binding.EINVAL
+    assert L.toploc_ring_append(fake, fake, 4, 12, 32, 0, None) == binding.EINVAL   # hidden % 8 != 0
+    assert L.toploc_ring_append(fake, fake, 0, 16, 32, 0, None) == binding.OK
+    for code in (0, -1, -2, -3, -99):
+        assert L.toploc_strerror(code)
