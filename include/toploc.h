@@ -136,6 +136,15 @@ int toploc_topk(const void *d_hidden_bf16, uint64_t n_chunks, const toploc_param
 int toploc_ring_append(void *d_ring_bf16, const void *d_step_bf16, uint32_t n_seq, uint32_t hidden,
                        uint32_t chunk_tokens, uint32_t step, void *hip_stream);
 
+/* Measurement aid, not part of the method: reads n_chunks * chunk_values bf16
+ * values with the access pattern of the selection kernel (one workgroup per
+ * chunk, 16-byte loads) and keeps only a running maximum, to show what a pure
+ * read of the tensor achieves on the device.  d_out: device, n_chunks uint32
+ * (written only for a chunk holding an all-ones word).  chunk_values must be a
+ * multiple of 8 and < 2^32. */
+int toploc_bench_read(const void *d_hidden_bf16, uint64_t n_chunks, uint64_t chunk_values, uint32_t *d_out,
+                      void *hip_stream);
+
 /* Kernel timing for benchmarks.  While enabled, every kernel launch of the
  * calling thread's device is bracketed by HIP events on the caller's stream.
  * toploc_profile_read synchronises those events and returns, per kernel slot
@@ -145,7 +154,8 @@ int toploc_ring_append(void *d_ring_bf16, const void *d_step_bf16, uint32_t n_se
 #define TOPLOC_KERNEL_INTERP 1   /* modulus + interpolation + encode kernel */
 #define TOPLOC_KERNEL_VERIFY 2   /* fused verify kernel                     */
 #define TOPLOC_KERNEL_RING 3     /* ring append kernel                      */
-#define TOPLOC_KERNEL_COUNT 4
+#define TOPLOC_KERNEL_READ 4     /* toploc_bench_read                       */
+#define TOPLOC_KERNEL_COUNT 5
 int toploc_profile_enable(int on);
 int toploc_profile_read(uint32_t *launches /*[TOPLOC_KERNEL_COUNT]*/, float *total_ms /*[TOPLOC_KERNEL_COUNT]*/);
 

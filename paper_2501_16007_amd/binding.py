@@ -17,8 +17,8 @@ PRIME = 65497
 MAX_K = 512
 OK, EINVAL, EWORKSPACE, EHIP = 0, -1, -2, -3
 CHUNK_OK, CHUNK_NO_MODULUS, CHUNK_NO_INVERSE, CHUNK_MALFORMED = 0, 1, 2, 3
-KERNEL_SELECT, KERNEL_INTERP, KERNEL_VERIFY, KERNEL_RING, KERNEL_COUNT = 0, 1, 2, 3, 4
-KERNEL_NAMES = ("select_kernel", "interp_kernel", "verify_kernel", "ring_kernel")
+KERNEL_SELECT, KERNEL_INTERP, KERNEL_VERIFY, KERNEL_RING, KERNEL_READ, KERNEL_COUNT = 0, 1, 2, 3, 4, 5
+KERNEL_NAMES = ("select_kernel", "interp_kernel", "verify_kernel", "ring_kernel", "read_kernel")
 BF16_THRESHOLDS = (38, 10, 8)  # T_exp, T_mean, T_median (Section 5.2 of the paper)
 
 RESULT_DTYPE = np.dtype(
@@ -40,6 +40,7 @@ EXPORTS = (
     "toploc_verify_proofs",
     "toploc_topk",
     "toploc_ring_append",
+    "toploc_bench_read",
     "toploc_profile_enable",
     "toploc_profile_read",
     "toploc_strerror",
@@ -86,6 +87,7 @@ def lib():
                                            c.c_size_t, P]
         L.toploc_topk.argtypes = [P, c.c_uint64, c.POINTER(Params), P, P, P]
         L.toploc_ring_append.argtypes = [P, P, c.c_uint32, c.c_uint32, c.c_uint32, c.c_uint32, P]
+        L.toploc_bench_read.argtypes = [P, c.c_uint64, c.c_uint64, P, P]
         L.toploc_profile_enable.argtypes = [c.c_int]
         L.toploc_profile_read.argtypes = [c.POINTER(c.c_uint32), c.POINTER(c.c_float)]
         L.toploc_strerror.argtypes = [c.c_int]
@@ -196,6 +198,17 @@ def toploc_ring_append(ring, step_vec, step):
     rc = lib().toploc_ring_append(ring.data_ptr(), step_vec.data_ptr(), n_seq, h, chunk_tokens, step, _stream(ring))
     if rc != OK:
         raise ToplocError(rc, "toploc_ring_append")
+
+
+def toploc_bench_read(hidden, out=None):
+    """Pure read of [n_chunks, N] with the selection kernel's access pattern (measurement aid)."""
+    n_chunks, n = hidden.shape
+    if out is None:
+        out = torch.zeros(max(1, n_chunks), dtype=torch.int32, device=hidden.device)
+    rc = lib().toploc_bench_read(hidden.data_ptr(), n_chunks, n, out.data_ptr(), _stream(hidden))
+    if rc != OK:
+        raise ToplocError(rc, "toploc_bench_read")
+    return out
 
 
 def toploc_profile_enable(on):

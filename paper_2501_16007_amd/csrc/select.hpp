@@ -5,40 +5,56 @@
 // |x| taken as the integer (bits & 0x7FFF).
 //
 // Method (a streaming filter with a rising threshold, not a sort):
-//   * every lane reads 16 bytes (8 values) per load, U loads per round;
-//   * a value is a candidate when it comes before the current threshold element
-//     (tm, ti); the first, coarse test is one packed 16-bit max over the 8 values
-//     against tm, so in steady state a wave spends ~1.3 VALU ops per value;
-//   * candidates go to an LDS buffer through a wave-aggregated counter;
-//   * when the buffer passes its soft limit the workgroup prunes it to the exact
-//     best k (radix select on the 8-bit exponent, then the 7-bit mantissa, then the
-//     index among equal magnitudes) and the k-th survivor becomes the threshold;
-//   * a buffer overflow loses nothing: the values of the round are still in
-//     registers, the lanes that found no room retry after the prune.
-// Since the threshold is always an element that k-1 seen elements precede, a value
-// that fails the test can never belong to the top-k, so the result is exact and
-// independent of the order in which waves append.
+//   * every lane reads 16 bytes (8 values) per load, U loads per round, and the
+//     loads of the next round are issued before the current round is examined;
+//   * the hot loop does one thing per vector: a packed 16-bit max over the 8
+//     magnitudes against the threshold magnitude tm (about 1.3 VALU ops per value).
+//     A vector that passes is copied whole into an LDS queue, nothing else;
+//   * when the queue passes its soft limit the workgroup drains it with all lanes
+//     evenly loaded: every queued value that comes before the threshold element
+//     (tm, ti) goes to the candidate buffer, and when that buffer passes its own
+//     limit it is pruned to the exact best k (radix select on the 8-bit exponent,
+//     then the 7-bit mantissa, then the index among equal magnitudes); the k-th
+//     survivor becomes the new threshold element;
+//   * the first threshold comes from the per-vector maxima of the first round, so
+//     nothing is ever flooded; a queue overflow loses nothing either: the vectors of
+//     the round are still in registers and the lanes that found no room retry after
+//     the drain.
+// The threshold is always an element that k-1 seen elements precede, so a value
+// that fails the test can never belong to the top-k: the result is exact and does
+// not depend on the order in which waves run.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#ifndef TOPLOC_PRUNE_ATTR
+#define TOPLOC_PRUNE_ATTR __forceinline__
+#endif
+#ifndef TOPLOC_DRAIN_ATTR
+#define TOPLOC_DRAIN_ATTR __forceinline__
+#endif
 
 namespace toploc {
 
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-template <int THREADS, int CAP>
+template <int THREADS, int CAP, int QCAP>
 struct SelectShared {
-    uint32_t cand_idx[CAP];   // flat index of a candidate
-    uint16_t cand_bits[CAP];  // its bf16 pattern
+    u32x4 qvec[QCAP];         // queue: vectors holding at least one magnitude >= tm
+    uint32_t qidx[QCAP];      // their vector index inside the chunk
+    uint32_t cand_idx[CAP];   // candidates: flat index
+    uint16_t cand_bits[CAP];  //             bf16 pattern
     uint16_t eq_slot[CAP];    // prune: slots whose magnitude equals the new threshold
     uint32_t hist_e[256];     // prune: exponent histogram
     uint32_t hist_m[128];     // prune: mantissa histogram inside the threshold exponent
-    uint32_t count;           // slots handed out (may run past CAP on overflow)
+    uint32_t qcount;          // queue slots handed out (may run past QCAP on overflow)
+    uint32_t count;           // candidate slots in use
     uint32_t eq_count;
     int32_t tm;               // threshold magnitude
     uint32_t ti;              // threshold index
-    uint32_t flag[3];         // "buffer passed the soft limit" for barrier round r mod 3
+    uint32_t flag[3];         // "queue passed its soft limit" for barrier round r mod 3
 };
 
 __device__ __forceinline__ uint32_t lane_id() { return __lane_id(); }
@@ -76,46 +92,31 @@ __device__ __forceinline__ void find_bin(const uint32_t* hist, uint32_t above0, 
     above = __shfl(fabove, src);
 }
 
-// Wave-aggregated append. Returns true for a lane that passed but found no room.
-template <int THREADS, int CAP>
-__device__ __forceinline__ bool append(SelectShared<THREADS, CAP>& s, bool pass, uint32_t idx, uint32_t bits,
-                                       uint32_t soft, uint32_t* flag)
+// the threshold element as the lanes carry it
+struct Threshold {
+    int32_t tm;
+    uint32_t ti;
+};
+
+__device__ __forceinline__ bool before(int32_t mag, uint32_t idx, const Threshold& t)
 {
-    const uint64_t mask = __ballot(pass);
-    if (mask == 0) return false;
-    const uint32_t lane = lane_id();
-    const int leader = __ffsll((long long)mask) - 1;
-    const uint32_t n = __popcll(mask);
-    uint32_t base = 0;
-    if ((int)lane == leader) {
-        base = atomicAdd(&s.count, n);
-        if (base + n > soft) *flag = 1u;
-    }
-    base = __shfl(base, leader);
-    const uint32_t slot = base + __popcll(mask & ((1ull << lane) - 1ull));
-    if (pass && slot < (uint32_t)CAP) {
-        s.cand_idx[slot] = idx;
-        s.cand_bits[slot] = (uint16_t)bits;
-        return false;
-    }
-    return pass;
+    return mag > t.tm || (mag == t.tm && idx < t.ti);
 }
 
-// Reduce the buffer to the exact best k entries and set the threshold to the k-th.
-// Called by all threads. On return count == min(k, entries) and *overflow tells
-// whether some lanes could not append in the round before.
-template <int THREADS, int CAP>
-__device__ __attribute__((noinline)) void prune(SelectShared<THREADS, CAP>& s, uint32_t k, int32_t& tm, uint32_t& ti, bool& overflow)
+// If the candidate buffer holds more than `limit` entries, reduce it to the exact
+// best k and make the k-th the threshold element.  Called by all threads, starts and
+// ends with a barrier.  Returns true when it pruned (then `t` is the new threshold).
+template <int THREADS, int CAP, int QCAP>
+__device__ TOPLOC_PRUNE_ATTR bool prune_if_above(SelectShared<THREADS, CAP, QCAP>& s, uint32_t k, uint32_t limit,
+                                                         Threshold& t)
 {
     constexpr int EPT = CAP / THREADS;
     const uint32_t tid = threadIdx.x;
-    __syncthreads();  // appends of the round are visible
-    const uint32_t raw = s.count;
-    overflow = raw > (uint32_t)CAP;
-    const uint32_t M = overflow ? (uint32_t)CAP : raw;
-    if (M <= k) {  // nothing to drop (uniform decision)
-        __syncthreads();
-        return;
+    __syncthreads();  // appends are visible
+    const uint32_t M = s.count;
+    if (M <= limit) {  // uniform decision
+        __syncthreads();  // everyone has read the count before anyone appends again
+        return false;
     }
     uint32_t idx[EPT];
     uint32_t bits[EPT];
@@ -127,7 +128,7 @@ __device__ __attribute__((noinline)) void prune(SelectShared<THREADS, CAP>& s, u
     }
     for (uint32_t b = tid; b < 256; b += THREADS) s.hist_e[b] = 0;
     for (uint32_t b = tid; b < 128; b += THREADS) s.hist_m[b] = 0;
-    __syncthreads();  // everyone holds its entries and has read `raw`
+    __syncthreads();  // everyone holds its entries and has read the count
     if (tid == 0) { s.count = 0; s.eq_count = 0; }
 #pragma unroll
     for (int i = 0; i < EPT; ++i)
@@ -159,13 +160,13 @@ __device__ __attribute__((noinline)) void prune(SelectShared<THREADS, CAP>& s, u
         if (rank == need - 1) { s.ti = mine; s.tm = (int32_t)new_tm; }
     }
     __syncthreads();
-    tm = s.tm;
-    ti = s.ti;
+    t.tm = s.tm;
+    t.ti = s.ti;
 #pragma unroll
     for (int i = 0; i < EPT; ++i) {
         if (tid + i * THREADS < M) {
             const int32_t mag = (int32_t)(bits[i] & 0x7FFFu);
-            if (mag > tm || (mag == tm && idx[i] <= ti)) {
+            if (mag > t.tm || (mag == t.tm && idx[i] <= t.ti)) {
                 const uint32_t q = atomicAdd(&s.count, 1u);
                 s.cand_idx[q] = idx[i];
                 s.cand_bits[q] = (uint16_t)bits[i];
@@ -173,67 +174,148 @@ __device__ __attribute__((noinline)) void prune(SelectShared<THREADS, CAP>& s, u
         }
     }
     __syncthreads();
+    return true;
 }
 
-// Top-k of src[0 .. 8*nvec) into s.cand_idx / s.cand_bits [0 .. k), in the order
-// (magnitude descending, index ascending).  Requires k <= 8*nvec, k <= CAP/2,
-// 8*nvec < 2^32.  All threads of the workgroup call it; it ends with a barrier.
-template <int THREADS, int U, int CAP>
-__device__ void select_topk(const u32x4* __restrict__ src, uint32_t nvec, uint32_t k, SelectShared<THREADS, CAP>& s)
+// Move every queued value that comes before the threshold element into the candidate
+// buffer, pruning whenever that buffer passes CAP/2; then empty the queue.  Two lanes
+// share a vector, so one batch adds at most 4*THREADS values: CAP/2 + 4*THREADS <= CAP.
+// Called by all threads after a barrier that made the queue writes visible; ends with
+// a barrier.  Returns true when lanes are still waiting for room in the queue.
+template <int THREADS, int CAP, int QCAP>
+__device__ TOPLOC_DRAIN_ATTR bool drain(SelectShared<THREADS, CAP, QCAP>& s, uint32_t k, Threshold& t)
+{
+    static_assert(CAP / 2 + 4 * THREADS <= CAP, "a batch must fit above the soft limit");
+    const uint32_t tid = threadIdx.x;
+    const uint32_t raw = s.qcount;
+    const uint32_t nq = raw < (uint32_t)QCAP ? raw : (uint32_t)QCAP;
+    const uint32_t half = tid & 1u;
+    for (uint32_t b0 = 0; b0 < nq; b0 += THREADS / 2) {
+        const uint32_t q = b0 + (tid >> 1);
+        if (q < nq) {
+            const u32x2 w = reinterpret_cast<const u32x2*>(&s.qvec[q])[half];
+            const uint32_t ebase = s.qidx[q] * 8u + half * 4u;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t bits = (((e >> 1) ? w.y : w.x) >> (16 * (e & 1))) & 0xFFFFu;
+                const int32_t mag = (int32_t)(bits & 0x7FFFu);
+                if (before(mag, ebase + e, t)) {
+                    const uint32_t slot = atomicAdd(&s.count, 1u);
+                    s.cand_idx[slot] = ebase + e;
+                    s.cand_bits[slot] = (uint16_t)bits;
+                }
+            }
+        }
+        (void)prune_if_above<THREADS, CAP, QCAP>(s, k, CAP / 2, t);
+    }
+    if (tid == 0) s.qcount = 0;
+    __syncthreads();
+    return raw > (uint32_t)QCAP;
+}
+
+// value e (0..7) of a 16-byte vector
+__device__ __forceinline__ uint32_t vec_elem(const u32x4& r, int e)
+{
+    const uint32_t w = (e >> 1) == 0 ? r.x : (e >> 1) == 1 ? r.y : (e >> 1) == 2 ? r.z : r.w;
+    return (w >> (16 * (e & 1))) & 0xFFFFu;
+}
+
+// largest of the 8 magnitudes of a vector
+__device__ __forceinline__ int32_t vec_max_mag(const u32x4& r)
+{
+    const uint32_t a = r.x & 0x7FFF7FFFu, b = r.y & 0x7FFF7FFFu;
+    const uint32_t c = r.z & 0x7FFF7FFFu, d = r.w & 0x7FFF7FFFu;
+    const u16x2 m01 = __builtin_elementwise_max(__builtin_bit_cast(u16x2, a), __builtin_bit_cast(u16x2, b));
+    const u16x2 m23 = __builtin_elementwise_max(__builtin_bit_cast(u16x2, c), __builtin_bit_cast(u16x2, d));
+    const u16x2 mm = __builtin_elementwise_max(m01, m23);
+    return (int32_t)(mm.x > mm.y ? mm.x : mm.y);
+}
+
+// Top-k of src[0 .. 8*nvec) into s.cand_idx / s.cand_bits [0 .. k); with SORT in the
+// order (magnitude descending, index ascending), else in no particular order.
+// Requires k <= 8*nvec, k <= CAP/2, 8*nvec < 2^32.  All threads of the workgroup call
+// it; it ends with a barrier.
+template <int THREADS, int U, int CAP, int QCAP, bool SORT>
+__device__ __forceinline__ void select_topk(const u32x4* __restrict__ src, uint32_t nvec, uint32_t k,
+                            SelectShared<THREADS, CAP, QCAP>& s)
 {
     static_assert(CAP % THREADS == 0, "CAP must be a multiple of THREADS");
-    static_assert(U >= 1 && U <= 4, "pending mask holds 8 bits per load");
-    constexpr uint32_t SOFT = CAP / 2;
+    static_assert(THREADS * U <= CAP, "the first round's per-vector maxima must fit the buffer");
+    constexpr uint32_t QSOFT = QCAP / 2;
+    constexpr uint32_t ROUND = THREADS * U;
     const uint32_t tid = threadIdx.x;
     if (tid == 0) {
-        s.count = 0; s.eq_count = 0; s.tm = 0; s.ti = 0xFFFFFFFFu;
+        s.qcount = 0; s.count = 0; s.eq_count = 0; s.tm = 0; s.ti = 0xFFFFFFFFu;
         s.flag[0] = 0; s.flag[1] = 0; s.flag[2] = 0;
     }
-    __syncthreads();
-    int32_t tm = 0;            // everything comes before (0, 0xFFFFFFFF): the buffer is empty
-    uint32_t ti = 0xFFFFFFFFu;
-    uint32_t round = 0;        // barrier rounds; flag[round % 3] belongs to the current one
+    Threshold t;
+    t.tm = 0;            // everything comes before (0, 0xFFFFFFFF): nothing seen yet
+    t.ti = 0xFFFFFFFFu;
+    uint32_t round = 0;  // barrier rounds; flag[round % 3] belongs to the current one
 
-    for (uint32_t base = 0; base < nvec; base += THREADS * U) {
-        u32x4 r[U];
-        uint32_t pend = 0;     // bit 8u+e: value e of load u still has to be placed
+    u32x4 cur[U], nxt[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint32_t v = u * THREADS + tid;
+        cur[u] = u32x4{0u, 0u, 0u, 0u};
+        if (v < nvec) cur[u] = __builtin_nontemporal_load(src + v);
+    }
+    // First threshold: the largest value of every vector of the first round is a real
+    // element, so the k-th best of those maxima already has k-1 elements before it.
+    // The maxima only set the threshold; the round itself is then filtered like any
+    // other (threshold element included, hence ti + 1).
+    const uint32_t first = nvec < ROUND ? nvec : ROUND;
+    if (first > k) {  // uniform
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const uint32_t v = base + u * THREADS + tid;
-            r[u] = u32x4{0u, 0u, 0u, 0u};
-            if (v < nvec) { r[u] = __builtin_nontemporal_load(src + v); pend |= 0xFFu << (8 * u); }
+            const uint32_t v = u * THREADS + tid;
+            if (v < nvec) {
+                uint32_t best = vec_elem(cur[u], 0), be = 0;
+#pragma unroll
+                for (int e = 1; e < 8; ++e) {
+                    const uint32_t b = vec_elem(cur[u], e);
+                    if ((b & 0x7FFFu) > (best & 0x7FFFu)) { best = b; be = e; }
+                }
+                s.cand_idx[v] = v * 8u + be;
+                s.cand_bits[v] = (uint16_t)best;
+            }
         }
-        // coarse filter: the largest of the 8 magnitudes against the threshold magnitude
+        __syncthreads();            // also orders the initialisation above
+        if (tid == 0) s.count = first;
+        (void)prune_if_above<THREADS, CAP, QCAP>(s, k, k, t);
+        t.ti += 1u;
+        if (tid == 0) s.count = 0;  // the maxima come back through the filter below
+    }
+    __syncthreads();
+
+    for (uint32_t base = 0; base < nvec; base += ROUND) {
+        // loads of the next round fly while this one is examined
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const uint32_t a = r[u].x & 0x7FFF7FFFu, b = r[u].y & 0x7FFF7FFFu;
-            const uint32_t c = r[u].z & 0x7FFF7FFFu, d = r[u].w & 0x7FFF7FFFu;
-            u16x2 m01 = __builtin_elementwise_max(__builtin_bit_cast(u16x2, a), __builtin_bit_cast(u16x2, b));
-            u16x2 m23 = __builtin_elementwise_max(__builtin_bit_cast(u16x2, c), __builtin_bit_cast(u16x2, d));
-            u16x2 mm = __builtin_elementwise_max(m01, m23);
-            const int32_t mx = (int32_t)(mm.x > mm.y ? mm.x : mm.y);
-            if (mx < tm) pend &= ~(0xFFu << (8 * u));
+            const uint32_t v = base + ROUND + u * THREADS + tid;
+            nxt[u] = u32x4{0u, 0u, 0u, 0u};
+            if (v < nvec) nxt[u] = __builtin_nontemporal_load(src + v);
         }
+        uint32_t pend = 0;  // bit u: vector u still has to be queued
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (base + u * THREADS + tid < nvec) pend |= 1u << u;
         while (true) {
             uint32_t* flag = &s.flag[round % 3u];
-            if (__any(pend != 0)) {
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    uint32_t pu = (pend >> (8 * u)) & 0xFFu;
-                    if (!__any(pu != 0)) continue;
-                    const uint32_t ebase = (base + u * THREADS + tid) * 8u;
-#pragma unroll 1
-                    for (uint32_t e = 0; e < 8; ++e) {
-                        const uint32_t q = e >> 1;
-                        const uint32_t w = q == 0 ? r[u].x : q == 1 ? r[u].y : q == 2 ? r[u].z : r[u].w;
-                        const uint32_t bits = (w >> (16u * (e & 1u))) & 0xFFFFu;
-                        const int32_t mag = (int32_t)(bits & 0x7FFFu);
-                        const uint32_t idx = ebase + e;
-                        const bool pass = ((pu >> e) & 1u) && (mag > tm || (mag == tm && idx < ti));
-                        const bool over = append<THREADS, CAP>(s, pass, idx, bits, SOFT, flag);
-                        if (!over) pu &= ~(1u << e);
+            for (int u = 0; u < U; ++u) {
+                if ((pend >> u) & 1u) {
+                    if (vec_max_mag(cur[u]) >= t.tm) {
+                        const uint32_t slot = atomicAdd(&s.qcount, 1u);
+                        if (slot >= QSOFT) *flag = 1u;
+                        if (slot < (uint32_t)QCAP) {
+                            s.qvec[slot] = cur[u];
+                            s.qidx[slot] = base + u * THREADS + tid;
+                            pend &= ~(1u << u);
+                        }
+                    } else {
+                        pend &= ~(1u << u);
                     }
-                    pend = (pend & ~(0xFFu << (8 * u))) | (pu << (8 * u));
                 }
             }
             __syncthreads();
@@ -241,45 +323,45 @@ __device__ void select_topk(const u32x4* __restrict__ src, uint32_t nvec, uint32
             if (tid == 0) s.flag[(round + 2u) % 3u] = 0;  // the previous round's flag: read by all before this barrier
             ++round;
             if (!f) break;
-            bool overflow;
-            prune<THREADS, CAP>(s, k, tm, ti, overflow);
-            if (!overflow) break;
+            if (!drain<THREADS, CAP, QCAP>(s, k, t)) break;
         }
+#pragma unroll
+        for (int u = 0; u < U; ++u) cur[u] = nxt[u];
     }
     __syncthreads();
-    if (s.count > k) {  // uniform: nobody appends any more
-        bool overflow;
-        prune<THREADS, CAP>(s, k, tm, ti, overflow);
-    }
-    // order the k survivors: rank = number of survivors that come before
-    constexpr int KPT = (CAP / 2 + THREADS - 1) / THREADS;
-    uint32_t my_idx[KPT], my_bits[KPT], my_rank[KPT];
+    (void)drain<THREADS, CAP, QCAP>(s, k, t);
+    (void)prune_if_above<THREADS, CAP, QCAP>(s, k, k, t);
+    if (SORT) {
+        // order the k survivors: rank = number of survivors that come before
+        constexpr int KPT = (CAP / 2 + THREADS - 1) / THREADS;
+        uint32_t my_idx[KPT], my_bits[KPT], my_rank[KPT];
 #pragma unroll
-    for (int i = 0; i < KPT; ++i) {
-        const uint32_t t = tid + i * THREADS;
-        my_idx[i] = 0; my_bits[i] = 0; my_rank[i] = 0;
-        if (t < k) {
-            my_idx[i] = s.cand_idx[t];
-            my_bits[i] = s.cand_bits[t];
-            const uint32_t mag = my_bits[i] & 0x7FFFu;
-            uint32_t rank = 0;
-            for (uint32_t u = 0; u < k; ++u) {
-                const uint32_t om = s.cand_bits[u] & 0x7FFFu;
-                const uint32_t oi = s.cand_idx[u];
-                rank += (om > mag || (om == mag && oi < my_idx[i])) ? 1u : 0u;
+        for (int i = 0; i < KPT; ++i) {
+            const uint32_t j = tid + i * THREADS;
+            my_idx[i] = 0; my_bits[i] = 0; my_rank[i] = 0;
+            if (j < k) {
+                my_idx[i] = s.cand_idx[j];
+                my_bits[i] = s.cand_bits[j];
+                const uint32_t mag = my_bits[i] & 0x7FFFu;
+                uint32_t rank = 0;
+                for (uint32_t u = 0; u < k; ++u) {
+                    const uint32_t om = s.cand_bits[u] & 0x7FFFu;
+                    const uint32_t oi = s.cand_idx[u];
+                    rank += (om > mag || (om == mag && oi < my_idx[i])) ? 1u : 0u;
+                }
+                my_rank[i] = rank;
             }
-            my_rank[i] = rank;
         }
-    }
-    __syncthreads();
+        __syncthreads();
 #pragma unroll
-    for (int i = 0; i < KPT; ++i) {
-        if (tid + i * THREADS < k) {
-            s.cand_idx[my_rank[i]] = my_idx[i];
-            s.cand_bits[my_rank[i]] = (uint16_t)my_bits[i];
+        for (int i = 0; i < KPT; ++i) {
+            if (tid + i * THREADS < k) {
+                s.cand_idx[my_rank[i]] = my_idx[i];
+                s.cand_bits[my_rank[i]] = (uint16_t)my_bits[i];
+            }
         }
+        __syncthreads();
     }
-    __syncthreads();
 }
 
 }  // namespace toploc

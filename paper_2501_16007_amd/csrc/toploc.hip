@@ -18,24 +18,41 @@
 
 namespace toploc {
 
-constexpr int kThreads = 256;   // 4 waves per workgroup
-constexpr int kLoads = 4;       // 16-byte loads in flight per lane and round
-constexpr int kCap = 2048;      // candidate buffer entries (>= 2 * TOPLOC_MAX_K... see host check)
+#ifndef TOPLOC_THREADS
+#define TOPLOC_THREADS 256
+#endif
+#ifndef TOPLOC_LOADS
+#define TOPLOC_LOADS 4
+#endif
+#ifndef TOPLOC_CAP
+#define TOPLOC_CAP 2048
+#endif
+#ifndef TOPLOC_MIN_WAVES
+#define TOPLOC_MIN_WAVES 4  // waves per SIMD the streaming kernels must reach (bounds their VGPRs)
+#endif
+#ifndef TOPLOC_QCAP
+#define TOPLOC_QCAP 512
+#endif
+constexpr int kThreads = TOPLOC_THREADS;  // threads per workgroup (one chunk each)
+constexpr int kLoads = TOPLOC_LOADS;      // 16-byte loads in flight per lane and round
+constexpr int kCap = TOPLOC_CAP;          // candidate buffer entries
+constexpr int kQcap = TOPLOC_QCAP;        // queue entries (16-byte vectors)
+static_assert(kCap >= 4 * (int)TOPLOC_MAX_K, "the soft limit CAP/2 must leave room above k");
 constexpr uint32_t kModHigh = 65536u;
 constexpr uint32_t kModLow = 32769u;  // 2^15 + 1
 
-typedef SelectShared<kThreads, kCap> SelShared;
+typedef SelectShared<kThreads, kCap, kQcap> SelShared;
 
 // ---------------------------------------------------------------------------
 // topk(h, k) alone: writes the ordered (index, value) pairs of every chunk
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void select_kernel(const u32x4* __restrict__ hidden, uint32_t nvec, uint32_t k,
+__global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void select_kernel(const u32x4* __restrict__ hidden, uint32_t nvec, uint32_t k,
                                                           uint32_t* __restrict__ out_idx, uint16_t* __restrict__ out_val,
                                                           uint32_t* __restrict__ out_idx2)
 {
     __shared__ SelShared s;
     const uint64_t chunk = blockIdx.x;
-    select_topk<kThreads, kLoads, kCap>(hidden + chunk * nvec, nvec, k, s);
+    select_topk<kThreads, kLoads, kCap, kQcap, true>(hidden + chunk * nvec, nvec, k, s);
     for (uint32_t t = threadIdx.x; t < k; t += kThreads) {
         const uint32_t i = s.cand_idx[t];
         out_idx[chunk * k + t] = i;
@@ -227,7 +244,7 @@ __global__ __launch_bounds__(kThreads) void interp_kernel(const uint32_t* __rest
 // Algorithm 2, fused: one pass over the recomputed chunk
 // ---------------------------------------------------------------------------
 template <int KMAX>
-__global__ __launch_bounds__(kThreads) void verify_kernel(const u32x4* __restrict__ hidden, uint32_t nvec, uint32_t k,
+__global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void verify_kernel(const u32x4* __restrict__ hidden, uint32_t nvec, uint32_t k,
                                                           const uint8_t* __restrict__ proofs, toploc_thresholds thr,
                                                           toploc_verify_result* __restrict__ results)
 {
@@ -260,7 +277,7 @@ __global__ __launch_bounds__(kThreads) void verify_kernel(const u32x4* __restric
         return;
     }
     // topk(h, k)
-    select_topk<kThreads, kLoads, kCap>(hidden + chunk * nvec, nvec, k, s);
+    select_topk<kThreads, kLoads, kCap, kQcap, false>(hidden + chunk * nvec, nvec, k, s);  // order is irrelevant here
     // P(i mod m) by Horner, extractBits, compare
     for (uint32_t j = tid; j < k; j += kThreads) {
         uint32_t x = s.cand_idx[j] % m;
@@ -328,6 +345,30 @@ __global__ __launch_bounds__(256) void ring_kernel(u32x4* __restrict__ ring, con
         const uint64_t v = i - sidx * hvec;
         ring[(sidx * chunk_tokens + slot) * hvec + v] = step_vec[i];
     }
+}
+
+// ---------------------------------------------------------------------------
+// Measurement aid: the same access pattern as the selection (one workgroup per
+// chunk, 16-byte non-temporal loads, kLoads per lane and round) with nothing
+// but a running maximum, to show what a pure read of the tensor achieves.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void read_kernel(const u32x4* __restrict__ hidden, uint32_t nvec,
+                                                        uint32_t* __restrict__ out)
+{
+    const u32x4* src = hidden + (uint64_t)blockIdx.x * nvec;
+    uint32_t m = 0;
+    for (uint32_t base = 0; base < nvec; base += kThreads * kLoads) {
+        u32x4 r[kLoads];
+#pragma unroll
+        for (int u = 0; u < kLoads; ++u) {
+            const uint32_t v = base + u * kThreads + threadIdx.x;
+            r[u] = u32x4{0u, 0u, 0u, 0u};
+            if (v < nvec) r[u] = __builtin_nontemporal_load(src + v);
+        }
+#pragma unroll
+        for (int u = 0; u < kLoads; ++u) m = max(m, max(max(r[u].x, r[u].y), max(r[u].z, r[u].w)));
+    }
+    if (m == 0xFFFFFFFFu) out[blockIdx.x] = m;  // practically never: keeps the loads alive
 }
 
 // ---------------------------------------------------------------------------
@@ -481,6 +522,22 @@ int toploc_ring_append(void* d_ring_bf16, const void* d_step_bf16, uint32_t n_se
         ProfScope ps(TOPLOC_KERNEL_RING, st);
         hipLaunchKernelGGL(ring_kernel, dim3((uint32_t)blocks), dim3(256), 0, st, (u32x4*)d_ring_bf16,
                            (const u32x4*)d_step_bf16, n_seq, hvec, chunk_tokens, step % chunk_tokens);
+    }
+    return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
+}
+
+int toploc_bench_read(const void* d_hidden_bf16, uint64_t n_chunks, uint64_t chunk_values, uint32_t* d_out,
+                      void* hip_stream)
+{
+    if (chunk_values == 0 || chunk_values % 8 != 0 || chunk_values >= (1ull << 32) || n_chunks >= (1ull << 31))
+        return TOPLOC_EINVAL;
+    if (n_chunks == 0) return TOPLOC_OK;
+    if (!d_hidden_bf16 || !d_out || !aligned16(d_hidden_bf16)) return TOPLOC_EINVAL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    {
+        ProfScope ps(TOPLOC_KERNEL_READ, st);
+        hipLaunchKernelGGL(read_kernel, dim3((uint32_t)n_chunks), dim3(kThreads), 0, st, (const u32x4*)d_hidden_bf16,
+                           (uint32_t)(chunk_values / 8), d_out);
     }
     return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
 }
