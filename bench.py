@@ -85,8 +85,9 @@ def main():
     tl.toploc_profile_enable(False)
     kernels = {}
     alg_bytes = {   # algorithmic HBM bytes per chunk: what the method itself must move
-        "select_kernel": 2 * n + 6 * k,          # read the chunk, hand k (index, value) pairs on
-        "interp_kernel": 6 * k + pb + 1,         # read the pairs, write the proof and status
+        "build_kernel": 2 * n + pb + 1,          # read the chunk, write the proof and status
+        "select_kernel": 2 * n + 6 * k,          # (k > 128) read the chunk, hand k (index, value) pairs on
+        "interp_kernel": 6 * k + pb + 1,         # (k > 128) read the pairs, write the proof and status
         "verify_kernel": 2 * n + pb + 20,        # read the chunk and the proof, write the record
     }
     for kn, (launches, total_ms) in prof.items():

@@ -89,9 +89,10 @@ typedef struct {
  * plus the modulus). Host only. */
 size_t toploc_proof_bytes(uint32_t k);
 
-/* Bytes of device scratch that build / verify / topk need for `n_chunks` chunks
- * with these parameters (top-k pairs handed from the selection kernel to the
- * interpolation kernel). 0 on invalid parameters. Host only. */
+/* Bytes of device scratch that toploc_build_proofs needs for `n_chunks` chunks with
+ * these parameters: 0 for k <= 128 (one fused kernel), else room for the top-k
+ * pairs handed from the selection kernel to the interpolation kernel.  Also 0 on
+ * invalid parameters.  Verify never needs scratch.  Host only. */
 size_t toploc_workspace_bytes(const toploc_params *params, uint64_t n_chunks);
 
 /* Algorithm 1 over n_chunks chunks: top-k by magnitude, injective modulus
@@ -102,7 +103,8 @@ size_t toploc_workspace_bytes(const toploc_params *params, uint64_t n_chunks);
  *   d_status        out, device, n_chunks bytes, TOPLOC_CHUNK_*
  *   d_topk_idx_opt  out, device, n_chunks*k uint32 flat indices in the order
  *                   (magnitude descending, index ascending); NULL to skip
- *   d_workspace     device scratch, 16-byte aligned, >= toploc_workspace_bytes()
+ *   d_workspace     device scratch, 16-byte aligned, >= toploc_workspace_bytes();
+ *                   may be NULL when that is 0
  * n_chunks = 0 is valid and enqueues nothing. */
 int toploc_build_proofs(const void *d_hidden_bf16, uint64_t n_chunks, const toploc_params *params,
                         uint8_t *d_proofs, uint8_t *d_status, uint32_t *d_topk_idx_opt,
@@ -150,12 +152,13 @@ int toploc_bench_read(const void *d_hidden_bf16, uint64_t n_chunks, uint64_t chu
  * toploc_profile_read synchronises those events and returns, per kernel slot
  * (TOPLOC_KERNEL_*), the number of launches and their summed duration in
  * milliseconds since the last reset, then resets.  Not thread safe. */
-#define TOPLOC_KERNEL_SELECT 0   /* top-k selection kernel (build, topk)    */
-#define TOPLOC_KERNEL_INTERP 1   /* modulus + interpolation + encode kernel */
+#define TOPLOC_KERNEL_SELECT 0   /* top-k selection kernel (topk; build with k > 128)       */
+#define TOPLOC_KERNEL_INTERP 1   /* modulus + interpolation + encode kernel (k > 128)       */
 #define TOPLOC_KERNEL_VERIFY 2   /* fused verify kernel                     */
 #define TOPLOC_KERNEL_RING 3     /* ring append kernel                      */
 #define TOPLOC_KERNEL_READ 4     /* toploc_bench_read                       */
-#define TOPLOC_KERNEL_COUNT 5
+#define TOPLOC_KERNEL_BUILD 5    /* fused build kernel (k <= 128)           */
+#define TOPLOC_KERNEL_COUNT 6
 int toploc_profile_enable(int on);
 int toploc_profile_read(uint32_t *launches /*[TOPLOC_KERNEL_COUNT]*/, float *total_ms /*[TOPLOC_KERNEL_COUNT]*/);
 

@@ -17,8 +17,8 @@ PRIME = 65497
 MAX_K = 512
 OK, EINVAL, EWORKSPACE, EHIP = 0, -1, -2, -3
 CHUNK_OK, CHUNK_NO_MODULUS, CHUNK_NO_INVERSE, CHUNK_MALFORMED = 0, 1, 2, 3
-KERNEL_SELECT, KERNEL_INTERP, KERNEL_VERIFY, KERNEL_RING, KERNEL_READ, KERNEL_COUNT = 0, 1, 2, 3, 4, 5
-KERNEL_NAMES = ("select_kernel", "interp_kernel", "verify_kernel", "ring_kernel", "read_kernel")
+KERNEL_SELECT, KERNEL_INTERP, KERNEL_VERIFY, KERNEL_RING, KERNEL_READ, KERNEL_BUILD, KERNEL_COUNT = 0, 1, 2, 3, 4, 5, 6
+KERNEL_NAMES = ("select_kernel", "interp_kernel", "verify_kernel", "ring_kernel", "read_kernel", "build_kernel")
 BF16_THRESHOLDS = (38, 10, 8)  # T_exp, T_mean, T_median (Section 5.2 of the paper)
 
 RESULT_DTYPE = np.dtype(

@@ -231,11 +231,11 @@ __device__ __forceinline__ int32_t vec_max_mag(const u32x4& r)
     return (int32_t)(mm.x > mm.y ? mm.x : mm.y);
 }
 
-// Top-k of src[0 .. 8*nvec) into s.cand_idx / s.cand_bits [0 .. k); with SORT in the
-// order (magnitude descending, index ascending), else in no particular order.
+// Top-k of src[0 .. 8*nvec) into s.cand_idx / s.cand_bits [0 .. k), in no particular
+// order (order_topk sorts them).
 // Requires k <= 8*nvec, k <= CAP/2, 8*nvec < 2^32.  All threads of the workgroup call
 // it; it ends with a barrier.
-template <int THREADS, int U, int CAP, int QCAP, bool SORT>
+template <int THREADS, int U, int CAP, int QCAP>
 __device__ __forceinline__ void select_topk(const u32x4* __restrict__ src, uint32_t nvec, uint32_t k,
                             SelectShared<THREADS, CAP, QCAP>& s)
 {
@@ -331,37 +331,43 @@ __device__ __forceinline__ void select_topk(const u32x4* __restrict__ src, uint3
     __syncthreads();
     (void)drain<THREADS, CAP, QCAP>(s, k, t);
     (void)prune_if_above<THREADS, CAP, QCAP>(s, k, k, t);
-    if (SORT) {
-        // order the k survivors: rank = number of survivors that come before
-        constexpr int KPT = (CAP / 2 + THREADS - 1) / THREADS;
-        uint32_t my_idx[KPT], my_bits[KPT], my_rank[KPT];
+}
+
+// Put the k survivors of select_topk into the order (magnitude descending, index
+// ascending): rank = number of survivors that come before.  All threads call; ends
+// with a barrier.
+template <int THREADS, int CAP, int QCAP>
+__device__ __forceinline__ void order_topk(SelectShared<THREADS, CAP, QCAP>& s, uint32_t k)
+{
+    const uint32_t tid = threadIdx.x;
+    constexpr int KPT = (CAP / 2 + THREADS - 1) / THREADS;
+    uint32_t my_idx[KPT], my_bits[KPT], my_rank[KPT];
 #pragma unroll
-        for (int i = 0; i < KPT; ++i) {
-            const uint32_t j = tid + i * THREADS;
-            my_idx[i] = 0; my_bits[i] = 0; my_rank[i] = 0;
-            if (j < k) {
-                my_idx[i] = s.cand_idx[j];
-                my_bits[i] = s.cand_bits[j];
-                const uint32_t mag = my_bits[i] & 0x7FFFu;
-                uint32_t rank = 0;
-                for (uint32_t u = 0; u < k; ++u) {
-                    const uint32_t om = s.cand_bits[u] & 0x7FFFu;
-                    const uint32_t oi = s.cand_idx[u];
-                    rank += (om > mag || (om == mag && oi < my_idx[i])) ? 1u : 0u;
-                }
-                my_rank[i] = rank;
+    for (int i = 0; i < KPT; ++i) {
+        const uint32_t j = tid + i * THREADS;
+        my_idx[i] = 0; my_bits[i] = 0; my_rank[i] = 0;
+        if (j < k) {
+            my_idx[i] = s.cand_idx[j];
+            my_bits[i] = s.cand_bits[j];
+            const uint32_t mag = my_bits[i] & 0x7FFFu;
+            uint32_t rank = 0;
+            for (uint32_t u = 0; u < k; ++u) {
+                const uint32_t om = s.cand_bits[u] & 0x7FFFu;
+                const uint32_t oi = s.cand_idx[u];
+                rank += (om > mag || (om == mag && oi < my_idx[i])) ? 1u : 0u;
             }
+            my_rank[i] = rank;
         }
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < KPT; ++i) {
-            if (tid + i * THREADS < k) {
-                s.cand_idx[my_rank[i]] = my_idx[i];
-                s.cand_bits[my_rank[i]] = (uint16_t)my_bits[i];
-            }
-        }
-        __syncthreads();
     }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < KPT; ++i) {
+        if (tid + i * THREADS < k) {
+            s.cand_idx[my_rank[i]] = my_idx[i];
+            s.cand_bits[my_rank[i]] = (uint16_t)my_bits[i];
+        }
+    }
+    __syncthreads();
 }
 
 }  // namespace toploc

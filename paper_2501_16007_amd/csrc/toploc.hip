@@ -1,9 +1,12 @@
 // TopLoc proof build / verify for MI355X (gfx950): kernels and the C ABI of
 // include/toploc.h.  One workgroup per chunk everywhere; chunks are independent.
 //
+//   build_kernel    all of Algorithm 1 in one launch (k <= 128): topk, then
+//                   findInjectiveModulus, i mod m, InterpolateModPolynomial, encode
+//                   while other workgroups of the compute unit keep streaming
 //   select_kernel   topk(h, k)                       (Algorithm 1 / 2, first step)
 //   interp_kernel   findInjectiveModulus, i mod m, InterpolateModPolynomial, encode
-//                   (Algorithm 1, remaining steps; Algorithms 3, 4, 6)
+//                   (Algorithm 1, remaining steps; Algorithms 3, 4, 6), k > 128
 //   verify_kernel   decode, topk, i mod m, Horner at the k points, extractBits,
 //                   err_e / err_m statistics, thresholds (Algorithm 2, Algorithm 5)
 //   ring_kernel     provider-side ring of the last chunk_tokens hidden vectors
@@ -14,6 +17,7 @@
 
 #include "../../include/toploc.h"
 #include "gf65497.hpp"
+#include "interp.hpp"
 #include "select.hpp"
 
 namespace toploc {
@@ -38,8 +42,6 @@ constexpr int kLoads = TOPLOC_LOADS;      // 16-byte loads in flight per lane an
 constexpr int kCap = TOPLOC_CAP;          // candidate buffer entries
 constexpr int kQcap = TOPLOC_QCAP;        // queue entries (16-byte vectors)
 static_assert(kCap >= 4 * (int)TOPLOC_MAX_K, "the soft limit CAP/2 must leave room above k");
-constexpr uint32_t kModHigh = 65536u;
-constexpr uint32_t kModLow = 32769u;  // 2^15 + 1
 
 typedef SelectShared<kThreads, kCap, kQcap> SelShared;
 
@@ -52,7 +54,8 @@ __global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void select_kernel(cons
 {
     __shared__ SelShared s;
     const uint64_t chunk = blockIdx.x;
-    select_topk<kThreads, kLoads, kCap, kQcap, true>(hidden + chunk * nvec, nvec, k, s);
+    select_topk<kThreads, kLoads, kCap, kQcap>(hidden + chunk * nvec, nvec, k, s);
+    order_topk<kThreads, kCap, kQcap>(s, k);
     for (uint32_t t = threadIdx.x; t < k; t += kThreads) {
         const uint32_t i = s.cand_idx[t];
         out_idx[chunk * k + t] = i;
@@ -62,155 +65,8 @@ __global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void select_kernel(cons
 }
 
 // ---------------------------------------------------------------------------
-// Algorithm 6 with the residues compared in the form Algorithms 3 and 5 consume
-// them, (i mod m) mod p: largest m in [2^15+1, 65536] for which the k points are
-// distinct.  xs[j] receives the mapped index.  Returns 0 when no m works.
-// bitmap: 2048 zeroed words, left zeroed.  All threads call.
+// Algorithm 1 after the selection (interp.hpp), as its own kernel for k > 128
 // ---------------------------------------------------------------------------
-template <int THREADS>
-__device__ uint32_t find_modulus(const uint32_t* idx, uint32_t k, uint32_t* xs, uint32_t* bitmap, uint32_t* collide)
-{
-    const uint32_t tid = threadIdx.x;
-    for (uint32_t m = kModHigh; m >= kModLow; --m) {
-        for (uint32_t j = tid; j < k; j += THREADS) {
-            uint32_t x = idx[j] % m;
-            x = x >= kPrime ? x - kPrime : x;  // x < 65536 < 2p
-            xs[j] = x;
-            const uint32_t bit = 1u << (x & 31u);
-            if (atomicOr(&bitmap[x >> 5], bit) & bit) *collide = 1u;
-        }
-        __syncthreads();
-        const uint32_t c = *collide;
-        for (uint32_t j = tid; j < k; j += THREADS) bitmap[xs[j] >> 5] = 0;
-        __syncthreads();
-        if (!c) return m;
-        if (tid == 0) *collide = 0;
-        __syncthreads();
-    }
-    return 0;
-}
-
-// ---------------------------------------------------------------------------
-// Interpolation over GF(p): the unique polynomial of degree < k through the k
-// points (x_j, y_j) -- what Algorithm 3 returns -- computed in Lagrange form so
-// that every step is k-wide parallel:
-//   W(X)  = prod_j (X - x_j)                       product tree, log2 k levels
-//   d_j   = W'(x_j)                                Horner, one lane per point
-//   a_j   = y_j / d_j                              Fermat inverse
-//   S_r   = sum_j a_j x_j^r,  r = 0..k-1           blocked Vandermonde product
-//   c_i   = sum_{r=0}^{k-1-i} W_{i+1+r} S_r        (from P = sum_j a_j W/(X - x_j))
-// ---------------------------------------------------------------------------
-template <int KMAX, int RB>
-struct InterpShared {
-    uint32_t idx[KMAX];
-    uint32_t xs[KMAX];
-    uint32_t ys[KMAX];
-    uint32_t pa[KMAX + 1];   // product tree ping
-    uint32_t pb[KMAX + 1];   // product tree pong
-    uint32_t wder[KMAX];     // coefficients of W'
-    uint32_t a[KMAX];
-    uint32_t S[KMAX];
-    union {
-        uint32_t bitmap[2048];            // modulus search
-        uint16_t V[RB * (KMAX + 2)];      // V[r][j] = x_j^(r0 + r), row pitch KMAX + 2
-    } u;
-    uint32_t collide;
-};
-
-// low coefficients f_0..f_{deg-1} of a monic polynomial of degree deg; f_deg = 1
-__device__ __forceinline__ uint32_t monic_coef(const uint32_t* f, uint32_t deg, uint32_t i)
-{
-    return i == deg ? 1u : f[i];
-}
-
-template <int THREADS, int KMAX, int RB>
-__device__ void interpolate(InterpShared<KMAX, RB>& s, uint32_t k, uint32_t* coef_out /* LDS, k entries */)
-{
-    const uint32_t tid = threadIdx.x;
-    // ---- W(X) = prod (X - x_j): pairwise products of monic polynomials ----
-    uint32_t* src = s.pa;
-    uint32_t* dst = s.pb;
-    for (uint32_t j = tid; j < k; j += THREADS) src[j] = s.xs[j] ? kPrime - s.xs[j] : 0u;
-    __syncthreads();
-    for (uint32_t d = 1; d < k; d <<= 1) {
-        for (uint32_t o = tid; o < k; o += THREADS) {
-            const uint32_t start = (o / (2 * d)) * (2 * d);
-            const uint32_t t = o - start;
-            const uint32_t df = (k - start) < d ? (k - start) : d;
-            const uint32_t rem = k - start - df;
-            const uint32_t dg = rem < d ? rem : d;
-            const uint32_t* f = src + start;
-            const uint32_t* g = src + start + df;
-            // h_t = sum_i f_i g_{t-i}, i in [max(0, t-dg), min(t, df)]
-            const uint32_t lo = t > dg ? t - dg : 0u;
-            const uint32_t hi = t < df ? t : df;
-            uint64_t acc = 0;
-            for (uint32_t i = lo; i <= hi; ++i)
-                acc += (uint64_t)mul24(monic_coef(f, df, i), monic_coef(g, dg, t - i));
-            dst[o] = reduce64(acc);
-        }
-        __syncthreads();
-        uint32_t* tmp = src; src = dst; dst = tmp;
-    }
-    const uint32_t* W = src;  // W_0..W_{k-1}; W_k = 1
-    // ---- W'(X) coefficients: wder_r = (r+1) W_{r+1} ----
-    for (uint32_t r = tid; r < k; r += THREADS) s.wder[r] = mulmod(r + 1, monic_coef(W, k, r + 1));
-    __syncthreads();
-    // ---- a_j = y_j / W'(x_j) ----
-    for (uint32_t j = tid; j < k; j += THREADS) {
-        const uint32_t x = s.xs[j];
-        uint32_t acc = s.wder[k - 1];
-        for (int r = (int)k - 2; r >= 0; --r) acc = muladdmod(acc, x, s.wder[r]);
-        s.a[j] = mulmod(s.ys[j], invmod(acc));
-        s.S[j] = 0;
-    }
-    __syncthreads();
-    // ---- S_r = sum_j a_j x_j^r, RB rows of the Vandermonde matrix at a time ----
-    constexpr uint32_t PITCH = KMAX + 2;
-    constexpr int KPT = (KMAX + THREADS - 1) / THREADS;
-    uint32_t pw[KPT];
-#pragma unroll
-    for (int i = 0; i < KPT; ++i) pw[i] = 1u;  // x_j^r0 carried from block to block
-    constexpr uint32_t SLICES = THREADS / RB;
-    const uint32_t r_local = tid % RB;
-    const uint32_t slice = tid / RB;
-    for (uint32_t r0 = 0; r0 < k; r0 += RB) {
-#pragma unroll
-        for (int i = 0; i < KPT; ++i) {
-            const uint32_t j = tid + i * THREADS;
-            if (j < k) {
-                const uint32_t x = s.xs[j];
-                uint32_t p = pw[i];
-                for (uint32_t r = 0; r < RB; ++r) {
-                    s.u.V[r * PITCH + j] = (uint16_t)p;
-                    p = mulmod(p, x);
-                }
-                pw[i] = p;
-            }
-        }
-        __syncthreads();
-        if (r0 + r_local < k) {
-            const uint32_t per = (k + SLICES - 1) / SLICES;
-            const uint32_t j0 = slice * per;
-            const uint32_t j1 = (j0 + per) < k ? (j0 + per) : k;
-            uint64_t acc = 0;
-            for (uint32_t j = j0; j < j1; ++j) acc += (uint64_t)mul24(s.a[j], (uint32_t)s.u.V[r_local * PITCH + j]);
-            if (j0 < j1) atomicAdd(&s.S[r0 + r_local], reduce64(acc));
-        }
-        __syncthreads();
-    }
-    for (uint32_t r = tid; r < k; r += THREADS) s.S[r] = reduce32(s.S[r]);  // sums of SLICES partial results
-    __syncthreads();
-    // ---- c_i = sum_{r=0}^{k-1-i} W_{i+1+r} S_r ----
-    for (uint32_t i = tid; i < k; i += THREADS) {
-        uint64_t acc = 0;
-        for (uint32_t r = 0; r + i < k; ++r)
-            acc += (uint64_t)mul24(monic_coef(W, k, i + 1 + r), s.S[r]);
-        coef_out[i] = reduce64(acc);
-    }
-    __syncthreads();
-}
-
 template <int KMAX, int RB>
 __global__ __launch_bounds__(kThreads) void interp_kernel(const uint32_t* __restrict__ topk_idx,
                                                           const uint16_t* __restrict__ topk_val, uint32_t k,
@@ -225,19 +81,41 @@ __global__ __launch_bounds__(kThreads) void interp_kernel(const uint32_t* __rest
         const uint32_t y = topk_val[chunk * k + j];
         s.ys[j] = y >= kPrime ? y - kPrime : y;
     }
-    for (uint32_t w = tid; w < 2048; w += kThreads) s.u.bitmap[w] = 0;
-    if (tid == 0) s.collide = 0;
-    __syncthreads();
-    const uint32_t m = find_modulus<kThreads>(s.idx, k, s.xs, s.u.bitmap, &s.collide);
-    uint16_t* proof = reinterpret_cast<uint16_t*>(proofs + chunk * (2 + 2 * (uint64_t)k));
-    if (m == 0) {  // uniform
-        for (uint32_t j = tid; j <= k; j += kThreads) proof[j] = 0;
-        if (tid == 0) status[chunk] = TOPLOC_CHUNK_NO_MODULUS;
-        return;
+    finish_proof<kThreads, KMAX, RB>(s, coef, k, reinterpret_cast<uint16_t*>(proofs + chunk * (2 + 2 * (uint64_t)k)),
+                                     status + chunk);
+}
+
+// Algorithm 1 in one launch, k <= KMAX <= kThreads: the selection streams the chunk,
+// then the same workgroup turns its k pairs into the proof out of LDS (the selection's
+// buffers are dead by then and are reused).
+template <int KMAX, int RB>
+__global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void build_kernel(const u32x4* __restrict__ hidden, uint32_t nvec,
+                                                                           uint32_t k, uint8_t* __restrict__ proofs,
+                                                                           uint8_t* __restrict__ status,
+                                                                           uint32_t* __restrict__ out_idx)
+{
+    static_assert(KMAX <= kThreads, "one pair per lane is carried across the phase change");
+    __shared__ union BuildShared {
+        SelShared sel;
+        InterpShared<KMAX, RB> itp;
+    } sh;
+    __shared__ uint32_t coef[KMAX];
+    const uint32_t tid = threadIdx.x;
+    const uint64_t chunk = blockIdx.x;
+    select_topk<kThreads, kLoads, kCap, kQcap>(hidden + chunk * nvec, nvec, k, sh.sel);
+    if (out_idx) {  // uniform: the caller wants the ordered indices
+        order_topk<kThreads, kCap, kQcap>(sh.sel, k);
+        if (tid < k) out_idx[chunk * k + tid] = sh.sel.cand_idx[tid];
     }
-    interpolate<kThreads, KMAX, RB>(s, k, coef);
-    if (tid == 0) { proof[0] = (uint16_t)(m & 0xFFFFu); status[chunk] = TOPLOC_CHUNK_OK; }
-    for (uint32_t j = tid; j < k; j += kThreads) proof[1 + j] = (uint16_t)coef[j];
+    uint32_t my_idx = 0, my_y = 0;
+    if (tid < k) { my_idx = sh.sel.cand_idx[tid]; my_y = sh.sel.cand_bits[tid]; }
+    __syncthreads();  // the selection's LDS is dead from here on
+    if (tid < k) {
+        sh.itp.idx[tid] = my_idx;
+        sh.itp.ys[tid] = my_y >= kPrime ? my_y - kPrime : my_y;
+    }
+    finish_proof<kThreads, KMAX, RB>(sh.itp, coef, k,
+                                     reinterpret_cast<uint16_t*>(proofs + chunk * (2 + 2 * (uint64_t)k)), status + chunk);
 }
 
 // ---------------------------------------------------------------------------
@@ -277,7 +155,7 @@ __global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void verify_kernel(cons
         return;
     }
     // topk(h, k)
-    select_topk<kThreads, kLoads, kCap, kQcap, false>(hidden + chunk * nvec, nvec, k, s);  // order is irrelevant here
+    select_topk<kThreads, kLoads, kCap, kQcap>(hidden + chunk * nvec, nvec, k, s);  // order is irrelevant here
     // P(i mod m) by Horner, extractBits, compare
     for (uint32_t j = tid; j < k; j += kThreads) {
         uint32_t x = s.cand_idx[j] % m;
@@ -428,6 +306,7 @@ size_t toploc_proof_bytes(uint32_t k) { return 2 + 2 * (size_t)k; }
 size_t toploc_workspace_bytes(const toploc_params* params, uint64_t n_chunks)
 {
     if (chunk_len(params) == 0) return 0;
+    if (params->k <= 128) return 0;  // one fused kernel, everything stays on chip
     const size_t vb = ((size_t)n_chunks * params->k * sizeof(uint16_t) + 15) & ~(size_t)15;
     return idx_bytes(n_chunks, params->k) + vb;
 }
@@ -456,12 +335,19 @@ int toploc_build_proofs(const void* d_hidden_bf16, uint64_t n_chunks, const topl
     const uint64_t n = chunk_len(params);
     if (n == 0 || n_chunks >= (1ull << 31)) return TOPLOC_EINVAL;
     if (n_chunks == 0) return TOPLOC_OK;
-    if (!d_hidden_bf16 || !d_proofs || !d_status || !d_workspace) return TOPLOC_EINVAL;
-    if (!aligned16(d_hidden_bf16) || !aligned16(d_workspace)) return TOPLOC_EINVAL;
+    if (!d_hidden_bf16 || !d_proofs || !d_status || !aligned16(d_hidden_bf16)) return TOPLOC_EINVAL;
     if ((reinterpret_cast<uintptr_t>(d_proofs) & 1u) != 0) return TOPLOC_EINVAL;
-    if (workspace_bytes < toploc_workspace_bytes(params, n_chunks)) return TOPLOC_EWORKSPACE;
+    const size_t need = toploc_workspace_bytes(params, n_chunks);
+    if (need && (!d_workspace || !aligned16(d_workspace))) return TOPLOC_EINVAL;
+    if (workspace_bytes < need) return TOPLOC_EWORKSPACE;
     const uint32_t k = params->k;
     hipStream_t st = (hipStream_t)hip_stream;
+    if (k <= 128) {
+        ProfScope ps(TOPLOC_KERNEL_BUILD, st);
+        hipLaunchKernelGGL((build_kernel<128, 64>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
+                           (const u32x4*)d_hidden_bf16, (uint32_t)(n / 8), k, d_proofs, d_status, d_topk_idx_opt);
+        return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
+    }
     uint32_t* ws_idx = (uint32_t*)d_workspace;
     uint16_t* ws_val = (uint16_t*)((char*)d_workspace + idx_bytes(n_chunks, k));
     {
@@ -472,12 +358,8 @@ int toploc_build_proofs(const void* d_hidden_bf16, uint64_t n_chunks, const topl
     if (!hip_ok(hipGetLastError())) return TOPLOC_EHIP;
     {
         ProfScope ps(TOPLOC_KERNEL_INTERP, st);
-        if (k <= 128)
-            hipLaunchKernelGGL((interp_kernel<128, 32>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
-                               (const uint32_t*)ws_idx, (const uint16_t*)ws_val, k, d_proofs, d_status);
-        else
-            hipLaunchKernelGGL((interp_kernel<512, 32>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
-                               (const uint32_t*)ws_idx, (const uint16_t*)ws_val, k, d_proofs, d_status);
+        hipLaunchKernelGGL((interp_kernel<512, 32>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
+                           (const uint32_t*)ws_idx, (const uint16_t*)ws_val, k, d_proofs, d_status);
     }
     return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
 }

@@ -35,7 +35,8 @@ def test_proof_size_matches_paper(golden):
 
 
 def test_workspace_bytes_and_parameter_validation():
-    assert binding.toploc_workspace_bytes(128, 32, 4096, 10) >= 10 * 128 * 6
+    assert binding.toploc_workspace_bytes(128, 32, 4096, 10) == 0      # fused kernel: no scratch
+    assert binding.toploc_workspace_bytes(512, 32, 4096, 10) >= 10 * 512 * 6
     assert binding.toploc_workspace_bytes(0, 32, 4096, 10) == 0        # k = 0
     assert binding.toploc_workspace_bytes(513, 32, 4096, 10) == 0      # k > TOPLOC_MAX_K
     assert binding.toploc_workspace_bytes(128, 32, 3, 10) == 0         # N = 96 < k
@@ -55,7 +56,9 @@ def test_calls_are_rejected_before_any_launch():
     assert L.toploc_build_proofs(None, 1, ctypes.byref(ok), fake, fake, None, fake, 1 << 20, None) == binding.EINVAL
     assert L.toploc_build_proofs(ctypes.c_void_p(0x1008), 1, ctypes.byref(ok), fake, fake, None, fake, 1 << 20,
                                  None) == binding.EINVAL               # misaligned input
-    assert L.toploc_build_proofs(fake, 1, ctypes.byref(ok), fake, fake, None, fake, 16, None) == binding.EWORKSPACE
+    big = binding.Params(512, 32, 4096, binding.PRIME)
+    assert L.toploc_build_proofs(fake, 1, ctypes.byref(big), fake, fake, None, fake, 16, None) == binding.EWORKSPACE
+    assert L.toploc_build_proofs(fake, 1, ctypes.byref(big), fake, fake, None, None, 1 << 20, None) == binding.EINVAL
     assert L.toploc_build_proofs(fake, 0, ctypes.byref(ok), fake, fake, None, fake, 0, None) == binding.OK
     assert L.toploc_verify_proofs(fake, 1, ctypes.byref(ok), fake, None, fake, None, 0, None) == binding.EINVAL
     assert L.toploc_verify_proofs(fake, 0, ctypes.byref(ok), fake, ctypes.byref(thr), fake, None, 0, None) == binding.OK
