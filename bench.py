@@ -29,6 +29,9 @@ def main():
     ap.add_argument("--k", type=int, default=128)
     ap.add_argument("--cpu-sample-chunks", type=int, default=512)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy and one pure read of the tensor, so that a "
+                         "rocprofv3 --pmc run of this command holds kernels of known traffic to scale by")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (chunks are independent; a multi-GPU run would "
@@ -96,6 +99,18 @@ def main():
             kernels[kn] = {"launches": launches, "avg_ms": avg_ms,
                            "GBps": alg_bytes[kn] * n_chunks / (avg_ms * 1e-3) / 1e9}
     dom = max(kernels, key=lambda kn: kernels[kn]["avg_ms"])
+    # HBM traffic per launch from the committed rocprofv3 --pmc summary (FETCH_SIZE and WRITE_SIZE, each
+    # scaled by a plain copy of known size); it holds for the workload it was taken on and is null otherwise
+    traffic = None
+    if args.workload == "config3" and k == 128:
+        import os
+        pmc = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
+                           "build_verify_kernels_70b_shape_hbm_traffic.txt")
+        if os.path.exists(pmc):
+            for line in open(pmc):
+                parts = line.split()
+                if len(parts) == 3 and parts[0] == "traffic_bytes_per_launch" and parts[1] == dom:
+                    traffic = float(parts[2])
     roofline = {
         "bound": "hbm",
         "kernel": dom,
@@ -103,10 +118,18 @@ def main():
         "peak": HBM_PEAK_GBPS,
         "unit": "GB/s",
         "frac": kernels[dom]["GBps"] / HBM_PEAK_GBPS,
-        "traffic": None,
+        "traffic": traffic,
         "avg_launch_ms": kernels[dom]["avg_ms"],
         "algorithmic_bytes_per_launch": alg_bytes[dom] * n_chunks,
     }
+
+    if args.calibration_copy:
+        gib = 1 << 30
+        src = chunks.reshape(-1)[: gib // 2]
+        dst = torch.empty_like(src)
+        dst.copy_(src)                       # reads 2^30 bytes, writes 2^30 bytes
+        tl.toploc_bench_read(chunks)         # reads the whole tensor, writes nothing
+        torch.cuda.synchronize()
 
     cpu = None
     if not args.no_cpu_baseline:
