@@ -21,6 +21,15 @@
 
 namespace toploc {
 
+#ifdef TOPLOC_TIMING
+__device__ unsigned long long g_tt[8];
+#define TT_MARK(i) do { if (threadIdx.x == 0) { const uint64_t now_ = wall_clock64(); atomicAdd(&g_tt[i], (unsigned long long)(now_ - tt0_)); tt0_ = now_; } } while (0)
+#define TT_START() uint64_t tt0_ = wall_clock64()
+#else
+#define TT_MARK(i) do { } while (0)
+#define TT_START() do { } while (0)
+#endif
+
 constexpr uint32_t kModHigh = 65536u;
 constexpr uint32_t kModLow = 32769u;  // 2^15 + 1
 
@@ -84,6 +93,7 @@ __device__ __forceinline__ void interpolate(InterpShared<KMAX, RB>& s, uint32_t 
     constexpr int PPT = (KMAX * L + THREADS - 1) / THREADS;  // points per lane
     const uint32_t tid = threadIdx.x;
     const uint32_t h = (L == 2) ? (tid & 1u) : 0u;
+    TT_START();
 
     // ---- W(X) = prod (X - x_j): pairwise products of monic polynomials ----
     uint32_t* src = s.pa;
@@ -91,26 +101,38 @@ __device__ __forceinline__ void interpolate(InterpShared<KMAX, RB>& s, uint32_t 
     for (uint32_t j = tid; j < k; j += THREADS) src[j] = s.xs[j] ? kPrime - s.xs[j] : 0u;
     __syncthreads();
     for (uint32_t d = 1; d < k; d <<= 1) {
-        for (uint32_t o = tid; o < k; o += THREADS) {
-            const uint32_t start = (o / (2 * d)) * (2 * d);
+        // lane pair (L = 2) or lane (L = 1) per output coefficient o; lane h takes every L-th term
+        for (uint32_t o = tid / L; o < k; o += THREADS / L) {
+            const uint32_t start = o & ~(2u * d - 1u);
             const uint32_t t = o - start;
             const uint32_t df = (k - start) < d ? (k - start) : d;
             const uint32_t rem = k - start - df;
             const uint32_t dg = rem < d ? rem : d;
-            const uint32_t* f = src + start;
-            const uint32_t* g = src + start + df;
-            // h_t = sum_i f_i g_{t-i}, i in [max(0, t-dg), min(t, df)]
-            const uint32_t lo = t > dg ? t - dg : 0u;
-            const uint32_t hi = t < df ? t : df;
+            const uint32_t* f = src + start;        // f_0..f_{df-1}, f_df = 1
+            const uint32_t* g = src + start + df;   // g_0..g_{dg-1}, g_dg = 1
+            // h_t = sum_i f_i g_{t-i}: the terms with both coefficients stored ...
+            const uint32_t lo = t + 1u > dg ? t + 1u - dg : 0u;
+            const uint32_t hi = t < df ? t + 1u : df;   // exclusive
             uint64_t acc = 0;
-            for (uint32_t i = lo; i <= hi; ++i)
-                acc += (uint64_t)mul24(monic_coef(f, df, i), monic_coef(g, dg, t - i));
-            dst[o] = reduce64(acc);
+#pragma unroll 4
+            for (uint32_t i = lo + h; i < hi; i += L) acc += (uint64_t)mul24(f[i], g[t - i]);
+            // ... and the two terms that meet a leading 1
+            if (h == 0) {
+                if (t >= df) acc += g[t - df];
+                if (t >= dg) acc += f[t - dg];
+            }
+            uint32_t c = reduce64(acc);
+            if (L == 2) {
+                c += __shfl_xor(c, 1);
+                c = c >= kPrime ? c - kPrime : c;
+            }
+            if (h == 0) dst[o] = c;
         }
         __syncthreads();
         uint32_t* tmp = src; src = dst; dst = tmp;
     }
     const uint32_t* W = src;  // W_0..W_{k-1}; W_k = 1
+    TT_MARK(1);
     // ---- W'(X) coefficients: wder_r = (r+1) W_{r+1} ----
     for (uint32_t r = tid; r < k; r += THREADS) {
         s.wder[r] = mulmod(r + 1, monic_coef(W, k, r + 1));
@@ -142,6 +164,7 @@ __device__ __forceinline__ void interpolate(InterpShared<KMAX, RB>& s, uint32_t 
         }
     }
     __syncthreads();
+    TT_MARK(2);
     // ---- S_r = sum_j a_j x_j^r, RB rows of the Vandermonde matrix at a time ----
     constexpr uint32_t PITCH = KMAX + 2;
     uint32_t pw[PPT];
@@ -169,20 +192,26 @@ __device__ __forceinline__ void interpolate(InterpShared<KMAX, RB>& s, uint32_t 
             const uint32_t j0 = slice * per;
             const uint32_t j1 = (j0 + per) < k ? (j0 + per) : k;
             uint64_t acc = 0;
-            for (uint32_t j = j0; j < j1; ++j) acc += (uint64_t)mul24(s.a[j], (uint32_t)s.u.V[r_local * PITCH + j]);
+            const uint16_t* row = &s.u.V[r_local * PITCH];
+#pragma unroll 8
+            for (uint32_t j = j0; j < j1; ++j) acc += (uint64_t)mul24(s.a[j], (uint32_t)row[j]);
             if (j0 < j1) atomicAdd(&s.S[r0 + r_local], reduce64(acc));
         }
         __syncthreads();
     }
     for (uint32_t r = tid; r < k; r += THREADS) s.S[r] = reduce32(s.S[r]);  // sums of SLICES partial results
     __syncthreads();
+    TT_MARK(3);
     // ---- c_i = sum_{r=0}^{k-1-i} W_{i+1+r} S_r, lane h takes r = h mod L ----
 #pragma unroll
     for (int n = 0; n < PPT; ++n) {
         const uint32_t i = (tid + n * THREADS) / L;
         if (i < k) {
             uint64_t acc = 0;
-            for (uint32_t r = h; r + i < k; r += L) acc += (uint64_t)mul24(monic_coef(W, k, i + 1 + r), s.S[r]);
+            const uint32_t last = k - 1u - i;                 // W_{i+1+last} = W_k = 1
+#pragma unroll 4
+            for (uint32_t r = h; r < last; r += L) acc += (uint64_t)mul24(W[i + 1u + r], s.S[r]);
+            if ((last % L) == h) acc += s.S[last];
             uint32_t c = reduce64(acc);
             if (L == 2) {
                 c += __shfl_xor(c, 1);
@@ -192,6 +221,7 @@ __device__ __forceinline__ void interpolate(InterpShared<KMAX, RB>& s, uint32_t 
         }
     }
     __syncthreads();
+    TT_MARK(4);
 }
 
 // Remaining steps of Algorithm 1 for one chunk whose top-k pairs sit in s.idx / s.ys
@@ -202,10 +232,12 @@ __device__ __forceinline__ void finish_proof(InterpShared<KMAX, RB>& s, uint32_t
                                              uint8_t* status)
 {
     const uint32_t tid = threadIdx.x;
+    TT_START();
     for (uint32_t w = tid; w < 2048; w += THREADS) s.u.bitmap[w] = 0;
     if (tid == 0) { s.collide[0] = 0; s.collide[1] = 0; }
     __syncthreads();
     const uint32_t m = find_modulus<THREADS, KMAX, RB>(s, k);
+    TT_MARK(0);
     if (m == 0) {  // uniform
         for (uint32_t j = tid; j <= k; j += THREADS) proof[j] = 0;
         if (tid == 0) *status = 1;  // TOPLOC_CHUNK_NO_MODULUS
@@ -214,6 +246,7 @@ __device__ __forceinline__ void finish_proof(InterpShared<KMAX, RB>& s, uint32_t
     interpolate<THREADS, KMAX, RB>(s, k, coef);
     if (tid == 0) { proof[0] = (uint16_t)(m & 0xFFFFu); *status = 0; }
     for (uint32_t j = tid; j < k; j += THREADS) proof[1 + j] = (uint16_t)coef[j];
+    TT_MARK(5);
 }
 
 }  // namespace toploc

@@ -107,6 +107,9 @@ __global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void build_kernel(const
         order_topk<kThreads, kCap, kQcap>(sh.sel, k);
         if (tid < k) out_idx[chunk * k + tid] = sh.sel.cand_idx[tid];
     }
+#ifdef TOPLOC_TAIL_PRIO
+    __builtin_amdgcn_s_setprio(TOPLOC_TAIL_PRIO);  // the arithmetic tail goes ahead of streaming waves
+#endif
     uint32_t my_idx = 0, my_y = 0;
     if (tid < k) { my_idx = sh.sel.cand_idx[tid]; my_y = sh.sel.cand_bits[tid]; }
     __syncthreads();  // the selection's LDS is dead from here on
@@ -423,6 +426,14 @@ int toploc_bench_read(const void* d_hidden_bf16, uint64_t n_chunks, uint64_t chu
     }
     return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
 }
+
+#ifdef TOPLOC_TIMING
+int toploc_debug_timing(uint64_t* out8, int reset)
+{
+    if (reset) { uint64_t z[8] = {0,0,0,0,0,0,0,0}; return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_tt), z, sizeof(z)); }
+    return (int)hipMemcpyFromSymbol(out8, HIP_SYMBOL(g_tt), 64);
+}
+#endif
 
 int toploc_profile_enable(int on)
 {
