@@ -34,6 +34,11 @@
 #define TOPLOC_DRAIN_ATTR __forceinline__
 #endif
 
+#ifndef TT_MARK
+#define TT_MARK(i) do { } while (0)
+#define TT_START() do { } while (0)
+#endif
+
 namespace toploc {
 
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
@@ -52,6 +57,8 @@ struct SelectShared {
     uint32_t qcount;          // queue slots handed out (may run past QCAP on overflow)
     uint32_t count;           // candidate slots in use
     uint32_t eq_count;
+    uint32_t hole_count;      // prune: slots below k whose entry does not survive
+    uint32_t move_count;      // prune: survivors at or above slot k, moved into the holes
     int32_t tm;               // threshold magnitude
     uint32_t ti;              // threshold index
     uint32_t flag[3];         // "queue passed its soft limit" for barrier round r mod 3
@@ -105,50 +112,45 @@ __device__ __forceinline__ bool before(int32_t mag, uint32_t idx, const Threshol
 
 // If the candidate buffer holds more than `limit` entries, reduce it to the exact
 // best k and make the k-th the threshold element.  Called by all threads, starts and
-// ends with a barrier.  Returns true when it pruned (then `t` is the new threshold).
+// ends with a barrier.  Returns the number of slots that had been handed out: a value
+// above CAP means appends were dropped, and nothing is pruned then (the caller redoes
+// them); a value in (limit, CAP] means it pruned and `t` is the new threshold.
 template <int THREADS, int CAP, int QCAP>
-__device__ TOPLOC_PRUNE_ATTR bool prune_if_above(SelectShared<THREADS, CAP, QCAP>& s, uint32_t k, uint32_t limit,
-                                                         Threshold& t)
+__device__ TOPLOC_PRUNE_ATTR uint32_t prune_if_above(SelectShared<THREADS, CAP, QCAP>& s, uint32_t k, uint32_t limit,
+                                                     Threshold& t)
 {
-    constexpr int EPT = CAP / THREADS;
     const uint32_t tid = threadIdx.x;
     __syncthreads();  // appends are visible
     const uint32_t M = s.count;
-    if (M <= limit) {  // uniform decision
+    if (M <= limit || M > (uint32_t)CAP) {  // uniform decision
         __syncthreads();  // everyone has read the count before anyone appends again
-        return false;
-    }
-    uint32_t idx[EPT];
-    uint32_t bits[EPT];
-#pragma unroll
-    for (int i = 0; i < EPT; ++i) {
-        const uint32_t slot = tid + i * THREADS;
-        idx[i] = 0; bits[i] = 0;
-        if (slot < M) { idx[i] = s.cand_idx[slot]; bits[i] = s.cand_bits[slot]; }
+        return M;
     }
     for (uint32_t b = tid; b < 256; b += THREADS) s.hist_e[b] = 0;
     for (uint32_t b = tid; b < 128; b += THREADS) s.hist_m[b] = 0;
-    __syncthreads();  // everyone holds its entries and has read the count
-    if (tid == 0) { s.count = 0; s.eq_count = 0; }
-#pragma unroll
-    for (int i = 0; i < EPT; ++i)
-        if (tid + i * THREADS < M) atomicAdd(&s.hist_e[(bits[i] & 0x7FFFu) >> 7], 1u);
+    if (tid == 0) { s.eq_count = 0; s.hole_count = 0; s.move_count = 0; }
+    __syncthreads();
+#pragma unroll 1
+    for (uint32_t slot = tid; slot < M; slot += THREADS)
+        atomicAdd(&s.hist_e[((uint32_t)s.cand_bits[slot] & 0x7FFFu) >> 7], 1u);
     __syncthreads();
     uint32_t e_star, above_e;
     find_bin<4>(s.hist_e, 0u, k, e_star, above_e);
-#pragma unroll
-    for (int i = 0; i < EPT; ++i)
-        if (tid + i * THREADS < M && ((bits[i] & 0x7FFFu) >> 7) == e_star) atomicAdd(&s.hist_m[bits[i] & 0x7Fu], 1u);
+#pragma unroll 1
+    for (uint32_t slot = tid; slot < M; slot += THREADS) {
+        const uint32_t mag = (uint32_t)s.cand_bits[slot] & 0x7FFFu;
+        if ((mag >> 7) == e_star) atomicAdd(&s.hist_m[mag & 0x7Fu], 1u);
+    }
     __syncthreads();
     uint32_t m_star, g;
     find_bin<2>(s.hist_m, above_e, k, m_star, g);
     const uint32_t new_tm = (e_star << 7) | m_star;
     const uint32_t need = k - g;  // how many of the entries with magnitude new_tm survive (>= 1)
-#pragma unroll
-    for (int i = 0; i < EPT; ++i)
-        if (tid + i * THREADS < M && (bits[i] & 0x7FFFu) == new_tm) {
+#pragma unroll 1
+    for (uint32_t slot = tid; slot < M; slot += THREADS)
+        if (((uint32_t)s.cand_bits[slot] & 0x7FFFu) == new_tm) {
             const uint32_t q = atomicAdd(&s.eq_count, 1u);
-            s.eq_slot[q] = (uint16_t)(tid + i * THREADS);
+            s.eq_slot[q] = (uint16_t)slot;
         }
     __syncthreads();
     const uint32_t E = s.eq_count;
@@ -162,51 +164,86 @@ __device__ TOPLOC_PRUNE_ATTR bool prune_if_above(SelectShared<THREADS, CAP, QCAP
     __syncthreads();
     t.tm = s.tm;
     t.ti = s.ti;
-#pragma unroll
-    for (int i = 0; i < EPT; ++i) {
-        if (tid + i * THREADS < M) {
-            const int32_t mag = (int32_t)(bits[i] & 0x7FFFu);
-            if (mag > t.tm || (mag == t.tm && idx[i] <= t.ti)) {
-                const uint32_t q = atomicAdd(&s.count, 1u);
-                s.cand_idx[q] = idx[i];
-                s.cand_bits[q] = (uint16_t)bits[i];
-            }
-        }
+    // Compact in place: exactly k entries survive.  Survivors already below slot k stay;
+    // every survivor at or above slot k moves into a slot below k that lost its entry.
+#pragma unroll 1
+    for (uint32_t slot = tid; slot < k; slot += THREADS) {
+        const int32_t mag = (int32_t)((uint32_t)s.cand_bits[slot] & 0x7FFFu);
+        if (!(mag > t.tm || (mag == t.tm && s.cand_idx[slot] <= t.ti)))
+            s.eq_slot[atomicAdd(&s.hole_count, 1u)] = (uint16_t)slot;  // eq_slot is free again: list of holes
     }
     __syncthreads();
-    return true;
+#pragma unroll 1
+    for (uint32_t slot = k + tid; slot < M; slot += THREADS) {
+        const uint32_t bits = s.cand_bits[slot];
+        const uint32_t idx = s.cand_idx[slot];
+        const int32_t mag = (int32_t)(bits & 0x7FFFu);
+        if (mag > t.tm || (mag == t.tm && idx <= t.ti)) {
+            const uint32_t dest = s.eq_slot[atomicAdd(&s.move_count, 1u)];
+            s.cand_idx[dest] = idx;
+            s.cand_bits[dest] = (uint16_t)bits;
+        }
+    }
+    if (tid == 0) s.count = k;
+    __syncthreads();
+    return M;
 }
 
-// Move every queued value that comes before the threshold element into the candidate
-// buffer, pruning whenever that buffer passes CAP/2; then empty the queue.  Two lanes
-// share a vector, so one batch adds at most 4*THREADS values: CAP/2 + 4*THREADS <= CAP.
-// Called by all threads after a barrier that made the queue writes visible; ends with
-// a barrier.  Returns true when lanes are still waiting for room in the queue.
+// Exact test of the queued vectors [q0, q1): two lanes share a vector; a value that comes
+// before the threshold element takes a candidate slot (slots past CAP are counted but
+// not written).
 template <int THREADS, int CAP, int QCAP>
-__device__ TOPLOC_DRAIN_ATTR bool drain(SelectShared<THREADS, CAP, QCAP>& s, uint32_t k, Threshold& t)
+__device__ __forceinline__ void drain_range(SelectShared<THREADS, CAP, QCAP>& s, uint32_t q0, uint32_t q1,
+                                            const Threshold& t)
 {
-    static_assert(CAP / 2 + 4 * THREADS <= CAP, "a batch must fit above the soft limit");
     const uint32_t tid = threadIdx.x;
-    const uint32_t raw = s.qcount;
-    const uint32_t nq = raw < (uint32_t)QCAP ? raw : (uint32_t)QCAP;
     const uint32_t half = tid & 1u;
-    for (uint32_t b0 = 0; b0 < nq; b0 += THREADS / 2) {
-        const uint32_t q = b0 + (tid >> 1);
-        if (q < nq) {
-            const u32x2 w = reinterpret_cast<const u32x2*>(&s.qvec[q])[half];
-            const uint32_t ebase = s.qidx[q] * 8u + half * 4u;
+    for (uint32_t q = q0 + (tid >> 1); q < q1; q += THREADS / 2) {
+        const u32x2 w = reinterpret_cast<const u32x2*>(&s.qvec[q])[half];
+        const uint32_t ebase = s.qidx[q] * 8u + half * 4u;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const uint32_t bits = (((e >> 1) ? w.y : w.x) >> (16 * (e & 1))) & 0xFFFFu;
-                const int32_t mag = (int32_t)(bits & 0x7FFFu);
-                if (before(mag, ebase + e, t)) {
-                    const uint32_t slot = atomicAdd(&s.count, 1u);
+        for (int e = 0; e < 4; ++e) {
+            const uint32_t bits = (((e >> 1) ? w.y : w.x) >> (16 * (e & 1))) & 0xFFFFu;
+            const int32_t mag = (int32_t)(bits & 0x7FFFu);
+            if (before(mag, ebase + e, t)) {
+                const uint32_t slot = atomicAdd(&s.count, 1u);
+                if (slot < (uint32_t)CAP) {
                     s.cand_idx[slot] = ebase + e;
                     s.cand_bits[slot] = (uint16_t)bits;
                 }
             }
         }
-        (void)prune_if_above<THREADS, CAP, QCAP>(s, k, CAP / 2, t);
+    }
+}
+
+// Move every queued value that comes before the threshold element into the candidate
+// buffer, prune that buffer when it holds more than `limit` (CAP/2 while streaming, k
+// at the end), then empty the queue.  Two lanes share
+// a vector.  The whole queue is taken in one sweep; should that ever hand out more than
+// CAP slots (the excess is dropped, not written), the sweep is undone and repeated in
+// batches of at most CAP/16 vectors with a prune check after each: a batch adds at most
+// CAP/2 values to a buffer holding at most CAP/2.
+// Called by all threads after a barrier that made the queue writes visible; ends with
+// a barrier.  Returns true when lanes are still waiting for room in the queue.
+template <int THREADS, int CAP, int QCAP>
+__device__ TOPLOC_DRAIN_ATTR bool drain(SelectShared<THREADS, CAP, QCAP>& s, uint32_t k, uint32_t limit, Threshold& t)
+{
+    constexpr uint32_t BATCH = (CAP / 16 < THREADS / 2) ? CAP / 16 : THREADS / 2;  // vectors: 8 * BATCH <= CAP / 2
+    const uint32_t tid = threadIdx.x;
+    const uint32_t raw = s.qcount;
+    const uint32_t nq = raw < (uint32_t)QCAP ? raw : (uint32_t)QCAP;
+    const uint32_t count0 = s.count;  // <= CAP/2; only drains and prunes change it
+    limit = limit < (uint32_t)(CAP / 2) ? limit : (uint32_t)(CAP / 2);
+    drain_range<THREADS, CAP, QCAP>(s, 0u, nq, t);
+    if (prune_if_above<THREADS, CAP, QCAP>(s, k, limit, t) > (uint32_t)CAP) {  // uniform; rare
+        if (tid == 0) s.count = count0;
+        __syncthreads();
+        for (uint32_t b0 = 0; b0 < nq; b0 += BATCH) {
+            const uint32_t b1 = b0 + BATCH < nq ? b0 + BATCH : nq;
+            drain_range<THREADS, CAP, QCAP>(s, b0, b1, t);
+            (void)prune_if_above<THREADS, CAP, QCAP>(s, k, CAP / 2, t);
+        }
+        (void)prune_if_above<THREADS, CAP, QCAP>(s, k, limit, t);
     }
     if (tid == 0) s.qcount = 0;
     __syncthreads();
@@ -240,7 +277,6 @@ __device__ __forceinline__ void select_topk(const u32x4* __restrict__ src, uint3
                             SelectShared<THREADS, CAP, QCAP>& s)
 {
     static_assert(CAP % THREADS == 0, "CAP must be a multiple of THREADS");
-    static_assert(THREADS * U <= CAP, "the first round's per-vector maxima must fit the buffer");
     constexpr uint32_t QSOFT = QCAP / 2;
     constexpr uint32_t ROUND = THREADS * U;
     const uint32_t tid = threadIdx.x;
@@ -253,6 +289,7 @@ __device__ __forceinline__ void select_topk(const u32x4* __restrict__ src, uint3
     t.ti = 0xFFFFFFFFu;
     uint32_t round = 0;  // barrier rounds; flag[round % 3] belongs to the current one
 
+    TT_START();
     u32x4 cur[U], nxt[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -260,41 +297,47 @@ __device__ __forceinline__ void select_topk(const u32x4* __restrict__ src, uint3
         cur[u] = u32x4{0u, 0u, 0u, 0u};
         if (v < nvec) cur[u] = __builtin_nontemporal_load(src + v);
     }
-    // First threshold: the largest value of every vector of the first round is a real
-    // element, so the k-th best of those maxima already has k-1 elements before it.
-    // The maxima only set the threshold; the round itself is then filtered like any
-    // other (threshold element included, hence ti + 1).
+#ifdef TOPLOC_EARLY_PREFETCH
+    // the second round's loads fly while the first threshold is set
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint32_t v = ROUND + u * THREADS + tid;
+        nxt[u] = u32x4{0u, 0u, 0u, 0u};
+        if (v < nvec) nxt[u] = __builtin_nontemporal_load(src + v);
+    }
+#endif
+    // First threshold: the largest magnitude of every vector of the first round belongs
+    // to a distinct real element.  If at least k of those maxima have exponent >= e, then
+    // k elements have magnitude >= e << 7, and nothing below that can be in the top-k.
+    // One exponent histogram finds the largest such e; exact thresholds follow from the
+    // first prune.
     const uint32_t first = nvec < ROUND ? nvec : ROUND;
-    if (first > k) {  // uniform
+    if (first >= k) {  // uniform
+        for (uint32_t b = tid; b < 256; b += THREADS) s.hist_e[b] = 0;
+        __syncthreads();
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const uint32_t v = u * THREADS + tid;
-            if (v < nvec) {
-                uint32_t best = vec_elem(cur[u], 0), be = 0;
-#pragma unroll
-                for (int e = 1; e < 8; ++e) {
-                    const uint32_t b = vec_elem(cur[u], e);
-                    if ((b & 0x7FFFu) > (best & 0x7FFFu)) { best = b; be = e; }
-                }
-                s.cand_idx[v] = v * 8u + be;
-                s.cand_bits[v] = (uint16_t)best;
-            }
-        }
-        __syncthreads();            // also orders the initialisation above
-        if (tid == 0) s.count = first;
-        (void)prune_if_above<THREADS, CAP, QCAP>(s, k, k, t);
-        t.ti += 1u;
-        if (tid == 0) s.count = 0;  // the maxima come back through the filter below
+        for (int u = 0; u < U; ++u)
+            if (u * THREADS + tid < nvec) atomicAdd(&s.hist_e[(uint32_t)vec_max_mag(cur[u]) >> 7], 1u);
+        __syncthreads();
+        uint32_t e_star, above;
+        find_bin<4>(s.hist_e, 0u, k, e_star, above);
+        t.tm = (int32_t)(e_star << 7);
     }
     __syncthreads();
+    TT_MARK(6);
 
     for (uint32_t base = 0; base < nvec; base += ROUND) {
         // loads of the next round fly while this one is examined
+#ifdef TOPLOC_EARLY_PREFETCH
+        if (base != 0)
+#endif
+        {
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const uint32_t v = base + ROUND + u * THREADS + tid;
-            nxt[u] = u32x4{0u, 0u, 0u, 0u};
-            if (v < nvec) nxt[u] = __builtin_nontemporal_load(src + v);
+            for (int u = 0; u < U; ++u) {
+                const uint32_t v = base + ROUND + u * THREADS + tid;
+                nxt[u] = u32x4{0u, 0u, 0u, 0u};
+                if (v < nvec) nxt[u] = __builtin_nontemporal_load(src + v);
+            }
         }
         uint32_t pend = 0;  // bit u: vector u still has to be queued
 #pragma unroll
@@ -323,14 +366,15 @@ __device__ __forceinline__ void select_topk(const u32x4* __restrict__ src, uint3
             if (tid == 0) s.flag[(round + 2u) % 3u] = 0;  // the previous round's flag: read by all before this barrier
             ++round;
             if (!f) break;
-            if (!drain<THREADS, CAP, QCAP>(s, k, t)) break;
+            if (!drain<THREADS, CAP, QCAP>(s, k, CAP / 2, t)) break;
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) cur[u] = nxt[u];
     }
     __syncthreads();
-    (void)drain<THREADS, CAP, QCAP>(s, k, t);
-    (void)prune_if_above<THREADS, CAP, QCAP>(s, k, k, t);
+    TT_MARK(7);
+    (void)drain<THREADS, CAP, QCAP>(s, k, k, t);  // prunes to exactly k
+    TT_MARK(5);
 }
 
 // Put the k survivors of select_topk into the order (magnitude descending, index

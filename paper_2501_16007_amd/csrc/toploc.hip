@@ -29,10 +29,10 @@ namespace toploc {
 #define TOPLOC_LOADS 4
 #endif
 #ifndef TOPLOC_CAP
-#define TOPLOC_CAP 2048
+#define TOPLOC_CAP 1024
 #endif
 #ifndef TOPLOC_MIN_WAVES
-#define TOPLOC_MIN_WAVES 4  // waves per SIMD the streaming kernels must reach (bounds their VGPRs)
+#define TOPLOC_MIN_WAVES 5  // waves per SIMD the streaming kernels must reach (bounds their VGPRs)
 #endif
 #ifndef TOPLOC_QCAP
 #define TOPLOC_QCAP 512
@@ -41,7 +41,7 @@ constexpr int kThreads = TOPLOC_THREADS;  // threads per workgroup (one chunk ea
 constexpr int kLoads = TOPLOC_LOADS;      // 16-byte loads in flight per lane and round
 constexpr int kCap = TOPLOC_CAP;          // candidate buffer entries
 constexpr int kQcap = TOPLOC_QCAP;        // queue entries (16-byte vectors)
-static_assert(kCap >= 4 * (int)TOPLOC_MAX_K, "the soft limit CAP/2 must leave room above k");
+static_assert(kCap >= 2 * (int)TOPLOC_MAX_K, "the soft limit CAP/2 must not be below k");
 
 typedef SelectShared<kThreads, kCap, kQcap> SelShared;
 
