@@ -32,7 +32,7 @@ namespace toploc {
 #define TOPLOC_CAP 1024
 #endif
 #ifndef TOPLOC_MIN_WAVES
-#define TOPLOC_MIN_WAVES 5  // waves per SIMD the streaming kernels must reach (bounds their VGPRs)
+#define TOPLOC_MIN_WAVES 6  // waves per SIMD the streaming kernels must reach (bounds their VGPRs)
 #endif
 #ifndef TOPLOC_QCAP
 #define TOPLOC_QCAP 512
@@ -67,28 +67,28 @@ __global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void select_kernel(cons
 // ---------------------------------------------------------------------------
 // Algorithm 1 after the selection (interp.hpp), as its own kernel for k > 128
 // ---------------------------------------------------------------------------
-template <int KMAX, int RB>
+template <int KMAX>
 __global__ __launch_bounds__(kThreads) void interp_kernel(const uint32_t* __restrict__ topk_idx,
                                                           const uint16_t* __restrict__ topk_val, uint32_t k,
                                                           uint8_t* __restrict__ proofs, uint8_t* __restrict__ status)
 {
-    __shared__ InterpShared<KMAX, RB> s;
+    __shared__ InterpShared<KMAX> s;
     __shared__ uint32_t coef[KMAX];
     const uint32_t tid = threadIdx.x;
     const uint64_t chunk = blockIdx.x;
     for (uint32_t j = tid; j < k; j += kThreads) {
         s.idx[j] = topk_idx[chunk * k + j];
         const uint32_t y = topk_val[chunk * k + j];
-        s.ys[j] = y >= kPrime ? y - kPrime : y;
+        s.ys[j] = (uint16_t)(y >= kPrime ? y - kPrime : y);
     }
-    finish_proof<kThreads, KMAX, RB>(s, coef, k, reinterpret_cast<uint16_t*>(proofs + chunk * (2 + 2 * (uint64_t)k)),
+    finish_proof<kThreads, KMAX>(s, coef, k, reinterpret_cast<uint16_t*>(proofs + chunk * (2 + 2 * (uint64_t)k)),
                                      status + chunk);
 }
 
 // Algorithm 1 in one launch, k <= KMAX <= kThreads: the selection streams the chunk,
 // then the same workgroup turns its k pairs into the proof out of LDS (the selection's
 // buffers are dead by then and are reused).
-template <int KMAX, int RB>
+template <int KMAX>
 __global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void build_kernel(const u32x4* __restrict__ hidden, uint32_t nvec,
                                                                            uint32_t k, uint8_t* __restrict__ proofs,
                                                                            uint8_t* __restrict__ status,
@@ -97,7 +97,7 @@ __global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void build_kernel(const
     static_assert(KMAX <= kThreads, "one pair per lane is carried across the phase change");
     __shared__ union BuildShared {
         SelShared sel;
-        InterpShared<KMAX, RB> itp;
+        InterpShared<KMAX> itp;
     } sh;
     __shared__ uint32_t coef[KMAX];
     const uint32_t tid = threadIdx.x;
@@ -115,9 +115,9 @@ __global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void build_kernel(const
     __syncthreads();  // the selection's LDS is dead from here on
     if (tid < k) {
         sh.itp.idx[tid] = my_idx;
-        sh.itp.ys[tid] = my_y >= kPrime ? my_y - kPrime : my_y;
+        sh.itp.ys[tid] = (uint16_t)(my_y >= kPrime ? my_y - kPrime : my_y);
     }
-    finish_proof<kThreads, KMAX, RB>(sh.itp, coef, k,
+    finish_proof<kThreads, KMAX>(sh.itp, coef, k,
                                      reinterpret_cast<uint16_t*>(proofs + chunk * (2 + 2 * (uint64_t)k)), status + chunk);
 }
 
@@ -347,7 +347,7 @@ int toploc_build_proofs(const void* d_hidden_bf16, uint64_t n_chunks, const topl
     hipStream_t st = (hipStream_t)hip_stream;
     if (k <= 128) {
         ProfScope ps(TOPLOC_KERNEL_BUILD, st);
-        hipLaunchKernelGGL((build_kernel<128, 64>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
+        hipLaunchKernelGGL((build_kernel<128>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
                            (const u32x4*)d_hidden_bf16, (uint32_t)(n / 8), k, d_proofs, d_status, d_topk_idx_opt);
         return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
     }
@@ -361,7 +361,7 @@ int toploc_build_proofs(const void* d_hidden_bf16, uint64_t n_chunks, const topl
     if (!hip_ok(hipGetLastError())) return TOPLOC_EHIP;
     {
         ProfScope ps(TOPLOC_KERNEL_INTERP, st);
-        hipLaunchKernelGGL((interp_kernel<512, 32>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
+        hipLaunchKernelGGL((interp_kernel<512>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
                            (const uint32_t*)ws_idx, (const uint16_t*)ws_val, k, d_proofs, d_status);
     }
     return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
