@@ -87,11 +87,14 @@ def main():
     prof = tl.toploc_profile_read()
     tl.toploc_profile_enable(False)
     kernels = {}
+    # parts a chunk is cut into when the batch is small or k > 128 (0 bytes of workspace: one fused launch)
+    parts = max(1, round(tl.toploc_workspace_bytes(k, 1, n, n_chunks) / (6.0 * k * n_chunks)))
     alg_bytes = {   # algorithmic HBM bytes per chunk: what the method itself must move
-        "build_kernel": 2 * n + pb + 1,          # read the chunk, write the proof and status
-        "select_kernel": 2 * n + 6 * k,          # (k > 128) read the chunk, hand k (index, value) pairs on
-        "interp_kernel": 6 * k + pb + 1,         # (k > 128) read the pairs, write the proof and status
-        "verify_kernel": 2 * n + pb + 20,        # read the chunk and the proof, write the record
+        "build_kernel": 2 * n + pb + 1,                     # read the chunk, write the proof and status
+        "verify_kernel": 2 * n + pb + 20,                   # read the chunk and the proof, write the record
+        "part_kernel": 2 * n + 6 * k * parts,               # split path: read the chunk, hand candidates on
+        "build_merge_kernel": 6 * k * parts + pb + 1,       # split path: read the candidates, write the proof
+        "verify_merge_kernel": 6 * k * parts + pb + 20,     # split path: candidates and proof in, record out
     }
     for kn, (launches, total_ms) in prof.items():
         if launches:

@@ -89,11 +89,18 @@ typedef struct {
  * plus the modulus). Host only. */
 size_t toploc_proof_bytes(uint32_t k);
 
-/* Bytes of device scratch that toploc_build_proofs needs for `n_chunks` chunks with
- * these parameters: 0 for k <= 128 (one fused kernel), else room for the top-k
- * pairs handed from the selection kernel to the interpolation kernel.  Also 0 on
- * invalid parameters.  Verify never needs scratch.  Host only. */
+/* Bytes of device scratch that toploc_build_proofs / toploc_verify_proofs use for
+ * `n_chunks` chunks with these parameters.  A batch too small to fill the chip with one
+ * workgroup per chunk is cut into parts (first launch: top-k of every part into this
+ * scratch, second launch: merge and finish), and so is every build with k > 128.
+ * 0 means one fused launch needs no scratch (large batches, k <= 128), or invalid
+ * parameters.  Host only. */
 size_t toploc_workspace_bytes(const toploc_params *params, uint64_t n_chunks);
+
+/* Tuning / test knob: 0 (default) lets the library choose into how many parts a chunk
+ * is cut, n >= 1 forces n parts per chunk (per longest segment for the *_segments
+ * calls).  Affects later calls, including the workspace_bytes functions. */
+int toploc_set_split(uint32_t parts_per_chunk);
 
 /* Algorithm 1 over n_chunks chunks: top-k by magnitude, injective modulus
  * (Algorithm 6), index map, interpolation over GF(p) (Algorithm 3), encode.
@@ -103,8 +110,10 @@ size_t toploc_workspace_bytes(const toploc_params *params, uint64_t n_chunks);
  *   d_status        out, device, n_chunks bytes, TOPLOC_CHUNK_*
  *   d_topk_idx_opt  out, device, n_chunks*k uint32 flat indices in the order
  *                   (magnitude descending, index ascending); NULL to skip
- *   d_workspace     device scratch, 16-byte aligned, >= toploc_workspace_bytes();
- *                   may be NULL when that is 0
+ *   d_workspace     device scratch, 16-byte aligned, >= toploc_workspace_bytes().
+ *                   For k <= 128 it may be NULL or too small: the fused launch is used
+ *                   then (slower on small batches only).  For k > 128 it is required
+ *                   (TOPLOC_EINVAL when NULL, TOPLOC_EWORKSPACE when too small).
  * n_chunks = 0 is valid and enqueues nothing. */
 int toploc_build_proofs(const void *d_hidden_bf16, uint64_t n_chunks, const toploc_params *params,
                         uint8_t *d_proofs, uint8_t *d_status, uint32_t *d_topk_idx_opt,
@@ -116,7 +125,8 @@ int toploc_build_proofs(const void *d_hidden_bf16, uint64_t n_chunks, const topl
  *   d_hidden_bf16   in,  device, recomputed activations, same layout as above
  *   d_proofs        in,  device, n_chunks * (2+2k) bytes
  *   thresholds      in,  host
- *   d_results       out, device, n_chunks records */
+ *   d_results       out, device, n_chunks records
+ *   d_workspace     device scratch as above; NULL or too small selects the fused launch */
 int toploc_verify_proofs(const void *d_hidden_bf16, uint64_t n_chunks, const toploc_params *params,
                          const uint8_t *d_proofs, const toploc_thresholds *thresholds,
                          toploc_verify_result *d_results, void *d_workspace, size_t workspace_bytes,
@@ -127,6 +137,29 @@ int toploc_verify_proofs(const void *d_hidden_bf16, uint64_t n_chunks, const top
  *   d_topk_val   out, device, n_chunks*k uint16 bf16 patterns, same order */
 int toploc_topk(const void *d_hidden_bf16, uint64_t n_chunks, const toploc_params *params,
                 uint32_t *d_topk_idx, uint16_t *d_topk_val, void *hip_stream);
+
+/* The same two algorithms over SEGMENTS of unequal length: the proof over a whole
+ * prompt (Section 5.5: a set of top-k values is also kept for the activations of the
+ * input prompt) and the ragged last chunk of a generation.  The activations are one
+ * [total_rows][hidden] bf16 matrix; segment i is rows h_row_offsets[i] ..
+ * h_row_offsets[i+1]-1 (n_segments + 1 non-decreasing HOST values), its flat index is
+ * (row - first row) * hidden + channel.  Every segment must hold at least k and fewer
+ * than 2^32 values; hidden must be a multiple of 8.  Proofs, status, results and the
+ * optional indices are laid out per segment exactly as per chunk above; prime and
+ * proof layout are the same.  Long segments are cut into parts like small batches.
+ * d_workspace (required, 16-byte aligned) must hold toploc_segments_workspace_bytes()
+ * bytes; the calls copy two small tables into it with hipMemcpyAsync from pageable
+ * host memory, which may wait for earlier work of the stream. */
+size_t toploc_segments_workspace_bytes(const uint64_t *h_row_offsets, uint64_t n_segments, uint32_t hidden,
+                                       uint32_t k);
+int toploc_build_proofs_segments(const void *d_hidden_bf16, const uint64_t *h_row_offsets, uint64_t n_segments,
+                                 uint32_t hidden, uint32_t k, uint8_t *d_proofs, uint8_t *d_status,
+                                 uint32_t *d_topk_idx_opt, void *d_workspace, size_t workspace_bytes,
+                                 void *hip_stream);
+int toploc_verify_proofs_segments(const void *d_hidden_bf16, const uint64_t *h_row_offsets, uint64_t n_segments,
+                                  uint32_t hidden, uint32_t k, const uint8_t *d_proofs,
+                                  const toploc_thresholds *thresholds, toploc_verify_result *d_results,
+                                  void *d_workspace, size_t workspace_bytes, void *hip_stream);
 
 /* Provider-side ring of the last chunk_tokens hidden vectors per sequence
  * (Section 5.8, Table 6: the provider keeps the last hidden states until the
@@ -152,13 +185,15 @@ int toploc_bench_read(const void *d_hidden_bf16, uint64_t n_chunks, uint64_t chu
  * toploc_profile_read synchronises those events and returns, per kernel slot
  * (TOPLOC_KERNEL_*), the number of launches and their summed duration in
  * milliseconds since the last reset, then resets.  Not thread safe. */
-#define TOPLOC_KERNEL_SELECT 0   /* top-k selection kernel (topk; build with k > 128)       */
-#define TOPLOC_KERNEL_INTERP 1   /* modulus + interpolation + encode kernel (k > 128)       */
-#define TOPLOC_KERNEL_VERIFY 2   /* fused verify kernel                     */
-#define TOPLOC_KERNEL_RING 3     /* ring append kernel                      */
-#define TOPLOC_KERNEL_READ 4     /* toploc_bench_read                       */
-#define TOPLOC_KERNEL_BUILD 5    /* fused build kernel (k <= 128)           */
-#define TOPLOC_KERNEL_COUNT 6
+#define TOPLOC_KERNEL_SELECT 0        /* topk alone (toploc_topk)                        */
+#define TOPLOC_KERNEL_PART 1          /* split path: top-k of one part                   */
+#define TOPLOC_KERNEL_BUILD_MERGE 2   /* split path: merge, modulus, interpolation       */
+#define TOPLOC_KERNEL_VERIFY_MERGE 3  /* split path: merge, evaluation, statistics       */
+#define TOPLOC_KERNEL_BUILD 4         /* fused build kernel (k <= 128)                   */
+#define TOPLOC_KERNEL_VERIFY 5        /* fused verify kernel                             */
+#define TOPLOC_KERNEL_RING 6          /* ring append kernel                              */
+#define TOPLOC_KERNEL_READ 7          /* toploc_bench_read                               */
+#define TOPLOC_KERNEL_COUNT 8
 int toploc_profile_enable(int on);
 int toploc_profile_read(uint32_t *launches /*[TOPLOC_KERNEL_COUNT]*/, float *total_ms /*[TOPLOC_KERNEL_COUNT]*/);
 

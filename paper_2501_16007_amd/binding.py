@@ -17,8 +17,10 @@ PRIME = 65497
 MAX_K = 512
 OK, EINVAL, EWORKSPACE, EHIP = 0, -1, -2, -3
 CHUNK_OK, CHUNK_NO_MODULUS, CHUNK_NO_INVERSE, CHUNK_MALFORMED = 0, 1, 2, 3
-KERNEL_SELECT, KERNEL_INTERP, KERNEL_VERIFY, KERNEL_RING, KERNEL_READ, KERNEL_BUILD, KERNEL_COUNT = 0, 1, 2, 3, 4, 5, 6
-KERNEL_NAMES = ("select_kernel", "interp_kernel", "verify_kernel", "ring_kernel", "read_kernel", "build_kernel")
+(KERNEL_SELECT, KERNEL_PART, KERNEL_BUILD_MERGE, KERNEL_VERIFY_MERGE, KERNEL_BUILD, KERNEL_VERIFY, KERNEL_RING,
+ KERNEL_READ, KERNEL_COUNT) = range(9)
+KERNEL_NAMES = ("select_kernel", "part_kernel", "build_merge_kernel", "verify_merge_kernel", "build_kernel",
+                "verify_kernel", "ring_kernel", "read_kernel")
 BF16_THRESHOLDS = (38, 10, 8)  # T_exp, T_mean, T_median (Section 5.2 of the paper)
 
 RESULT_DTYPE = np.dtype(
@@ -36,6 +38,10 @@ RESULT_DTYPE = np.dtype(
 EXPORTS = (
     "toploc_proof_bytes",
     "toploc_workspace_bytes",
+    "toploc_set_split",
+    "toploc_segments_workspace_bytes",
+    "toploc_build_proofs_segments",
+    "toploc_verify_proofs_segments",
     "toploc_build_proofs",
     "toploc_verify_proofs",
     "toploc_topk",
@@ -86,6 +92,12 @@ def lib():
         L.toploc_verify_proofs.argtypes = [P, c.c_uint64, c.POINTER(Params), P, c.POINTER(Thresholds), P, P,
                                            c.c_size_t, P]
         L.toploc_topk.argtypes = [P, c.c_uint64, c.POINTER(Params), P, P, P]
+        L.toploc_set_split.argtypes = [c.c_uint32]
+        L.toploc_segments_workspace_bytes.argtypes = [P, c.c_uint64, c.c_uint32, c.c_uint32]
+        L.toploc_segments_workspace_bytes.restype = c.c_size_t
+        L.toploc_build_proofs_segments.argtypes = [P, P, c.c_uint64, c.c_uint32, c.c_uint32, P, P, P, P, c.c_size_t, P]
+        L.toploc_verify_proofs_segments.argtypes = [P, P, c.c_uint64, c.c_uint32, c.c_uint32, P, c.POINTER(Thresholds), P,
+                                                    P, c.c_size_t, P]
         L.toploc_ring_append.argtypes = [P, P, c.c_uint32, c.c_uint32, c.c_uint32, c.c_uint32, P]
         L.toploc_bench_read.argtypes = [P, c.c_uint64, c.c_uint64, P, P]
         L.toploc_profile_enable.argtypes = [c.c_int]
@@ -154,7 +166,7 @@ def toploc_build_proofs(hidden, k=128, chunk_tokens=32, want_topk=False, workspa
     return (proofs, status, idx) if want_topk else (proofs, status)
 
 
-def toploc_verify_proofs(hidden, proofs, k=128, chunk_tokens=32, thresholds=BF16_THRESHOLDS, out=None):
+def toploc_verify_proofs(hidden, proofs, k=128, chunk_tokens=32, thresholds=BF16_THRESHOLDS, out=None, workspace=None):
     """Algorithm 2 over every chunk. Returns a uint8 device tensor [n_chunks, 20]; see results_numpy."""
     n_chunks, h = _chunks(hidden, chunk_tokens)
     if proofs.dtype != torch.uint8 or not proofs.is_cuda or not proofs.is_contiguous() or \
@@ -164,8 +176,10 @@ def toploc_verify_proofs(hidden, proofs, k=128, chunk_tokens=32, thresholds=BF16
     t = Thresholds(*thresholds)
     res = out if out is not None else torch.empty((n_chunks, RESULT_DTYPE.itemsize), dtype=torch.uint8,
                                                   device=hidden.device)
+    if workspace is None:
+        workspace = new_workspace(k, chunk_tokens, h, n_chunks, hidden.device)
     rc = lib().toploc_verify_proofs(hidden.data_ptr(), n_chunks, ctypes.byref(p), proofs.data_ptr(), ctypes.byref(t),
-                                    res.data_ptr(), None, 0, _stream(hidden))
+                                    res.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream(hidden))
     if rc != OK:
         raise ToplocError(rc, "toploc_verify_proofs")
     return res
@@ -187,6 +201,60 @@ def toploc_topk(hidden, k=128, chunk_tokens=32):
     if rc != OK:
         raise ToplocError(rc, "toploc_topk")
     return idx, val
+
+
+def toploc_set_split(parts_per_chunk):
+    """0: the library chooses into how many parts a chunk is cut; n: force n parts (tuning / tests)."""
+    rc = lib().toploc_set_split(parts_per_chunk)
+    if rc != OK:
+        raise ToplocError(rc, "toploc_set_split")
+
+
+def _segments(hidden, row_offsets):
+    if hidden.dtype != torch.bfloat16 or not hidden.is_cuda or not hidden.is_contiguous() or hidden.dim() != 2:
+        raise ValueError("hidden must be a contiguous [total_rows, H] bf16 tensor on the GPU")
+    off = np.ascontiguousarray(row_offsets, dtype=np.uint64)
+    if off.ndim != 1 or off.size < 1 or int(off[-1]) > hidden.shape[0]:
+        raise ValueError("row_offsets must be a 1-D array of n_segments + 1 row numbers inside the tensor")
+    return off, off.size - 1, hidden.shape[1]
+
+
+def toploc_segments_workspace_bytes(row_offsets, hidden_size, k):
+    off = np.ascontiguousarray(row_offsets, dtype=np.uint64)
+    return int(lib().toploc_segments_workspace_bytes(off.ctypes.data_as(ctypes.c_void_p), off.size - 1, hidden_size, k))
+
+
+def toploc_build_proofs_segments(hidden, row_offsets, k=128, want_topk=False):
+    """Algorithm 1 over segments of rows [row_offsets[i], row_offsets[i+1]) of hidden [total_rows, H]."""
+    off, n_seg, h = _segments(hidden, row_offsets)
+    dev = hidden.device
+    proofs = torch.empty((n_seg, 2 + 2 * k), dtype=torch.uint8, device=dev)
+    status = torch.empty(n_seg, dtype=torch.uint8, device=dev)
+    idx = torch.empty((n_seg, k), dtype=torch.int32, device=dev) if want_topk else None
+    ws = torch.empty(max(16, toploc_segments_workspace_bytes(off, h, k)), dtype=torch.uint8, device=dev)
+    rc = lib().toploc_build_proofs_segments(
+        hidden.data_ptr(), off.ctypes.data_as(ctypes.c_void_p), n_seg, h, k, proofs.data_ptr(), status.data_ptr(),
+        idx.data_ptr() if want_topk else None, ws.data_ptr(), ws.numel(), _stream(hidden))
+    if rc != OK:
+        raise ToplocError(rc, "toploc_build_proofs_segments")
+    return (proofs, status, idx) if want_topk else (proofs, status)
+
+
+def toploc_verify_proofs_segments(hidden, row_offsets, proofs, k=128, thresholds=BF16_THRESHOLDS):
+    """Algorithm 2 over segments. Returns a uint8 device tensor [n_segments, 20]; see results_numpy."""
+    off, n_seg, h = _segments(hidden, row_offsets)
+    if proofs.dtype != torch.uint8 or not proofs.is_cuda or not proofs.is_contiguous() or \
+            proofs.numel() != n_seg * (2 + 2 * k):
+        raise ValueError("proofs must be a contiguous uint8 device tensor of n_segments * (2+2k) bytes")
+    t = Thresholds(*thresholds)
+    res = torch.empty((n_seg, RESULT_DTYPE.itemsize), dtype=torch.uint8, device=hidden.device)
+    ws = torch.empty(max(16, toploc_segments_workspace_bytes(off, h, k)), dtype=torch.uint8, device=hidden.device)
+    rc = lib().toploc_verify_proofs_segments(
+        hidden.data_ptr(), off.ctypes.data_as(ctypes.c_void_p), n_seg, h, k, proofs.data_ptr(), ctypes.byref(t),
+        res.data_ptr(), ws.data_ptr(), ws.numel(), _stream(hidden))
+    if rc != OK:
+        raise ToplocError(rc, "toploc_verify_proofs_segments")
+    return res
 
 
 def toploc_ring_append(ring, step_vec, step):

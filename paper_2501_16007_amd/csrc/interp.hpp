@@ -24,15 +24,6 @@
 
 namespace toploc {
 
-#ifdef TOPLOC_TIMING
-__device__ unsigned long long g_tt[8];
-#define TT_MARK(i) do { if (threadIdx.x == 0) { const uint64_t now_ = wall_clock64(); atomicAdd(&g_tt[i], (unsigned long long)(now_ - tt0_)); tt0_ = now_; } } while (0)
-#define TT_START() uint64_t tt0_ = wall_clock64()
-#else
-#define TT_MARK(i) do { } while (0)
-#define TT_START() do { } while (0)
-#endif
-
 constexpr uint32_t kModHigh = 65536u;
 constexpr uint32_t kModLow = 32769u;  // 2^15 + 1
 constexpr uint32_t kBaby = 16u;       // baby-step table width
@@ -95,7 +86,6 @@ __device__ __forceinline__ void interpolate(InterpShared<KMAX>& s, uint32_t k, u
     const uint32_t tid = threadIdx.x;
     const uint32_t h = (L == 2) ? (tid & 1u) : 0u;
     const uint32_t n_giant = (k + kBaby - 1u) / kBaby;
-    TT_START();
 
     // ---- W(X) = prod (X - x_j): pairwise products of monic polynomials ----
     uint16_t* src = s.pa;
@@ -133,7 +123,6 @@ __device__ __forceinline__ void interpolate(InterpShared<KMAX>& s, uint32_t k, u
         uint16_t* tmp = src; src = dst; dst = tmp;
     }
     const uint16_t* W = src;  // W_0..W_{k-1}; W_k = 1
-    TT_MARK(1);
     // ---- W'(X) coefficients: wder_r = (r+1) W_{r+1}; power tables of every point ----
     for (uint32_t r = tid; r < k; r += THREADS)
         s.wder[r] = (uint16_t)mulmod(r + 1, r + 1 == k ? 1u : (uint32_t)W[r + 1]);
@@ -196,7 +185,6 @@ __device__ __forceinline__ void interpolate(InterpShared<KMAX>& s, uint32_t k, u
         }
     }
     __syncthreads();
-    TT_MARK(2);
     // ---- S_r = sum_j (a_j x_j^(16 r1)) x_j^r0, r = 16 r1 + r0; lane h takes j = h mod L ----
     for (uint32_t r = tid / L; r < k; r += THREADS / L) {
         const uint16_t* arow = &s.u.pw.G[(r / kBaby) * KMAX];
@@ -212,7 +200,6 @@ __device__ __forceinline__ void interpolate(InterpShared<KMAX>& s, uint32_t k, u
         if (h == 0) s.S[r] = (uint16_t)v;
     }
     __syncthreads();
-    TT_MARK(3);
     // ---- c_i = sum_{r=0}^{k-1-i} W_{i+1+r} S_r, lane h takes r = h mod L ----
     for (uint32_t i = tid / L; i < k; i += THREADS / L) {
         uint64_t acc = 0;
@@ -228,7 +215,6 @@ __device__ __forceinline__ void interpolate(InterpShared<KMAX>& s, uint32_t k, u
         if (h == 0) coef_out[i] = c;
     }
     __syncthreads();
-    TT_MARK(4);
 }
 
 // Remaining steps of Algorithm 1 for one chunk whose top-k pairs sit in s.idx / s.ys
@@ -239,12 +225,10 @@ __device__ __forceinline__ void finish_proof(InterpShared<KMAX>& s, uint32_t* co
                                              uint8_t* status)
 {
     const uint32_t tid = threadIdx.x;
-    TT_START();
     for (uint32_t w = tid; w < 2048; w += THREADS) s.u.bitmap[w] = 0;
     if (tid == 0) { s.collide[0] = 0; s.collide[1] = 0; }
     __syncthreads();
     const uint32_t m = find_modulus<THREADS, KMAX>(s, k);
-    TT_MARK(0);
     if (m == 0) {  // uniform
         for (uint32_t j = tid; j <= k; j += THREADS) proof[j] = 0;
         if (tid == 0) *status = 1;  // TOPLOC_CHUNK_NO_MODULUS
@@ -253,7 +237,6 @@ __device__ __forceinline__ void finish_proof(InterpShared<KMAX>& s, uint32_t* co
     interpolate<THREADS, KMAX>(s, k, coef);
     if (tid == 0) { proof[0] = (uint16_t)(m & 0xFFFFu); *status = 0; }
     for (uint32_t j = tid; j < k; j += THREADS) proof[1 + j] = (uint16_t)coef[j];
-    TT_MARK(5);
 }
 
 }  // namespace toploc

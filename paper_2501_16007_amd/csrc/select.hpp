@@ -34,11 +34,6 @@
 #define TOPLOC_DRAIN_ATTR __forceinline__
 #endif
 
-#ifndef TT_MARK
-#define TT_MARK(i) do { } while (0)
-#define TT_START() do { } while (0)
-#endif
-
 namespace toploc {
 
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
@@ -268,15 +263,15 @@ __device__ __forceinline__ int32_t vec_max_mag(const u32x4& r)
     return (int32_t)(mm.x > mm.y ? mm.x : mm.y);
 }
 
-// Top-k of src[0 .. 8*nvec) into s.cand_idx / s.cand_bits [0 .. k), in no particular
-// order (order_topk sorts them).
-// Requires k <= 8*nvec, k <= CAP/2, 8*nvec < 2^32.  All threads of the workgroup call
-// it; it ends with a barrier.
+// Top-k of the vectors [v0, v1) of the chunk at src (8 values per vector, flat index of
+// value e of vector v is 8v + e) into s.cand_idx / s.cand_bits [0 .. k), in no
+// particular order (order_topk sorts them).
+// Requires k <= 8*(v1 - v0), k <= CAP/2, 8*v1 < 2^32.  All threads of the workgroup
+// call it; it ends with a barrier.
 template <int THREADS, int U, int CAP, int QCAP>
-__device__ __forceinline__ void select_topk(const u32x4* __restrict__ src, uint32_t nvec, uint32_t k,
-                            SelectShared<THREADS, CAP, QCAP>& s)
+__device__ __forceinline__ void select_topk(const u32x4* __restrict__ src, uint32_t v0, uint32_t v1, uint32_t k,
+                                            SelectShared<THREADS, CAP, QCAP>& s)
 {
-    static_assert(CAP % THREADS == 0, "CAP must be a multiple of THREADS");
     constexpr uint32_t QSOFT = QCAP / 2;
     constexpr uint32_t ROUND = THREADS * U;
     const uint32_t tid = threadIdx.x;
@@ -289,60 +284,44 @@ __device__ __forceinline__ void select_topk(const u32x4* __restrict__ src, uint3
     t.ti = 0xFFFFFFFFu;
     uint32_t round = 0;  // barrier rounds; flag[round % 3] belongs to the current one
 
-    TT_START();
     u32x4 cur[U], nxt[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const uint32_t v = u * THREADS + tid;
+        const uint32_t v = v0 + u * THREADS + tid;
         cur[u] = u32x4{0u, 0u, 0u, 0u};
-        if (v < nvec) cur[u] = __builtin_nontemporal_load(src + v);
+        if (v < v1) cur[u] = __builtin_nontemporal_load(src + v);
     }
-#ifdef TOPLOC_EARLY_PREFETCH
-    // the second round's loads fly while the first threshold is set
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const uint32_t v = ROUND + u * THREADS + tid;
-        nxt[u] = u32x4{0u, 0u, 0u, 0u};
-        if (v < nvec) nxt[u] = __builtin_nontemporal_load(src + v);
-    }
-#endif
     // First threshold: the largest magnitude of every vector of the first round belongs
     // to a distinct real element.  If at least k of those maxima have exponent >= e, then
     // k elements have magnitude >= e << 7, and nothing below that can be in the top-k.
     // One exponent histogram finds the largest such e; exact thresholds follow from the
     // first prune.
-    const uint32_t first = nvec < ROUND ? nvec : ROUND;
+    const uint32_t first = (v1 - v0) < ROUND ? (v1 - v0) : ROUND;
     if (first >= k) {  // uniform
         for (uint32_t b = tid; b < 256; b += THREADS) s.hist_e[b] = 0;
         __syncthreads();
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            if (u * THREADS + tid < nvec) atomicAdd(&s.hist_e[(uint32_t)vec_max_mag(cur[u]) >> 7], 1u);
+            if (v0 + u * THREADS + tid < v1) atomicAdd(&s.hist_e[(uint32_t)vec_max_mag(cur[u]) >> 7], 1u);
         __syncthreads();
         uint32_t e_star, above;
         find_bin<4>(s.hist_e, 0u, k, e_star, above);
         t.tm = (int32_t)(e_star << 7);
     }
     __syncthreads();
-    TT_MARK(6);
 
-    for (uint32_t base = 0; base < nvec; base += ROUND) {
+    for (uint32_t base = v0; base < v1; base += ROUND) {
         // loads of the next round fly while this one is examined
-#ifdef TOPLOC_EARLY_PREFETCH
-        if (base != 0)
-#endif
-        {
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const uint32_t v = base + ROUND + u * THREADS + tid;
-                nxt[u] = u32x4{0u, 0u, 0u, 0u};
-                if (v < nvec) nxt[u] = __builtin_nontemporal_load(src + v);
-            }
+        for (int u = 0; u < U; ++u) {
+            const uint32_t v = base + ROUND + u * THREADS + tid;
+            nxt[u] = u32x4{0u, 0u, 0u, 0u};
+            if (v < v1) nxt[u] = __builtin_nontemporal_load(src + v);
         }
         uint32_t pend = 0;  // bit u: vector u still has to be queued
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            if (base + u * THREADS + tid < nvec) pend |= 1u << u;
+            if (base + u * THREADS + tid < v1) pend |= 1u << u;
         while (true) {
             uint32_t* flag = &s.flag[round % 3u];
 #pragma unroll
@@ -372,9 +351,35 @@ __device__ __forceinline__ void select_topk(const u32x4* __restrict__ src, uint3
         for (int u = 0; u < U; ++u) cur[u] = nxt[u];
     }
     __syncthreads();
-    TT_MARK(7);
     (void)drain<THREADS, CAP, QCAP>(s, k, k, t);  // prunes to exactly k
-    TT_MARK(5);
+}
+
+// Top-k of candidate lists: `n` (index, pattern) pairs in global memory, entries whose
+// index is 0xFFFFFFFF are padding.  They are loaded in batches of CAP/2 with a prune
+// after each, so any n fits.  Leaves min(k, valid entries) survivors in
+// s.cand_idx / s.cand_bits, unordered.  All threads call; ends with a barrier.
+template <int THREADS, int CAP, int QCAP>
+__device__ __forceinline__ void merge_topk(const uint32_t* __restrict__ c_idx, const uint16_t* __restrict__ c_bits,
+                                           uint32_t n, uint32_t k, SelectShared<THREADS, CAP, QCAP>& s)
+{
+    const uint32_t tid = threadIdx.x;
+    if (tid == 0) { s.count = 0; s.eq_count = 0; s.tm = 0; s.ti = 0xFFFFFFFFu; }
+    __syncthreads();
+    Threshold t;
+    t.tm = 0;
+    t.ti = 0xFFFFFFFFu;
+    for (uint32_t b0 = 0; b0 < n; b0 += CAP / 2) {
+        const uint32_t b1 = b0 + CAP / 2 < n ? b0 + CAP / 2 : n;
+        for (uint32_t i = b0 + tid; i < b1; i += THREADS) {
+            const uint32_t idx = c_idx[i];
+            if (idx != 0xFFFFFFFFu) {
+                const uint32_t slot = atomicAdd(&s.count, 1u);
+                s.cand_idx[slot] = idx;
+                s.cand_bits[slot] = c_bits[i];
+            }
+        }
+        (void)prune_if_above<THREADS, CAP, QCAP>(s, k, b1 == n ? k : (uint32_t)(CAP / 2), t);
+    }
 }
 
 // Put the k survivors of select_topk into the order (magnitude descending, index

@@ -1,15 +1,19 @@
 // TopLoc proof build / verify for MI355X (gfx950): kernels and the C ABI of
-// include/toploc.h.  One workgroup per chunk everywhere; chunks are independent.
+// include/toploc.h.  Chunks (and segments) are independent.
 //
-//   build_kernel    all of Algorithm 1 in one launch (k <= 128): topk, then
-//                   findInjectiveModulus, i mod m, InterpolateModPolynomial, encode
-//                   while other workgroups of the compute unit keep streaming
-//   select_kernel   topk(h, k)                       (Algorithm 1 / 2, first step)
-//   interp_kernel   findInjectiveModulus, i mod m, InterpolateModPolynomial, encode
-//                   (Algorithm 1, remaining steps; Algorithms 3, 4, 6), k > 128
-//   verify_kernel   decode, topk, i mod m, Horner at the k points, extractBits,
-//                   err_e / err_m statistics, thresholds (Algorithm 2, Algorithm 5)
-//   ring_kernel     provider-side ring of the last chunk_tokens hidden vectors
+// Large batches, one 256-lane workgroup per chunk, one launch:
+//   build_kernel    all of Algorithm 1 (k <= 128): topk, then findInjectiveModulus,
+//                   i mod m, InterpolateModPolynomial, encode out of LDS while other
+//                   workgroups of the compute unit keep streaming
+//   verify_kernel   all of Algorithm 2: decode, topk, i mod m, Horner at the k points,
+//                   extractBits, err_e / err_m statistics, thresholds
+//   select_kernel   topk(h, k) alone, ordered (toploc_topk)
+// Small batches, long segments, k > 128: a chunk is cut into parts so that the launch
+// fills the chip, and a second launch merges the parts' candidates:
+//   part_kernel          topk of one part of one chunk / segment -> k candidates
+//   build_merge_kernel   topk of the candidates, then the rest of Algorithm 1
+//   verify_merge_kernel  topk of the candidates, then the rest of Algorithm 2
+//   ring_kernel          provider-side ring of the last chunk_tokens hidden vectors
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdio.h>
@@ -19,76 +23,70 @@
 #include "gf65497.hpp"
 #include "interp.hpp"
 #include "select.hpp"
+#include "verify.hpp"
 
-namespace toploc {
-
-#ifndef TOPLOC_THREADS
-#define TOPLOC_THREADS 256
-#endif
 #ifndef TOPLOC_LOADS
 #define TOPLOC_LOADS 4
-#endif
-#ifndef TOPLOC_CAP
-#define TOPLOC_CAP 1024
-#endif
-#ifndef TOPLOC_MIN_WAVES
-#define TOPLOC_MIN_WAVES 6  // waves per SIMD the streaming kernels must reach (bounds their VGPRs)
 #endif
 #ifndef TOPLOC_QCAP
 #define TOPLOC_QCAP 512
 #endif
-constexpr int kThreads = TOPLOC_THREADS;  // threads per workgroup (one chunk each)
-constexpr int kLoads = TOPLOC_LOADS;      // 16-byte loads in flight per lane and round
-constexpr int kCap = TOPLOC_CAP;          // candidate buffer entries
-constexpr int kQcap = TOPLOC_QCAP;        // queue entries (16-byte vectors)
-static_assert(kCap >= 2 * (int)TOPLOC_MAX_K, "the soft limit CAP/2 must not be below k");
+#ifndef TOPLOC_MIN_WAVES
+#define TOPLOC_MIN_WAVES 6  // waves per SIMD the streaming kernels must reach (bounds their VGPRs)
+#endif
 
-typedef SelectShared<kThreads, kCap, kQcap> SelShared;
+namespace toploc {
+
+constexpr int kThreads = 256;             // lanes per streaming workgroup
+constexpr int kLoads = TOPLOC_LOADS;      // 16-byte loads in flight per lane and round
+constexpr int kQcap = TOPLOC_QCAP;        // queue entries (16-byte vectors)
+constexpr int kCapSmall = 1024;           // candidate buffer for k <= 128
+constexpr int kCapLarge = 2048;           // candidate buffer for k <= TOPLOC_MAX_K
+constexpr uint32_t kRoundVecs = kThreads * kLoads;
+static_assert(kCapLarge >= 4 * (int)TOPLOC_MAX_K && kCapSmall >= 4 * 128, "soft limit CAP/2 must leave room above k");
+
+// Where a workgroup of a split launch finds its piece.  Fixed chunks need no table:
+// chunk = block / parts, part = block % parts.  Segments come with two tables.
+struct PartDesc {          // one per workgroup of part_kernel
+    uint64_t seg_vec;      // first vector of the segment, from the tensor base
+    uint32_t v0, v1;       // vectors [v0, v1) of the segment
+};
+struct SegDesc {           // one per workgroup of a merge kernel
+    uint32_t first_part;   // candidate slots first_part .. first_part + n_parts - 1
+    uint32_t n_parts;
+};
+struct Layout {
+    const PartDesc* part_table;  // NULL: fixed chunks
+    const SegDesc* seg_table;    // NULL: fixed chunks
+    uint32_t nvec;               // fixed chunks: vectors per chunk
+    uint32_t parts;              // fixed chunks: parts per chunk
+    uint32_t part_vecs;          // fixed chunks: vectors per part
+};
 
 // ---------------------------------------------------------------------------
 // topk(h, k) alone: writes the ordered (index, value) pairs of every chunk
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void select_kernel(const u32x4* __restrict__ hidden, uint32_t nvec, uint32_t k,
-                                                          uint32_t* __restrict__ out_idx, uint16_t* __restrict__ out_val,
-                                                          uint32_t* __restrict__ out_idx2)
+template <int CAP>
+__global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void select_kernel(const u32x4* __restrict__ hidden, uint32_t nvec,
+                                                                            uint32_t k, uint32_t* __restrict__ out_idx,
+                                                                            uint16_t* __restrict__ out_val)
 {
-    __shared__ SelShared s;
+    __shared__ SelectShared<kThreads, CAP, kQcap> s;
     const uint64_t chunk = blockIdx.x;
-    select_topk<kThreads, kLoads, kCap, kQcap>(hidden + chunk * nvec, nvec, k, s);
-    order_topk<kThreads, kCap, kQcap>(s, k);
+    select_topk<kThreads, kLoads, CAP, kQcap>(hidden + chunk * nvec, 0u, nvec, k, s);
+    order_topk<kThreads, CAP, kQcap>(s, k);
     for (uint32_t t = threadIdx.x; t < k; t += kThreads) {
-        const uint32_t i = s.cand_idx[t];
-        out_idx[chunk * k + t] = i;
+        out_idx[chunk * k + t] = s.cand_idx[t];
         out_val[chunk * k + t] = s.cand_bits[t];
-        if (out_idx2) out_idx2[chunk * k + t] = i;
     }
 }
 
 // ---------------------------------------------------------------------------
-// Algorithm 1 after the selection (interp.hpp), as its own kernel for k > 128
-// ---------------------------------------------------------------------------
-template <int KMAX>
-__global__ __launch_bounds__(kThreads) void interp_kernel(const uint32_t* __restrict__ topk_idx,
-                                                          const uint16_t* __restrict__ topk_val, uint32_t k,
-                                                          uint8_t* __restrict__ proofs, uint8_t* __restrict__ status)
-{
-    __shared__ InterpShared<KMAX> s;
-    __shared__ uint32_t coef[KMAX];
-    const uint32_t tid = threadIdx.x;
-    const uint64_t chunk = blockIdx.x;
-    for (uint32_t j = tid; j < k; j += kThreads) {
-        s.idx[j] = topk_idx[chunk * k + j];
-        const uint32_t y = topk_val[chunk * k + j];
-        s.ys[j] = (uint16_t)(y >= kPrime ? y - kPrime : y);
-    }
-    finish_proof<kThreads, KMAX>(s, coef, k, reinterpret_cast<uint16_t*>(proofs + chunk * (2 + 2 * (uint64_t)k)),
-                                     status + chunk);
-}
-
 // Algorithm 1 in one launch, k <= KMAX <= kThreads: the selection streams the chunk,
 // then the same workgroup turns its k pairs into the proof out of LDS (the selection's
 // buffers are dead by then and are reused).
-template <int KMAX>
+// ---------------------------------------------------------------------------
+template <int KMAX, int CAP>
 __global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void build_kernel(const u32x4* __restrict__ hidden, uint32_t nvec,
                                                                            uint32_t k, uint8_t* __restrict__ proofs,
                                                                            uint8_t* __restrict__ status,
@@ -96,20 +94,17 @@ __global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void build_kernel(const
 {
     static_assert(KMAX <= kThreads, "one pair per lane is carried across the phase change");
     __shared__ union BuildShared {
-        SelShared sel;
+        SelectShared<kThreads, CAP, kQcap> sel;
         InterpShared<KMAX> itp;
     } sh;
     __shared__ uint32_t coef[KMAX];
     const uint32_t tid = threadIdx.x;
     const uint64_t chunk = blockIdx.x;
-    select_topk<kThreads, kLoads, kCap, kQcap>(hidden + chunk * nvec, nvec, k, sh.sel);
+    select_topk<kThreads, kLoads, CAP, kQcap>(hidden + chunk * nvec, 0u, nvec, k, sh.sel);
     if (out_idx) {  // uniform: the caller wants the ordered indices
-        order_topk<kThreads, kCap, kQcap>(sh.sel, k);
+        order_topk<kThreads, CAP, kQcap>(sh.sel, k);
         if (tid < k) out_idx[chunk * k + tid] = sh.sel.cand_idx[tid];
     }
-#ifdef TOPLOC_TAIL_PRIO
-    __builtin_amdgcn_s_setprio(TOPLOC_TAIL_PRIO);  // the arithmetic tail goes ahead of streaming waves
-#endif
     uint32_t my_idx = 0, my_y = 0;
     if (tid < k) { my_idx = sh.sel.cand_idx[tid]; my_y = sh.sel.cand_bits[tid]; }
     __syncthreads();  // the selection's LDS is dead from here on
@@ -117,101 +112,134 @@ __global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void build_kernel(const
         sh.itp.idx[tid] = my_idx;
         sh.itp.ys[tid] = (uint16_t)(my_y >= kPrime ? my_y - kPrime : my_y);
     }
-    finish_proof<kThreads, KMAX>(sh.itp, coef, k,
-                                     reinterpret_cast<uint16_t*>(proofs + chunk * (2 + 2 * (uint64_t)k)), status + chunk);
+    finish_proof<kThreads, KMAX>(sh.itp, coef, k, reinterpret_cast<uint16_t*>(proofs + chunk * (2 + 2 * (uint64_t)k)),
+                                 status + chunk);
 }
 
 // ---------------------------------------------------------------------------
 // Algorithm 2, fused: one pass over the recomputed chunk
 // ---------------------------------------------------------------------------
-template <int KMAX>
-__global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void verify_kernel(const u32x4* __restrict__ hidden, uint32_t nvec, uint32_t k,
-                                                          const uint8_t* __restrict__ proofs, toploc_thresholds thr,
-                                                          toploc_verify_result* __restrict__ results)
+template <int KMAX, int CAP>
+__global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void verify_kernel(const u32x4* __restrict__ hidden, uint32_t nvec,
+                                                                            uint32_t k, const uint8_t* __restrict__ proofs,
+                                                                            toploc_thresholds thr,
+                                                                            toploc_verify_result* __restrict__ results)
 {
-    __shared__ SelShared s;
-    __shared__ uint32_t coef[KMAX];
-    __shared__ uint32_t hist_d[128];   // err_m as a histogram of |m_p - m_v| in [0, 127]
-    __shared__ uint32_t err_e, mant_sum, bad;
-    const uint32_t tid = threadIdx.x;
+    __shared__ SelectShared<kThreads, CAP, kQcap> s;
+    __shared__ VerifyShared<KMAX> vs;
     const uint64_t chunk = blockIdx.x;
-    // decode(p)
     const uint16_t* proof = reinterpret_cast<const uint16_t*>(proofs + chunk * (2 + 2 * (uint64_t)k));
-    if (tid == 0) { err_e = 0; mant_sum = 0; bad = 0; }
-    for (uint32_t b = tid; b < 128; b += kThreads) hist_d[b] = 0;
+    if (!verify_decode<kThreads, KMAX>(vs, proof, k, results + chunk)) return;
+    select_topk<kThreads, kLoads, CAP, kQcap>(hidden + chunk * nvec, 0u, nvec, k, s);  // order is irrelevant here
+    verify_tail<kThreads, KMAX>(vs, s.cand_idx, s.cand_bits, k, thr, results + chunk);
+}
+
+// ---------------------------------------------------------------------------
+// Split path, first launch: top-k of one part.  Writes k candidate slots per part,
+// the unused ones (part shorter than k values) padded with index 0xFFFFFFFF.
+// ---------------------------------------------------------------------------
+template <int CAP>
+__global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void part_kernel(const u32x4* __restrict__ hidden, Layout lay,
+                                                                          uint32_t k, uint32_t* __restrict__ c_idx,
+                                                                          uint16_t* __restrict__ c_bits)
+{
+    __shared__ SelectShared<kThreads, CAP, kQcap> s;
+    const uint32_t tid = threadIdx.x;
+    const uint64_t slot = blockIdx.x;
+    const u32x4* src;
+    uint32_t v0, v1;
+    if (lay.part_table) {
+        const PartDesc d = lay.part_table[slot];
+        src = hidden + d.seg_vec;
+        v0 = d.v0;
+        v1 = d.v1;
+    } else {
+        const uint64_t chunk = slot / lay.parts;
+        const uint32_t part = (uint32_t)(slot - chunk * lay.parts);
+        src = hidden + chunk * lay.nvec;
+        v0 = part * lay.part_vecs;
+        v1 = v0 + lay.part_vecs < lay.nvec ? v0 + lay.part_vecs : lay.nvec;
+        if (v0 > v1) v0 = v1;
+    }
+    const uint32_t have = (v1 - v0) * 8u;
+    const uint32_t k_eff = have < k ? have : k;
+    if (k_eff) select_topk<kThreads, kLoads, CAP, kQcap>(src, v0, v1, k_eff, s);
+    for (uint32_t t = tid; t < k; t += kThreads) {
+        c_idx[slot * k + t] = t < k_eff ? s.cand_idx[t] : 0xFFFFFFFFu;
+        c_bits[slot * k + t] = t < k_eff ? s.cand_bits[t] : (uint16_t)0;
+    }
+}
+
+// candidate slots of the chunk / segment a merge workgroup owns
+__device__ __forceinline__ void merge_range(const Layout& lay, uint64_t unit, uint64_t& first, uint32_t& n_parts)
+{
+    if (lay.seg_table) {
+        const SegDesc d = lay.seg_table[unit];
+        first = d.first_part;
+        n_parts = d.n_parts;
+    } else {
+        first = unit * lay.parts;
+        n_parts = lay.parts;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Split path, second launch of a build: top-k of the candidates, then the rest of
+// Algorithm 1 (interp.hpp).
+// ---------------------------------------------------------------------------
+template <int THREADS, int KMAX, int CAP>
+__global__ __launch_bounds__(THREADS) void build_merge_kernel(Layout lay, uint32_t k, const uint32_t* __restrict__ c_idx,
+                                                              const uint16_t* __restrict__ c_bits,
+                                                              uint8_t* __restrict__ proofs, uint8_t* __restrict__ status,
+                                                              uint32_t* __restrict__ out_idx)
+{
+    static_assert(KMAX <= THREADS, "one pair per lane is carried across the phase change");
+    __shared__ union MergeShared {
+        SelectShared<THREADS, CAP, 1> sel;
+        InterpShared<KMAX> itp;
+    } sh;
+    __shared__ uint32_t coef[KMAX];
+    const uint32_t tid = threadIdx.x;
+    const uint64_t unit = blockIdx.x;
+    uint64_t first;
+    uint32_t n_parts;
+    merge_range(lay, unit, first, n_parts);
+    merge_topk<THREADS, CAP, 1>(c_idx + first * k, c_bits + first * k, n_parts * k, k, sh.sel);
+    if (out_idx) {
+        order_topk<THREADS, CAP, 1>(sh.sel, k);
+        if (tid < k) out_idx[unit * k + tid] = sh.sel.cand_idx[tid];
+    }
+    uint32_t my_idx = 0, my_y = 0;
+    if (tid < k) { my_idx = sh.sel.cand_idx[tid]; my_y = sh.sel.cand_bits[tid]; }
     __syncthreads();
-    const uint32_t mf = proof[0];
-    const uint32_t m = mf ? mf : kModHigh;
-    for (uint32_t j = tid; j < k; j += kThreads) {
-        const uint32_t c = proof[1 + j];
-        coef[j] = c;
-        if (c >= kPrime) bad = 1u;
+    if (tid < k) {
+        sh.itp.idx[tid] = my_idx;
+        sh.itp.ys[tid] = (uint16_t)(my_y >= kPrime ? my_y - kPrime : my_y);
     }
-    if (tid == 0 && m < kModLow) bad = 1u;
-    __syncthreads();
-    if (bad) {  // uniform
-        if (tid == 0) {
-            toploc_verify_result r = {};
-            r.status = TOPLOC_CHUNK_MALFORMED;
-            results[chunk] = r;
-        }
-        return;
-    }
-    // topk(h, k)
-    select_topk<kThreads, kLoads, kCap, kQcap>(hidden + chunk * nvec, nvec, k, s);  // order is irrelevant here
-    // P(i mod m) by Horner, extractBits, compare
-    for (uint32_t j = tid; j < k; j += kThreads) {
-        uint32_t x = s.cand_idx[j] % m;
-        x = x >= kPrime ? x - kPrime : x;
-        uint32_t acc = coef[k - 1];
-        for (int i = (int)k - 2; i >= 0; --i) acc = muladdmod(acc, x, coef[i]);
-        const uint32_t v = s.cand_bits[j];
-        const uint32_t e_p = (acc >> 7) & 0xFFu, m_p = acc & 0x7Fu;
-        const uint32_t e_v = (v >> 7) & 0xFFu, m_v = v & 0x7Fu;
-        if (e_p == e_v) {
-            const uint32_t d = m_p > m_v ? m_p - m_v : m_v - m_p;
-            atomicAdd(&hist_d[d], 1u);
-            atomicAdd(&mant_sum, d);
-        } else {
-            atomicAdd(&err_e, 1u);
-        }
-    }
-    __syncthreads();
-    if (tid < 64) {
-        // |err_m| and its lower median from the histogram: the smallest d whose
-        // cumulative count reaches floor((n-1)/2) + 1
-        const uint32_t h0 = hist_d[2 * tid], h1 = hist_d[2 * tid + 1];
-        uint32_t v = h0 + h1;  // inclusive prefix sum over lanes
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const uint32_t o = __shfl_up(v, d);
-            if ((int)tid >= d) v += o;
-        }
-        const uint32_t n = __shfl(v, 63);
-        const uint32_t target = n ? (n - 1) / 2 + 1 : 0;
-        const uint32_t before = v - h0 - h1;
-        uint32_t med = 0xFFFFFFFFu;
-        if (n && before < target && before + h0 >= target) med = 2 * tid;
-        else if (n && before + h0 < target && v >= target) med = 2 * tid + 1;
-        const uint64_t mask = __ballot(med != 0xFFFFFFFFu);
-        const int srcl = mask ? (__ffsll((long long)mask) - 1) : 0;
-        med = __shfl(med, srcl);
-        if (tid == 0) {
-            toploc_verify_result r = {};
-            r.err_exp = err_e;
-            r.n_match = n;
-            r.mant_sum = mant_sum;
-            r.mant_median = n ? med : 0u;
-            bool reject = err_e > thr.t_exp;
-            if (n) {
-                if ((uint64_t)mant_sum > (uint64_t)thr.t_mean * n) reject = true;   // mean(err_m) > T_mean
-                if (r.mant_median > thr.t_median) reject = true;
-            }
-            r.accept = reject ? 0 : 1;
-            r.status = TOPLOC_CHUNK_OK;
-            results[chunk] = r;
-        }
-    }
+    finish_proof<THREADS, KMAX>(sh.itp, coef, k, reinterpret_cast<uint16_t*>(proofs + unit * (2 + 2 * (uint64_t)k)),
+                                status + unit);
+}
+
+// ---------------------------------------------------------------------------
+// Split path, second launch of a verify: top-k of the candidates, then the rest of
+// Algorithm 2 (verify.hpp).
+// ---------------------------------------------------------------------------
+template <int THREADS, int KMAX, int CAP>
+__global__ __launch_bounds__(THREADS) void verify_merge_kernel(Layout lay, uint32_t k, const uint32_t* __restrict__ c_idx,
+                                                               const uint16_t* __restrict__ c_bits,
+                                                               const uint8_t* __restrict__ proofs, toploc_thresholds thr,
+                                                               toploc_verify_result* __restrict__ results)
+{
+    __shared__ SelectShared<THREADS, CAP, 1> s;
+    __shared__ VerifyShared<KMAX> vs;
+    const uint64_t unit = blockIdx.x;
+    const uint16_t* proof = reinterpret_cast<const uint16_t*>(proofs + unit * (2 + 2 * (uint64_t)k));
+    if (!verify_decode<THREADS, KMAX>(vs, proof, k, results + unit)) return;
+    uint64_t first;
+    uint32_t n_parts;
+    merge_range(lay, unit, first, n_parts);
+    merge_topk<THREADS, CAP, 1>(c_idx + first * k, c_bits + first * k, n_parts * k, k, s);
+    verify_tail<THREADS, KMAX>(vs, s.cand_idx, s.cand_bits, k, thr, results + unit);
 }
 
 // ---------------------------------------------------------------------------
@@ -257,6 +285,7 @@ __global__ __launch_bounds__(kThreads) void read_kernel(const u32x4* __restrict_
 // ---------------------------------------------------------------------------
 static int g_last_hip_error = 0;
 static int g_profile_on = 0;
+static uint32_t g_force_parts = 0;  // toploc_set_split: 0 = choose, n = cut every chunk into n parts
 struct ProfRec { int slot; hipEvent_t a, b; };
 static std::vector<ProfRec> g_prof;
 
@@ -281,6 +310,7 @@ struct ProfScope {
 };
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+static size_t up16(size_t b) { return (b + 15) & ~(size_t)15; }
 
 // N (values per chunk) when the parameters are usable, else 0
 static uint64_t chunk_len(const toploc_params* p)
@@ -292,10 +322,138 @@ static uint64_t chunk_len(const toploc_params* p)
     return n;
 }
 
-static size_t idx_bytes(uint64_t n_chunks, uint32_t k)
+// A launch wants a few workgroups per resident slot of the 256 compute units; a part
+// should still stream a few rounds.
+constexpr uint64_t kTargetGroups = 3072;
+constexpr uint64_t kMinPartVecs = 4 * kRoundVecs;
+
+// vectors per part for `total_vecs` vectors of input whose longest unit has `max_unit_vecs`
+static uint64_t pick_part_vecs(uint64_t total_vecs, uint64_t max_unit_vecs)
 {
-    const size_t b = (size_t)n_chunks * k * sizeof(uint32_t);
-    return (b + 15) & ~(size_t)15;
+    if (g_force_parts) {
+        const uint64_t pv = (max_unit_vecs + g_force_parts - 1) / g_force_parts;
+        return pv ? pv : 1;
+    }
+    uint64_t pv = (total_vecs + kTargetGroups - 1) / kTargetGroups;
+    pv = (pv + kRoundVecs - 1) / kRoundVecs * kRoundVecs;
+    return pv < kMinPartVecs ? kMinPartVecs : pv;
+}
+
+struct FixedPlan { uint32_t parts; uint32_t part_vecs; };
+static FixedPlan plan_fixed(uint64_t n_chunks, uint64_t nvec)
+{
+    const uint64_t pv = pick_part_vecs(n_chunks * nvec, nvec);
+    FixedPlan f;
+    f.parts = (uint32_t)((nvec + pv - 1) / pv);
+    f.part_vecs = (uint32_t)(pv < nvec ? pv : nvec);
+    return f;
+}
+
+// candidate arrays for `slots` parts: [slots*k] uint32 then [slots*k] uint16, each 16-byte aligned
+static size_t cand_bytes(uint64_t slots, uint32_t k)
+{
+    return up16((size_t)slots * k * sizeof(uint32_t)) + up16((size_t)slots * k * sizeof(uint16_t));
+}
+
+static void launch_part(hipStream_t st, const void* d_hidden, const Layout& lay, uint64_t slots, uint32_t k, uint32_t* c_idx,
+                        uint16_t* c_bits)
+{
+    ProfScope ps(TOPLOC_KERNEL_PART, st);
+    if (k <= 128)
+        hipLaunchKernelGGL((part_kernel<kCapSmall>), dim3((uint32_t)slots), dim3(kThreads), 0, st, (const u32x4*)d_hidden, lay,
+                           k, c_idx, c_bits);
+    else
+        hipLaunchKernelGGL((part_kernel<kCapLarge>), dim3((uint32_t)slots), dim3(kThreads), 0, st, (const u32x4*)d_hidden, lay,
+                           k, c_idx, c_bits);
+}
+
+static void launch_build_merge(hipStream_t st, const Layout& lay, uint64_t units, uint32_t k, const uint32_t* c_idx,
+                               const uint16_t* c_bits, uint8_t* d_proofs, uint8_t* d_status, uint32_t* d_topk_idx_opt)
+{
+    ProfScope ps(TOPLOC_KERNEL_BUILD_MERGE, st);
+    if (k <= 128)
+        hipLaunchKernelGGL((build_merge_kernel<256, 128, kCapSmall>), dim3((uint32_t)units), dim3(256), 0, st, lay, k, c_idx,
+                           c_bits, d_proofs, d_status, d_topk_idx_opt);
+    else
+        hipLaunchKernelGGL((build_merge_kernel<1024, 512, kCapLarge>), dim3((uint32_t)units), dim3(1024), 0, st, lay, k, c_idx,
+                           c_bits, d_proofs, d_status, d_topk_idx_opt);
+}
+
+static void launch_verify_merge(hipStream_t st, const Layout& lay, uint64_t units, uint32_t k, const uint32_t* c_idx,
+                                const uint16_t* c_bits, const uint8_t* d_proofs, const toploc_thresholds& thr,
+                                toploc_verify_result* d_results)
+{
+    ProfScope ps(TOPLOC_KERNEL_VERIFY_MERGE, st);
+    if (k <= 128)
+        hipLaunchKernelGGL((verify_merge_kernel<256, 128, kCapSmall>), dim3((uint32_t)units), dim3(256), 0, st, lay, k, c_idx,
+                           c_bits, d_proofs, thr, d_results);
+    else
+        hipLaunchKernelGGL((verify_merge_kernel<512, 512, kCapLarge>), dim3((uint32_t)units), dim3(512), 0, st, lay, k, c_idx,
+                           c_bits, d_proofs, thr, d_results);
+}
+
+// Segments: tables of parts and of segments, laid out behind the candidate arrays.
+struct SegPlan {
+    std::vector<PartDesc> parts;
+    std::vector<SegDesc> segs;
+    bool ok = false;
+};
+static SegPlan plan_segments(const uint64_t* h_row_offsets, uint64_t n_segments, uint32_t hidden, uint32_t k)
+{
+    SegPlan pl;
+    if (!h_row_offsets || hidden == 0 || hidden % 8 != 0 || k == 0 || k > TOPLOC_MAX_K || n_segments >= (1ull << 31)) return pl;
+    const uint64_t hv = hidden / 8;
+    uint64_t max_vecs = 0;
+    for (uint64_t i = 0; i < n_segments; ++i) {
+        if (h_row_offsets[i + 1] < h_row_offsets[i]) return pl;
+        const uint64_t rows = h_row_offsets[i + 1] - h_row_offsets[i];
+        if (rows * hidden < k || rows * hidden >= (1ull << 32)) return pl;
+        if (rows * hv > max_vecs) max_vecs = rows * hv;
+    }
+    const uint64_t total_vecs = n_segments ? (h_row_offsets[n_segments] - h_row_offsets[0]) * hv : 0;
+    const uint64_t pv = pick_part_vecs(total_vecs, max_vecs);
+    pl.segs.reserve(n_segments);
+    for (uint64_t i = 0; i < n_segments; ++i) {
+        const uint64_t nvec = (h_row_offsets[i + 1] - h_row_offsets[i]) * hv;
+        SegDesc sd;
+        sd.first_part = (uint32_t)pl.parts.size();
+        sd.n_parts = (uint32_t)((nvec + pv - 1) / pv);
+        for (uint64_t v0 = 0; v0 < nvec; v0 += pv) {
+            PartDesc pd;
+            pd.seg_vec = h_row_offsets[i] * hv;
+            pd.v0 = (uint32_t)v0;
+            pd.v1 = (uint32_t)(v0 + pv < nvec ? v0 + pv : nvec);
+            pl.parts.push_back(pd);
+        }
+        pl.segs.push_back(sd);
+        if (pl.parts.size() >= (1ull << 31)) return pl;
+    }
+    pl.ok = true;
+    return pl;
+}
+
+static size_t seg_workspace_bytes(const SegPlan& pl, uint32_t k)
+{
+    return cand_bytes(pl.parts.size(), k) + up16(pl.parts.size() * sizeof(PartDesc)) + up16(pl.segs.size() * sizeof(SegDesc));
+}
+
+// copies the tables behind the candidate arrays and fills the layout
+static bool stage_segments(const SegPlan& pl, uint32_t k, void* d_workspace, hipStream_t st, Layout& lay, uint32_t*& c_idx,
+                           uint16_t*& c_bits)
+{
+    char* w = (char*)d_workspace;
+    c_idx = (uint32_t*)w;
+    c_bits = (uint16_t*)(w + up16(pl.parts.size() * (size_t)k * sizeof(uint32_t)));
+    char* t_parts = w + cand_bytes(pl.parts.size(), k);
+    char* t_segs = t_parts + up16(pl.parts.size() * sizeof(PartDesc));
+    if (!hip_ok(hipMemcpyAsync(t_parts, pl.parts.data(), pl.parts.size() * sizeof(PartDesc), hipMemcpyHostToDevice, st)))
+        return false;
+    if (!hip_ok(hipMemcpyAsync(t_segs, pl.segs.data(), pl.segs.size() * sizeof(SegDesc), hipMemcpyHostToDevice, st)))
+        return false;
+    lay.part_table = (const PartDesc*)t_parts;
+    lay.seg_table = (const SegDesc*)t_segs;
+    lay.nvec = 0; lay.parts = 0; lay.part_vecs = 0;
+    return true;
 }
 
 }  // namespace toploc
@@ -308,10 +466,18 @@ size_t toploc_proof_bytes(uint32_t k) { return 2 + 2 * (size_t)k; }
 
 size_t toploc_workspace_bytes(const toploc_params* params, uint64_t n_chunks)
 {
-    if (chunk_len(params) == 0) return 0;
-    if (params->k <= 128) return 0;  // one fused kernel, everything stays on chip
-    const size_t vb = ((size_t)n_chunks * params->k * sizeof(uint16_t) + 15) & ~(size_t)15;
-    return idx_bytes(n_chunks, params->k) + vb;
+    const uint64_t n = chunk_len(params);
+    if (n == 0 || n_chunks == 0) return 0;
+    const FixedPlan f = plan_fixed(n_chunks, n / 8);
+    if (f.parts == 1 && params->k <= 128) return 0;  // one fused kernel, everything stays on chip
+    return cand_bytes(n_chunks * f.parts, params->k);
+}
+
+int toploc_set_split(uint32_t parts_per_chunk)
+{
+    if (parts_per_chunk > 4096) return TOPLOC_EINVAL;
+    g_force_parts = parts_per_chunk;
+    return TOPLOC_OK;
 }
 
 int toploc_topk(const void* d_hidden_bf16, uint64_t n_chunks, const toploc_params* params, uint32_t* d_topk_idx,
@@ -324,9 +490,12 @@ int toploc_topk(const void* d_hidden_bf16, uint64_t n_chunks, const toploc_param
     hipStream_t st = (hipStream_t)hip_stream;
     {
         ProfScope ps(TOPLOC_KERNEL_SELECT, st);
-        hipLaunchKernelGGL(select_kernel, dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
-                           (const u32x4*)d_hidden_bf16, (uint32_t)(n / 8), params->k, d_topk_idx, d_topk_val,
-                           (uint32_t*)nullptr);
+        if (params->k <= 128)
+            hipLaunchKernelGGL((select_kernel<kCapSmall>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
+                               (const u32x4*)d_hidden_bf16, (uint32_t)(n / 8), params->k, d_topk_idx, d_topk_val);
+        else
+            hipLaunchKernelGGL((select_kernel<kCapLarge>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
+                               (const u32x4*)d_hidden_bf16, (uint32_t)(n / 8), params->k, d_topk_idx, d_topk_val);
     }
     return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
 }
@@ -340,30 +509,27 @@ int toploc_build_proofs(const void* d_hidden_bf16, uint64_t n_chunks, const topl
     if (n_chunks == 0) return TOPLOC_OK;
     if (!d_hidden_bf16 || !d_proofs || !d_status || !aligned16(d_hidden_bf16)) return TOPLOC_EINVAL;
     if ((reinterpret_cast<uintptr_t>(d_proofs) & 1u) != 0) return TOPLOC_EINVAL;
-    const size_t need = toploc_workspace_bytes(params, n_chunks);
-    if (need && (!d_workspace || !aligned16(d_workspace))) return TOPLOC_EINVAL;
-    if (workspace_bytes < need) return TOPLOC_EWORKSPACE;
+    if (d_workspace && !aligned16(d_workspace)) return TOPLOC_EINVAL;
     const uint32_t k = params->k;
+    const uint32_t nvec = (uint32_t)(n / 8);
     hipStream_t st = (hipStream_t)hip_stream;
-    if (k <= 128) {
+    FixedPlan f = plan_fixed(n_chunks, nvec);
+    const bool have_ws = d_workspace && workspace_bytes >= cand_bytes(n_chunks * f.parts, k);
+    if (k <= 128 && (f.parts == 1 || !have_ws)) {  // one launch; also the answer to a missing workspace
         ProfScope ps(TOPLOC_KERNEL_BUILD, st);
-        hipLaunchKernelGGL((build_kernel<128>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
-                           (const u32x4*)d_hidden_bf16, (uint32_t)(n / 8), k, d_proofs, d_status, d_topk_idx_opt);
+        hipLaunchKernelGGL((build_kernel<128, kCapSmall>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
+                           (const u32x4*)d_hidden_bf16, nvec, k, d_proofs, d_status, d_topk_idx_opt);
         return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
     }
-    uint32_t* ws_idx = (uint32_t*)d_workspace;
-    uint16_t* ws_val = (uint16_t*)((char*)d_workspace + idx_bytes(n_chunks, k));
-    {
-        ProfScope ps(TOPLOC_KERNEL_SELECT, st);
-        hipLaunchKernelGGL(select_kernel, dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
-                           (const u32x4*)d_hidden_bf16, (uint32_t)(n / 8), k, ws_idx, ws_val, d_topk_idx_opt);
-    }
+    if (!have_ws) return d_workspace ? TOPLOC_EWORKSPACE : TOPLOC_EINVAL;
+    const uint64_t slots = n_chunks * f.parts;
+    if (slots >= (1ull << 31)) return TOPLOC_EINVAL;
+    Layout lay = {nullptr, nullptr, nvec, f.parts, f.part_vecs};
+    uint32_t* c_idx = (uint32_t*)d_workspace;
+    uint16_t* c_bits = (uint16_t*)((char*)d_workspace + up16((size_t)slots * k * sizeof(uint32_t)));
+    launch_part(st, d_hidden_bf16, lay, slots, k, c_idx, c_bits);
     if (!hip_ok(hipGetLastError())) return TOPLOC_EHIP;
-    {
-        ProfScope ps(TOPLOC_KERNEL_INTERP, st);
-        hipLaunchKernelGGL((interp_kernel<512>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
-                           (const uint32_t*)ws_idx, (const uint16_t*)ws_val, k, d_proofs, d_status);
-    }
+    launch_build_merge(st, lay, n_chunks, k, c_idx, c_bits, d_proofs, d_status, d_topk_idx_opt);
     return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
 }
 
@@ -371,24 +537,88 @@ int toploc_verify_proofs(const void* d_hidden_bf16, uint64_t n_chunks, const top
                          const uint8_t* d_proofs, const toploc_thresholds* thresholds, toploc_verify_result* d_results,
                          void* d_workspace, size_t workspace_bytes, void* hip_stream)
 {
-    (void)d_workspace; (void)workspace_bytes;  // the fused kernel keeps everything on chip
     const uint64_t n = chunk_len(params);
     if (n == 0 || n_chunks >= (1ull << 31) || !thresholds) return TOPLOC_EINVAL;
     if (n_chunks == 0) return TOPLOC_OK;
     if (!d_hidden_bf16 || !d_proofs || !d_results || !aligned16(d_hidden_bf16)) return TOPLOC_EINVAL;
     if ((reinterpret_cast<uintptr_t>(d_proofs) & 1u) != 0 || (reinterpret_cast<uintptr_t>(d_results) & 3u) != 0)
         return TOPLOC_EINVAL;
+    if (d_workspace && !aligned16(d_workspace)) return TOPLOC_EINVAL;
     const uint32_t k = params->k;
+    const uint32_t nvec = (uint32_t)(n / 8);
     hipStream_t st = (hipStream_t)hip_stream;
-    {
+    FixedPlan f = plan_fixed(n_chunks, nvec);
+    const uint64_t slots = n_chunks * f.parts;
+    const bool split = f.parts > 1 && d_workspace && workspace_bytes >= cand_bytes(slots, k) && slots < (1ull << 31);
+    if (!split) {  // one launch; a missing workspace only costs speed on small batches
         ProfScope ps(TOPLOC_KERNEL_VERIFY, st);
         if (k <= 128)
-            hipLaunchKernelGGL((verify_kernel<128>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
-                               (const u32x4*)d_hidden_bf16, (uint32_t)(n / 8), k, d_proofs, *thresholds, d_results);
+            hipLaunchKernelGGL((verify_kernel<128, kCapSmall>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
+                               (const u32x4*)d_hidden_bf16, nvec, k, d_proofs, *thresholds, d_results);
         else
-            hipLaunchKernelGGL((verify_kernel<512>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
-                               (const u32x4*)d_hidden_bf16, (uint32_t)(n / 8), k, d_proofs, *thresholds, d_results);
+            hipLaunchKernelGGL((verify_kernel<512, kCapLarge>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
+                               (const u32x4*)d_hidden_bf16, nvec, k, d_proofs, *thresholds, d_results);
+        return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
     }
+    Layout lay = {nullptr, nullptr, nvec, f.parts, f.part_vecs};
+    uint32_t* c_idx = (uint32_t*)d_workspace;
+    uint16_t* c_bits = (uint16_t*)((char*)d_workspace + up16((size_t)slots * k * sizeof(uint32_t)));
+    launch_part(st, d_hidden_bf16, lay, slots, k, c_idx, c_bits);
+    if (!hip_ok(hipGetLastError())) return TOPLOC_EHIP;
+    launch_verify_merge(st, lay, n_chunks, k, c_idx, c_bits, d_proofs, *thresholds, d_results);
+    return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
+}
+
+size_t toploc_segments_workspace_bytes(const uint64_t* h_row_offsets, uint64_t n_segments, uint32_t hidden, uint32_t k)
+{
+    const SegPlan pl = plan_segments(h_row_offsets, n_segments, hidden, k);
+    if (!pl.ok || n_segments == 0) return 0;
+    return seg_workspace_bytes(pl, k);
+}
+
+int toploc_build_proofs_segments(const void* d_hidden_bf16, const uint64_t* h_row_offsets, uint64_t n_segments,
+                                 uint32_t hidden, uint32_t k, uint8_t* d_proofs, uint8_t* d_status,
+                                 uint32_t* d_topk_idx_opt, void* d_workspace, size_t workspace_bytes, void* hip_stream)
+{
+    const SegPlan pl = plan_segments(h_row_offsets, n_segments, hidden, k);
+    if (!pl.ok) return TOPLOC_EINVAL;
+    if (n_segments == 0) return TOPLOC_OK;
+    if (!d_hidden_bf16 || !d_proofs || !d_status || !d_workspace || !aligned16(d_hidden_bf16) || !aligned16(d_workspace))
+        return TOPLOC_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(d_proofs) & 1u) != 0) return TOPLOC_EINVAL;
+    if (workspace_bytes < seg_workspace_bytes(pl, k)) return TOPLOC_EWORKSPACE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    Layout lay;
+    uint32_t* c_idx;
+    uint16_t* c_bits;
+    if (!stage_segments(pl, k, d_workspace, st, lay, c_idx, c_bits)) return TOPLOC_EHIP;
+    launch_part(st, d_hidden_bf16, lay, pl.parts.size(), k, c_idx, c_bits);
+    if (!hip_ok(hipGetLastError())) return TOPLOC_EHIP;
+    launch_build_merge(st, lay, n_segments, k, c_idx, c_bits, d_proofs, d_status, d_topk_idx_opt);
+    return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
+}
+
+int toploc_verify_proofs_segments(const void* d_hidden_bf16, const uint64_t* h_row_offsets, uint64_t n_segments,
+                                  uint32_t hidden, uint32_t k, const uint8_t* d_proofs,
+                                  const toploc_thresholds* thresholds, toploc_verify_result* d_results, void* d_workspace,
+                                  size_t workspace_bytes, void* hip_stream)
+{
+    const SegPlan pl = plan_segments(h_row_offsets, n_segments, hidden, k);
+    if (!pl.ok || !thresholds) return TOPLOC_EINVAL;
+    if (n_segments == 0) return TOPLOC_OK;
+    if (!d_hidden_bf16 || !d_proofs || !d_results || !d_workspace || !aligned16(d_hidden_bf16) || !aligned16(d_workspace))
+        return TOPLOC_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(d_proofs) & 1u) != 0 || (reinterpret_cast<uintptr_t>(d_results) & 3u) != 0)
+        return TOPLOC_EINVAL;
+    if (workspace_bytes < seg_workspace_bytes(pl, k)) return TOPLOC_EWORKSPACE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    Layout lay;
+    uint32_t* c_idx;
+    uint16_t* c_bits;
+    if (!stage_segments(pl, k, d_workspace, st, lay, c_idx, c_bits)) return TOPLOC_EHIP;
+    launch_part(st, d_hidden_bf16, lay, pl.parts.size(), k, c_idx, c_bits);
+    if (!hip_ok(hipGetLastError())) return TOPLOC_EHIP;
+    launch_verify_merge(st, lay, n_segments, k, c_idx, c_bits, d_proofs, *thresholds, d_results);
     return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
 }
 
@@ -427,14 +657,6 @@ int toploc_bench_read(const void* d_hidden_bf16, uint64_t n_chunks, uint64_t chu
     return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
 }
 
-#ifdef TOPLOC_TIMING
-int toploc_debug_timing(uint64_t* out8, int reset)
-{
-    if (reset) { uint64_t z[8] = {0,0,0,0,0,0,0,0}; return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_tt), z, sizeof(z)); }
-    return (int)hipMemcpyFromSymbol(out8, HIP_SYMBOL(g_tt), 64);
-}
-#endif
-
 int toploc_profile_enable(int on)
 {
     g_profile_on = on ? 1 : 0;
@@ -466,8 +688,8 @@ const char* toploc_strerror(int code)
     switch (code) {
     case TOPLOC_OK: return "ok";
     case TOPLOC_EINVAL: return "invalid argument (null or misaligned pointer, k = 0, k > chunk length, k > TOPLOC_MAX_K, "
-                               "chunk length not a multiple of 8 or >= 2^32, prime != 65497)";
-    case TOPLOC_EWORKSPACE: return "workspace smaller than toploc_workspace_bytes()";
+                               "chunk length not a multiple of 8 or >= 2^32, prime != 65497, workspace missing where needed)";
+    case TOPLOC_EWORKSPACE: return "workspace smaller than the workspace_bytes function reports";
     case TOPLOC_EHIP: return "a HIP runtime call failed (see toploc_last_hip_error)";
     default: return "unknown toploc error code";
     }

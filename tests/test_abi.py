@@ -35,8 +35,9 @@ def test_proof_size_matches_paper(golden):
 
 
 def test_workspace_bytes_and_parameter_validation():
-    assert binding.toploc_workspace_bytes(128, 32, 4096, 10) == 0      # fused kernel: no scratch
-    assert binding.toploc_workspace_bytes(512, 32, 4096, 10) >= 10 * 512 * 6
+    assert binding.toploc_workspace_bytes(128, 32, 8192, 16384) == 0   # large batch: one fused kernel, no scratch
+    assert binding.toploc_workspace_bytes(128, 32, 4096, 10) >= 10 * 2 * 128 * 6   # small batch: chunks are cut
+    assert binding.toploc_workspace_bytes(512, 32, 8192, 16384) >= 16384 * 512 * 6  # k > 128 always hands pairs on
     assert binding.toploc_workspace_bytes(0, 32, 4096, 10) == 0        # k = 0
     assert binding.toploc_workspace_bytes(513, 32, 4096, 10) == 0      # k > TOPLOC_MAX_K
     assert binding.toploc_workspace_bytes(128, 32, 3, 10) == 0         # N = 96 < k
@@ -59,6 +60,17 @@ def test_calls_are_rejected_before_any_launch():
     big = binding.Params(512, 32, 4096, binding.PRIME)
     assert L.toploc_build_proofs(fake, 1, ctypes.byref(big), fake, fake, None, fake, 16, None) == binding.EWORKSPACE
     assert L.toploc_build_proofs(fake, 1, ctypes.byref(big), fake, fake, None, None, 1 << 20, None) == binding.EINVAL
+    off = (ctypes.c_uint64 * 3)(0, 5, 4)                                     # decreasing offsets
+    assert L.toploc_segments_workspace_bytes(off, 2, 4096, 128) == 0
+    assert L.toploc_build_proofs_segments(fake, off, 2, 4096, 128, fake, fake, None, fake, 1 << 30, None) == binding.EINVAL
+    off = (ctypes.c_uint64 * 3)(0, 5, 9)
+    assert L.toploc_segments_workspace_bytes(off, 2, 4096, 128) > 0
+    assert L.toploc_segments_workspace_bytes(off, 2, 4100, 128) == 0         # hidden % 8 != 0
+    assert L.toploc_build_proofs_segments(fake, off, 2, 4096, 128, fake, fake, None, fake, 16, None) == binding.EWORKSPACE
+    assert L.toploc_verify_proofs_segments(fake, off, 0, 4096, 128, fake, ctypes.byref(thr), fake, fake, 0, None) == binding.OK
+    off = (ctypes.c_uint64 * 2)(0, 0)                                        # a segment shorter than k
+    assert L.toploc_build_proofs_segments(fake, off, 1, 4096, 128, fake, fake, None, fake, 1 << 30, None) == binding.EINVAL
+    assert L.toploc_set_split(5000) == binding.EINVAL and L.toploc_set_split(0) == binding.OK
     assert L.toploc_build_proofs(fake, 0, ctypes.byref(ok), fake, fake, None, fake, 0, None) == binding.OK
     assert L.toploc_verify_proofs(fake, 1, ctypes.byref(ok), fake, None, fake, None, 0, None) == binding.EINVAL
     assert L.toploc_verify_proofs(fake, 0, ctypes.byref(ok), fake, ctypes.byref(thr), fake, None, 0, None) == binding.OK

@@ -1,0 +1,150 @@
+"""Split launches and variable-length segments vs the CPU oracle, through the C ABI.
+
+A chunk or a segment may be cut into parts whose candidates a second launch merges;
+whatever the cut, top-k indices, proof bytes, status and verify records must equal the
+oracle's, which sees every segment as one flat array (Algorithm 1 and 2 on the whole
+prompt, Section 5.5, or on a ragged last chunk).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle as orc
+from paper_2501_16007_amd import binding as tl
+from paper_2501_16007_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+FIELDS = ("err_exp", "n_match", "mant_sum", "mant_median", "accept", "status")
+
+
+def say(msg):
+    print("[case] " + msg, flush=True)
+
+
+@pytest.fixture(autouse=True)
+def library_chooses_the_split_again():
+    yield
+    tl.toploc_set_split(0)
+
+
+def _fixed_case(chunks, k, parts, what):
+    """Fixed chunks with the chunk cut into `parts` parts (0: the library's choice)."""
+    say("%s n_chunks=%d N=%d k=%d parts=%d" % (what, chunks.shape[0], chunks.shape[1], k, parts))
+    bits = synth.bits_numpy(chunks)
+    o_proofs, o_status, o_idx = orc.build(bits, k, want_topk=True)
+    o_res = orc.verify(bits, o_proofs, k)
+    tl.toploc_set_split(parts)
+    proofs, status, idx = tl.toploc_build_proofs(chunks, k=k, chunk_tokens=1, want_topk=True)
+    res = tl.toploc_verify_proofs(chunks, torch.from_numpy(o_proofs).to(DEV), k=k, chunk_tokens=1)
+    torch.cuda.synchronize()
+    assert np.array_equal(idx.cpu().numpy().view(np.uint32), o_idx), what + ": indices"
+    assert np.array_equal(status.cpu().numpy(), o_status), what + ": status"
+    assert np.array_equal(proofs.cpu().numpy(), o_proofs), what + ": proof bytes"
+    g = tl.results_numpy(res)
+    for f in FIELDS:
+        assert np.array_equal(g[f], o_res[f]), what + ": " + f
+
+
+@pytest.mark.parametrize("parts", [1, 2, 3, 7, 16])
+@pytest.mark.parametrize("k", [128, 512])
+def test_fixed_chunks_any_cut_gives_the_same_bytes(parts, k):
+    x = synth.activations(5, 32, 4096, 4100 + k, n_outlier=8, device=DEV).reshape(5, 32 * 4096)
+    _fixed_case(x, k, parts, "cut")
+
+
+def test_parts_shorter_than_k_are_padded():
+    # N = 2048 values in 16 parts of 128 values, k = 512: every part holds fewer than k
+    x = synth.activations(3, 32, 64, 4200, n_outlier=2, device=DEV).reshape(3, 2048)
+    _fixed_case(x, 512, 16, "short parts")
+    # more parts than vectors: trailing parts are empty
+    y = synth.activations(2, 1, 64, 4201, n_outlier=2, device=DEV).reshape(2, 64)
+    _fixed_case(y, 16, 12, "empty parts")
+
+
+def test_ties_across_part_borders():
+    rng = np.random.default_rng(43)
+    vals = np.array([0x3F80, 0xBF80, 0x4000, 0x0000], dtype=np.uint16)
+    bits = vals[rng.integers(0, len(vals), size=(3, 32 * 1024))]
+    _fixed_case(synth.from_bits(bits, DEV), 128, 5, "ties")
+    _fixed_case(synth.from_bits(bits, DEV), 512, 3, "ties k=512")
+
+
+def test_small_batch_default_plan_matches():
+    x = synth.activations(2, 32, 8192, 4300, n_outlier=16, device=DEV).reshape(2, 32 * 8192)
+    assert tl.toploc_workspace_bytes(128, 1, 32 * 8192, 2) > 0      # the library cuts such a batch
+    _fixed_case(x, 128, 0, "default plan")
+
+
+def _segment_case(hidden, rows, k, seed, parts=0, what="segments"):
+    """rows: rows per segment.  One [total_rows, hidden] matrix, oracle per segment."""
+    total = int(sum(rows))
+    say("%s H=%d rows=%s k=%d parts=%d" % (what, hidden, list(rows), k, parts))
+    x = synth.activations(1, total, hidden, seed, n_outlier=min(8, hidden), device=DEV).reshape(total, hidden)
+    off = np.concatenate([[0], np.cumsum(rows)]).astype(np.uint64)
+    bits = synth.bits_numpy(x)
+    tl.toploc_set_split(parts)
+    proofs, status, idx = tl.toploc_build_proofs_segments(x, off, k=k, want_topk=True)
+    torch.cuda.synchronize()
+    proofs_np, status_np, idx_np = proofs.cpu().numpy(), status.cpu().numpy(), idx.cpu().numpy().view(np.uint32)
+    o_all = np.zeros_like(proofs_np)
+    for i in range(len(rows)):
+        seg = bits[int(off[i]):int(off[i + 1])].reshape(1, -1)
+        o_proofs, o_status, o_idx = orc.build(seg, k, want_topk=True)
+        assert np.array_equal(idx_np[i], o_idx[0]), "%s: segment %d indices" % (what, i)
+        assert status_np[i] == o_status[0], "%s: segment %d status" % (what, i)
+        assert np.array_equal(proofs_np[i], o_proofs[0]), "%s: segment %d proof bytes" % (what, i)
+        o_all[i] = o_proofs[0]
+    # verify against a perturbed recomputation so that the statistics are not all zero
+    rec = synth.perturb_relative(x, 2.0 ** -7, seed + 1)
+    res = tl.toploc_verify_proofs_segments(rec, off, torch.from_numpy(o_all).to(DEV), k=k)
+    torch.cuda.synchronize()
+    g = tl.results_numpy(res)
+    rbits = synth.bits_numpy(rec)
+    for i in range(len(rows)):
+        seg = rbits[int(off[i]):int(off[i + 1])].reshape(1, -1)
+        o = orc.verify(seg, o_all[i:i + 1], k)
+        for f in FIELDS:
+            assert g[f][i] == o[f][0], "%s: segment %d field %s" % (what, i, f)
+
+
+def test_segments_prompt_plus_ragged_last_chunk():
+    # a 100-token prompt as one proof, three full 32-token chunks, a ragged last chunk of 7 tokens
+    _segment_case(4096, [100, 32, 32, 32, 7], 128, 5000)
+
+
+def test_segments_one_row_and_tiny_hidden():
+    _segment_case(8, [1, 2, 1, 5], 8, 5001)
+    _segment_case(256, [1, 1, 3], 128, 5002)
+
+
+def test_segments_long_prompt_many_parts():
+    # a 2048-token prompt at hidden 4096 is 8 Mi values: cut into many parts by default
+    _segment_case(4096, [2048, 32, 5], 128, 5003)
+
+
+def test_segments_forced_cuts_and_large_k():
+    _segment_case(1024, [64, 9, 33], 512, 5004, parts=1)
+    _segment_case(1024, [64, 9, 33], 512, 5004, parts=6)
+    _segment_case(5120, [40, 32, 1], 32, 5005, parts=3)
+
+
+def test_segments_equal_fixed_chunks_on_a_regular_layout():
+    x = synth.activations(3, 64, 2048, 5100, n_outlier=4, device=DEV)        # 6 chunks of 32 rows
+    chunks = synth.as_chunks(x)
+    off = np.arange(7, dtype=np.uint64) * 32
+    p_seg, s_seg, i_seg = tl.toploc_build_proofs_segments(x.reshape(-1, 2048), off, k=128, want_topk=True)
+    p_fix, s_fix, i_fix = tl.toploc_build_proofs(chunks, k=128, chunk_tokens=1, want_topk=True)
+    torch.cuda.synchronize()
+    assert torch.equal(p_seg, p_fix) and torch.equal(s_seg, s_fix) and torch.equal(i_seg, i_fix)
+
+
+def test_segments_empty_and_invalid():
+    x = torch.zeros((4, 64), dtype=torch.bfloat16, device=DEV)
+    proofs, status = tl.toploc_build_proofs_segments(x, np.zeros(1, dtype=np.uint64), k=8)
+    assert proofs.shape == (0, 18) and status.shape == (0,)
+    with pytest.raises(tl.ToplocError):
+        tl.toploc_build_proofs_segments(x, np.array([0, 1, 4], dtype=np.uint64), k=128)   # segment 0 holds 64 < k values
+    with pytest.raises(ValueError):
+        tl.toploc_build_proofs_segments(x, np.array([0, 9], dtype=np.uint64), k=8)        # past the tensor
