@@ -27,7 +27,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="config3", choices=["config3", "config2"])
     ap.add_argument("--k", type=int, default=128)
-    ap.add_argument("--cpu-sample-chunks", type=int, default=512)
+    ap.add_argument("--cpu-sample-chunks", type=int, default=6144)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy and one pure read of the tensor, so that a "
@@ -111,9 +111,9 @@ def main():
                            "build_verify_kernels_70b_shape_hbm_traffic.txt")
         if os.path.exists(pmc):
             for line in open(pmc):
-                parts = line.split()
-                if len(parts) == 3 and parts[0] == "traffic_bytes_per_launch" and parts[1] == dom:
-                    traffic = float(parts[2])
+                cols = line.split()
+                if len(cols) == 3 and cols[0] == "traffic_bytes_per_launch" and cols[1] == dom:
+                    traffic = float(cols[2])
     roofline = {
         "bound": "hbm",
         "kernel": dom,
