@@ -25,7 +25,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="config3", choices=["config3", "config2"])
+    ap.add_argument("--workload", default="config3", choices=["config3", "config2", "config4", "config5"],
+                    help="config3 is the benchmark line; config2 is the 8B shape; config4 (verification stress) and "
+                         "config5 (online decode-step path) print their own report line")
     ap.add_argument("--k", type=int, default=128)
     ap.add_argument("--cpu-sample-chunks", type=int, default=6144)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -44,6 +46,10 @@ def main():
 
     dev = "cuda:0"
     k = args.k
+    if args.workload == "config4":
+        return report_config4(args, tl, synth, torch, dev)
+    if args.workload == "config5":
+        return report_config5(args, tl, synth, torch, dev)
     if args.workload == "config3":
         x = synth.config3(dev)
         name = "llama-3.1-70b-shaped: 128 seq x 4096 tok x hidden 8192 bf16, 32-token chunks, k=%d" % k
@@ -179,6 +185,108 @@ def main():
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))
+
+
+def _kernel_ms(tl, torch, fn, reps):
+    """{kernel: average ms per launch} over `reps` calls of fn, HIP events on the launch stream."""
+    fn()
+    torch.cuda.synchronize()
+    tl.toploc_profile_enable(True)
+    tl.toploc_profile_read()
+    for _ in range(reps):
+        fn()
+    torch.cuda.synchronize()
+    prof = tl.toploc_profile_read()
+    tl.toploc_profile_enable(False)
+    return {kn: ms / n for kn, (n, ms) in prof.items() if n}
+
+
+def report_config4(args, tl, synth, torch, dev):
+    """Verification stress at the 8B shape: proofs of the original tensor verified against three
+    recomputed tensors; verify chunks/s and verdict counts with the paper's bf16 thresholds."""
+    k = args.k
+    x = synth.config2(dev)
+    chunks = synth.as_chunks(x)
+    n_chunks, n = chunks.shape
+    proofs, status = tl.toploc_build_proofs(chunks, k=k, chunk_tokens=1)
+    results = torch.empty((n_chunks, 20), dtype=torch.uint8, device=dev)
+    ws = tl.new_workspace(k, 1, n, n_chunks, dev)
+    variants = {}
+    makers = (("a_reordered_rel_2^-7", lambda: synth.perturb_relative(x, 2.0 ** -7, synth.BASE_SEED + 41)),
+              ("b_other_seed_and_channels", lambda: synth.activations(x.shape[0], x.shape[1], x.shape[2],
+                                                                      synth.BASE_SEED + 42, n_outlier=8, device=dev)),
+              ("c_fp8_e4m3_roundtrip", lambda: synth.roundtrip_e4m3(x)))
+    for name, make in makers:
+        rec = synth.as_chunks(make())
+        ms = _kernel_ms(tl, torch, lambda: tl.toploc_verify_proofs(rec, proofs, k=k, chunk_tokens=1, out=results,
+                                                                   workspace=ws), args.steps)
+        g = tl.results_numpy(results)
+        tot = sum(ms.values())
+        variants[name] = {
+            "accepted": int(g["accept"].sum()), "rejected": int(n_chunks - g["accept"].sum()),
+            "err_exp_max": int(g["err_exp"].max()), "err_exp_mean": float(g["err_exp"].mean()),
+            "mant_mean_diff": float(g["mant_sum"].sum()) / max(1, int(g["n_match"].sum())),
+            "verify_ms": tot, "verify_chunks_per_s": n_chunks / (tot * 1e-3),
+            "verify_GBps": n_chunks * n * 2 / (tot * 1e-3) / 1e9,
+        }
+        del rec
+    print(json.dumps({
+        "metric": "verify throughput and verdict counts, verification stress", "unit": "chunks/s",
+        "value": min(v["verify_chunks_per_s"] for v in variants.values()), "n_gpus": 1, "steps": args.steps,
+        "dtype": "u16", "data": "synthetic", "thresholds": list(tl.BF16_THRESHOLDS),
+        "config": {"workload": "8B shape 64 x 2048 x 4096 bf16, k=%d, three recomputed tensors" % k,
+                   "n_chunks": n_chunks, "chunk_values": n, "k": k},
+        "variants": variants}))
+
+
+def report_config5(args, tl, synth, torch, dev):
+    """Online decode-step path: 1024 sequences append one 5120-wide vector per step into a 32-token
+    ring; every 32nd step one batched emission (build of all rings).  Per-step overhead and proof rate."""
+    n_seq, hidden, T = 1024, 5120, 32
+    n_windows = 4                               # distinct data windows, reused over the 1024 steps
+    steps = synth.config5_steps(n_seq, hidden, n_windows * T, device=dev)
+    ring = torch.zeros((n_seq, T, hidden), dtype=torch.bfloat16, device=dev)
+    chunks = ring.reshape(n_seq, T * hidden)
+    n_steps = 1024
+    out = {}
+    for k in (32, 128, 512):
+        pb = 2 + 2 * k
+        proofs = torch.empty((n_seq, pb), dtype=torch.uint8, device=dev)
+        status = torch.empty(n_seq, dtype=torch.uint8, device=dev)
+        ws = tl.new_workspace(k, 1, T * hidden, n_seq, dev)
+
+        def run(emit):
+            for st in range(n_steps):
+                tl.toploc_ring_append(ring, steps[st % (n_windows * T)], st)
+                if emit and st % T == T - 1:
+                    tl.toploc_build_proofs(chunks, k=k, chunk_tokens=1, workspace=ws, out=(proofs, status))
+        run(True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run(True)
+        torch.cuda.synchronize()
+        t_all = time.perf_counter() - t0
+        assert int(status.max()) == 0
+        ms = _kernel_ms(tl, torch, lambda: tl.toploc_build_proofs(chunks, k=k, chunk_tokens=1, workspace=ws,
+                                                                  out=(proofs, status)), 10)
+        app = _kernel_ms(tl, torch, lambda: tl.toploc_ring_append(ring, steps[0], 0), 50)
+        emit_ms = sum(ms.values())
+        out["k=%d" % k] = {
+            "append_kernel_us": app["ring_kernel"] * 1e3,
+            "emission_kernels_us": emit_ms * 1e3,
+            "amortised_us_per_step_wall": t_all / n_steps * 1e6,
+            "amortised_us_per_token": t_all / n_steps / n_seq * 1e6,
+            "emission_activation_GBps": n_seq * T * hidden * 2 / (emit_ms * 1e-3) / 1e9,
+            "proof_bytes_per_emission": n_seq * pb,
+            "proof_GBps": n_seq * pb / (emit_ms * 1e-3) / 1e9,
+            "kernels_ms": ms,
+        }
+    print(json.dumps({
+        "metric": "online path: per-step overhead", "unit": "us/step", "value": out["k=128"]["amortised_us_per_step_wall"],
+        "higher_is_better": False, "n_gpus": 1, "steps": n_steps, "dtype": "u16", "data": "synthetic",
+        "config": {"workload": "1024 sequences x hidden 5120 bf16, 32-token ring, emission every 32 steps",
+                   "n_seq": n_seq, "hidden": hidden},
+        "per_k": out}))
 
 
 if __name__ == "__main__":

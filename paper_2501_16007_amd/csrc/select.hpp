@@ -263,6 +263,93 @@ __device__ __forceinline__ int32_t vec_max_mag(const u32x4& r)
     return (int32_t)(mm.x > mm.y ? mm.x : mm.y);
 }
 
+// number of set bits of `mask` below the calling lane
+__device__ __forceinline__ uint32_t lanes_below(uint64_t mask)
+{
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
+// One round of loads: vectors b + u*THREADS + tid, u < U.  A round that lies wholly inside
+// [.., v1) is loaded without per-lane tests; vectors past v1 read as zero.
+template <int THREADS, int U>
+__device__ __forceinline__ void load_round(u32x4 (&buf)[U], const u32x4* __restrict__ src, uint32_t b, uint32_t v1)
+{
+    const uint32_t tid = threadIdx.x;
+    if (b + THREADS * U <= v1) {  // uniform
+        const u32x4* p = src + b;
+#pragma unroll
+        for (int u = 0; u < U; ++u) buf[u] = __builtin_nontemporal_load(p + u * THREADS + tid);
+    } else {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t v = b + u * THREADS + tid;
+            buf[u] = u32x4{0u, 0u, 0u, 0u};
+            if (v < v1) buf[u] = __builtin_nontemporal_load(src + v);
+        }
+    }
+}
+
+// Examine the round held in buf (vectors b + u*THREADS + tid): every vector with a
+// magnitude >= t.tm goes to the queue.  A wave with nothing to queue goes straight to the
+// barrier; otherwise the wave takes all its queue slots with one LDS atomic.  One barrier
+// per pass; the workgroup drains the queue when it passed its soft limit, and lanes that
+// found the queue full retry after the drain (against the new threshold).
+template <int THREADS, int U, int CAP, int QCAP>
+__device__ __forceinline__ void examine_round(const u32x4 (&buf)[U], uint32_t b, uint32_t v1, uint32_t k,
+                                              SelectShared<THREADS, CAP, QCAP>& s, Threshold& t, uint32_t& round)
+{
+    constexpr uint32_t QSOFT = QCAP / 2;
+    const uint32_t tid = threadIdx.x;
+    int32_t m[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) m[u] = vec_max_mag(buf[u]);
+    uint32_t pend = 0;  // bit u: vector u still has to be queued
+    if (b + THREADS * U <= v1) {  // uniform
+#pragma unroll
+        for (int u = 0; u < U; ++u) pend |= (m[u] >= t.tm) ? (1u << u) : 0u;
+    } else {
+#pragma unroll
+        for (int u = 0; u < U; ++u) pend |= (m[u] >= t.tm && b + u * THREADS + tid < v1) ? (1u << u) : 0u;
+    }
+    while (true) {
+        uint32_t* flag = &s.flag[round % 3u];
+        if (__ballot(pend != 0u)) {  // uniform within the wave
+            uint64_t want[U];
+            uint32_t total = 0;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                want[u] = __ballot((pend >> u) & 1u);
+                total += (uint32_t)__popcll(want[u]);
+            }
+            uint32_t first = 0;
+            if (lane_id() == 0) first = atomicAdd(&s.qcount, total);
+            first = __builtin_amdgcn_readfirstlane(first);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if ((pend >> u) & 1u) {
+                    const uint32_t slot = first + lanes_below(want[u]);
+                    if (slot >= QSOFT) *flag = 1u;
+                    if (slot < (uint32_t)QCAP) {
+                        s.qvec[slot] = buf[u];
+                        s.qidx[slot] = b + u * THREADS + tid;
+                        pend &= ~(1u << u);
+                    }
+                }
+                first += (uint32_t)__popcll(want[u]);
+            }
+        }
+        __syncthreads();
+        const uint32_t f = *flag;
+        if (tid == 0) s.flag[(round + 2u) % 3u] = 0;  // the previous round's flag: read by all before this barrier
+        ++round;
+        if (!f) break;  // no slot at or past the soft limit was handed out: nothing is pending either
+        if (!drain<THREADS, CAP, QCAP>(s, k, CAP / 2, t)) break;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (m[u] < t.tm) pend &= ~(1u << u);
+    }
+}
+
 // Top-k of the vectors [v0, v1) of the chunk at src (8 values per vector, flat index of
 // value e of vector v is 8v + e) into s.cand_idx / s.cand_bits [0 .. k), in no
 // particular order (order_topk sorts them).
@@ -272,7 +359,6 @@ template <int THREADS, int U, int CAP, int QCAP>
 __device__ __forceinline__ void select_topk(const u32x4* __restrict__ src, uint32_t v0, uint32_t v1, uint32_t k,
                                             SelectShared<THREADS, CAP, QCAP>& s)
 {
-    constexpr uint32_t QSOFT = QCAP / 2;
     constexpr uint32_t ROUND = THREADS * U;
     const uint32_t tid = threadIdx.x;
     if (tid == 0) {
@@ -284,13 +370,8 @@ __device__ __forceinline__ void select_topk(const u32x4* __restrict__ src, uint3
     t.ti = 0xFFFFFFFFu;
     uint32_t round = 0;  // barrier rounds; flag[round % 3] belongs to the current one
 
-    u32x4 cur[U], nxt[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const uint32_t v = v0 + u * THREADS + tid;
-        cur[u] = u32x4{0u, 0u, 0u, 0u};
-        if (v < v1) cur[u] = __builtin_nontemporal_load(src + v);
-    }
+    u32x4 even[U], odd[U];  // two rounds in registers: one is examined while the other one's loads fly
+    load_round<THREADS, U>(even, src, v0, v1);
     // First threshold: the largest magnitude of every vector of the first round belongs
     // to a distinct real element.  If at least k of those maxima have exponent >= e, then
     // k elements have magnitude >= e << 7, and nothing below that can be in the top-k.
@@ -302,7 +383,7 @@ __device__ __forceinline__ void select_topk(const u32x4* __restrict__ src, uint3
         __syncthreads();
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            if (v0 + u * THREADS + tid < v1) atomicAdd(&s.hist_e[(uint32_t)vec_max_mag(cur[u]) >> 7], 1u);
+            if (v0 + u * THREADS + tid < v1) atomicAdd(&s.hist_e[(uint32_t)vec_max_mag(even[u]) >> 7], 1u);
         __syncthreads();
         uint32_t e_star, above;
         find_bin<4>(s.hist_e, 0u, k, e_star, above);
@@ -310,45 +391,16 @@ __device__ __forceinline__ void select_topk(const u32x4* __restrict__ src, uint3
     }
     __syncthreads();
 
-    for (uint32_t base = v0; base < v1; base += ROUND) {
-        // loads of the next round fly while this one is examined
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const uint32_t v = base + ROUND + u * THREADS + tid;
-            nxt[u] = u32x4{0u, 0u, 0u, 0u};
-            if (v < v1) nxt[u] = __builtin_nontemporal_load(src + v);
-        }
-        uint32_t pend = 0;  // bit u: vector u still has to be queued
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (base + u * THREADS + tid < v1) pend |= 1u << u;
-        while (true) {
-            uint32_t* flag = &s.flag[round % 3u];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if ((pend >> u) & 1u) {
-                    if (vec_max_mag(cur[u]) >= t.tm) {
-                        const uint32_t slot = atomicAdd(&s.qcount, 1u);
-                        if (slot >= QSOFT) *flag = 1u;
-                        if (slot < (uint32_t)QCAP) {
-                            s.qvec[slot] = cur[u];
-                            s.qidx[slot] = base + u * THREADS + tid;
-                            pend &= ~(1u << u);
-                        }
-                    } else {
-                        pend &= ~(1u << u);
-                    }
-                }
-            }
-            __syncthreads();
-            const uint32_t f = *flag;
-            if (tid == 0) s.flag[(round + 2u) % 3u] = 0;  // the previous round's flag: read by all before this barrier
-            ++round;
-            if (!f) break;
-            if (!drain<THREADS, CAP, QCAP>(s, k, CAP / 2, t)) break;
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) cur[u] = nxt[u];
+    uint32_t base = v0;  // v1 - v0 >= 1
+    while (true) {
+        load_round<THREADS, U>(odd, src, base + ROUND, v1);
+        examine_round<THREADS, U, CAP, QCAP>(even, base, v1, k, s, t, round);
+        base += ROUND;
+        if (base >= v1) break;
+        load_round<THREADS, U>(even, src, base + ROUND, v1);
+        examine_round<THREADS, U, CAP, QCAP>(odd, base, v1, k, s, t, round);
+        base += ROUND;
+        if (base >= v1) break;
     }
     __syncthreads();
     (void)drain<THREADS, CAP, QCAP>(s, k, k, t);  // prunes to exactly k

@@ -32,7 +32,7 @@
 #define TOPLOC_QCAP 512
 #endif
 #ifndef TOPLOC_MIN_WAVES
-#define TOPLOC_MIN_WAVES 6  // waves per SIMD the streaming kernels must reach (bounds their VGPRs)
+#define TOPLOC_MIN_WAVES 5  // waves per SIMD the streaming kernels must reach (bounds their VGPRs; 6 would spill)
 #endif
 
 namespace toploc {
@@ -322,31 +322,47 @@ static uint64_t chunk_len(const toploc_params* p)
     return n;
 }
 
-// A launch wants a few workgroups per resident slot of the 256 compute units; a part
-// should still stream a few rounds.
-constexpr uint64_t kTargetGroups = 3072;
+// How a launch is cut.  One workgroup keeps about 16 KB of loads in flight, so roughly a
+// thousand streaming workgroups are needed to saturate HBM: a batch with fewer chunks is
+// cut into parts until there are that many, but a part still streams a few rounds (every
+// part pays for finding its own threshold), and no part is longer than kMaxPartVecs so
+// that one long segment cannot become the launch's straggler.
+constexpr uint64_t kTargetGroups = 1024;
 constexpr uint64_t kMinPartVecs = 4 * kRoundVecs;
+constexpr uint64_t kMaxPartVecs = 64 * kRoundVecs;
 
-// vectors per part for `total_vecs` vectors of input whose longest unit has `max_unit_vecs`
-static uint64_t pick_part_vecs(uint64_t total_vecs, uint64_t max_unit_vecs)
+static uint64_t clamp_part_vecs(uint64_t pv)
 {
-    if (g_force_parts) {
-        const uint64_t pv = (max_unit_vecs + g_force_parts - 1) / g_force_parts;
-        return pv ? pv : 1;
-    }
-    uint64_t pv = (total_vecs + kTargetGroups - 1) / kTargetGroups;
     pv = (pv + kRoundVecs - 1) / kRoundVecs * kRoundVecs;
-    return pv < kMinPartVecs ? kMinPartVecs : pv;
+    return pv < kMinPartVecs ? kMinPartVecs : pv > kMaxPartVecs ? kMaxPartVecs : pv;
 }
 
 struct FixedPlan { uint32_t parts; uint32_t part_vecs; };
 static FixedPlan plan_fixed(uint64_t n_chunks, uint64_t nvec)
 {
-    const uint64_t pv = pick_part_vecs(n_chunks * nvec, nvec);
+    uint64_t pv;
+    if (g_force_parts) {
+        pv = (nvec + g_force_parts - 1) / g_force_parts;
+        pv = pv ? pv : 1;
+    } else {
+        const uint64_t want = n_chunks < kTargetGroups ? kTargetGroups / n_chunks : 1;  // parts per chunk
+        pv = clamp_part_vecs((nvec + want - 1) / want);
+    }
     FixedPlan f;
     f.parts = (uint32_t)((nvec + pv - 1) / pv);
     f.part_vecs = (uint32_t)(pv < nvec ? pv : nvec);
     return f;
+}
+
+// vectors per part for segments: `total_vecs` vectors in `n_units` segments, the longest of `max_unit_vecs`
+static uint64_t pick_part_vecs(uint64_t total_vecs, uint64_t max_unit_vecs, uint64_t n_units)
+{
+    if (g_force_parts) {
+        const uint64_t pv = (max_unit_vecs + g_force_parts - 1) / g_force_parts;
+        return pv ? pv : 1;
+    }
+    const uint64_t groups = n_units > kTargetGroups ? n_units : kTargetGroups;
+    return clamp_part_vecs((total_vecs + groups - 1) / groups);
 }
 
 // candidate arrays for `slots` parts: [slots*k] uint32 then [slots*k] uint16, each 16-byte aligned
@@ -411,7 +427,7 @@ static SegPlan plan_segments(const uint64_t* h_row_offsets, uint64_t n_segments,
         if (rows * hv > max_vecs) max_vecs = rows * hv;
     }
     const uint64_t total_vecs = n_segments ? (h_row_offsets[n_segments] - h_row_offsets[0]) * hv : 0;
-    const uint64_t pv = pick_part_vecs(total_vecs, max_vecs);
+    const uint64_t pv = pick_part_vecs(total_vecs, max_vecs, n_segments);
     pl.segs.reserve(n_segments);
     for (uint64_t i = 0; i < n_segments; ++i) {
         const uint64_t nvec = (h_row_offsets[i + 1] - h_row_offsets[i]) * hv;

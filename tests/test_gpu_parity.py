@@ -300,3 +300,62 @@ def test_config5_online_ring_small():
             assert torch.equal(ring, want)
             for k in (32, 128, 512):
                 check_chunks(ring.reshape(n_seq, T * hidden), k, what="config 5 emission at step %d" % step)
+
+
+def test_config4_full_size_verdict_counts_and_sampled_parity():
+    """64 x 2048 x 4096 (4096 chunks): proofs built on the GPU from the original tensor, the three
+    recomputed tensors verified at full size; the oracle checks a seeded sample of every variant."""
+    x = synth.config2(DEV)
+    chunks = synth.as_chunks(x)
+    n_chunks = chunks.shape[0]
+    proofs, status = tl.toploc_build_proofs(chunks, k=128, chunk_tokens=1)
+    torch.cuda.synchronize()
+    assert int(status.max()) == 0
+    sel = np.sort(np.random.default_rng(404).choice(n_chunks, 24, replace=False))
+    selt = torch.from_numpy(sel).to(DEV)
+    o_proofs, _ = orc.build(synth.bits_numpy(chunks[selt]), 128)
+    assert np.array_equal(proofs[selt].cpu().numpy(), o_proofs)
+    accepted = {}
+    for name, make in (("a_reordered", lambda: synth.perturb_relative(x, 2.0 ** -7, synth.BASE_SEED + 41)),
+                       ("b_other_model", lambda: synth.activations(64, 2048, 4096, synth.BASE_SEED + 42, n_outlier=8,
+                                                                   device=DEV)),
+                       ("c_fp8_roundtrip", lambda: synth.roundtrip_e4m3(x))):
+        say("config 4 full size " + name)
+        rec = synth.as_chunks(make())
+        res = tl.toploc_verify_proofs(rec, proofs, k=128, chunk_tokens=1)
+        torch.cuda.synchronize()
+        g = tl.results_numpy(res)
+        o = orc.verify(synth.bits_numpy(rec[selt]), o_proofs, 128)
+        assert_results_equal(g[sel], o, "config 4 full size " + name)
+        accepted[name] = int(g["accept"].sum())
+        assert (g["status"] == tl.CHUNK_OK).all()
+        del rec
+    say("config 4 full size: accepted of %d chunks: %s" % (n_chunks, accepted))
+    assert accepted["a_reordered"] == n_chunks
+    assert accepted["b_other_model"] == 0
+
+
+def test_config5_full_width_one_emission_sampled():
+    """1024 concurrent sequences x hidden 5120: 32 appended steps, then one batched emission per k."""
+    n_seq, hidden, T = 1024, 5120, 32
+    steps = synth.config5_steps(n_seq, hidden, T, device=DEV)            # [32, 1024, 5120]
+    ring = torch.zeros((n_seq, T, hidden), dtype=torch.bfloat16, device=DEV)
+    for step in range(T):
+        tl.toploc_ring_append(ring, steps[step], step + 7 * T)           # any step number: slot = step mod T
+    torch.cuda.synchronize()
+    assert torch.equal(ring, steps.transpose(0, 1))
+    chunks = ring.reshape(n_seq, T * hidden)
+    sel = np.sort(np.random.default_rng(505).choice(n_seq, 12, replace=False))
+    selt = torch.from_numpy(sel).to(DEV)
+    sample_bits = synth.bits_numpy(chunks[selt])
+    for k in (32, 128, 512):
+        say("config 5 full width k=%d" % k)
+        proofs, status, idx = tl.toploc_build_proofs(chunks, k=k, chunk_tokens=1, want_topk=True)
+        res = tl.toploc_verify_proofs(chunks, proofs, k=k, chunk_tokens=1)
+        torch.cuda.synchronize()
+        g = tl.results_numpy(res)
+        assert int(status.max()) == 0 and (g["accept"] == 1).all() and (g["n_match"] == k).all()
+        o_proofs, o_status, o_idx = orc.build(sample_bits, k, want_topk=True)
+        assert np.array_equal(proofs[selt].cpu().numpy(), o_proofs)
+        assert np.array_equal(idx[selt].cpu().numpy().view(np.uint32), o_idx)
+        assert_results_equal(g[sel], orc.verify(sample_bits, o_proofs, k), "config 5 full width k=%d" % k)
