@@ -27,6 +27,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#ifndef TOPLOC_PRUNE_LIMIT
+#define TOPLOC_PRUNE_LIMIT(cap, k) ((cap) / 2)
+#endif
 #ifndef TOPLOC_PRUNE_ATTR
 #define TOPLOC_PRUNE_ATTR __forceinline__
 #endif
@@ -343,7 +346,7 @@ __device__ __forceinline__ void examine_round(const u32x4 (&buf)[U], uint32_t b,
         if (tid == 0) s.flag[(round + 2u) % 3u] = 0;  // the previous round's flag: read by all before this barrier
         ++round;
         if (!f) break;  // no slot at or past the soft limit was handed out: nothing is pending either
-        if (!drain<THREADS, CAP, QCAP>(s, k, CAP / 2, t)) break;
+        if (!drain<THREADS, CAP, QCAP>(s, k, TOPLOC_PRUNE_LIMIT(CAP, k), t)) break;
 #pragma unroll
         for (int u = 0; u < U; ++u)
             if (m[u] < t.tm) pend &= ~(1u << u);

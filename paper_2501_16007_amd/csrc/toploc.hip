@@ -40,7 +40,10 @@ namespace toploc {
 constexpr int kThreads = 256;             // lanes per streaming workgroup
 constexpr int kLoads = TOPLOC_LOADS;      // 16-byte loads in flight per lane and round
 constexpr int kQcap = TOPLOC_QCAP;        // queue entries (16-byte vectors)
-constexpr int kCapSmall = 1024;           // candidate buffer for k <= 128
+#ifndef TOPLOC_CAP_SMALL
+#define TOPLOC_CAP_SMALL 1024
+#endif
+constexpr int kCapSmall = TOPLOC_CAP_SMALL;  // candidate buffer for k <= 128
 constexpr int kCapLarge = 2048;           // candidate buffer for k <= TOPLOC_MAX_K
 constexpr uint32_t kRoundVecs = kThreads * kLoads;
 static_assert(kCapLarge >= 4 * (int)TOPLOC_MAX_K && kCapSmall >= 4 * 128, "soft limit CAP/2 must leave room above k");
