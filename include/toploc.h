@@ -61,6 +61,7 @@ extern "C" {
 #define TOPLOC_CHUNK_NO_INVERSE 2   /* Algorithm 4's error exit; unreachable once the    */
                                     /* modulus makes the points distinct in GF(p)        */
 #define TOPLOC_CHUNK_MALFORMED 3    /* verify: decoded m < 2^15+1 or a coefficient >= p  */
+#define TOPLOC_CHUNK_SHORT 4        /* streaming emit: fewer than k values were appended */
 
 typedef struct {
     uint32_t k;             /* top-k parameter of Algorithms 1 and 2 (128 in the paper) */
@@ -171,6 +172,33 @@ int toploc_verify_proofs_segments(const void *d_hidden_bf16, const uint64_t *h_r
 int toploc_ring_append(void *d_ring_bf16, const void *d_step_bf16, uint32_t n_seq, uint32_t hidden,
                        uint32_t chunk_tokens, uint32_t step, void *hip_stream);
 
+/* Online path without the ring (a design of this build; the paper's provider keeps the
+ * last hidden states, Table 6, only to take their top-k when the proof is cut).  Per
+ * sequence the library keeps the running top-k of the rows appended so far -- at most k
+ * (flat index, bf16 pattern) pairs and the k-th element as threshold, 16 + 6k bytes
+ * with each part rounded up to 16 bytes -- so a decode step costs one read of its
+ * [n_seq][hidden] vectors and the emission never re-reads activations.  The proofs are
+ * byte for byte those toploc_build_proofs gives for the chunk made of the appended rows.
+ *   toploc_stream_state_bytes   size of d_state for n_seq sequences (0: invalid k)
+ *   toploc_stream_reset         empties every sequence's state
+ *   toploc_stream_append        row `token` (0-based position inside the chunk, each
+ *                               position at most once per chunk, any order) of every
+ *                               sequence: d_step_bf16 [n_seq][hidden]; the flat index of
+ *                               channel c is token*hidden + c.  hidden % 8 == 0 and
+ *                               chunk_tokens*hidden < 2^32
+ *   toploc_stream_emit          Algorithm 1 steps 2-5 on every sequence's k pairs: proofs,
+ *                               status (TOPLOC_CHUNK_SHORT when fewer than k values were
+ *                               appended) and optionally the ordered indices, laid out as by
+ *                               toploc_build_proofs; then empties the states
+ * d_state is 16-byte aligned device memory owned by the caller; calls on one state must
+ * be ordered on one stream. */
+size_t toploc_stream_state_bytes(uint32_t n_seq, uint32_t k);
+int toploc_stream_reset(void *d_state, uint32_t n_seq, uint32_t k, void *hip_stream);
+int toploc_stream_append(void *d_state, const void *d_step_bf16, uint32_t n_seq, uint32_t hidden, uint32_t chunk_tokens,
+                         uint32_t token, uint32_t k, void *hip_stream);
+int toploc_stream_emit(void *d_state, uint32_t n_seq, uint32_t k, uint8_t *d_proofs, uint8_t *d_status,
+                       uint32_t *d_topk_idx_opt, void *hip_stream);
+
 /* Measurement aid, not part of the method: reads n_chunks * chunk_values bf16
  * values with the access pattern of the selection kernel (one workgroup per
  * chunk, 16-byte loads) and keeps only a running maximum, to show what a pure
@@ -193,7 +221,9 @@ int toploc_bench_read(const void *d_hidden_bf16, uint64_t n_chunks, uint64_t chu
 #define TOPLOC_KERNEL_VERIFY 5        /* fused verify kernel                             */
 #define TOPLOC_KERNEL_RING 6          /* ring append kernel                              */
 #define TOPLOC_KERNEL_READ 7          /* toploc_bench_read                               */
-#define TOPLOC_KERNEL_COUNT 8
+#define TOPLOC_KERNEL_STREAM_APPEND 8 /* toploc_stream_append                            */
+#define TOPLOC_KERNEL_STREAM_EMIT 9   /* toploc_stream_emit                              */
+#define TOPLOC_KERNEL_COUNT 10
 int toploc_profile_enable(int on);
 int toploc_profile_read(uint32_t *launches /*[TOPLOC_KERNEL_COUNT]*/, float *total_ms /*[TOPLOC_KERNEL_COUNT]*/);
 

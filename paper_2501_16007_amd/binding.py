@@ -16,11 +16,11 @@ LIB_PATH = os.path.join(_HERE, "libtoploc_hip.so")
 PRIME = 65497
 MAX_K = 512
 OK, EINVAL, EWORKSPACE, EHIP = 0, -1, -2, -3
-CHUNK_OK, CHUNK_NO_MODULUS, CHUNK_NO_INVERSE, CHUNK_MALFORMED = 0, 1, 2, 3
+CHUNK_OK, CHUNK_NO_MODULUS, CHUNK_NO_INVERSE, CHUNK_MALFORMED, CHUNK_SHORT = 0, 1, 2, 3, 4
 (KERNEL_SELECT, KERNEL_PART, KERNEL_BUILD_MERGE, KERNEL_VERIFY_MERGE, KERNEL_BUILD, KERNEL_VERIFY, KERNEL_RING,
- KERNEL_READ, KERNEL_COUNT) = range(9)
+ KERNEL_READ, KERNEL_STREAM_APPEND, KERNEL_STREAM_EMIT, KERNEL_COUNT) = range(11)
 KERNEL_NAMES = ("select_kernel", "part_kernel", "build_merge_kernel", "verify_merge_kernel", "build_kernel",
-                "verify_kernel", "ring_kernel", "read_kernel")
+                "verify_kernel", "ring_kernel", "read_kernel", "stream_append_kernel", "stream_emit_kernel")
 BF16_THRESHOLDS = (38, 10, 8)  # T_exp, T_mean, T_median (Section 5.2 of the paper)
 
 RESULT_DTYPE = np.dtype(
@@ -45,6 +45,10 @@ EXPORTS = (
     "toploc_build_proofs",
     "toploc_verify_proofs",
     "toploc_topk",
+    "toploc_stream_state_bytes",
+    "toploc_stream_reset",
+    "toploc_stream_append",
+    "toploc_stream_emit",
     "toploc_ring_append",
     "toploc_bench_read",
     "toploc_profile_enable",
@@ -99,6 +103,11 @@ def lib():
         L.toploc_verify_proofs_segments.argtypes = [P, P, c.c_uint64, c.c_uint32, c.c_uint32, P, c.POINTER(Thresholds), P,
                                                     P, c.c_size_t, P]
         L.toploc_ring_append.argtypes = [P, P, c.c_uint32, c.c_uint32, c.c_uint32, c.c_uint32, P]
+        L.toploc_stream_state_bytes.argtypes = [c.c_uint32, c.c_uint32]
+        L.toploc_stream_state_bytes.restype = c.c_size_t
+        L.toploc_stream_reset.argtypes = [P, c.c_uint32, c.c_uint32, P]
+        L.toploc_stream_append.argtypes = [P, P, c.c_uint32, c.c_uint32, c.c_uint32, c.c_uint32, c.c_uint32, P]
+        L.toploc_stream_emit.argtypes = [P, c.c_uint32, c.c_uint32, P, P, P, P]
         L.toploc_bench_read.argtypes = [P, c.c_uint64, c.c_uint64, P, P]
         L.toploc_profile_enable.argtypes = [c.c_int]
         L.toploc_profile_read.argtypes = [c.POINTER(c.c_uint32), c.POINTER(c.c_float)]
@@ -266,6 +275,55 @@ def toploc_ring_append(ring, step_vec, step):
     rc = lib().toploc_ring_append(ring.data_ptr(), step_vec.data_ptr(), n_seq, h, chunk_tokens, step, _stream(ring))
     if rc != OK:
         raise ToplocError(rc, "toploc_ring_append")
+
+
+def toploc_stream_state_bytes(n_seq, k):
+    return int(lib().toploc_stream_state_bytes(n_seq, k))
+
+
+def toploc_stream_new_state(n_seq, k, device):
+    """Device memory for the running top-k of n_seq sequences, emptied."""
+    nbytes = toploc_stream_state_bytes(n_seq, k)
+    if nbytes == 0 and n_seq:
+        raise ToplocError(EINVAL, "toploc_stream_state_bytes")
+    state = torch.empty(max(16, nbytes), dtype=torch.uint8, device=device)
+    toploc_stream_reset(state, n_seq, k)
+    return state
+
+
+def toploc_stream_reset(state, n_seq, k):
+    rc = lib().toploc_stream_reset(state.data_ptr(), n_seq, k, _stream(state))
+    if rc != OK:
+        raise ToplocError(rc, "toploc_stream_reset")
+
+
+def toploc_stream_append(state, step_vec, token, k=128, chunk_tokens=32):
+    """Row `token` of the current chunk for every sequence: step_vec [n_seq, H] bf16."""
+    if step_vec.dtype != torch.bfloat16 or not step_vec.is_cuda or not step_vec.is_contiguous() or step_vec.dim() != 2:
+        raise ValueError("step_vec must be a contiguous [n_seq, H] bf16 tensor on the GPU")
+    n_seq, h = step_vec.shape
+    if state.numel() < toploc_stream_state_bytes(n_seq, k):
+        raise ValueError("state too small for n_seq sequences")
+    rc = lib().toploc_stream_append(state.data_ptr(), step_vec.data_ptr(), n_seq, h, chunk_tokens, token, k,
+                                    _stream(step_vec))
+    if rc != OK:
+        raise ToplocError(rc, "toploc_stream_append")
+
+
+def toploc_stream_emit(state, n_seq, k=128, want_topk=False, out=None):
+    """Proofs of the chunks appended since the last emission; empties the states."""
+    dev = state.device
+    if out is None:
+        proofs = torch.empty((n_seq, 2 + 2 * k), dtype=torch.uint8, device=dev)
+        status = torch.empty(n_seq, dtype=torch.uint8, device=dev)
+    else:
+        proofs, status = out
+    idx = torch.empty((n_seq, k), dtype=torch.int32, device=dev) if want_topk else None
+    rc = lib().toploc_stream_emit(state.data_ptr(), n_seq, k, proofs.data_ptr(), status.data_ptr(),
+                                  idx.data_ptr() if want_topk else None, _stream(state))
+    if rc != OK:
+        raise ToplocError(rc, "toploc_stream_emit")
+    return (proofs, status, idx) if want_topk else (proofs, status)
 
 
 def toploc_bench_read(hidden, out=None):

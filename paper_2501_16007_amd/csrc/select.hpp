@@ -353,35 +353,53 @@ __device__ __forceinline__ void examine_round(const u32x4 (&buf)[U], uint32_t b,
     }
 }
 
+// What a selection starts from.  A plain selection starts from nothing; the online path
+// continues an earlier one (one token row per call): its seed() puts the n survivors of the
+// earlier calls (n <= k) into s.cand_idx / s.cand_bits [0, n) and reports the threshold
+// those calls ended with, and k then counts seeds and new values together.  seed() runs
+// after the loads of the first round were issued, so that its own global reads overlap them.
+struct SelectStart {
+    uint32_t n;   // seeds placed in the candidate buffer
+    Threshold t;  // first threshold; (0, 0xFFFFFFFF): everything comes before it, nothing seen yet
+    uint32_t k;   // how many to select
+};
+struct NoSeed {
+    uint32_t k;
+    template <typename Shared>
+    __device__ __forceinline__ SelectStart seed(Shared&) const { return SelectStart{0u, Threshold{0, 0xFFFFFFFFu}, k}; }
+};
+
 // Top-k of the vectors [v0, v1) of the chunk at src (8 values per vector, flat index of
 // value e of vector v is 8v + e) into s.cand_idx / s.cand_bits [0 .. k), in no
 // particular order (order_topk sorts them).
-// Requires k <= 8*(v1 - v0), k <= CAP/2, 8*v1 < 2^32.  All threads of the workgroup
-// call it; it ends with a barrier.
-template <int THREADS, int U, int CAP, int QCAP>
-__device__ __forceinline__ void select_topk(const u32x4* __restrict__ src, uint32_t v0, uint32_t v1, uint32_t k,
-                                            SelectShared<THREADS, CAP, QCAP>& s)
+// Requires k <= seeds + 8*(v1 - v0), k <= CAP/4, 8*v1 < 2^32.  All threads of the workgroup
+// call it; it ends with a barrier.  Returns k and the threshold the selection ended with:
+// (0, 0xFFFFFFFF) as long as nothing had to be pruned, else the k-th element.
+template <int THREADS, int U, int CAP, int QCAP, typename Seed>
+__device__ __forceinline__ SelectStart select_topk_from(const u32x4* __restrict__ src, uint32_t v0, uint32_t v1,
+                                                        SelectShared<THREADS, CAP, QCAP>& s, const Seed& seeder)
 {
     constexpr uint32_t ROUND = THREADS * U;
     const uint32_t tid = threadIdx.x;
-    if (tid == 0) {
-        s.qcount = 0; s.count = 0; s.eq_count = 0; s.tm = 0; s.ti = 0xFFFFFFFFu;
-        s.flag[0] = 0; s.flag[1] = 0; s.flag[2] = 0;
-    }
-    Threshold t;
-    t.tm = 0;            // everything comes before (0, 0xFFFFFFFF): nothing seen yet
-    t.ti = 0xFFFFFFFFu;
-    uint32_t round = 0;  // barrier rounds; flag[round % 3] belongs to the current one
-
     u32x4 even[U], odd[U];  // two rounds in registers: one is examined while the other one's loads fly
     load_round<THREADS, U>(even, src, v0, v1);
+    const SelectStart start = seeder.seed(s);
+    const uint32_t k = start.k;
+    const uint32_t n_seed = start.n;
+    if (tid == 0) {
+        s.qcount = 0; s.count = n_seed; s.eq_count = 0; s.tm = start.t.tm; s.ti = start.t.ti;
+        s.flag[0] = 0; s.flag[1] = 0; s.flag[2] = 0;
+    }
+    Threshold t = start.t;
+    uint32_t round = 0;    // barrier rounds; flag[round % 3] belongs to the current one
+
     // First threshold: the largest magnitude of every vector of the first round belongs
     // to a distinct real element.  If at least k of those maxima have exponent >= e, then
     // k elements have magnitude >= e << 7, and nothing below that can be in the top-k.
     // One exponent histogram finds the largest such e; exact thresholds follow from the
     // first prune.
     const uint32_t first = (v1 - v0) < ROUND ? (v1 - v0) : ROUND;
-    if (first >= k) {  // uniform
+    if (n_seed == 0 && first >= k) {  // uniform
         for (uint32_t b = tid; b < 256; b += THREADS) s.hist_e[b] = 0;
         __syncthreads();
 #pragma unroll
@@ -407,6 +425,14 @@ __device__ __forceinline__ void select_topk(const u32x4* __restrict__ src, uint3
     }
     __syncthreads();
     (void)drain<THREADS, CAP, QCAP>(s, k, k, t);  // prunes to exactly k
+    return SelectStart{k, t, k};
+}
+
+template <int THREADS, int U, int CAP, int QCAP>
+__device__ __forceinline__ void select_topk(const u32x4* __restrict__ src, uint32_t v0, uint32_t v1, uint32_t k,
+                                            SelectShared<THREADS, CAP, QCAP>& s)
+{
+    (void)select_topk_from<THREADS, U, CAP, QCAP>(src, v0, v1, s, NoSeed{k});
 }
 
 // Top-k of candidate lists: `n` (index, pattern) pairs in global memory, entries whose

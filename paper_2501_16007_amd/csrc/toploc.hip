@@ -246,6 +246,134 @@ __global__ __launch_bounds__(THREADS) void verify_merge_kernel(Layout lay, uint3
 }
 
 // ---------------------------------------------------------------------------
+// Online path without the ring: per sequence the running top-k of the rows appended so
+// far.  State of one sequence: header, k indices, k patterns (each part 16-byte aligned).
+// ---------------------------------------------------------------------------
+struct StreamHeader {
+    uint32_t count;  // pairs held (<= k)
+    int32_t tm;      // threshold element the selection ended with
+    uint32_t ti;
+    uint32_t rows;   // rows appended since the last emission
+};
+static_assert(sizeof(StreamHeader) == 16, "state layout");
+
+__host__ __device__ __forceinline__ size_t stream_idx_bytes(uint32_t k) { return ((size_t)k * 4 + 15) & ~(size_t)15; }
+__host__ __device__ __forceinline__ size_t stream_stride(uint32_t k)
+{
+    return sizeof(StreamHeader) + stream_idx_bytes(k) + (((size_t)k * 2 + 15) & ~(size_t)15);
+}
+
+__global__ __launch_bounds__(256) void stream_reset_kernel(char* __restrict__ state, uint32_t n_seq, size_t stride)
+{
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n_seq) *reinterpret_cast<StreamHeader*>(state + (size_t)i * stride) = StreamHeader{0u, 0, 0xFFFFFFFFu, 0u};
+}
+
+// What a sequence holds enters the selection of its next row: all k slots are read
+// before the header says how many of them count, so that header, pairs and the row's
+// first vectors are in flight together.
+template <int CAP>
+struct StreamSeed {
+    const StreamHeader* hdr;
+    const uint32_t* g_idx;
+    const uint16_t* g_bits;
+    uint32_t k, row_values;
+    __device__ __forceinline__ SelectStart seed(SelectShared<kThreads, CAP, kQcap>& s) const
+    {
+        constexpr int SPT = (CAP / 4 + kThreads - 1) / kThreads;  // k <= CAP/4 slots over the lanes
+        uint32_t si[SPT], sb[SPT];
+#pragma unroll
+        for (int j = 0; j < SPT; ++j) {
+            const uint32_t i = threadIdx.x + j * kThreads;
+            si[j] = 0; sb[j] = 0;
+            if (i < k) { si[j] = g_idx[i]; sb[j] = g_bits[i]; }
+        }
+        const StreamHeader h = *hdr;
+#pragma unroll
+        for (int j = 0; j < SPT; ++j) {
+            const uint32_t i = threadIdx.x + j * kThreads;
+            if (i < h.count) { s.cand_idx[i] = si[j]; s.cand_bits[i] = (uint16_t)sb[j]; }
+        }
+        const uint64_t have = (uint64_t)h.count + row_values;
+        return SelectStart{h.count, Threshold{h.tm, h.ti}, have < k ? (uint32_t)have : k};
+    }
+};
+
+// One appended row per sequence: the selection of select.hpp over the row's vectors,
+// seeded with the pairs and the threshold the sequence holds.  `row_base` is the
+// sequence's row pointer moved back by v0 vectors, so that vector v0 + j of the
+// selection is vector j of the row and flat indices come out as token*hidden + channel.
+template <int CAP>
+__global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void stream_append_kernel(char* __restrict__ state, size_t stride,
+                                                                                   const u32x4* __restrict__ step_vec,
+                                                                                   uint32_t hvec, uint32_t v0, uint32_t k)
+{
+    __shared__ SelectShared<kThreads, CAP, kQcap> s;
+    const uint32_t tid = threadIdx.x;
+    char* st = state + (size_t)blockIdx.x * stride;
+    StreamHeader* hdr = reinterpret_cast<StreamHeader*>(st);
+    uint32_t* g_idx = reinterpret_cast<uint32_t*>(st + sizeof(StreamHeader));
+    uint16_t* g_bits = reinterpret_cast<uint16_t*>(st + sizeof(StreamHeader) + stream_idx_bytes(k));
+    const u32x4* row_base = reinterpret_cast<const u32x4*>(
+        reinterpret_cast<uintptr_t>(step_vec + (size_t)blockIdx.x * hvec) - (uintptr_t)v0 * sizeof(u32x4));
+    const uint32_t rows = hdr->rows;
+    const SelectStart end = select_topk_from<kThreads, kLoads, CAP, kQcap>(
+        row_base, v0, v0 + hvec, s, StreamSeed<CAP>{hdr, g_idx, g_bits, k, hvec * 8u});
+    for (uint32_t i = tid; i < end.k; i += kThreads) {
+        g_idx[i] = s.cand_idx[i];
+        g_bits[i] = s.cand_bits[i];
+    }
+    if (tid == 0) *hdr = StreamHeader{end.k, end.t.tm, end.t.ti, rows + 1u};
+}
+
+// Emission: steps 2-5 of Algorithm 1 on the k pairs a sequence holds, then the state is emptied.
+template <int THREADS, int KMAX, int CAP>
+__global__ __launch_bounds__(THREADS) void stream_emit_kernel(char* __restrict__ state, size_t stride, uint32_t k,
+                                                              uint8_t* __restrict__ proofs, uint8_t* __restrict__ status,
+                                                              uint32_t* __restrict__ out_idx)
+{
+    static_assert(KMAX <= THREADS, "one pair per lane is carried across the phase change");
+    __shared__ union EmitShared {
+        SelectShared<THREADS, CAP, 1> sel;
+        InterpShared<KMAX> itp;
+    } sh;
+    __shared__ uint32_t coef[KMAX];
+    const uint32_t tid = threadIdx.x;
+    const uint64_t seq = blockIdx.x;
+    char* st = state + seq * stride;
+    StreamHeader* hdr = reinterpret_cast<StreamHeader*>(st);
+    const uint32_t* g_idx = reinterpret_cast<const uint32_t*>(st + sizeof(StreamHeader));
+    const uint16_t* g_bits = reinterpret_cast<const uint16_t*>(st + sizeof(StreamHeader) + stream_idx_bytes(k));
+    const uint32_t count = hdr->count;
+    uint16_t* proof = reinterpret_cast<uint16_t*>(proofs + seq * (2 + 2 * (uint64_t)k));
+    __syncthreads();  // every lane has read the header
+    if (tid == 0) *hdr = StreamHeader{0u, 0, 0xFFFFFFFFu, 0u};
+    if (count < k) {  // uniform
+        for (uint32_t j = tid; j <= k; j += THREADS) proof[j] = 0;
+        if (out_idx)
+            for (uint32_t j = tid; j < k; j += THREADS) out_idx[seq * k + j] = 0xFFFFFFFFu;
+        if (tid == 0) status[seq] = TOPLOC_CHUNK_SHORT;
+        return;
+    }
+    uint32_t my_idx = 0, my_y = 0;
+    if (out_idx) {  // uniform: the caller wants the ordered indices
+        for (uint32_t j = tid; j < k; j += THREADS) { sh.sel.cand_idx[j] = g_idx[j]; sh.sel.cand_bits[j] = g_bits[j]; }
+        __syncthreads();
+        order_topk<THREADS, CAP, 1>(sh.sel, k);
+        if (tid < k) { out_idx[seq * k + tid] = sh.sel.cand_idx[tid]; my_idx = sh.sel.cand_idx[tid]; my_y = sh.sel.cand_bits[tid]; }
+        __syncthreads();
+    } else if (tid < k) {
+        my_idx = g_idx[tid];
+        my_y = g_bits[tid];
+    }
+    if (tid < k) {
+        sh.itp.idx[tid] = my_idx;
+        sh.itp.ys[tid] = (uint16_t)(my_y >= kPrime ? my_y - kPrime : my_y);
+    }
+    finish_proof<THREADS, KMAX>(sh.itp, coef, k, proof, status + seq);
+}
+
+// ---------------------------------------------------------------------------
 // ring[s][step mod T][:] = step_vec[s][:]
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void ring_kernel(u32x4* __restrict__ ring, const u32x4* __restrict__ step_vec,
@@ -638,6 +766,67 @@ int toploc_verify_proofs_segments(const void* d_hidden_bf16, const uint64_t* h_r
     launch_part(st, d_hidden_bf16, lay, pl.parts.size(), k, c_idx, c_bits);
     if (!hip_ok(hipGetLastError())) return TOPLOC_EHIP;
     launch_verify_merge(st, lay, n_segments, k, c_idx, c_bits, d_proofs, *thresholds, d_results);
+    return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
+}
+
+size_t toploc_stream_state_bytes(uint32_t n_seq, uint32_t k)
+{
+    if (k == 0 || k > TOPLOC_MAX_K) return 0;
+    return (size_t)n_seq * stream_stride(k);
+}
+
+int toploc_stream_reset(void* d_state, uint32_t n_seq, uint32_t k, void* hip_stream)
+{
+    if (k == 0 || k > TOPLOC_MAX_K) return TOPLOC_EINVAL;
+    if (n_seq == 0) return TOPLOC_OK;
+    if (!d_state || !aligned16(d_state)) return TOPLOC_EINVAL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    hipLaunchKernelGGL(stream_reset_kernel, dim3((n_seq + 255) / 256), dim3(256), 0, st, (char*)d_state, n_seq,
+                       stream_stride(k));
+    return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
+}
+
+int toploc_stream_append(void* d_state, const void* d_step_bf16, uint32_t n_seq, uint32_t hidden, uint32_t chunk_tokens,
+                         uint32_t token, uint32_t k, void* hip_stream)
+{
+    if (k == 0 || k > TOPLOC_MAX_K || hidden == 0 || hidden % 8 != 0 || chunk_tokens == 0 || token >= chunk_tokens)
+        return TOPLOC_EINVAL;
+    const uint64_t chunk_values = (uint64_t)chunk_tokens * hidden;
+    if (chunk_values >= (1ull << 32)) return TOPLOC_EINVAL;
+    if (n_seq == 0) return TOPLOC_OK;
+    if (!d_state || !d_step_bf16 || !aligned16(d_state) || !aligned16(d_step_bf16)) return TOPLOC_EINVAL;
+    if (reinterpret_cast<uintptr_t>(d_step_bf16) < chunk_values * 2) return TOPLOC_EINVAL;  // the kernel forms row - v0
+    hipStream_t st = (hipStream_t)hip_stream;
+    const uint32_t hvec = hidden / 8;
+    {
+        ProfScope ps(TOPLOC_KERNEL_STREAM_APPEND, st);
+        if (k <= 128)
+            hipLaunchKernelGGL((stream_append_kernel<kCapSmall>), dim3(n_seq), dim3(kThreads), 0, st, (char*)d_state,
+                               stream_stride(k), (const u32x4*)d_step_bf16, hvec, token * hvec, k);
+        else
+            hipLaunchKernelGGL((stream_append_kernel<kCapLarge>), dim3(n_seq), dim3(kThreads), 0, st, (char*)d_state,
+                               stream_stride(k), (const u32x4*)d_step_bf16, hvec, token * hvec, k);
+    }
+    return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
+}
+
+int toploc_stream_emit(void* d_state, uint32_t n_seq, uint32_t k, uint8_t* d_proofs, uint8_t* d_status,
+                       uint32_t* d_topk_idx_opt, void* hip_stream)
+{
+    if (k == 0 || k > TOPLOC_MAX_K) return TOPLOC_EINVAL;
+    if (n_seq == 0) return TOPLOC_OK;
+    if (!d_state || !d_proofs || !d_status || !aligned16(d_state)) return TOPLOC_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(d_proofs) & 1u) != 0) return TOPLOC_EINVAL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    {
+        ProfScope ps(TOPLOC_KERNEL_STREAM_EMIT, st);
+        if (k <= 128)
+            hipLaunchKernelGGL((stream_emit_kernel<256, 128, kCapSmall>), dim3(n_seq), dim3(256), 0, st, (char*)d_state,
+                               stream_stride(k), k, d_proofs, d_status, d_topk_idx_opt);
+        else
+            hipLaunchKernelGGL((stream_emit_kernel<1024, 512, kCapLarge>), dim3(n_seq), dim3(1024), 0, st, (char*)d_state,
+                               stream_stride(k), k, d_proofs, d_status, d_topk_idx_opt);
+    }
     return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
 }
 

@@ -79,3 +79,21 @@ def test_calls_are_rejected_before_any_launch():
     assert L.toploc_ring_append(fake, fake, 0, 16, 32, 0, None) == binding.OK
     for code in (0, -1, -2, -3, -99):
         assert L.toploc_strerror(code)
+
+
+def test_stream_state_size_and_argument_checks():
+    L = binding.lib()
+    fake = ctypes.c_void_p(1 << 40)  # never dereferenced: every call below is refused or empty
+    assert binding.toploc_stream_state_bytes(1, 128) == 16 + 512 + 256       # header, k indices, k patterns
+    assert binding.toploc_stream_state_bytes(1024, 32) == 1024 * (16 + 128 + 64)
+    assert binding.toploc_stream_state_bytes(3, 5) == 3 * (16 + 32 + 16)     # parts rounded up to 16 bytes
+    assert binding.toploc_stream_state_bytes(4, 0) == 0 and binding.toploc_stream_state_bytes(4, 513) == 0
+    assert L.toploc_stream_append(fake, fake, 4, 4096, 32, 32, 128, None) == binding.EINVAL   # token >= chunk_tokens
+    assert L.toploc_stream_append(fake, fake, 4, 4100, 32, 0, 128, None) == binding.EINVAL    # hidden % 8 != 0
+    assert L.toploc_stream_append(fake, fake, 4, 1 << 20, 1 << 12, 0, 128, None) == binding.EINVAL  # chunk >= 2^32 values
+    assert L.toploc_stream_append(None, fake, 4, 4096, 32, 0, 128, None) == binding.EINVAL
+    assert L.toploc_stream_append(fake, fake, 0, 4096, 32, 0, 128, None) == binding.OK
+    assert L.toploc_stream_emit(fake, 0, 128, fake, fake, None, None) == binding.OK
+    assert L.toploc_stream_emit(fake, 1, 0, fake, fake, None, None) == binding.EINVAL
+    assert L.toploc_stream_reset(fake, 0, 128, None) == binding.OK
+    assert L.toploc_stream_reset(None, 3, 128, None) == binding.EINVAL

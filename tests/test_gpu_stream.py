@@ -1,0 +1,111 @@
+"""Online path without the ring: the running top-k kept per sequence while rows are
+appended must give, at emission, the bytes Algorithm 1 gives for the assembled chunk
+(the CPU oracle sees the chunk as one flat array)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as orc
+from paper_2501_16007_amd import binding as tl
+from paper_2501_16007_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def say(msg):
+    print("[case] " + msg, flush=True)
+
+
+def run_stream(steps, k, T, order=None):
+    """steps [T, n_seq, H] -> (proofs, status, idx) after appending the T rows (in `order`) and emitting."""
+    n_seq = steps.shape[1]
+    state = tl.toploc_stream_new_state(n_seq, k, DEV)
+    for t in (range(T) if order is None else order):
+        tl.toploc_stream_append(state, steps[t], t, k=k, chunk_tokens=T)
+    proofs, status, idx = tl.toploc_stream_emit(state, n_seq, k=k, want_topk=True)
+    torch.cuda.synchronize()
+    return state, proofs.cpu().numpy(), status.cpu().numpy(), idx.cpu().numpy().view(np.uint32)
+
+
+def check_against_oracle(steps, k, T, order=None, what=""):
+    say("%s n_seq=%d H=%d T=%d k=%d" % (what, steps.shape[1], steps.shape[2], T, k))
+    chunk_bits = synth.bits_numpy(steps.transpose(0, 1).contiguous()).reshape(steps.shape[1], -1)
+    o_proofs, o_status, o_idx = orc.build(chunk_bits, k, want_topk=True)
+    state, proofs, status, idx = run_stream(steps, k, T, order)
+    assert np.array_equal(idx, o_idx), what + ": indices"
+    assert np.array_equal(status, o_status), what + ": status"
+    assert np.array_equal(proofs, o_proofs), what + ": proof bytes"
+    return state
+
+
+@pytest.mark.parametrize("hidden,T,k,n_seq", [
+    (5120, 32, 128, 6),     # the online workload's width
+    (5120, 32, 32, 3),
+    (5120, 32, 512, 3),
+    (4096, 32, 128, 4),
+    (8192, 32, 128, 2),
+    (64, 32, 128, 3),       # a row holds fewer than k values: the state fills over two rows
+    (8, 16, 16, 2),         # one vector per row
+    (1000, 7, 64, 3),       # ragged sizes
+])
+def test_stream_matches_oracle_on_the_assembled_chunk(hidden, T, k, n_seq):
+    steps = synth.config5_steps(n_seq, hidden, T, seed=7000 + hidden + k, device=DEV)
+    check_against_oracle(steps, k, T, what="stream")
+
+
+def test_stream_rows_in_any_order_and_state_reuse():
+    T, k, n_seq, hidden = 32, 128, 4, 2048
+    steps = synth.config5_steps(n_seq, hidden, 2 * T, seed=7100, device=DEV)
+    order = np.random.default_rng(71).permutation(T).tolist()
+    state = check_against_oracle(steps[:T], k, T, order=order, what="shuffled rows")
+    # the emission emptied the state: a second chunk through the same memory
+    for t in range(T):
+        tl.toploc_stream_append(state, steps[T + t], t, k=k, chunk_tokens=T)
+    proofs, status = tl.toploc_stream_emit(state, n_seq, k=k)
+    torch.cuda.synchronize()
+    bits = synth.bits_numpy(steps[T:].transpose(0, 1).contiguous()).reshape(n_seq, -1)
+    o_proofs, o_status = orc.build(bits, k)
+    assert np.array_equal(proofs.cpu().numpy(), o_proofs) and np.array_equal(status.cpu().numpy(), o_status)
+
+
+def test_stream_ties_and_equal_rows():
+    T, k, n_seq, hidden = 8, 128, 2, 512
+    vals = np.array([0x3F80, 0xBF80, 0x4000, 0x0000], dtype=np.uint16)
+    bits = vals[np.random.default_rng(72).integers(0, 4, size=(T, n_seq, hidden))]
+    bits[:, 1, :] = 0x3F80                      # sequence 1: every value equal, the lowest indices win
+    steps = synth.from_bits(bits, DEV)
+    check_against_oracle(steps, k, T, what="ties")
+
+
+def test_stream_short_chunk_is_reported():
+    n_seq, hidden, k = 3, 16, 128
+    steps = synth.config5_steps(n_seq, hidden, 4, seed=7200, device=DEV)
+    state = tl.toploc_stream_new_state(n_seq, k, DEV)
+    for t in range(4):                          # 64 values < k
+        tl.toploc_stream_append(state, steps[t], t, k=k, chunk_tokens=32)
+    proofs, status, idx = tl.toploc_stream_emit(state, n_seq, k=k, want_topk=True)
+    torch.cuda.synchronize()
+    assert (status.cpu().numpy() == tl.CHUNK_SHORT).all() and not proofs.cpu().numpy().any()
+
+
+def test_stream_equals_the_ring_path_at_full_width():
+    """1024 sequences x 5120: streamed proofs equal toploc_build_proofs over the ring; oracle on a sample."""
+    n_seq, hidden, T = 1024, 5120, 32
+    steps = synth.config5_steps(n_seq, hidden, T, device=DEV)
+    ring = torch.zeros((n_seq, T, hidden), dtype=torch.bfloat16, device=DEV)
+    for t in range(T):
+        tl.toploc_ring_append(ring, steps[t], t)
+    chunks = ring.reshape(n_seq, T * hidden)
+    sel = np.sort(np.random.default_rng(73).choice(n_seq, 8, replace=False))
+    sample_bits = synth.bits_numpy(chunks[torch.from_numpy(sel).to(DEV)])
+    for k in (32, 128, 512):
+        say("full width k=%d" % k)
+        _, proofs, status, idx = run_stream(steps, k, T)
+        r_proofs, r_status, r_idx = tl.toploc_build_proofs(chunks, k=k, chunk_tokens=1, want_topk=True)
+        torch.cuda.synchronize()
+        assert np.array_equal(proofs, r_proofs.cpu().numpy()) and np.array_equal(status, r_status.cpu().numpy())
+        assert np.array_equal(idx, r_idx.cpu().numpy().view(np.uint32))
+        o_proofs, o_status, o_idx = orc.build(sample_bits, k, want_topk=True)
+        assert np.array_equal(proofs[sel], o_proofs) and np.array_equal(idx[sel], o_idx)
