@@ -13,6 +13,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "toploc_oracle.c")
+_SRC32 = os.path.join(_HERE, "toploc_oracle_f32.c")
 _LIB = os.path.join(_HERE, "libtoploc_oracle.so")
 
 PRIME = 65497
@@ -36,9 +37,10 @@ assert RESULT_DTYPE.itemsize == 20
 
 def build_library(force=False):
     """Compile the oracle with gcc (plain C11, -O2, OpenMP over chunks)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < max(os.path.getmtime(_SRC),
+                                                                          os.path.getmtime(_SRC32)):
         subprocess.check_call(
-            ["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-fopenmp", "-fPIC", "-shared", _SRC, "-o", _LIB]
+            ["gcc", "-O2", "-std=gnu11", "-Wall", "-Wextra", "-fopenmp", "-fPIC", "-shared", _SRC, _SRC32, "-o", _LIB]
         )
     return _LIB
 
@@ -67,6 +69,14 @@ def _load():
         ]
         lib.toploc_oracle_decide.argtypes = [c.c_uint32, P, c.c_uint32, c.c_uint32, c.c_uint32, c.c_uint32, P]
         lib.toploc_oracle_max_threads.restype = c.c_int
+        lib.toploc_oracle32_topk.argtypes = [P, c.c_int, c.c_uint64, c.c_uint32, P, P]
+        lib.toploc_oracle32_interpolate.argtypes = [P, P, c.c_uint32, c.c_uint64, P]
+        lib.toploc_oracle32_horner.argtypes = [P, c.c_uint32, c.c_uint64, c.c_uint64]
+        lib.toploc_oracle32_horner.restype = c.c_uint64
+        lib.toploc_oracle32_find_injective_modulus.argtypes = [P, c.c_uint32, c.POINTER(c.c_uint32)]
+        lib.toploc_oracle32_build.argtypes = [P, c.c_uint64, c.c_uint64, c.c_uint32, c.c_uint64, P, P, P, c.c_int]
+        lib.toploc_oracle32_verify.argtypes = [P, c.c_int, c.c_uint64, c.c_uint64, c.c_uint32, P, c.c_int, c.c_uint64,
+                                               c.c_uint32, c.c_uint32, c.c_uint32, P, c.c_int]
         _lib = lib
     return _lib
 
@@ -183,3 +193,93 @@ def decide(err_e, err_m, thresholds=(T_EXP, T_MEAN, T_MEDIAN)):
         int(err_e), _ptr(err_m), err_m.size, int(thresholds[0]), int(thresholds[1]), int(thresholds[2]), _ptr(res)
     )
     return res[0]
+
+
+# ---------------------------------------------------------------------------
+# 32-bit variant (oracle/toploc_oracle_f32.c): fp32 proofs and validation across precisions
+# ---------------------------------------------------------------------------
+PRIME32 = 4294967291          # 2^32 - 5
+BF16, F32 = 0, 1
+F32_THRESHOLDS = (8, 256, 128)  # T_exp, T_mean, T_median for fp32 inference, Section 5.2
+
+
+def proof_bytes32(k):
+    return 2 + 4 * k
+
+
+def _patterns(h, dtype):
+    return np.ascontiguousarray(h, dtype=np.uint32 if dtype == F32 else np.uint16)
+
+
+def topk32(h_bits, k, dtype=F32):
+    """1-D patterns (uint32 for F32, uint16 for BF16). Returns (idx uint32[k], val uint32[k])."""
+    h = _patterns(h_bits, dtype).ravel()
+    idx = np.empty(k, dtype=np.uint32)
+    val = np.empty(k, dtype=np.uint32)
+    rc = _load().toploc_oracle32_topk(_ptr(h), dtype, h.size, k, _ptr(idx), _ptr(val))
+    if rc:
+        raise ValueError("oracle topk32: bad arguments")
+    return idx, val
+
+
+def interpolate32(x, y, M=PRIME32):
+    x = np.ascontiguousarray(x, dtype=np.uint64)
+    y = np.ascontiguousarray(y, dtype=np.uint64)
+    assert x.shape == y.shape and x.ndim == 1
+    c = np.empty(x.size, dtype=np.uint64)
+    rc = _load().toploc_oracle32_interpolate(_ptr(x), _ptr(y), x.size, int(M), _ptr(c))
+    if rc == ENOINV:
+        raise ZeroDivisionError("interpolate32: non-invertible denominator")
+    if rc:
+        raise ValueError("interpolate32: bad arguments")
+    return c
+
+
+def horner32(c, x, M=PRIME32):
+    c = np.ascontiguousarray(c, dtype=np.uint64)
+    return int(_load().toploc_oracle32_horner(_ptr(c), c.size, int(x), int(M)))
+
+
+def find_injective_modulus32(idx):
+    idx = np.ascontiguousarray(idx, dtype=np.uint32)
+    m = ctypes.c_uint32(0)
+    rc = _load().toploc_oracle32_find_injective_modulus(_ptr(idx), idx.size, ctypes.byref(m))
+    if rc:
+        raise ValueError("No injective modulus found!")
+    return int(m.value)
+
+
+def build32(h_bits, k, M=PRIME32, want_topk=False, n_threads=0):
+    """h_bits: uint32 [n_chunks, N] fp32 patterns. Returns (proofs uint8 [n_chunks, 2+4k], status[, idx])."""
+    h = np.ascontiguousarray(h_bits, dtype=np.uint32)
+    assert h.ndim == 2
+    n_chunks, n = h.shape
+    proofs = np.zeros((n_chunks, proof_bytes32(k)), dtype=np.uint8)
+    status = np.zeros(n_chunks, dtype=np.uint8)
+    idx = np.zeros((n_chunks, k), dtype=np.uint32) if want_topk else None
+    nt = n_threads if n_threads > 0 else max_threads()
+    rc = _load().toploc_oracle32_build(_ptr(h), n_chunks, n, k, int(M), _ptr(proofs), _ptr(status),
+                                       _ptr(idx) if want_topk else None, nt)
+    if rc:
+        raise ValueError("oracle build32: bad arguments")
+    return (proofs, status, idx) if want_topk else (proofs, status)
+
+
+def verify_mixed(h_bits, h_dtype, proofs, p_dtype, k, thresholds=None, n_threads=0):
+    """Algorithm 2 with activations of h_dtype and proofs of p_dtype; comparisons and (by default)
+    thresholds are those of the validator's precision h_dtype."""
+    h = _patterns(h_bits, h_dtype)
+    assert h.ndim == 2
+    n_chunks, n = h.shape
+    proofs = np.ascontiguousarray(proofs, dtype=np.uint8)
+    assert proofs.shape == (n_chunks, proof_bytes32(k) if p_dtype == F32 else proof_bytes(k))
+    if thresholds is None:
+        thresholds = F32_THRESHOLDS if h_dtype == F32 else (T_EXP, T_MEAN, T_MEDIAN)
+    res = np.zeros(n_chunks, dtype=RESULT_DTYPE)
+    nt = n_threads if n_threads > 0 else max_threads()
+    rc = _load().toploc_oracle32_verify(_ptr(h), h_dtype, n_chunks, n, k, _ptr(proofs), p_dtype,
+                                        PRIME32 if p_dtype == F32 else PRIME, int(thresholds[0]), int(thresholds[1]),
+                                        int(thresholds[2]), _ptr(res), nt)
+    if rc:
+        raise ValueError("oracle verify_mixed: bad arguments")
+    return res
