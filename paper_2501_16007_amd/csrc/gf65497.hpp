@@ -70,4 +70,36 @@ __device__ __forceinline__ uint32_t invmod(uint32_t a)
     return r;
 }
 
+// The field as the interpolation and evaluation code sees it.
+struct Field16 {
+    typedef uint16_t elem_t;                 // a residue in LDS
+    static constexpr uint32_t P = kPrime;
+    static constexpr int WORDS = 1;          // 16-bit words of an encoded coefficient
+
+    static __device__ __forceinline__ uint32_t from_pattern(uint32_t bits) { return bits >= P ? bits - P : bits; }
+    // (i mod m) < 65536 < 2p: residues 65497..65535 alias 0..38
+    static __device__ __forceinline__ uint32_t from_residue(uint32_t x) { return x >= P ? x - P : x; }
+    static __device__ __forceinline__ uint32_t mulmod(uint32_t a, uint32_t b) { return toploc::mulmod(a, b); }
+    static __device__ __forceinline__ uint32_t muladdmod(uint32_t a, uint32_t b, uint32_t c)
+    {
+        return toploc::muladdmod(a, b, c);
+    }
+    static __device__ __forceinline__ uint32_t addmod(uint32_t a, uint32_t b)   // a, b < p
+    {
+        const uint32_t s = a + b;
+        return s >= P ? s - P : s;
+    }
+    static __device__ __forceinline__ uint32_t submod(uint32_t a, uint32_t b) { return toploc::submod(a, b); }
+    static __device__ __forceinline__ uint32_t neg(uint32_t a) { return a ? P - a : 0u; }
+    static __device__ __forceinline__ uint32_t inv(uint32_t a) { return invmod(a); }
+    // sum of fewer than 2^20 products of residues, unreduced in 64 bits
+    struct Acc {
+        uint64_t v;
+        __device__ __forceinline__ Acc() : v(0) {}
+        __device__ __forceinline__ void mac(uint32_t a, uint32_t b) { v += (uint64_t)mul24(a, b); }
+        __device__ __forceinline__ void add(uint32_t x) { v += x; }
+        __device__ __forceinline__ uint32_t reduce() const { return reduce64(v); }
+    };
+};
+
 }  // namespace toploc

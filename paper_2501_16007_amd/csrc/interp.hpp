@@ -1,7 +1,8 @@
 // Steps 2-5 of the paper's Algorithm 1 for one chunk, one workgroup:
 // findInjectiveModulus (Algorithm 6), i mod m, InterpolateModPolynomial (what
-// Algorithm 3 returns, with the inverses of Algorithm 4) -- all in GF(65497) on the
-// integer ALUs, operands staged in LDS.
+// Algorithm 3 returns, with the inverses of Algorithm 4) -- all in GF(p) on the integer
+// ALUs, operands staged in LDS.  The field F is GF(65497) for bf16 patterns (gf65497.hpp)
+// and GF(2^32 - 5) for fp32 patterns (gf32.hpp).
 //
 // The interpolating polynomial of degree < k through k points is unique, so any
 // exact method yields the bytes the paper's Newton form would.  The Lagrange form
@@ -15,11 +16,12 @@
 // Powers come from two small tables per point, x^r = x^(16 r1) * x^(r0) with r = 16 r1 + r0
 // (baby steps B[j][r0], giant steps G[r1][j]): about 25 modular multiplications per point
 // instead of k, and both matrix products (d and S) become sums of plain products, which
-// are accumulated unreduced in 64 bits and reduced once.
+// are accumulated unreduced (64 bits, 96 bits in the larger field) and reduced once.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "gf32.hpp"
 #include "gf65497.hpp"
 
 namespace toploc {
@@ -28,21 +30,22 @@ constexpr uint32_t kModHigh = 65536u;
 constexpr uint32_t kModLow = 32769u;  // 2^15 + 1
 constexpr uint32_t kBaby = 16u;       // baby-step table width
 
-template <int KMAX>
+template <int KMAX, typename F = Field16>
 struct InterpShared {
     static_assert(KMAX % 16 == 0, "giant steps cover 16 powers each");
+    typedef typename F::elem_t E;
     uint32_t idx[KMAX];       // top-k flat indices
-    uint16_t xs[KMAX];        // (idx mod m) mod p
-    uint16_t ys[KMAX];        // bf16 pattern mod p
-    uint16_t pa[KMAX + 2];    // product tree ping
-    uint16_t pb[KMAX + 2];    // product tree pong
-    uint16_t wder[KMAX];      // coefficients of W'
-    uint16_t S[KMAX];
+    E xs[KMAX];               // (idx mod m) mod p
+    E ys[KMAX];               // pattern mod p
+    E pa[KMAX + 2];           // product tree ping
+    E pb[KMAX + 2];           // product tree pong
+    E wder[KMAX];             // coefficients of W'
+    E S[KMAX];
     union {
-        uint32_t bitmap[2048];                    // modulus search: one bit per field element
+        uint32_t bitmap[2048];                    // modulus search: one bit per residue below 65536
         struct {
-            uint16_t B[KMAX * 16];                // B[j][r0] = x_j^r0
-            uint16_t G[(KMAX / 16) * KMAX];       // G[r1][j] = x_j^(16 r1), later a_j x_j^(16 r1)
+            E B[KMAX * 16];                       // B[j][r0] = x_j^r0
+            E G[(KMAX / 16) * KMAX];              // G[r1][j] = x_j^(16 r1), later a_j x_j^(16 r1)
         } pw;
     } u;
     uint32_t collide[2];
@@ -52,16 +55,15 @@ struct InterpShared {
 // (i mod m) mod p: the largest m in [2^15+1, 65536] for which the k points are
 // distinct.  xs[j] receives the mapped index.  Returns 0 when no m works.
 // All threads call; s.u.bitmap must be zero and is left zero; ends with a barrier.
-template <int THREADS, int KMAX>
-__device__ __forceinline__ uint32_t find_modulus(InterpShared<KMAX>& s, uint32_t k)
+template <int THREADS, int KMAX, typename F>
+__device__ __forceinline__ uint32_t find_modulus(InterpShared<KMAX, F>& s, uint32_t k)
 {
     const uint32_t tid = threadIdx.x;
     for (uint32_t m = kModHigh; m >= kModLow; --m) {
         uint32_t* flag = &s.collide[m & 1u];
         for (uint32_t j = tid; j < k; j += THREADS) {
-            uint32_t x = s.idx[j] % m;
-            x = x >= kPrime ? x - kPrime : x;  // x < 65536 < 2p
-            s.xs[j] = (uint16_t)x;
+            const uint32_t x = F::from_residue(s.idx[j] % m);  // < 65536
+            s.xs[j] = (typename F::elem_t)x;
             const uint32_t bit = 1u << (x & 31u);
             if (atomicOr(&s.u.bitmap[x >> 5], bit) & bit) *flag = 1u;
         }
@@ -77,9 +79,11 @@ __device__ __forceinline__ uint32_t find_modulus(InterpShared<KMAX>& s, uint32_t
 
 // coef_out[0..k) <- coefficients (ascending powers) of the polynomial through
 // (s.xs[j], s.ys[j]); the xs must be distinct.  All threads call; ends with a barrier.
-template <int THREADS, int KMAX>
-__device__ __forceinline__ void interpolate(InterpShared<KMAX>& s, uint32_t k, uint32_t* coef_out)
+template <int THREADS, int KMAX, typename F>
+__device__ __forceinline__ void interpolate(InterpShared<KMAX, F>& s, uint32_t k, uint32_t* coef_out)
 {
+    typedef typename F::elem_t E;
+    typedef typename F::Acc Acc;
     // L lanes share a point or an output (alternate terms) when the workgroup has lanes to spare
     constexpr int L = (2 * KMAX <= THREADS) ? 2 : 1;
     constexpr int PPT = (KMAX * L + THREADS - 1) / THREADS;  // points per lane
@@ -88,9 +92,9 @@ __device__ __forceinline__ void interpolate(InterpShared<KMAX>& s, uint32_t k, u
     const uint32_t n_giant = (k + kBaby - 1u) / kBaby;
 
     // ---- W(X) = prod (X - x_j): pairwise products of monic polynomials ----
-    uint16_t* src = s.pa;
-    uint16_t* dst = s.pb;
-    for (uint32_t j = tid; j < k; j += THREADS) src[j] = (uint16_t)(s.xs[j] ? kPrime - s.xs[j] : 0u);
+    E* src = s.pa;
+    E* dst = s.pb;
+    for (uint32_t j = tid; j < k; j += THREADS) src[j] = (E)F::neg(s.xs[j]);
     __syncthreads();
     for (uint32_t d = 1; d < k; d <<= 1) {
         for (uint32_t o = tid / L; o < k; o += THREADS / L) {
@@ -99,33 +103,30 @@ __device__ __forceinline__ void interpolate(InterpShared<KMAX>& s, uint32_t k, u
             const uint32_t df = (k - start) < d ? (k - start) : d;
             const uint32_t rem = k - start - df;
             const uint32_t dg = rem < d ? rem : d;
-            const uint16_t* f = src + start;        // f_0..f_{df-1}, f_df = 1
-            const uint16_t* g = src + start + df;   // g_0..g_{dg-1}, g_dg = 1
+            const E* f = src + start;        // f_0..f_{df-1}, f_df = 1
+            const E* g = src + start + df;   // g_0..g_{dg-1}, g_dg = 1
             // h_t = sum_i f_i g_{t-i}: the terms with both coefficients stored ...
             const uint32_t lo = t + 1u > dg ? t + 1u - dg : 0u;
             const uint32_t hi = t < df ? t + 1u : df;   // exclusive
-            uint64_t acc = 0;
+            Acc acc;
 #pragma unroll 4
-            for (uint32_t i = lo + h; i < hi; i += L) acc += (uint64_t)mul24(f[i], g[t - i]);
+            for (uint32_t i = lo + h; i < hi; i += L) acc.mac(f[i], g[t - i]);
             // ... and the two terms that meet a leading 1
             if (h == 0) {
-                if (t >= df) acc += g[t - df];
-                if (t >= dg) acc += f[t - dg];
+                if (t >= df) acc.add(g[t - df]);
+                if (t >= dg) acc.add(f[t - dg]);
             }
-            uint32_t c = reduce64(acc);
-            if (L == 2) {
-                c += __shfl_xor(c, 1);
-                c = c >= kPrime ? c - kPrime : c;
-            }
-            if (h == 0) dst[o] = (uint16_t)c;
+            uint32_t c = acc.reduce();
+            if (L == 2) c = F::addmod(c, __shfl_xor(c, 1));
+            if (h == 0) dst[o] = (E)c;
         }
         __syncthreads();
-        uint16_t* tmp = src; src = dst; dst = tmp;
+        E* tmp = src; src = dst; dst = tmp;
     }
-    const uint16_t* W = src;  // W_0..W_{k-1}; W_k = 1
+    const E* W = src;  // W_0..W_{k-1}; W_k = 1
     // ---- W'(X) coefficients: wder_r = (r+1) W_{r+1}; power tables of every point ----
     for (uint32_t r = tid; r < k; r += THREADS)
-        s.wder[r] = (uint16_t)mulmod(r + 1, r + 1 == k ? 1u : (uint32_t)W[r + 1]);
+        s.wder[r] = (E)F::mulmod(r + 1, r + 1 == k ? 1u : (uint32_t)W[r + 1]);
 #pragma unroll
     for (int i = 0; i < PPT; ++i) {
         const uint32_t j = (tid + i * THREADS) / L;
@@ -135,19 +136,19 @@ __device__ __forceinline__ void interpolate(InterpShared<KMAX>& s, uint32_t k, u
                 uint32_t p = 1u;
 #pragma unroll
                 for (uint32_t r0 = 0; r0 < kBaby; ++r0) {
-                    s.u.pw.B[j * kBaby + r0] = (uint16_t)p;
-                    p = mulmod(p, x);
+                    s.u.pw.B[j * kBaby + r0] = (E)p;
+                    p = F::mulmod(p, x);
                 }
             }
             if (L == 1 || h == 1) {   // giant steps 1, x^16, x^32, ..
-                uint32_t x16 = mulmod(x, x);
-                x16 = mulmod(x16, x16);
-                x16 = mulmod(x16, x16);
-                x16 = mulmod(x16, x16);
+                uint32_t x16 = F::mulmod(x, x);
+                x16 = F::mulmod(x16, x16);
+                x16 = F::mulmod(x16, x16);
+                x16 = F::mulmod(x16, x16);
                 uint32_t p = 1u;
                 for (uint32_t r1 = 0; r1 < n_giant; ++r1) {
-                    s.u.pw.G[r1 * KMAX + j] = (uint16_t)p;
-                    p = mulmod(p, x16);
+                    s.u.pw.G[r1 * KMAX + j] = (E)p;
+                    p = F::mulmod(p, x16);
                 }
             }
         }
@@ -161,57 +162,50 @@ __device__ __forceinline__ void interpolate(InterpShared<KMAX>& s, uint32_t k, u
             uint32_t brow[kBaby];
 #pragma unroll
             for (uint32_t r0 = 0; r0 < kBaby; ++r0) brow[r0] = s.u.pw.B[j * kBaby + r0];
-            uint32_t d = 0;
+            Acc dacc;   // sum over r1 of (inner sum mod p) * x_j^(16 r1)
             for (uint32_t r1 = h; r1 < n_giant; r1 += L) {
                 const uint32_t rbase = r1 * kBaby;
-                uint64_t acc = 0;
+                Acc acc;
 #pragma unroll
                 for (uint32_t r0 = 0; r0 < kBaby; ++r0)
-                    if (rbase + r0 < k) acc += (uint64_t)mul24(s.wder[rbase + r0], brow[r0]);
-                d += mulmod(reduce64(acc), s.u.pw.G[r1 * KMAX + j]);   // at most 32 terms < p: no overflow
+                    if (rbase + r0 < k) acc.mac(s.wder[rbase + r0], brow[r0]);
+                dacc.mac(acc.reduce(), s.u.pw.G[r1 * KMAX + j]);
             }
-            d = reduce32(d);
+            uint32_t d = dacc.reduce();
             uint32_t a = 0;
             if (L == 2) {
-                d += __shfl_xor(d, 1);
-                d = d >= kPrime ? d - kPrime : d;
-                if (h == 0) a = mulmod(s.ys[j], invmod(d));
+                d = F::addmod(d, __shfl_xor(d, 1));
+                if (h == 0) a = F::mulmod(s.ys[j], F::inv(d));
                 a = __shfl(a, (int)(__lane_id() & ~1u));
             } else {
-                a = mulmod(s.ys[j], invmod(d));
+                a = F::mulmod(s.ys[j], F::inv(d));
             }
             for (uint32_t r1 = h; r1 < n_giant; r1 += L)
-                s.u.pw.G[r1 * KMAX + j] = (uint16_t)mulmod(a, s.u.pw.G[r1 * KMAX + j]);
+                s.u.pw.G[r1 * KMAX + j] = (E)F::mulmod(a, s.u.pw.G[r1 * KMAX + j]);
         }
     }
     __syncthreads();
     // ---- S_r = sum_j (a_j x_j^(16 r1)) x_j^r0, r = 16 r1 + r0; lane h takes j = h mod L ----
     for (uint32_t r = tid / L; r < k; r += THREADS / L) {
-        const uint16_t* arow = &s.u.pw.G[(r / kBaby) * KMAX];
-        const uint16_t* bcol = &s.u.pw.B[r % kBaby];
-        uint64_t acc = 0;
+        const E* arow = &s.u.pw.G[(r / kBaby) * KMAX];
+        const E* bcol = &s.u.pw.B[r % kBaby];
+        Acc acc;
 #pragma unroll 8
-        for (uint32_t j = h; j < k; j += L) acc += (uint64_t)mul24(arow[j], bcol[j * kBaby]);
-        uint32_t v = reduce64(acc);
-        if (L == 2) {
-            v += __shfl_xor(v, 1);
-            v = v >= kPrime ? v - kPrime : v;
-        }
-        if (h == 0) s.S[r] = (uint16_t)v;
+        for (uint32_t j = h; j < k; j += L) acc.mac(arow[j], bcol[j * kBaby]);
+        uint32_t v = acc.reduce();
+        if (L == 2) v = F::addmod(v, __shfl_xor(v, 1));
+        if (h == 0) s.S[r] = (E)v;
     }
     __syncthreads();
     // ---- c_i = sum_{r=0}^{k-1-i} W_{i+1+r} S_r, lane h takes r = h mod L ----
     for (uint32_t i = tid / L; i < k; i += THREADS / L) {
-        uint64_t acc = 0;
+        Acc acc;
         const uint32_t last = k - 1u - i;                 // W_{i+1+last} = W_k = 1
 #pragma unroll 4
-        for (uint32_t r = h; r < last; r += L) acc += (uint64_t)mul24(W[i + 1u + r], s.S[r]);
-        if ((last % L) == h) acc += s.S[last];
-        uint32_t c = reduce64(acc);
-        if (L == 2) {
-            c += __shfl_xor(c, 1);
-            c = c >= kPrime ? c - kPrime : c;
-        }
+        for (uint32_t r = h; r < last; r += L) acc.mac(W[i + 1u + r], s.S[r]);
+        if ((last % L) == h) acc.add(s.S[last]);
+        uint32_t c = acc.reduce();
+        if (L == 2) c = F::addmod(c, __shfl_xor(c, 1));
         if (h == 0) coef_out[i] = c;
     }
     __syncthreads();
@@ -219,24 +213,28 @@ __device__ __forceinline__ void interpolate(InterpShared<KMAX>& s, uint32_t k, u
 
 // Remaining steps of Algorithm 1 for one chunk whose top-k pairs sit in s.idx / s.ys
 // (ys already reduced mod p): modulus, index map, interpolation, encode.  `proof`
-// points at the chunk's 2 + 2k bytes, `status` at its status byte.
-template <int THREADS, int KMAX>
-__device__ __forceinline__ void finish_proof(InterpShared<KMAX>& s, uint32_t* coef, uint32_t k, uint16_t* proof,
+// points at the chunk's 2 + 2k bytes (2 + 4k in the 32-bit field: a coefficient is written
+// as F::WORDS 16-bit words, low word first), `status` at its status byte.
+template <int THREADS, int KMAX, typename F>
+__device__ __forceinline__ void finish_proof(InterpShared<KMAX, F>& s, uint32_t* coef, uint32_t k, uint16_t* proof,
                                              uint8_t* status)
 {
     const uint32_t tid = threadIdx.x;
     for (uint32_t w = tid; w < 2048; w += THREADS) s.u.bitmap[w] = 0;
     if (tid == 0) { s.collide[0] = 0; s.collide[1] = 0; }
     __syncthreads();
-    const uint32_t m = find_modulus<THREADS, KMAX>(s, k);
+    const uint32_t m = find_modulus<THREADS>(s, k);
     if (m == 0) {  // uniform
-        for (uint32_t j = tid; j <= k; j += THREADS) proof[j] = 0;
+        for (uint32_t j = tid; j <= k * F::WORDS; j += THREADS) proof[j] = 0;
         if (tid == 0) *status = 1;  // TOPLOC_CHUNK_NO_MODULUS
         return;
     }
-    interpolate<THREADS, KMAX>(s, k, coef);
+    interpolate<THREADS>(s, k, coef);
     if (tid == 0) { proof[0] = (uint16_t)(m & 0xFFFFu); *status = 0; }
-    for (uint32_t j = tid; j < k; j += THREADS) proof[1 + j] = (uint16_t)coef[j];
+    for (uint32_t j = tid; j < k; j += THREADS) {
+        proof[1 + j * F::WORDS] = (uint16_t)coef[j];
+        if (F::WORDS == 2) proof[2 + j * F::WORDS] = (uint16_t)(coef[j] >> 16);
+    }
 }
 
 }  // namespace toploc

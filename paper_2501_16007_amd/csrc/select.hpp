@@ -1,8 +1,8 @@
-// Exact top-k by magnitude over one chunk of bf16 patterns, one workgroup per
+// Exact top-k by magnitude over one chunk of bf16 (or fp32) patterns, one workgroup per
 // chunk, one pass over HBM.  This is topk(h, k) of the paper's Algorithm 1 and
 // Algorithm 2 ("top-k magnitude elements", Section 5.3) with the total order
 //     a before b  <=>  |a| > |b|  or  (|a| == |b| and index(a) < index(b)),
-// |x| taken as the integer (bits & 0x7FFF).
+// |x| taken as the integer (bits & 0x7FFF), for fp32 (bits & 0x7FFFFFFF).
 //
 // Method (a streaming filter with a rising threshold, not a sort):
 //   * every lane reads 16 bytes (8 values) per load, U loads per round, and the
@@ -43,15 +43,59 @@ typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-template <int THREADS, int CAP, int QCAP>
+// largest of the 8 bf16 magnitudes of a vector
+__device__ __forceinline__ int32_t vec_max_mag(const u32x4& r)
+{
+    const uint32_t a = r.x & 0x7FFF7FFFu, b = r.y & 0x7FFF7FFFu;
+    const uint32_t c = r.z & 0x7FFF7FFFu, d = r.w & 0x7FFF7FFFu;
+    const u16x2 m01 = __builtin_elementwise_max(__builtin_bit_cast(u16x2, a), __builtin_bit_cast(u16x2, b));
+    const u16x2 m23 = __builtin_elementwise_max(__builtin_bit_cast(u16x2, c), __builtin_bit_cast(u16x2, d));
+    const u16x2 mm = __builtin_elementwise_max(m01, m23);
+    return (int32_t)(mm.x > mm.y ? mm.x : mm.y);
+}
+
+// What the selection needs to know about the element type.  A 16-byte vector holds ELEMS
+// patterns; the magnitude is (pattern & MAG_MASK); the prune resolves the magnitude in
+// LEVELS radix digits, most significant first, digit l being width(l) bits at shift(l)
+// (exponent, then mantissa pieces); half a vector (8 bytes) holds ELEMS/2 patterns.
+struct Bf16Fmt {
+    typedef uint16_t bits_t;
+    static constexpr int ELEMS = 8;
+    static constexpr uint32_t MAG_MASK = 0x7FFFu;
+    static constexpr int LEVELS = 2;
+    static constexpr int shift(int l) { return l == 0 ? 7 : 0; }
+    static constexpr int width(int l) { return l == 0 ? 8 : 7; }
+    static __device__ __forceinline__ int32_t vec_max(const u32x4& r) { return vec_max_mag(r); }
+    static __device__ __forceinline__ uint32_t half_elem(const u32x2& w, int e)
+    {
+        return (((e >> 1) ? w.y : w.x) >> (16 * (e & 1))) & 0xFFFFu;
+    }
+};
+struct F32Fmt {
+    typedef uint32_t bits_t;
+    static constexpr int ELEMS = 4;
+    static constexpr uint32_t MAG_MASK = 0x7FFFFFFFu;
+    static constexpr int LEVELS = 4;
+    static constexpr int shift(int l) { return l == 0 ? 23 : l == 1 ? 15 : l == 2 ? 7 : 0; }
+    static constexpr int width(int l) { return l == 3 ? 7 : 8; }
+    static __device__ __forceinline__ int32_t vec_max(const u32x4& r)
+    {
+        const uint32_t a = r.x & MAG_MASK, b = r.y & MAG_MASK, c = r.z & MAG_MASK, d = r.w & MAG_MASK;
+        const uint32_t ab = a > b ? a : b, cd = c > d ? c : d;
+        return (int32_t)(ab > cd ? ab : cd);
+    }
+    static __device__ __forceinline__ uint32_t half_elem(const u32x2& w, int e) { return e ? w.y : w.x; }
+};
+
+template <int THREADS, int CAP, int QCAP, typename Fmt = Bf16Fmt>
 struct SelectShared {
+    typedef Fmt fmt;
     u32x4 qvec[QCAP];         // queue: vectors holding at least one magnitude >= tm
     uint32_t qidx[QCAP];      // their vector index inside the chunk
     uint32_t cand_idx[CAP];   // candidates: flat index
-    uint16_t cand_bits[CAP];  //             bf16 pattern
+    typename Fmt::bits_t cand_bits[CAP];  //     pattern
     uint16_t eq_slot[CAP];    // prune: slots whose magnitude equals the new threshold
-    uint32_t hist_e[256];     // prune: exponent histogram
-    uint32_t hist_m[128];     // prune: mantissa histogram inside the threshold exponent
+    uint32_t hist[Fmt::LEVELS][256];  // prune: one histogram per radix digit
     uint32_t qcount;          // queue slots handed out (may run past QCAP on overflow)
     uint32_t count;           // candidate slots in use
     uint32_t eq_count;
@@ -113,8 +157,8 @@ __device__ __forceinline__ bool before(int32_t mag, uint32_t idx, const Threshol
 // ends with a barrier.  Returns the number of slots that had been handed out: a value
 // above CAP means appends were dropped, and nothing is pruned then (the caller redoes
 // them); a value in (limit, CAP] means it pruned and `t` is the new threshold.
-template <int THREADS, int CAP, int QCAP>
-__device__ TOPLOC_PRUNE_ATTR uint32_t prune_if_above(SelectShared<THREADS, CAP, QCAP>& s, uint32_t k, uint32_t limit,
+template <int THREADS, int CAP, int QCAP, typename Fmt>
+__device__ TOPLOC_PRUNE_ATTR uint32_t prune_if_above(SelectShared<THREADS, CAP, QCAP, Fmt>& s, uint32_t k, uint32_t limit,
                                                      Threshold& t)
 {
     const uint32_t tid = threadIdx.x;
@@ -124,29 +168,30 @@ __device__ TOPLOC_PRUNE_ATTR uint32_t prune_if_above(SelectShared<THREADS, CAP, 
         __syncthreads();  // everyone has read the count before anyone appends again
         return M;
     }
-    for (uint32_t b = tid; b < 256; b += THREADS) s.hist_e[b] = 0;
-    for (uint32_t b = tid; b < 128; b += THREADS) s.hist_m[b] = 0;
+    for (uint32_t b = tid; b < 256u * Fmt::LEVELS; b += THREADS) (&s.hist[0][0])[b] = 0;
     if (tid == 0) { s.eq_count = 0; s.hole_count = 0; s.move_count = 0; }
     __syncthreads();
+    // radix descent: digit l of the k-th largest magnitude, among the entries that share its higher digits
+    uint32_t prefix = 0, above = 0;
+#pragma unroll
+    for (int l = 0; l < Fmt::LEVELS; ++l) {
+        const int sh = Fmt::shift(l), w = Fmt::width(l);  // constants once the loop is unrolled
 #pragma unroll 1
-    for (uint32_t slot = tid; slot < M; slot += THREADS)
-        atomicAdd(&s.hist_e[((uint32_t)s.cand_bits[slot] & 0x7FFFu) >> 7], 1u);
-    __syncthreads();
-    uint32_t e_star, above_e;
-    find_bin<4>(s.hist_e, 0u, k, e_star, above_e);
-#pragma unroll 1
-    for (uint32_t slot = tid; slot < M; slot += THREADS) {
-        const uint32_t mag = (uint32_t)s.cand_bits[slot] & 0x7FFFu;
-        if ((mag >> 7) == e_star) atomicAdd(&s.hist_m[mag & 0x7Fu], 1u);
+        for (uint32_t slot = tid; slot < M; slot += THREADS) {
+            const uint32_t mag = (uint32_t)s.cand_bits[slot] & Fmt::MAG_MASK;
+            if (l == 0 || (mag >> (sh + w)) == prefix) atomicAdd(&s.hist[l][(mag >> sh) & ((1u << w) - 1u)], 1u);
+        }
+        __syncthreads();
+        uint32_t digit;
+        if (w == 8) find_bin<4>(s.hist[l], above, k, digit, above);
+        else find_bin<2>(s.hist[l], above, k, digit, above);
+        prefix = (prefix << w) | digit;
     }
-    __syncthreads();
-    uint32_t m_star, g;
-    find_bin<2>(s.hist_m, above_e, k, m_star, g);
-    const uint32_t new_tm = (e_star << 7) | m_star;
-    const uint32_t need = k - g;  // how many of the entries with magnitude new_tm survive (>= 1)
+    const uint32_t new_tm = prefix;
+    const uint32_t need = k - above;  // how many of the entries with magnitude new_tm survive (>= 1)
 #pragma unroll 1
     for (uint32_t slot = tid; slot < M; slot += THREADS)
-        if (((uint32_t)s.cand_bits[slot] & 0x7FFFu) == new_tm) {
+        if (((uint32_t)s.cand_bits[slot] & Fmt::MAG_MASK) == new_tm) {
             const uint32_t q = atomicAdd(&s.eq_count, 1u);
             s.eq_slot[q] = (uint16_t)slot;
         }
@@ -166,7 +211,7 @@ __device__ TOPLOC_PRUNE_ATTR uint32_t prune_if_above(SelectShared<THREADS, CAP, 
     // every survivor at or above slot k moves into a slot below k that lost its entry.
 #pragma unroll 1
     for (uint32_t slot = tid; slot < k; slot += THREADS) {
-        const int32_t mag = (int32_t)((uint32_t)s.cand_bits[slot] & 0x7FFFu);
+        const int32_t mag = (int32_t)((uint32_t)s.cand_bits[slot] & Fmt::MAG_MASK);
         if (!(mag > t.tm || (mag == t.tm && s.cand_idx[slot] <= t.ti)))
             s.eq_slot[atomicAdd(&s.hole_count, 1u)] = (uint16_t)slot;  // eq_slot is free again: list of holes
     }
@@ -175,11 +220,11 @@ __device__ TOPLOC_PRUNE_ATTR uint32_t prune_if_above(SelectShared<THREADS, CAP, 
     for (uint32_t slot = k + tid; slot < M; slot += THREADS) {
         const uint32_t bits = s.cand_bits[slot];
         const uint32_t idx = s.cand_idx[slot];
-        const int32_t mag = (int32_t)(bits & 0x7FFFu);
+        const int32_t mag = (int32_t)(bits & Fmt::MAG_MASK);
         if (mag > t.tm || (mag == t.tm && idx <= t.ti)) {
             const uint32_t dest = s.eq_slot[atomicAdd(&s.move_count, 1u)];
             s.cand_idx[dest] = idx;
-            s.cand_bits[dest] = (uint16_t)bits;
+            s.cand_bits[dest] = (typename Fmt::bits_t)bits;
         }
     }
     if (tid == 0) s.count = k;
@@ -187,27 +232,28 @@ __device__ TOPLOC_PRUNE_ATTR uint32_t prune_if_above(SelectShared<THREADS, CAP, 
     return M;
 }
 
-// Exact test of the queued vectors [q0, q1): two lanes share a vector; a value that comes
+// Exact test of the queued vectors [q0, q1): two lanes share a vector (half of its values each); a value that comes
 // before the threshold element takes a candidate slot (slots past CAP are counted but
 // not written).
-template <int THREADS, int CAP, int QCAP>
-__device__ __forceinline__ void drain_range(SelectShared<THREADS, CAP, QCAP>& s, uint32_t q0, uint32_t q1,
+template <int THREADS, int CAP, int QCAP, typename Fmt>
+__device__ __forceinline__ void drain_range(SelectShared<THREADS, CAP, QCAP, Fmt>& s, uint32_t q0, uint32_t q1,
                                             const Threshold& t)
 {
+    constexpr int HALF = Fmt::ELEMS / 2;
     const uint32_t tid = threadIdx.x;
     const uint32_t half = tid & 1u;
     for (uint32_t q = q0 + (tid >> 1); q < q1; q += THREADS / 2) {
         const u32x2 w = reinterpret_cast<const u32x2*>(&s.qvec[q])[half];
-        const uint32_t ebase = s.qidx[q] * 8u + half * 4u;
+        const uint32_t ebase = s.qidx[q] * (uint32_t)Fmt::ELEMS + half * (uint32_t)HALF;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const uint32_t bits = (((e >> 1) ? w.y : w.x) >> (16 * (e & 1))) & 0xFFFFu;
-            const int32_t mag = (int32_t)(bits & 0x7FFFu);
+        for (int e = 0; e < HALF; ++e) {
+            const uint32_t bits = Fmt::half_elem(w, e);
+            const int32_t mag = (int32_t)(bits & Fmt::MAG_MASK);
             if (before(mag, ebase + e, t)) {
                 const uint32_t slot = atomicAdd(&s.count, 1u);
                 if (slot < (uint32_t)CAP) {
                     s.cand_idx[slot] = ebase + e;
-                    s.cand_bits[slot] = (uint16_t)bits;
+                    s.cand_bits[slot] = (typename Fmt::bits_t)bits;
                 }
             }
         }
@@ -223,47 +269,29 @@ __device__ __forceinline__ void drain_range(SelectShared<THREADS, CAP, QCAP>& s,
 // CAP/2 values to a buffer holding at most CAP/2.
 // Called by all threads after a barrier that made the queue writes visible; ends with
 // a barrier.  Returns true when lanes are still waiting for room in the queue.
-template <int THREADS, int CAP, int QCAP>
-__device__ TOPLOC_DRAIN_ATTR bool drain(SelectShared<THREADS, CAP, QCAP>& s, uint32_t k, uint32_t limit, Threshold& t)
+template <int THREADS, int CAP, int QCAP, typename Fmt>
+__device__ TOPLOC_DRAIN_ATTR bool drain(SelectShared<THREADS, CAP, QCAP, Fmt>& s, uint32_t k, uint32_t limit, Threshold& t)
 {
-    constexpr uint32_t BATCH = (CAP / 16 < THREADS / 2) ? CAP / 16 : THREADS / 2;  // vectors: 8 * BATCH <= CAP / 2
+    constexpr uint32_t BATCH = (CAP / 16 < THREADS / 2) ? CAP / 16 : THREADS / 2;  // vectors: ELEMS * BATCH <= CAP / 2
     const uint32_t tid = threadIdx.x;
     const uint32_t raw = s.qcount;
     const uint32_t nq = raw < (uint32_t)QCAP ? raw : (uint32_t)QCAP;
     const uint32_t count0 = s.count;  // <= CAP/2; only drains and prunes change it
     limit = limit < (uint32_t)(CAP / 2) ? limit : (uint32_t)(CAP / 2);
-    drain_range<THREADS, CAP, QCAP>(s, 0u, nq, t);
-    if (prune_if_above<THREADS, CAP, QCAP>(s, k, limit, t) > (uint32_t)CAP) {  // uniform; rare
+    drain_range(s, 0u, nq, t);
+    if (prune_if_above(s, k, limit, t) > (uint32_t)CAP) {  // uniform; rare
         if (tid == 0) s.count = count0;
         __syncthreads();
         for (uint32_t b0 = 0; b0 < nq; b0 += BATCH) {
             const uint32_t b1 = b0 + BATCH < nq ? b0 + BATCH : nq;
-            drain_range<THREADS, CAP, QCAP>(s, b0, b1, t);
-            (void)prune_if_above<THREADS, CAP, QCAP>(s, k, CAP / 2, t);
+            drain_range(s, b0, b1, t);
+            (void)prune_if_above(s, k, CAP / 2, t);
         }
-        (void)prune_if_above<THREADS, CAP, QCAP>(s, k, limit, t);
+        (void)prune_if_above(s, k, limit, t);
     }
     if (tid == 0) s.qcount = 0;
     __syncthreads();
     return raw > (uint32_t)QCAP;
-}
-
-// value e (0..7) of a 16-byte vector
-__device__ __forceinline__ uint32_t vec_elem(const u32x4& r, int e)
-{
-    const uint32_t w = (e >> 1) == 0 ? r.x : (e >> 1) == 1 ? r.y : (e >> 1) == 2 ? r.z : r.w;
-    return (w >> (16 * (e & 1))) & 0xFFFFu;
-}
-
-// largest of the 8 magnitudes of a vector
-__device__ __forceinline__ int32_t vec_max_mag(const u32x4& r)
-{
-    const uint32_t a = r.x & 0x7FFF7FFFu, b = r.y & 0x7FFF7FFFu;
-    const uint32_t c = r.z & 0x7FFF7FFFu, d = r.w & 0x7FFF7FFFu;
-    const u16x2 m01 = __builtin_elementwise_max(__builtin_bit_cast(u16x2, a), __builtin_bit_cast(u16x2, b));
-    const u16x2 m23 = __builtin_elementwise_max(__builtin_bit_cast(u16x2, c), __builtin_bit_cast(u16x2, d));
-    const u16x2 mm = __builtin_elementwise_max(m01, m23);
-    return (int32_t)(mm.x > mm.y ? mm.x : mm.y);
 }
 
 // number of set bits of `mask` below the calling lane
@@ -297,15 +325,15 @@ __device__ __forceinline__ void load_round(u32x4 (&buf)[U], const u32x4* __restr
 // barrier; otherwise the wave takes all its queue slots with one LDS atomic.  One barrier
 // per pass; the workgroup drains the queue when it passed its soft limit, and lanes that
 // found the queue full retry after the drain (against the new threshold).
-template <int THREADS, int U, int CAP, int QCAP>
+template <int THREADS, int U, int CAP, int QCAP, typename Fmt>
 __device__ __forceinline__ void examine_round(const u32x4 (&buf)[U], uint32_t b, uint32_t v1, uint32_t k,
-                                              SelectShared<THREADS, CAP, QCAP>& s, Threshold& t, uint32_t& round)
+                                              SelectShared<THREADS, CAP, QCAP, Fmt>& s, Threshold& t, uint32_t& round)
 {
     constexpr uint32_t QSOFT = QCAP / 2;
     const uint32_t tid = threadIdx.x;
     int32_t m[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) m[u] = vec_max_mag(buf[u]);
+    for (int u = 0; u < U; ++u) m[u] = Fmt::vec_max(buf[u]);
     uint32_t pend = 0;  // bit u: vector u still has to be queued
     if (b + THREADS * U <= v1) {  // uniform
 #pragma unroll
@@ -346,7 +374,7 @@ __device__ __forceinline__ void examine_round(const u32x4 (&buf)[U], uint32_t b,
         if (tid == 0) s.flag[(round + 2u) % 3u] = 0;  // the previous round's flag: read by all before this barrier
         ++round;
         if (!f) break;  // no slot at or past the soft limit was handed out: nothing is pending either
-        if (!drain<THREADS, CAP, QCAP>(s, k, TOPLOC_PRUNE_LIMIT(CAP, k), t)) break;
+        if (!drain(s, k, TOPLOC_PRUNE_LIMIT(CAP, k), t)) break;
 #pragma unroll
         for (int u = 0; u < U; ++u)
             if (m[u] < t.tm) pend &= ~(1u << u);
@@ -370,14 +398,14 @@ struct NoSeed {
 };
 
 // Top-k of the vectors [v0, v1) of the chunk at src (8 values per vector, flat index of
-// value e of vector v is 8v + e) into s.cand_idx / s.cand_bits [0 .. k), in no
+// value e of vector v is ELEMS*v + e) into s.cand_idx / s.cand_bits [0 .. k), in no
 // particular order (order_topk sorts them).
-// Requires k <= seeds + 8*(v1 - v0), k <= CAP/4, 8*v1 < 2^32.  All threads of the workgroup
+// Requires k <= seeds + ELEMS*(v1 - v0), k <= CAP/4, ELEMS*v1 < 2^32.  All threads of the workgroup
 // call it; it ends with a barrier.  Returns k and the threshold the selection ended with:
 // (0, 0xFFFFFFFF) as long as nothing had to be pruned, else the k-th element.
-template <int THREADS, int U, int CAP, int QCAP, typename Seed>
+template <int THREADS, int U, int CAP, int QCAP, typename Fmt, typename Seed>
 __device__ __forceinline__ SelectStart select_topk_from(const u32x4* __restrict__ src, uint32_t v0, uint32_t v1,
-                                                        SelectShared<THREADS, CAP, QCAP>& s, const Seed& seeder)
+                                                        SelectShared<THREADS, CAP, QCAP, Fmt>& s, const Seed& seeder)
 {
     constexpr uint32_t ROUND = THREADS * U;
     const uint32_t tid = threadIdx.x;
@@ -395,53 +423,54 @@ __device__ __forceinline__ SelectStart select_topk_from(const u32x4* __restrict_
 
     // First threshold: the largest magnitude of every vector of the first round belongs
     // to a distinct real element.  If at least k of those maxima have exponent >= e, then
-    // k elements have magnitude >= e << 7, and nothing below that can be in the top-k.
+    // k elements have magnitude >= e << (mantissa bits), and nothing below that can be in the top-k.
     // One exponent histogram finds the largest such e; exact thresholds follow from the
     // first prune.
     const uint32_t first = (v1 - v0) < ROUND ? (v1 - v0) : ROUND;
     if (n_seed == 0 && first >= k) {  // uniform
-        for (uint32_t b = tid; b < 256; b += THREADS) s.hist_e[b] = 0;
+        for (uint32_t b = tid; b < 256; b += THREADS) s.hist[0][b] = 0;
         __syncthreads();
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            if (v0 + u * THREADS + tid < v1) atomicAdd(&s.hist_e[(uint32_t)vec_max_mag(even[u]) >> 7], 1u);
+            if (v0 + u * THREADS + tid < v1) atomicAdd(&s.hist[0][(uint32_t)Fmt::vec_max(even[u]) >> Fmt::shift(0)], 1u);
         __syncthreads();
         uint32_t e_star, above;
-        find_bin<4>(s.hist_e, 0u, k, e_star, above);
-        t.tm = (int32_t)(e_star << 7);
+        find_bin<4>(s.hist[0], 0u, k, e_star, above);
+        t.tm = (int32_t)(e_star << Fmt::shift(0));
     }
     __syncthreads();
 
     uint32_t base = v0;  // v1 - v0 >= 1
     while (true) {
         load_round<THREADS, U>(odd, src, base + ROUND, v1);
-        examine_round<THREADS, U, CAP, QCAP>(even, base, v1, k, s, t, round);
+        examine_round<THREADS, U>(even, base, v1, k, s, t, round);
         base += ROUND;
         if (base >= v1) break;
         load_round<THREADS, U>(even, src, base + ROUND, v1);
-        examine_round<THREADS, U, CAP, QCAP>(odd, base, v1, k, s, t, round);
+        examine_round<THREADS, U>(odd, base, v1, k, s, t, round);
         base += ROUND;
         if (base >= v1) break;
     }
     __syncthreads();
-    (void)drain<THREADS, CAP, QCAP>(s, k, k, t);  // prunes to exactly k
+    (void)drain(s, k, k, t);  // prunes to exactly k
     return SelectStart{k, t, k};
 }
 
-template <int THREADS, int U, int CAP, int QCAP>
+template <int THREADS, int U, int CAP, int QCAP, typename Fmt>
 __device__ __forceinline__ void select_topk(const u32x4* __restrict__ src, uint32_t v0, uint32_t v1, uint32_t k,
-                                            SelectShared<THREADS, CAP, QCAP>& s)
+                                            SelectShared<THREADS, CAP, QCAP, Fmt>& s)
 {
-    (void)select_topk_from<THREADS, U, CAP, QCAP>(src, v0, v1, s, NoSeed{k});
+    (void)select_topk_from<THREADS, U>(src, v0, v1, s, NoSeed{k});
 }
 
 // Top-k of candidate lists: `n` (index, pattern) pairs in global memory, entries whose
 // index is 0xFFFFFFFF are padding.  They are loaded in batches of CAP/2 with a prune
 // after each, so any n fits.  Leaves min(k, valid entries) survivors in
 // s.cand_idx / s.cand_bits, unordered.  All threads call; ends with a barrier.
-template <int THREADS, int CAP, int QCAP>
-__device__ __forceinline__ void merge_topk(const uint32_t* __restrict__ c_idx, const uint16_t* __restrict__ c_bits,
-                                           uint32_t n, uint32_t k, SelectShared<THREADS, CAP, QCAP>& s)
+template <int THREADS, int CAP, int QCAP, typename Fmt>
+__device__ __forceinline__ void merge_topk(const uint32_t* __restrict__ c_idx,
+                                           const typename Fmt::bits_t* __restrict__ c_bits, uint32_t n, uint32_t k,
+                                           SelectShared<THREADS, CAP, QCAP, Fmt>& s)
 {
     const uint32_t tid = threadIdx.x;
     if (tid == 0) { s.count = 0; s.eq_count = 0; s.tm = 0; s.ti = 0xFFFFFFFFu; }
@@ -459,15 +488,15 @@ __device__ __forceinline__ void merge_topk(const uint32_t* __restrict__ c_idx, c
                 s.cand_bits[slot] = c_bits[i];
             }
         }
-        (void)prune_if_above<THREADS, CAP, QCAP>(s, k, b1 == n ? k : (uint32_t)(CAP / 2), t);
+        (void)prune_if_above(s, k, b1 == n ? k : (uint32_t)(CAP / 2), t);
     }
 }
 
 // Put the k survivors of select_topk into the order (magnitude descending, index
 // ascending): rank = number of survivors that come before.  All threads call; ends
 // with a barrier.
-template <int THREADS, int CAP, int QCAP>
-__device__ __forceinline__ void order_topk(SelectShared<THREADS, CAP, QCAP>& s, uint32_t k)
+template <int THREADS, int CAP, int QCAP, typename Fmt>
+__device__ __forceinline__ void order_topk(SelectShared<THREADS, CAP, QCAP, Fmt>& s, uint32_t k)
 {
     const uint32_t tid = threadIdx.x;
     constexpr int KPT = (CAP / 2 + THREADS - 1) / THREADS;
@@ -479,10 +508,10 @@ __device__ __forceinline__ void order_topk(SelectShared<THREADS, CAP, QCAP>& s, 
         if (j < k) {
             my_idx[i] = s.cand_idx[j];
             my_bits[i] = s.cand_bits[j];
-            const uint32_t mag = my_bits[i] & 0x7FFFu;
+            const uint32_t mag = my_bits[i] & Fmt::MAG_MASK;
             uint32_t rank = 0;
             for (uint32_t u = 0; u < k; ++u) {
-                const uint32_t om = s.cand_bits[u] & 0x7FFFu;
+                const uint32_t om = s.cand_bits[u] & Fmt::MAG_MASK;
                 const uint32_t oi = s.cand_idx[u];
                 rank += (om > mag || (om == mag && oi < my_idx[i])) ? 1u : 0u;
             }
@@ -494,7 +523,7 @@ __device__ __forceinline__ void order_topk(SelectShared<THREADS, CAP, QCAP>& s, 
     for (int i = 0; i < KPT; ++i) {
         if (tid + i * THREADS < k) {
             s.cand_idx[my_rank[i]] = my_idx[i];
-            s.cand_bits[my_rank[i]] = (uint16_t)my_bits[i];
+            s.cand_bits[my_rank[i]] = (typename Fmt::bits_t)my_bits[i];
         }
     }
     __syncthreads();

@@ -115,7 +115,7 @@ __global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void build_kernel(const
         sh.itp.idx[tid] = my_idx;
         sh.itp.ys[tid] = (uint16_t)(my_y >= kPrime ? my_y - kPrime : my_y);
     }
-    finish_proof<kThreads, KMAX>(sh.itp, coef, k, reinterpret_cast<uint16_t*>(proofs + chunk * (2 + 2 * (uint64_t)k)),
+    finish_proof<kThreads>(sh.itp, coef, k, reinterpret_cast<uint16_t*>(proofs + chunk * (2 + 2 * (uint64_t)k)),
                                  status + chunk);
 }
 
@@ -219,7 +219,7 @@ __global__ __launch_bounds__(THREADS) void build_merge_kernel(Layout lay, uint32
         sh.itp.idx[tid] = my_idx;
         sh.itp.ys[tid] = (uint16_t)(my_y >= kPrime ? my_y - kPrime : my_y);
     }
-    finish_proof<THREADS, KMAX>(sh.itp, coef, k, reinterpret_cast<uint16_t*>(proofs + unit * (2 + 2 * (uint64_t)k)),
+    finish_proof<THREADS>(sh.itp, coef, k, reinterpret_cast<uint16_t*>(proofs + unit * (2 + 2 * (uint64_t)k)),
                                 status + unit);
 }
 
@@ -370,7 +370,7 @@ __global__ __launch_bounds__(THREADS) void stream_emit_kernel(char* __restrict__
         sh.itp.idx[tid] = my_idx;
         sh.itp.ys[tid] = (uint16_t)(my_y >= kPrime ? my_y - kPrime : my_y);
     }
-    finish_proof<THREADS, KMAX>(sh.itp, coef, k, proof, status + seq);
+    finish_proof<THREADS>(sh.itp, coef, k, proof, status + seq);
 }
 
 // ---------------------------------------------------------------------------
