@@ -48,6 +48,14 @@ extern "C" {
 #define TOPLOC_PRIME 65497u     /* the field modulus M of Algorithms 3 and 5            */
 #define TOPLOC_MAX_K 512u       /* largest supported top-k parameter                    */
 
+/* Precisions (Section 5.6 validates across fp32 and bf16).  An fp32 value enters the
+ * polynomial as its 32-bit pattern over GF(TOPLOC_PRIME32); such a proof is 2 + 4k bytes:
+ * the same 2-byte modulus field, then 4-byte little-endian coefficients. */
+#define TOPLOC_DTYPE_BF16 0u
+#define TOPLOC_DTYPE_F32 1u
+#define TOPLOC_PRIME32 4294967291u  /* 2^32 - 5: the field modulus when fp32 patterns are encoded */
+#define TOPLOC_MAX_K_F32 128u       /* largest k of the calls that involve fp32                    */
+
 /* call-level return codes */
 #define TOPLOC_OK 0
 #define TOPLOC_EINVAL (-1)      /* null / misaligned pointer, k = 0, k > N, k > MAX_K,   */
@@ -171,6 +179,27 @@ int toploc_verify_proofs_segments(const void *d_hidden_bf16, const uint64_t *h_r
  * aligned. */
 int toploc_ring_append(void *d_ring_bf16, const void *d_step_bf16, uint32_t n_seq, uint32_t hidden,
                        uint32_t chunk_tokens, uint32_t step, void *hip_stream);
+
+/* fp32 activations and validation across precisions (Section 5.6, Table 5; fp32 thresholds
+ * {8, 256, 128} in Section 5.2).  Top-k ranks fp32 values by (pattern & 0x7FFFFFFF).
+ *   toploc_proof_bytes_dtype   2 + 2k (TOPLOC_DTYPE_BF16) or 2 + 4k (TOPLOC_DTYPE_F32)
+ *   toploc_build_proofs_f32    Algorithm 1 over [n_chunks][chunk_tokens*hidden] fp32 values;
+ *                              params->prime must be TOPLOC_PRIME32, k <= TOPLOC_MAX_K_F32;
+ *                              proofs are 2 + 4k bytes each; other arguments as toploc_build_proofs
+ *   toploc_verify_proofs_mixed Algorithm 2 with activations of `hidden_dtype` and proofs of
+ *                              `proof_dtype` (params->prime: the proof's field).  Exponent and
+ *                              mantissa are compared in the validator's (the activations')
+ *                              precision: an fp32 proof's mantissa is scaled to bf16's 7 bits
+ *                              (>> 16) for a bf16 validator, a bf16 proof's value gets 16 zero
+ *                              bits appended for an fp32 validator.  Thresholds are the caller's
+ *                              (the paper uses the validator's precision's).
+ * Both run as one fused launch per call and need no workspace. */
+size_t toploc_proof_bytes_dtype(uint32_t k, uint32_t dtype);
+int toploc_build_proofs_f32(const void *d_hidden_f32, uint64_t n_chunks, const toploc_params *params, uint8_t *d_proofs,
+                            uint8_t *d_status, uint32_t *d_topk_idx_opt, void *hip_stream);
+int toploc_verify_proofs_mixed(const void *d_hidden, uint32_t hidden_dtype, uint64_t n_chunks, const toploc_params *params,
+                               const uint8_t *d_proofs, uint32_t proof_dtype, const toploc_thresholds *thresholds,
+                               toploc_verify_result *d_results, void *hip_stream);
 
 /* Online path without the ring (a design of this build; the paper's provider keeps the
  * last hidden states, Table 6, only to take their top-k when the proof is cut).  Per

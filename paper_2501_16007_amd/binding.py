@@ -22,6 +22,10 @@ CHUNK_OK, CHUNK_NO_MODULUS, CHUNK_NO_INVERSE, CHUNK_MALFORMED, CHUNK_SHORT = 0, 
 KERNEL_NAMES = ("select_kernel", "part_kernel", "build_merge_kernel", "verify_merge_kernel", "build_kernel",
                 "verify_kernel", "ring_kernel", "read_kernel", "stream_append_kernel", "stream_emit_kernel")
 BF16_THRESHOLDS = (38, 10, 8)  # T_exp, T_mean, T_median (Section 5.2 of the paper)
+F32_THRESHOLDS = (8, 256, 128)  # the same for fp32 inference
+DTYPE_BF16, DTYPE_F32 = 0, 1
+PRIME32 = 4294967291
+MAX_K_F32 = 128
 
 RESULT_DTYPE = np.dtype(
     [
@@ -45,6 +49,9 @@ EXPORTS = (
     "toploc_build_proofs",
     "toploc_verify_proofs",
     "toploc_topk",
+    "toploc_proof_bytes_dtype",
+    "toploc_build_proofs_f32",
+    "toploc_verify_proofs_mixed",
     "toploc_stream_state_bytes",
     "toploc_stream_reset",
     "toploc_stream_append",
@@ -103,6 +110,11 @@ def lib():
         L.toploc_verify_proofs_segments.argtypes = [P, P, c.c_uint64, c.c_uint32, c.c_uint32, P, c.POINTER(Thresholds), P,
                                                     P, c.c_size_t, P]
         L.toploc_ring_append.argtypes = [P, P, c.c_uint32, c.c_uint32, c.c_uint32, c.c_uint32, P]
+        L.toploc_proof_bytes_dtype.argtypes = [c.c_uint32, c.c_uint32]
+        L.toploc_proof_bytes_dtype.restype = c.c_size_t
+        L.toploc_build_proofs_f32.argtypes = [P, c.c_uint64, c.POINTER(Params), P, P, P, P]
+        L.toploc_verify_proofs_mixed.argtypes = [P, c.c_uint32, c.c_uint64, c.POINTER(Params), P, c.c_uint32,
+                                                 c.POINTER(Thresholds), P, P]
         L.toploc_stream_state_bytes.argtypes = [c.c_uint32, c.c_uint32]
         L.toploc_stream_state_bytes.restype = c.c_size_t
         L.toploc_stream_reset.argtypes = [P, c.c_uint32, c.c_uint32, P]
@@ -275,6 +287,64 @@ def toploc_ring_append(ring, step_vec, step):
     rc = lib().toploc_ring_append(ring.data_ptr(), step_vec.data_ptr(), n_seq, h, chunk_tokens, step, _stream(ring))
     if rc != OK:
         raise ToplocError(rc, "toploc_ring_append")
+
+
+def toploc_proof_bytes_dtype(k, dtype):
+    return int(lib().toploc_proof_bytes_dtype(k, dtype))
+
+
+def _chunks_any(hidden, chunk_tokens):
+    """Like _chunks for a bf16 or fp32 tensor: (n_chunks, H, dtype code)."""
+    if hidden.dtype not in (torch.bfloat16, torch.float32) or not hidden.is_cuda or not hidden.is_contiguous():
+        raise ValueError("hidden must be a contiguous bf16 or fp32 tensor on the GPU")
+    dt = DTYPE_F32 if hidden.dtype == torch.float32 else DTYPE_BF16
+    if hidden.dim() == 3:
+        n_seq, n_tok, h = hidden.shape
+        if n_tok % chunk_tokens:
+            raise ValueError("n_tok must be a multiple of chunk_tokens")
+        return n_seq * (n_tok // chunk_tokens), h, dt
+    if hidden.dim() == 2:
+        n_chunks, n = hidden.shape
+        if n % chunk_tokens:
+            raise ValueError("chunk length must be a multiple of chunk_tokens")
+        return n_chunks, n // chunk_tokens, dt
+    raise ValueError("hidden must be [n_seq, n_tok, H] or [n_chunks, chunk_tokens*H]")
+
+
+def toploc_build_proofs_f32(hidden, k=128, chunk_tokens=32, want_topk=False):
+    """Algorithm 1 over fp32 activations. Returns (proofs uint8 [n_chunks, 2+4k], status[, idx])."""
+    n_chunks, h, dt = _chunks_any(hidden, chunk_tokens)
+    if dt != DTYPE_F32:
+        raise ValueError("hidden must be fp32")
+    dev = hidden.device
+    p = Params(k, chunk_tokens, h, PRIME32)
+    proofs = torch.empty((n_chunks, 2 + 4 * k), dtype=torch.uint8, device=dev)
+    status = torch.empty(n_chunks, dtype=torch.uint8, device=dev)
+    idx = torch.empty((n_chunks, k), dtype=torch.int32, device=dev) if want_topk else None
+    rc = lib().toploc_build_proofs_f32(hidden.data_ptr(), n_chunks, ctypes.byref(p), proofs.data_ptr(), status.data_ptr(),
+                                       idx.data_ptr() if want_topk else None, _stream(hidden))
+    if rc != OK:
+        raise ToplocError(rc, "toploc_build_proofs_f32")
+    return (proofs, status, idx) if want_topk else (proofs, status)
+
+
+def toploc_verify_proofs_mixed(hidden, proofs, proof_dtype, k=128, chunk_tokens=32, thresholds=None):
+    """Algorithm 2 with bf16 or fp32 activations and bf16 or fp32 proofs; thresholds default to the
+    paper's for the validator's precision. Returns a uint8 device tensor [n_chunks, 20]."""
+    n_chunks, h, dt = _chunks_any(hidden, chunk_tokens)
+    pb = 2 + (4 if proof_dtype == DTYPE_F32 else 2) * k
+    if proofs.dtype != torch.uint8 or not proofs.is_cuda or not proofs.is_contiguous() or proofs.numel() != n_chunks * pb:
+        raise ValueError("proofs must be a contiguous uint8 device tensor of n_chunks proofs of proof_dtype")
+    if thresholds is None:
+        thresholds = F32_THRESHOLDS if dt == DTYPE_F32 else BF16_THRESHOLDS
+    p = Params(k, chunk_tokens, h, PRIME32 if proof_dtype == DTYPE_F32 else PRIME)
+    t = Thresholds(*thresholds)
+    res = torch.empty((n_chunks, RESULT_DTYPE.itemsize), dtype=torch.uint8, device=hidden.device)
+    rc = lib().toploc_verify_proofs_mixed(hidden.data_ptr(), dt, n_chunks, ctypes.byref(p), proofs.data_ptr(), proof_dtype,
+                                          ctypes.byref(t), res.data_ptr(), _stream(hidden))
+    if rc != OK:
+        raise ToplocError(rc, "toploc_verify_proofs_mixed")
+    return res
 
 
 def toploc_stream_state_bytes(n_seq, k):

@@ -77,7 +77,7 @@ __global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void select_kernel(cons
     __shared__ SelectShared<kThreads, CAP, kQcap> s;
     const uint64_t chunk = blockIdx.x;
     select_topk<kThreads, kLoads, CAP, kQcap>(hidden + chunk * nvec, 0u, nvec, k, s);
-    order_topk<kThreads, CAP, kQcap>(s, k);
+    order_topk(s, k);
     for (uint32_t t = threadIdx.x; t < k; t += kThreads) {
         out_idx[chunk * k + t] = s.cand_idx[t];
         out_val[chunk * k + t] = s.cand_bits[t];
@@ -89,7 +89,7 @@ __global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void select_kernel(cons
 // then the same workgroup turns its k pairs into the proof out of LDS (the selection's
 // buffers are dead by then and are reused).
 // ---------------------------------------------------------------------------
-template <int KMAX, int CAP>
+template <int KMAX, int CAP, typename F = Field16, typename Fmt = Bf16Fmt>
 __global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void build_kernel(const u32x4* __restrict__ hidden, uint32_t nvec,
                                                                            uint32_t k, uint8_t* __restrict__ proofs,
                                                                            uint8_t* __restrict__ status,
@@ -97,15 +97,15 @@ __global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void build_kernel(const
 {
     static_assert(KMAX <= kThreads, "one pair per lane is carried across the phase change");
     __shared__ union BuildShared {
-        SelectShared<kThreads, CAP, kQcap> sel;
-        InterpShared<KMAX> itp;
+        SelectShared<kThreads, CAP, kQcap, Fmt> sel;
+        InterpShared<KMAX, F> itp;
     } sh;
     __shared__ uint32_t coef[KMAX];
     const uint32_t tid = threadIdx.x;
     const uint64_t chunk = blockIdx.x;
-    select_topk<kThreads, kLoads, CAP, kQcap>(hidden + chunk * nvec, 0u, nvec, k, sh.sel);
+    select_topk<kThreads, kLoads>(hidden + chunk * nvec, 0u, nvec, k, sh.sel);
     if (out_idx) {  // uniform: the caller wants the ordered indices
-        order_topk<kThreads, CAP, kQcap>(sh.sel, k);
+        order_topk(sh.sel, k);
         if (tid < k) out_idx[chunk * k + tid] = sh.sel.cand_idx[tid];
     }
     uint32_t my_idx = 0, my_y = 0;
@@ -113,28 +113,30 @@ __global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void build_kernel(const
     __syncthreads();  // the selection's LDS is dead from here on
     if (tid < k) {
         sh.itp.idx[tid] = my_idx;
-        sh.itp.ys[tid] = (uint16_t)(my_y >= kPrime ? my_y - kPrime : my_y);
+        sh.itp.ys[tid] = (typename F::elem_t)F::from_pattern(my_y);
     }
-    finish_proof<kThreads>(sh.itp, coef, k, reinterpret_cast<uint16_t*>(proofs + chunk * (2 + 2 * (uint64_t)k)),
-                                 status + chunk);
+    finish_proof<kThreads>(sh.itp, coef, k,
+                           reinterpret_cast<uint16_t*>(proofs + chunk * (2 + 2 * (uint64_t)F::WORDS * k)), status + chunk);
 }
 
 // ---------------------------------------------------------------------------
 // Algorithm 2, fused: one pass over the recomputed chunk
 // ---------------------------------------------------------------------------
-template <int KMAX, int CAP>
+// F is the proof's field, Fmt the format of the recomputed activations (Section 5.6
+// validates across the two precisions).
+template <int KMAX, int CAP, typename F = Field16, typename Fmt = Bf16Fmt>
 __global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void verify_kernel(const u32x4* __restrict__ hidden, uint32_t nvec,
                                                                             uint32_t k, const uint8_t* __restrict__ proofs,
                                                                             toploc_thresholds thr,
                                                                             toploc_verify_result* __restrict__ results)
 {
-    __shared__ SelectShared<kThreads, CAP, kQcap> s;
-    __shared__ VerifyShared<KMAX> vs;
+    __shared__ SelectShared<kThreads, CAP, kQcap, Fmt> s;
+    __shared__ VerifyShared<KMAX, Fmt::ELEMS == 4> vs;
     const uint64_t chunk = blockIdx.x;
-    const uint16_t* proof = reinterpret_cast<const uint16_t*>(proofs + chunk * (2 + 2 * (uint64_t)k));
-    if (!verify_decode<kThreads, KMAX>(vs, proof, k, results + chunk)) return;
-    select_topk<kThreads, kLoads, CAP, kQcap>(hidden + chunk * nvec, 0u, nvec, k, s);  // order is irrelevant here
-    verify_tail<kThreads, KMAX>(vs, s.cand_idx, s.cand_bits, k, thr, results + chunk);
+    const uint16_t* proof = reinterpret_cast<const uint16_t*>(proofs + chunk * (2 + 2 * (uint64_t)F::WORDS * k));
+    if (!verify_decode<kThreads, F>(vs, proof, k, results + chunk)) return;
+    select_topk<kThreads, kLoads>(hidden + chunk * nvec, 0u, nvec, k, s);  // order is irrelevant here
+    verify_tail<kThreads, F, Fmt>(vs, s.cand_idx, s.cand_bits, k, thr, results + chunk);
 }
 
 // ---------------------------------------------------------------------------
@@ -207,9 +209,9 @@ __global__ __launch_bounds__(THREADS) void build_merge_kernel(Layout lay, uint32
     uint64_t first;
     uint32_t n_parts;
     merge_range(lay, unit, first, n_parts);
-    merge_topk<THREADS, CAP, 1>(c_idx + first * k, c_bits + first * k, n_parts * k, k, sh.sel);
+    merge_topk(c_idx + first * k, c_bits + first * k, n_parts * k, k, sh.sel);
     if (out_idx) {
-        order_topk<THREADS, CAP, 1>(sh.sel, k);
+        order_topk(sh.sel, k);
         if (tid < k) out_idx[unit * k + tid] = sh.sel.cand_idx[tid];
     }
     uint32_t my_idx = 0, my_y = 0;
@@ -237,12 +239,12 @@ __global__ __launch_bounds__(THREADS) void verify_merge_kernel(Layout lay, uint3
     __shared__ VerifyShared<KMAX> vs;
     const uint64_t unit = blockIdx.x;
     const uint16_t* proof = reinterpret_cast<const uint16_t*>(proofs + unit * (2 + 2 * (uint64_t)k));
-    if (!verify_decode<THREADS, KMAX>(vs, proof, k, results + unit)) return;
+    if (!verify_decode<THREADS, Field16>(vs, proof, k, results + unit)) return;
     uint64_t first;
     uint32_t n_parts;
     merge_range(lay, unit, first, n_parts);
-    merge_topk<THREADS, CAP, 1>(c_idx + first * k, c_bits + first * k, n_parts * k, k, s);
-    verify_tail<THREADS, KMAX>(vs, s.cand_idx, s.cand_bits, k, thr, results + unit);
+    merge_topk(c_idx + first * k, c_bits + first * k, n_parts * k, k, s);
+    verify_tail<THREADS, Field16, Bf16Fmt>(vs, s.cand_idx, s.cand_bits, k, thr, results + unit);
 }
 
 // ---------------------------------------------------------------------------
@@ -359,7 +361,7 @@ __global__ __launch_bounds__(THREADS) void stream_emit_kernel(char* __restrict__
     if (out_idx) {  // uniform: the caller wants the ordered indices
         for (uint32_t j = tid; j < k; j += THREADS) { sh.sel.cand_idx[j] = g_idx[j]; sh.sel.cand_bits[j] = g_bits[j]; }
         __syncthreads();
-        order_topk<THREADS, CAP, 1>(sh.sel, k);
+        order_topk(sh.sel, k);
         if (tid < k) { out_idx[seq * k + tid] = sh.sel.cand_idx[tid]; my_idx = sh.sel.cand_idx[tid]; my_y = sh.sel.cand_bits[tid]; }
         __syncthreads();
     } else if (tid < k) {
@@ -766,6 +768,72 @@ int toploc_verify_proofs_segments(const void* d_hidden_bf16, const uint64_t* h_r
     launch_part(st, d_hidden_bf16, lay, pl.parts.size(), k, c_idx, c_bits);
     if (!hip_ok(hipGetLastError())) return TOPLOC_EHIP;
     launch_verify_merge(st, lay, n_segments, k, c_idx, c_bits, d_proofs, *thresholds, d_results);
+    return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
+}
+
+// N (values per chunk) for the calls that involve fp32: k <= TOPLOC_MAX_K_F32, the chunk a
+// whole number of 16-byte vectors in both formats
+static uint64_t chunk_len_mixed(const toploc_params* p, uint32_t hidden_dtype, uint32_t proof_dtype)
+{
+    if (!p || hidden_dtype > TOPLOC_DTYPE_F32 || proof_dtype > TOPLOC_DTYPE_F32) return 0;
+    if (p->prime != (proof_dtype == TOPLOC_DTYPE_F32 ? TOPLOC_PRIME32 : TOPLOC_PRIME)) return 0;
+    const uint32_t kmax = (hidden_dtype == TOPLOC_DTYPE_F32 || proof_dtype == TOPLOC_DTYPE_F32) ? TOPLOC_MAX_K_F32 : TOPLOC_MAX_K;
+    if (p->k == 0 || p->k > kmax || p->chunk_tokens == 0 || p->hidden == 0) return 0;
+    const uint64_t n = (uint64_t)p->chunk_tokens * p->hidden;
+    if (n % 8 != 0 || n >= (1ull << 32) || p->k > n) return 0;
+    return n;
+}
+
+size_t toploc_proof_bytes_dtype(uint32_t k, uint32_t dtype)
+{
+    return 2 + (size_t)k * (dtype == TOPLOC_DTYPE_F32 ? 4 : 2);
+}
+
+int toploc_build_proofs_f32(const void* d_hidden_f32, uint64_t n_chunks, const toploc_params* params, uint8_t* d_proofs,
+                            uint8_t* d_status, uint32_t* d_topk_idx_opt, void* hip_stream)
+{
+    const uint64_t n = chunk_len_mixed(params, TOPLOC_DTYPE_F32, TOPLOC_DTYPE_F32);
+    if (n == 0 || n_chunks >= (1ull << 31)) return TOPLOC_EINVAL;
+    if (n_chunks == 0) return TOPLOC_OK;
+    if (!d_hidden_f32 || !d_proofs || !d_status || !aligned16(d_hidden_f32)) return TOPLOC_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(d_proofs) & 1u) != 0) return TOPLOC_EINVAL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    {
+        ProfScope ps(TOPLOC_KERNEL_BUILD, st);
+        hipLaunchKernelGGL((build_kernel<128, kCapSmall, Field32, F32Fmt>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
+                           (const u32x4*)d_hidden_f32, (uint32_t)(n / 4), params->k, d_proofs, d_status, d_topk_idx_opt);
+    }
+    return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
+}
+
+int toploc_verify_proofs_mixed(const void* d_hidden, uint32_t hidden_dtype, uint64_t n_chunks, const toploc_params* params,
+                               const uint8_t* d_proofs, uint32_t proof_dtype, const toploc_thresholds* thresholds,
+                               toploc_verify_result* d_results, void* hip_stream)
+{
+    const uint64_t n = chunk_len_mixed(params, hidden_dtype, proof_dtype);
+    if (n == 0 || n_chunks >= (1ull << 31) || !thresholds) return TOPLOC_EINVAL;
+    if (n_chunks == 0) return TOPLOC_OK;
+    if (!d_hidden || !d_proofs || !d_results || !aligned16(d_hidden)) return TOPLOC_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(d_proofs) & 1u) != 0 || (reinterpret_cast<uintptr_t>(d_results) & 3u) != 0)
+        return TOPLOC_EINVAL;
+    if (hidden_dtype == TOPLOC_DTYPE_BF16 && proof_dtype == TOPLOC_DTYPE_BF16)
+        return toploc_verify_proofs(d_hidden, n_chunks, params, d_proofs, thresholds, d_results, nullptr, 0, hip_stream);
+    hipStream_t st = (hipStream_t)hip_stream;
+    const uint32_t k = params->k;
+    const dim3 grid((uint32_t)n_chunks), block(kThreads);
+    const u32x4* h = (const u32x4*)d_hidden;
+    {
+        ProfScope ps(TOPLOC_KERNEL_VERIFY, st);
+        if (hidden_dtype == TOPLOC_DTYPE_F32 && proof_dtype == TOPLOC_DTYPE_F32)
+            hipLaunchKernelGGL((verify_kernel<128, kCapSmall, Field32, F32Fmt>), grid, block, 0, st, h, (uint32_t)(n / 4), k,
+                               d_proofs, *thresholds, d_results);
+        else if (hidden_dtype == TOPLOC_DTYPE_F32)   // bf16 proof, fp32 validator
+            hipLaunchKernelGGL((verify_kernel<128, kCapSmall, Field16, F32Fmt>), grid, block, 0, st, h, (uint32_t)(n / 4), k,
+                               d_proofs, *thresholds, d_results);
+        else                                          // fp32 proof, bf16 validator
+            hipLaunchKernelGGL((verify_kernel<128, kCapSmall, Field32, Bf16Fmt>), grid, block, 0, st, h, (uint32_t)(n / 8), k,
+                               d_proofs, *thresholds, d_results);
+    }
     return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
 }
 

@@ -1,41 +1,53 @@
 // The paper's Algorithm 2 after topk(h, k) for one chunk, one workgroup: decode,
 // index map, Horner evaluation of the proof polynomial at the k mapped indices
 // (Algorithm 5), extractBits, the err_e / err_m statistics and the three thresholds
-// (Section 5.2).  All integer arithmetic; err_m is kept as a 128-bin histogram so that
-// the mean test and the median are exact.
+// (Section 5.2).  All integer arithmetic.
+//
+// Two precisions meet here (Section 5.6): the proof's (its field F: GF(65497) carries
+// bf16 patterns, GF(2^32 - 5) fp32 patterns) and the validator's (the format of the
+// recomputed activations).  Exponent and mantissa are compared in the validator's
+// precision: an fp32 proof value met by bf16 activations has its 23-bit mantissa scaled
+// down to 7 bits (>> 16), a bf16 proof value met by fp32 activations gets 16 zero bits
+// appended (<< 16).  With a bf16 validator err_m lies in [0, 127] and is kept as a
+// histogram, so the mean test and the median are exact; with an fp32 validator the
+// differences (< 2^23) are kept as a list and the lower median is found by rank.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 #include "../../include/toploc.h"
+#include "gf32.hpp"
 #include "gf65497.hpp"
 #include "interp.hpp"
+#include "select.hpp"
 
 namespace toploc {
 
-template <int KMAX>
+template <int KMAX, bool WIDE = false>
 struct VerifyShared {
-    uint32_t coef[KMAX];     // c_0..c_{k-1}
-    uint32_t hist_d[128];    // err_m as a histogram of |m_p - m_v| in [0, 127]
-    uint32_t err_e, mant_sum, bad, m;
+    uint32_t coef[KMAX];                 // c_0..c_{k-1}
+    uint32_t hist_d[128];                // bf16 validator: err_m as a histogram of |m_p - m_v| in [0, 127]
+    uint32_t diffs[WIDE ? KMAX : 1];     // fp32 validator: err_m as a list
+    uint32_t err_e, mant_sum, bad, m, n_match, median;
 };
 
 // decode(p): coefficients and modulus into LDS.  Returns false (uniformly) for a
 // malformed proof, after writing its result record.  All threads call; ends with a barrier.
-template <int THREADS, int KMAX>
-__device__ __forceinline__ bool verify_decode(VerifyShared<KMAX>& vs, const uint16_t* __restrict__ proof, uint32_t k,
+template <int THREADS, typename F, int KMAX, bool WIDE>
+__device__ __forceinline__ bool verify_decode(VerifyShared<KMAX, WIDE>& vs, const uint16_t* __restrict__ proof, uint32_t k,
                                               toploc_verify_result* __restrict__ result)
 {
     const uint32_t tid = threadIdx.x;
-    if (tid == 0) { vs.err_e = 0; vs.mant_sum = 0; vs.bad = 0; }
+    if (tid == 0) { vs.err_e = 0; vs.mant_sum = 0; vs.bad = 0; vs.n_match = 0; vs.median = 0; }
     for (uint32_t b = tid; b < 128; b += THREADS) vs.hist_d[b] = 0;
     __syncthreads();
     const uint32_t mf = proof[0];
     const uint32_t m = mf ? mf : kModHigh;   // the 2-byte field stores m mod 65536
     for (uint32_t j = tid; j < k; j += THREADS) {
-        const uint32_t c = proof[1 + j];
+        uint32_t c = proof[1 + j * F::WORDS];
+        if (F::WORDS == 2) c |= (uint32_t)proof[2 + j * F::WORDS] << 16;
         vs.coef[j] = c;
-        if (c >= kPrime) vs.bad = 1u;
+        if (c >= F::P) vs.bad = 1u;
     }
     if (tid == 0) {
         vs.m = m;
@@ -53,33 +65,63 @@ __device__ __forceinline__ bool verify_decode(VerifyShared<KMAX>& vs, const uint
     return true;
 }
 
+// extractBits of a proof value (a pattern of the field's precision), expressed in the
+// validator's precision Fmt
+template <typename F, typename Fmt>
+__device__ __forceinline__ void extract_proof_bits(uint32_t p, uint32_t& e, uint32_t& mant)
+{
+    if (F::WORDS == 2) { e = (p >> 23) & 0xFFu; mant = p & 0x7FFFFFu; }
+    else               { e = (p >> 7) & 0xFFu;  mant = p & 0x7Fu; }
+    if (F::WORDS == 2 && Fmt::ELEMS == 8) mant >>= 16;   // fp32 mantissa scaled to bf16's width
+    if (F::WORDS == 1 && Fmt::ELEMS == 4) mant <<= 16;   // 16 zero bits appended to the bf16 pattern
+}
+
 // The loop and the decision of Algorithm 2 over the k selected (index, pattern) pairs
 // in LDS (any order).  All threads call.
-template <int THREADS, int KMAX>
-__device__ __forceinline__ void verify_tail(VerifyShared<KMAX>& vs, const uint32_t* cand_idx, const uint16_t* cand_bits,
-                                            uint32_t k, const toploc_thresholds& thr,
+template <int THREADS, typename F, typename Fmt, int KMAX, bool WIDE>
+__device__ __forceinline__ void verify_tail(VerifyShared<KMAX, WIDE>& vs, const uint32_t* cand_idx,
+                                            const typename Fmt::bits_t* cand_bits, uint32_t k, const toploc_thresholds& thr,
                                             toploc_verify_result* __restrict__ result)
 {
+    static_assert(WIDE == (Fmt::ELEMS == 4), "an fp32 validator keeps err_m as a list");
     const uint32_t tid = threadIdx.x;
     const uint32_t m = vs.m;
     for (uint32_t j = tid; j < k; j += THREADS) {
-        uint32_t x = cand_idx[j] % m;
-        x = x >= kPrime ? x - kPrime : x;
+        const uint32_t x = F::from_residue(cand_idx[j] % m);
         uint32_t acc = vs.coef[k - 1];
-        for (int i = (int)k - 2; i >= 0; --i) acc = muladdmod(acc, x, vs.coef[i]);
+        for (int i = (int)k - 2; i >= 0; --i) acc = F::muladdmod(acc, x, vs.coef[i]);
         const uint32_t v = cand_bits[j];
-        const uint32_t e_p = (acc >> 7) & 0xFFu, m_p = acc & 0x7Fu;
-        const uint32_t e_v = (v >> 7) & 0xFFu, m_v = v & 0x7Fu;
+        uint32_t e_p, m_p, e_v, m_v;
+        extract_proof_bits<F, Fmt>(acc, e_p, m_p);
+        if (Fmt::ELEMS == 4) { e_v = (v >> 23) & 0xFFu; m_v = v & 0x7FFFFFu; }
+        else                 { e_v = (v >> 7) & 0xFFu;  m_v = v & 0x7Fu; }
         if (e_p == e_v) {
             const uint32_t d = m_p > m_v ? m_p - m_v : m_v - m_p;
-            atomicAdd(&vs.hist_d[d], 1u);
-            atomicAdd(&vs.mant_sum, d);
+            if (WIDE) vs.diffs[atomicAdd(&vs.n_match, 1u)] = d;
+            else atomicAdd(&vs.hist_d[d], 1u);
+            atomicAdd(&vs.mant_sum, d);   // k * (2^23 - 1) < 2^32 for k <= 512
         } else {
             atomicAdd(&vs.err_e, 1u);
         }
     }
     __syncthreads();
-    if (tid < 64) {
+    uint32_t n, med = 0;
+    if (WIDE) {
+        // lower median by rank: the entry that floor((n-1)/2) entries precede, ties by slot
+        n = vs.n_match;
+        const uint32_t target = n ? (n - 1) / 2 : 0;
+        for (uint32_t j = tid; j < n; j += THREADS) {
+            const uint32_t mine = vs.diffs[j];
+            uint32_t rank = 0;
+            for (uint32_t u = 0; u < n; ++u) {
+                const uint32_t o = vs.diffs[u];
+                rank += (o < mine || (o == mine && u < j)) ? 1u : 0u;
+            }
+            if (rank == target) vs.median = mine;
+        }
+        __syncthreads();
+        med = vs.median;
+    } else if (tid < 64) {
         // |err_m| and its lower median from the histogram: the smallest d whose
         // cumulative count reaches floor((n-1)/2) + 1
         const uint32_t h0 = vs.hist_d[2 * tid], h1 = vs.hist_d[2 * tid + 1];
@@ -89,30 +131,32 @@ __device__ __forceinline__ void verify_tail(VerifyShared<KMAX>& vs, const uint32
             const uint32_t o = __shfl_up(v, d);
             if ((int)tid >= d) v += o;
         }
-        const uint32_t n = __shfl(v, 63);
+        n = __shfl(v, 63);
         const uint32_t target = n ? (n - 1) / 2 + 1 : 0;
         const uint32_t before = v - h0 - h1;
-        uint32_t med = 0xFFFFFFFFu;
+        med = 0xFFFFFFFFu;
         if (n && before < target && before + h0 >= target) med = 2 * tid;
         else if (n && before + h0 < target && v >= target) med = 2 * tid + 1;
         const uint64_t mask = __ballot(med != 0xFFFFFFFFu);
         const int srcl = mask ? (__ffsll((long long)mask) - 1) : 0;
         med = __shfl(med, srcl);
-        if (tid == 0) {
-            toploc_verify_result r = {};
-            r.err_exp = vs.err_e;
-            r.n_match = n;
-            r.mant_sum = vs.mant_sum;
-            r.mant_median = n ? med : 0u;
-            bool reject = vs.err_e > thr.t_exp;
-            if (n) {
-                if ((uint64_t)vs.mant_sum > (uint64_t)thr.t_mean * n) reject = true;   // mean(err_m) > T_mean
-                if (r.mant_median > thr.t_median) reject = true;
-            }
-            r.accept = reject ? 0 : 1;
-            r.status = TOPLOC_CHUNK_OK;
-            *result = r;
+    } else {
+        n = 0;
+    }
+    if (tid == 0) {
+        toploc_verify_result r = {};
+        r.err_exp = vs.err_e;
+        r.n_match = n;
+        r.mant_sum = vs.mant_sum;
+        r.mant_median = n ? med : 0u;
+        bool reject = vs.err_e > thr.t_exp;
+        if (n) {
+            if ((uint64_t)vs.mant_sum > (uint64_t)thr.t_mean * n) reject = true;   // mean(err_m) > T_mean
+            if (r.mant_median > thr.t_median) reject = true;
         }
+        r.accept = reject ? 0 : 1;
+        r.status = TOPLOC_CHUNK_OK;
+        *result = r;
     }
 }
 

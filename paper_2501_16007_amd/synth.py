@@ -31,8 +31,8 @@ def outlier_channels(hidden, n_outlier, seed):
 
 
 def activations(n_seq, n_tok, hidden, seed, n_outlier=8, outlier_scale=20.0, lognormal_sigma=0.5,
-                device="cpu", channel_seed=None):
-    """bf16 tensor [n_seq, n_tok, hidden]: N(0,1) bulk; `n_outlier` fixed channels
+                device="cpu", channel_seed=None, dtype=torch.bfloat16):
+    """bf16 (or fp32) tensor [n_seq, n_tok, hidden]: N(0,1) bulk; `n_outlier` fixed channels
     multiplied by outlier_scale * exp(lognormal_sigma * z), z ~ N(0,1) drawn per
     (sequence, channel).  lognormal_sigma = 0 gives the plain x`outlier_scale` case.
     Built one sequence at a time so the fp32 staging stays small."""
@@ -42,12 +42,12 @@ def activations(n_seq, n_tok, hidden, seed, n_outlier=8, outlier_scale=20.0, log
     gs = _gen(seed + 2, "cpu")
     z = torch.randn((n_seq, n_outlier), generator=gs)
     scale = (outlier_scale * torch.exp(lognormal_sigma * z)).to(device)
-    out = torch.empty((n_seq, n_tok, hidden), dtype=torch.bfloat16, device=device)
+    out = torch.empty((n_seq, n_tok, hidden), dtype=dtype, device=device)
     for s in range(n_seq):
         x = torch.randn((n_tok, hidden), generator=g, device=device, dtype=torch.float32)
         if n_outlier:
             x[:, ch] *= scale[s][None, :]
-        out[s] = x.to(torch.bfloat16)
+        out[s] = x.to(dtype)
     return out
 
 
@@ -60,13 +60,18 @@ def as_chunks(x, chunk_tokens=CHUNK_TOKENS):
 
 
 def bits_numpy(x):
-    """bf16 tensor -> numpy uint16 array of the bit patterns (host copy)."""
+    """bf16 (fp32) tensor -> numpy uint16 (uint32) array of the bit patterns (host copy)."""
+    if x.dtype == torch.float32:
+        return x.contiguous().view(torch.int32).cpu().numpy().view(np.uint32)
     return x.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
 
 
 def from_bits(bits, device="cpu"):
-    """numpy uint16 patterns -> bf16 tensor."""
-    t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16).copy())
+    """numpy uint16 patterns -> bf16 tensor; uint32 patterns -> fp32 tensor."""
+    bits = np.ascontiguousarray(bits)
+    if bits.dtype == np.uint32:
+        return torch.from_numpy(bits.view(np.int32).copy()).view(torch.float32).to(device)
+    t = torch.from_numpy(bits.view(np.int16).copy())
     return t.view(torch.bfloat16).to(device)
 
 
