@@ -25,9 +25,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="config3", choices=["config3", "config2", "config4", "config5"],
+    ap.add_argument("--workload", default="config3", choices=["config3", "config2", "config4", "config5", "config3_f32"],
                     help="config3 is the benchmark line; config2 is the 8B shape; config4 (verification stress) and "
-                         "config5 (online decode-step path) print their own report line")
+                         "config5 (online decode-step path) print their own report line; config3_f32 is the 70B "
+                         "shape with fp32 activations (64 sequences, the same 8 GiB) through the fp32 calls")
     ap.add_argument("--k", type=int, default=128)
     ap.add_argument("--cpu-sample-chunks", type=int, default=6144)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -50,7 +51,11 @@ def main():
         return report_config4(args, tl, synth, torch, dev)
     if args.workload == "config5":
         return report_config5(args, tl, synth, torch, dev)
-    if args.workload == "config3":
+    f32 = args.workload == "config3_f32"
+    if f32:
+        x = synth.activations(64, 4096, 8192, synth.BASE_SEED + 3, n_outlier=16, device=dev, dtype=torch.float32)
+        name = "llama-3.1-70b-shaped, fp32: 64 seq x 4096 tok x hidden 8192 fp32, 32-token chunks, k=%d" % k
+    elif args.workload == "config3":
         x = synth.config3(dev)
         name = "llama-3.1-70b-shaped: 128 seq x 4096 tok x hidden 8192 bf16, 32-token chunks, k=%d" % k
     else:
@@ -58,8 +63,8 @@ def main():
         name = "llama-3.1-8b-shaped: 64 seq x 2048 tok x hidden 4096 bf16, 32-token chunks, k=%d" % k
     chunks = synth.as_chunks(x)
     n_chunks, n = chunks.shape
-    act_bytes = n_chunks * n * 2
-    pb = 2 + 2 * k
+    act_bytes = n_chunks * n * (4 if f32 else 2)
+    pb = 2 + (4 if f32 else 2) * k
 
     proofs = torch.empty((n_chunks, pb), dtype=torch.uint8, device=dev)
     status = torch.empty(n_chunks, dtype=torch.uint8, device=dev)
@@ -67,6 +72,12 @@ def main():
     ws = tl.new_workspace(k, 1, n, n_chunks, dev)
 
     def step():
+        if f32:
+            p, st = tl.toploc_build_proofs_f32(chunks, k=k, chunk_tokens=1)
+            proofs.copy_(p)
+            status.copy_(st)
+            results.copy_(tl.toploc_verify_proofs_mixed(chunks, p, tl.DTYPE_F32, k=k, chunk_tokens=1))
+            return
         tl.toploc_build_proofs(chunks, k=k, chunk_tokens=1, workspace=ws, out=(proofs, status))
         tl.toploc_verify_proofs(chunks, proofs, k=k, chunk_tokens=1, out=results)
 
@@ -95,9 +106,10 @@ def main():
     kernels = {}
     # parts a chunk is cut into when the batch is small or k > 128 (0 bytes of workspace: one fused launch)
     parts = max(1, round(tl.toploc_workspace_bytes(k, 1, n, n_chunks) / (6.0 * k * n_chunks)))
+    eb = 4 if f32 else 2
     alg_bytes = {   # algorithmic HBM bytes per chunk: what the method itself must move
-        "build_kernel": 2 * n + pb + 1,                     # read the chunk, write the proof and status
-        "verify_kernel": 2 * n + pb + 20,                   # read the chunk and the proof, write the record
+        "build_kernel": eb * n + pb + 1,                    # read the chunk, write the proof and status
+        "verify_kernel": eb * n + pb + 20,                  # read the chunk and the proof, write the record
         "part_kernel": 2 * n + 6 * k * parts,               # split path: read the chunk, hand candidates on
         "build_merge_kernel": 6 * k * parts + pb + 1,       # split path: read the candidates, write the proof
         "verify_merge_kernel": 6 * k * parts + pb + 20,     # split path: candidates and proof in, record out
@@ -148,13 +160,17 @@ def main():
         sample = synth.bits_numpy(chunks[sel])
         cores = orc.max_threads()
         t0 = time.perf_counter()
-        o_proofs, o_status = orc.build(sample, k)
-        o_res = orc.verify(sample, o_proofs, k)
+        if f32:
+            o_proofs, o_status = orc.build32(sample, k)
+            o_res = orc.verify_mixed(sample, orc.F32, o_proofs, orc.F32, k)
+        else:
+            o_proofs, o_status = orc.build(sample, k)
+            o_res = orc.verify(sample, o_proofs, k)
         cdt = time.perf_counter() - t0
         assert np.array_equal(proofs[sel].cpu().numpy(), o_proofs), "GPU proofs differ from the oracle on the sample"
         assert bool((o_res["accept"] == 1).all())
         cpu = {
-            "value": 2 * sample.size * 2 / cdt / 1e9,
+            "value": 2 * sample.size * eb / cdt / 1e9,
             "unit": "GB/s",
             "cores": cores,
             "kind": "oracle",
@@ -174,7 +190,7 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "u16",
+        "dtype": "u32" if f32 else "u16",
         "data": "synthetic",
         "config": {"workload": name, "n_chunks": n_chunks, "chunk_values": n, "k": k,
                    "activation_bytes": act_bytes},
