@@ -89,8 +89,8 @@ __global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void select_kernel(cons
 // then the same workgroup turns its k pairs into the proof out of LDS (the selection's
 // buffers are dead by then and are reused).
 // ---------------------------------------------------------------------------
-template <int KMAX, int CAP, typename F = Field16, typename Fmt = Bf16Fmt>
-__global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void build_kernel(const u32x4* __restrict__ hidden, uint32_t nvec,
+template <int KMAX, int CAP, typename F = Field16, typename Fmt = Bf16Fmt, int U = kLoads, int WAVES = TOPLOC_MIN_WAVES>
+__global__ __launch_bounds__(kThreads, WAVES) void build_kernel(const u32x4* __restrict__ hidden, uint32_t nvec,
                                                                            uint32_t k, uint8_t* __restrict__ proofs,
                                                                            uint8_t* __restrict__ status,
                                                                            uint32_t* __restrict__ out_idx)
@@ -103,7 +103,7 @@ __global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void build_kernel(const
     __shared__ uint32_t coef[KMAX];
     const uint32_t tid = threadIdx.x;
     const uint64_t chunk = blockIdx.x;
-    select_topk<kThreads, kLoads>(hidden + chunk * nvec, 0u, nvec, k, sh.sel);
+    select_topk<kThreads, U>(hidden + chunk * nvec, 0u, nvec, k, sh.sel);
     if (out_idx) {  // uniform: the caller wants the ordered indices
         order_topk(sh.sel, k);
         if (tid < k) out_idx[chunk * k + tid] = sh.sel.cand_idx[tid];
@@ -124,8 +124,8 @@ __global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void build_kernel(const
 // ---------------------------------------------------------------------------
 // F is the proof's field, Fmt the format of the recomputed activations (Section 5.6
 // validates across the two precisions).
-template <int KMAX, int CAP, typename F = Field16, typename Fmt = Bf16Fmt>
-__global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void verify_kernel(const u32x4* __restrict__ hidden, uint32_t nvec,
+template <int KMAX, int CAP, typename F = Field16, typename Fmt = Bf16Fmt, int U = kLoads, int WAVES = TOPLOC_MIN_WAVES>
+__global__ __launch_bounds__(kThreads, WAVES) void verify_kernel(const u32x4* __restrict__ hidden, uint32_t nvec,
                                                                             uint32_t k, const uint8_t* __restrict__ proofs,
                                                                             toploc_thresholds thr,
                                                                             toploc_verify_result* __restrict__ results)
@@ -135,9 +135,17 @@ __global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void verify_kernel(cons
     const uint64_t chunk = blockIdx.x;
     const uint16_t* proof = reinterpret_cast<const uint16_t*>(proofs + chunk * (2 + 2 * (uint64_t)F::WORDS * k));
     if (!verify_decode<kThreads, F>(vs, proof, k, results + chunk)) return;
-    select_topk<kThreads, kLoads>(hidden + chunk * nvec, 0u, nvec, k, s);  // order is irrelevant here
+    select_topk<kThreads, U>(hidden + chunk * nvec, 0u, nvec, k, s);  // order is irrelevant here
     verify_tail<kThreads, F, Fmt>(vs, s.cand_idx, s.cand_bits, k, thr, results + chunk);
 }
+
+// Two shapes of the fused kernels.  A launch of many generations of workgroups is served
+// best by 4 loads per lane and round at 5 waves per SIMD; a launch of only a few
+// generations (the 8B shape's 4096 chunks of 256 KB) spends a larger share of each
+// workgroup's life outside the streaming loop and gains more from a sixth resident
+// workgroup per compute unit, which 3 loads per lane leave registers for.
+constexpr int kLoadsShort = 3, kWavesShort = 6;
+constexpr uint64_t kShortLaunchGroups = 6 * 5 * 256;  // fewer than about six generations
 
 // ---------------------------------------------------------------------------
 // Split path, first launch: top-k of one part.  Writes k candidate slots per part,
@@ -666,8 +674,13 @@ int toploc_build_proofs(const void* d_hidden_bf16, uint64_t n_chunks, const topl
     const bool have_ws = d_workspace && workspace_bytes >= cand_bytes(n_chunks * f.parts, k);
     if (k <= 128 && (f.parts == 1 || !have_ws)) {  // one launch; also the answer to a missing workspace
         ProfScope ps(TOPLOC_KERNEL_BUILD, st);
-        hipLaunchKernelGGL((build_kernel<128, kCapSmall>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
-                           (const u32x4*)d_hidden_bf16, nvec, k, d_proofs, d_status, d_topk_idx_opt);
+        if (n_chunks < kShortLaunchGroups)
+            hipLaunchKernelGGL((build_kernel<128, kCapSmall, Field16, Bf16Fmt, kLoadsShort, kWavesShort>),
+                               dim3((uint32_t)n_chunks), dim3(kThreads), 0, st, (const u32x4*)d_hidden_bf16, nvec, k,
+                               d_proofs, d_status, d_topk_idx_opt);
+        else
+            hipLaunchKernelGGL((build_kernel<128, kCapSmall>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
+                               (const u32x4*)d_hidden_bf16, nvec, k, d_proofs, d_status, d_topk_idx_opt);
         return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
     }
     if (!have_ws) return d_workspace ? TOPLOC_EWORKSPACE : TOPLOC_EINVAL;
@@ -701,7 +714,11 @@ int toploc_verify_proofs(const void* d_hidden_bf16, uint64_t n_chunks, const top
     const bool split = f.parts > 1 && d_workspace && workspace_bytes >= cand_bytes(slots, k) && slots < (1ull << 31);
     if (!split) {  // one launch; a missing workspace only costs speed on small batches
         ProfScope ps(TOPLOC_KERNEL_VERIFY, st);
-        if (k <= 128)
+        if (k <= 128 && n_chunks < kShortLaunchGroups)
+            hipLaunchKernelGGL((verify_kernel<128, kCapSmall, Field16, Bf16Fmt, kLoadsShort, kWavesShort>),
+                               dim3((uint32_t)n_chunks), dim3(kThreads), 0, st, (const u32x4*)d_hidden_bf16, nvec, k,
+                               d_proofs, *thresholds, d_results);
+        else if (k <= 128)
             hipLaunchKernelGGL((verify_kernel<128, kCapSmall>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
                                (const u32x4*)d_hidden_bf16, nvec, k, d_proofs, *thresholds, d_results);
         else
