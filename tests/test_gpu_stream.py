@@ -109,3 +109,41 @@ def test_stream_equals_the_ring_path_at_full_width():
         assert np.array_equal(idx, r_idx.cpu().numpy().view(np.uint32))
         o_proofs, o_status, o_idx = orc.build(sample_bits, k, want_topk=True)
         assert np.array_equal(proofs[sel], o_proofs) and np.array_equal(idx[sel], o_idx)
+
+
+def test_stream_window_captured_in_a_graph_replays_like_eager():
+    """32 appends and the emission captured once (no memset nodes: the library only launches kernels),
+    replayed three times on fresh data with eager work and synchronisations in between."""
+    n_seq, hidden, T, k = 64, 5120, 32, 128
+    steps = synth.config5_steps(n_seq, hidden, 3 * T, seed=7300, device=DEV)
+    static = torch.empty((T, n_seq, hidden), dtype=torch.bfloat16, device=DEV)
+    state = tl.toploc_stream_new_state(n_seq, k, DEV)
+    proofs = torch.empty((n_seq, 2 + 2 * k), dtype=torch.uint8, device=DEV)
+    status = torch.empty(n_seq, dtype=torch.uint8, device=DEV)
+
+    def window():
+        for t in range(T):
+            tl.toploc_stream_append(state, static[t], t, k=k, chunk_tokens=T)
+        tl.toploc_stream_emit(state, n_seq, k=k, out=(proofs, status))
+
+    static.copy_(steps[:T])
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        window()                                   # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        window()
+    for rep in range(3):
+        static.copy_(steps[rep * T:(rep + 1) * T])
+        proofs.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        replayed = proofs.clone()
+        window()                                   # the same window, eager
+        torch.cuda.synchronize()
+        assert torch.equal(replayed, proofs) and int(status.max()) == 0, "replay %d differs from eager" % rep
+        bits = synth.bits_numpy(static.transpose(0, 1).contiguous()).reshape(n_seq, -1)
+        o_proofs, _ = orc.build(bits[:8], k)
+        assert np.array_equal(replayed[:8].cpu().numpy(), o_proofs)
