@@ -411,6 +411,7 @@ __device__ __forceinline__ SelectStart select_topk_from(const u32x4* __restrict_
     const uint32_t tid = threadIdx.x;
     u32x4 even[U], odd[U];  // two rounds in registers: one is examined while the other one's loads fly
     load_round<THREADS, U>(even, src, v0, v1);
+    load_round<THREADS, U>(odd, src, v0 + ROUND, v1);   // in flight while the first threshold is found
     const SelectStart start = seeder.seed(s);
     const uint32_t k = start.k;
     const uint32_t n_seed = start.n;
@@ -442,7 +443,6 @@ __device__ __forceinline__ SelectStart select_topk_from(const u32x4* __restrict_
 
     uint32_t base = v0;  // v1 - v0 >= 1
     while (true) {
-        load_round<THREADS, U>(odd, src, base + ROUND, v1);
         examine_round<THREADS, U>(even, base, v1, k, s, t, round);
         base += ROUND;
         if (base >= v1) break;
@@ -450,6 +450,7 @@ __device__ __forceinline__ SelectStart select_topk_from(const u32x4* __restrict_
         examine_round<THREADS, U>(odd, base, v1, k, s, t, round);
         base += ROUND;
         if (base >= v1) break;
+        load_round<THREADS, U>(odd, src, base + ROUND, v1);
     }
     __syncthreads();
     (void)drain(s, k, k, t);  // prunes to exactly k

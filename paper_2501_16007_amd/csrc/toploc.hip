@@ -122,6 +122,22 @@ __global__ __launch_bounds__(kThreads, WAVES) void build_kernel(const u32x4* __r
 // ---------------------------------------------------------------------------
 // Algorithm 2, fused: one pass over the recomputed chunk
 // ---------------------------------------------------------------------------
+// decode(p) as the first thing a selection does after issuing its first loads
+template <typename F, int KMAX, bool WIDE>
+struct DecodeFirst {
+    VerifyShared<KMAX, WIDE>& vs;
+    const uint16_t* proof;
+    uint32_t k;
+    toploc_verify_result* result;
+    bool* ok;
+    template <typename Shared>
+    __device__ __forceinline__ SelectStart seed(Shared&) const
+    {
+        *ok = verify_decode<kThreads, F>(vs, proof, k, result);
+        return SelectStart{0u, Threshold{0, 0xFFFFFFFFu}, k};
+    }
+};
+
 // F is the proof's field, Fmt the format of the recomputed activations (Section 5.6
 // validates across the two precisions).
 template <int KMAX, int CAP, typename F = Field16, typename Fmt = Bf16Fmt, int U = kLoads, int WAVES = TOPLOC_MIN_WAVES>
@@ -134,8 +150,12 @@ __global__ __launch_bounds__(kThreads, WAVES) void verify_kernel(const u32x4* __
     __shared__ VerifyShared<KMAX, Fmt::ELEMS == 4> vs;
     const uint64_t chunk = blockIdx.x;
     const uint16_t* proof = reinterpret_cast<const uint16_t*>(proofs + chunk * (2 + 2 * (uint64_t)F::WORDS * k));
-    if (!verify_decode<kThreads, F>(vs, proof, k, results + chunk)) return;
-    select_topk<kThreads, U>(hidden + chunk * nvec, 0u, nvec, k, s);  // order is irrelevant here
+    // decode(p) runs once the chunk's first loads are in flight; a malformed proof has its record
+    // written there and the selection's result is dropped
+    bool ok = true;
+    const DecodeFirst<F, KMAX, Fmt::ELEMS == 4> first{vs, proof, k, results + chunk, &ok};
+    (void)select_topk_from<kThreads, U>(hidden + chunk * nvec, 0u, nvec, s, first);  // order is irrelevant here
+    if (!ok) return;  // uniform
     verify_tail<kThreads, F, Fmt>(vs, s.cand_idx, s.cand_bits, k, thr, results + chunk);
 }
 
