@@ -5,16 +5,16 @@
 // |x| taken as the integer (bits & 0x7FFF), for fp32 (bits & 0x7FFFFFFF).
 //
 // Method (a streaming filter with a rising threshold, not a sort):
-//   * every lane reads 16 bytes (8 values) per load, U loads per round, and the
-//     loads of the next round are issued before the current round is examined;
-//   * the hot loop does one thing per vector: a packed 16-bit max over the 8
-//     magnitudes against the threshold magnitude tm (about 1.3 VALU ops per value).
-//     A vector that passes is copied whole into an LDS queue, nothing else;
+//   * every lane reads 16 bytes (8 bf16 or 4 fp32 values) per load, U loads per round, and
+//     the loads of the next round are issued before the current round is examined;
+//   * the hot loop does one thing per vector: the largest of its magnitudes (a packed
+//     16-bit max tree for bf16) against the threshold magnitude tm, about 1.3 VALU ops
+//     per value.  A vector that passes is copied whole into an LDS queue, nothing else;
 //   * when the queue passes its soft limit the workgroup drains it with all lanes
 //     evenly loaded: every queued value that comes before the threshold element
 //     (tm, ti) goes to the candidate buffer, and when that buffer passes its own
 //     limit it is pruned to the exact best k (radix select on the 8-bit exponent,
-//     then the 7-bit mantissa, then the index among equal magnitudes); the k-th
+//     then the mantissa, then the index among equal magnitudes); the k-th
 //     survivor becomes the new threshold element;
 //   * the first threshold comes from the per-vector maxima of the first round, so
 //     nothing is ever flooded; a queue overflow loses nothing either: the vectors of
@@ -385,7 +385,8 @@ __device__ __forceinline__ void examine_round(const u32x4 (&buf)[U], uint32_t b,
 // continues an earlier one (one token row per call): its seed() puts the n survivors of the
 // earlier calls (n <= k) into s.cand_idx / s.cand_bits [0, n) and reports the threshold
 // those calls ended with, and k then counts seeds and new values together.  seed() runs
-// after the loads of the first round were issued, so that its own global reads overlap them.
+// after the loads of the first two rounds were issued, so that its own global reads overlap
+// them (the verify kernel decodes its proof there for the same reason).
 struct SelectStart {
     uint32_t n;   // seeds placed in the candidate buffer
     Threshold t;  // first threshold; (0, 0xFFFFFFFF): everything comes before it, nothing seen yet
