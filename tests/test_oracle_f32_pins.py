@@ -35,7 +35,10 @@ def lagrange_coeffs(xs, ys, M):
     return out
 
 
-def test_prime_and_sizes():
+def test_prime_and_sizes(golden):
+    g = {r[0]: int(r[1]) for r in golden("sizes_and_thresholds.txt")}
+    assert orc.F32_THRESHOLDS == (g["t_exp_fp32"], g["t_mean_fp32"], g["t_median_fp32"])
+    assert g["mantissa_bits_fp32"] - g["mantissa_bits_bf16"] == 16          # the shift between the two precisions
     assert P32 == 2 ** 32 - 5
     assert all(P32 % q for q in range(2, 65536))     # trial division up to sqrt(2^32)
     assert orc.proof_bytes32(128) == 514 and orc.proof_bytes32(1) == 6
