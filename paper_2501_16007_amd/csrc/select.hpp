@@ -37,6 +37,17 @@
 #define TOPLOC_DRAIN_ATTR __forceinline__
 #endif
 
+#ifdef TOPLOC_TIMING
+// debug builds only: wall-clock ticks (100 MHz) per phase, summed over workgroups by lane 0
+__device__ unsigned long long g_toploc_ticks[16];
+#define TOPLOC_TICK_BEGIN(name) const long long tick_##name = wall_clock64()
+#define TOPLOC_TICK_END(name, slot) \
+    do { if (threadIdx.x == 0) atomicAdd(&g_toploc_ticks[slot], (unsigned long long)(wall_clock64() - tick_##name)); } while (0)
+#else
+#define TOPLOC_TICK_BEGIN(name)
+#define TOPLOC_TICK_END(name, slot)
+#endif
+
 namespace toploc {
 
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
@@ -274,6 +285,7 @@ __device__ TOPLOC_DRAIN_ATTR bool drain(SelectShared<THREADS, CAP, QCAP, Fmt>& s
 {
     constexpr uint32_t BATCH = (CAP / 16 < THREADS / 2) ? CAP / 16 : THREADS / 2;  // vectors: ELEMS * BATCH <= CAP / 2
     const uint32_t tid = threadIdx.x;
+
     const uint32_t raw = s.qcount;
     const uint32_t nq = raw < (uint32_t)QCAP ? raw : (uint32_t)QCAP;
     const uint32_t count0 = s.count;  // <= CAP/2; only drains and prunes change it
@@ -374,7 +386,10 @@ __device__ __forceinline__ void examine_round(const u32x4 (&buf)[U], uint32_t b,
         if (tid == 0) s.flag[(round + 2u) % 3u] = 0;  // the previous round's flag: read by all before this barrier
         ++round;
         if (!f) break;  // no slot at or past the soft limit was handed out: nothing is pending either
-        if (!drain(s, k, TOPLOC_PRUNE_LIMIT(CAP, k), t)) break;
+        TOPLOC_TICK_BEGIN(drain);
+        const bool again = drain(s, k, TOPLOC_PRUNE_LIMIT(CAP, k), t);
+        TOPLOC_TICK_END(drain, 2);
+        if (!again) break;
 #pragma unroll
         for (int u = 0; u < U; ++u)
             if (m[u] < t.tm) pend &= ~(1u << u);
@@ -410,6 +425,7 @@ __device__ __forceinline__ SelectStart select_topk_from(const u32x4* __restrict_
 {
     constexpr uint32_t ROUND = THREADS * U;
     const uint32_t tid = threadIdx.x;
+    TOPLOC_TICK_BEGIN(boot);
     u32x4 even[U], odd[U];  // two rounds in registers: one is examined while the other one's loads fly
     load_round<THREADS, U>(even, src, v0, v1);
     load_round<THREADS, U>(odd, src, v0 + ROUND, v1);   // in flight while the first threshold is found
@@ -442,6 +458,8 @@ __device__ __forceinline__ SelectStart select_topk_from(const u32x4* __restrict_
     }
     __syncthreads();
 
+    TOPLOC_TICK_END(boot, 0);
+    TOPLOC_TICK_BEGIN(stream);
     uint32_t base = v0;  // v1 - v0 >= 1
     while (true) {
         examine_round<THREADS, U>(even, base, v1, k, s, t, round);
@@ -454,7 +472,10 @@ __device__ __forceinline__ SelectStart select_topk_from(const u32x4* __restrict_
         load_round<THREADS, U>(odd, src, base + ROUND, v1);
     }
     __syncthreads();
+    TOPLOC_TICK_END(stream, 1);
+    TOPLOC_TICK_BEGIN(fin);
     (void)drain(s, k, k, t);  // prunes to exactly k
+    TOPLOC_TICK_END(fin, 3);
     return SelectStart{k, t, k};
 }
 

@@ -130,8 +130,10 @@ __global__ __launch_bounds__(kThreads, WAVES) void build_kernel(const u32x4* __r
         sh.itp.idx[tid] = my_idx;
         sh.itp.ys[tid] = (typename F::elem_t)F::from_pattern(my_y);
     }
+    TOPLOC_TICK_BEGIN(tail);
     finish_proof<kThreads>(sh.itp, coef, k,
                            reinterpret_cast<uint16_t*>(proofs + chunk * (2 + 2 * (uint64_t)F::WORDS * k)), status + chunk);
+    TOPLOC_TICK_END(tail, 5);
 }
 
 // ---------------------------------------------------------------------------
@@ -171,7 +173,9 @@ __global__ __launch_bounds__(kThreads, WAVES) void verify_kernel(const u32x4* __
     const DecodeFirst<F, KMAX, Fmt::ELEMS == 4> first{vs, proof, k, results + chunk, &ok};
     (void)select_topk_from<kThreads, U>(hidden + chunk * nvec, 0u, nvec, s, first);  // order is irrelevant here
     if (!ok) return;  // uniform
+    TOPLOC_TICK_BEGIN(tail);
     verify_tail<kThreads, F, Fmt>(vs, s.cand_idx, s.cand_bits, k, thr, results + chunk);
+    TOPLOC_TICK_END(tail, 4);
 }
 
 // Two shapes of the fused kernels.  A launch of many generations of workgroups is served
@@ -1024,5 +1028,15 @@ const char* toploc_strerror(int code)
 }
 
 int toploc_last_hip_error(void) { return g_last_hip_error; }
+
+#ifdef TOPLOC_TIMING
+// debug builds only: read (out != NULL) or clear the per-phase tick sums
+int toploc_debug_ticks(unsigned long long* out)
+{
+    unsigned long long z[16] = {0};
+    if (out) return hip_ok(hipMemcpyFromSymbol(out, HIP_SYMBOL(g_toploc_ticks), sizeof(z))) ? TOPLOC_OK : TOPLOC_EHIP;
+    return hip_ok(hipMemcpyToSymbol(HIP_SYMBOL(g_toploc_ticks), z, sizeof(z))) ? TOPLOC_OK : TOPLOC_EHIP;
+}
+#endif
 
 }  // extern "C"
