@@ -107,9 +107,11 @@ struct SelectShared {
     typename Fmt::bits_t cand_bits[CAP];  //     pattern
     uint16_t eq_slot[CAP];    // prune: slots whose magnitude equals the new threshold
     uint32_t hist[Fmt::LEVELS][256];  // prune: one histogram per radix digit
-    uint32_t qcount;          // queue slots handed out (may run past QCAP on overflow)
+    uint32_t qcount[2];       // queue slots handed out (may run past QCAP on overflow); one counter per
+                              // drain epoch, so that the next epoch's is cleared without a barrier of its own
     uint32_t count;           // candidate slots in use
     uint32_t eq_count;
+    uint32_t found_bin, found_above;  // prune: what wave 0 found in a histogram, for the other waves
     uint32_t hole_count;      // prune: slots below k whose entry does not survive
     uint32_t move_count;      // prune: survivors at or above slot k, moved into the holes
     int32_t tm;               // threshold magnitude
@@ -164,11 +166,14 @@ __device__ __forceinline__ bool before(int32_t mag, uint32_t idx, const Threshol
 }
 
 // If the candidate buffer holds more than `limit` entries, reduce it to the exact
-// best k and make the k-th the threshold element.  Called by all threads, starts and
-// ends with a barrier.  Returns the number of slots that had been handed out: a value
-// above CAP means appends were dropped, and nothing is pruned then (the caller redoes
-// them); a value in (limit, CAP] means it pruned and `t` is the new threshold.
-template <int THREADS, int CAP, int QCAP, typename Fmt>
+// best k and make the k-th the threshold element.  Called by all threads, starts with a
+// barrier and, when it prunes, ends with one.  When it does not prune it ends with a
+// barrier only if SYNC_AFTER: a caller whose next append to the buffer lies behind a
+// barrier of its own anyway (the streaming loop: one per round) saves that one.  Returns the
+// number of slots that had been handed out: a value above CAP means appends were dropped,
+// and nothing is pruned then (the caller redoes them); a value in (limit, CAP] means it
+// pruned and `t` is the new threshold.
+template <bool SYNC_AFTER = true, int THREADS, int CAP, int QCAP, typename Fmt>
 __device__ TOPLOC_PRUNE_ATTR uint32_t prune_if_above(SelectShared<THREADS, CAP, QCAP, Fmt>& s, uint32_t k, uint32_t limit,
                                                      Threshold& t)
 {
@@ -176,7 +181,7 @@ __device__ TOPLOC_PRUNE_ATTR uint32_t prune_if_above(SelectShared<THREADS, CAP, 
     __syncthreads();  // appends are visible
     const uint32_t M = s.count;
     if (M <= limit || M > (uint32_t)CAP) {  // uniform decision
-        __syncthreads();  // everyone has read the count before anyone appends again
+        if (SYNC_AFTER) __syncthreads();  // everyone has read the count before anyone appends again
         return M;
     }
     for (uint32_t b = tid; b < 256u * Fmt::LEVELS; b += THREADS) (&s.hist[0][0])[b] = 0;
@@ -193,9 +198,15 @@ __device__ TOPLOC_PRUNE_ATTR uint32_t prune_if_above(SelectShared<THREADS, CAP, 
             if (l == 0 || (mag >> (sh + w)) == prefix) atomicAdd(&s.hist[l][(mag >> sh) & ((1u << w) - 1u)], 1u);
         }
         __syncthreads();
-        uint32_t digit;
-        if (w == 8) find_bin<4>(s.hist[l], above, k, digit, above);
-        else find_bin<2>(s.hist[l], above, k, digit, above);
+        if (tid < 64) {  // one wave searches the histogram; the others only wait
+            uint32_t d, a;
+            if (w == 8) find_bin<4>(s.hist[l], above, k, d, a);
+            else find_bin<2>(s.hist[l], above, k, d, a);
+            if (tid == 0) { s.found_bin = d; s.found_above = a; }
+        }
+        __syncthreads();
+        const uint32_t digit = s.found_bin;
+        above = s.found_above;
         prefix = (prefix << w) | digit;
     }
     const uint32_t new_tm = prefix;
@@ -278,20 +289,27 @@ __device__ __forceinline__ void drain_range(SelectShared<THREADS, CAP, QCAP, Fmt
 // CAP slots (the excess is dropped, not written), the sweep is undone and repeated in
 // batches of at most CAP/16 vectors with a prune check after each: a batch adds at most
 // CAP/2 values to a buffer holding at most CAP/2.
-// Called by all threads after a barrier that made the queue writes visible; ends with
-// a barrier.  Returns true when lanes are still waiting for room in the queue.
+// Called by all threads after a barrier that made the queue writes visible.  `epoch`
+// (uniform) says which queue counter the pushes used; the drain clears the other one and
+// switches to it, so the usual drain costs one barrier: the caller must pass one more
+// barrier before it touches the candidate buffer again (the streaming loop has one per
+// round; select_topk_from ends with one).  Returns true when lanes are still waiting for
+// room in the queue.
 template <int THREADS, int CAP, int QCAP, typename Fmt>
-__device__ TOPLOC_DRAIN_ATTR bool drain(SelectShared<THREADS, CAP, QCAP, Fmt>& s, uint32_t k, uint32_t limit, Threshold& t)
+__device__ TOPLOC_DRAIN_ATTR bool drain(SelectShared<THREADS, CAP, QCAP, Fmt>& s, uint32_t k, uint32_t limit, Threshold& t,
+                                        uint32_t& epoch)
 {
     constexpr uint32_t BATCH = (CAP / 16 < THREADS / 2) ? CAP / 16 : THREADS / 2;  // vectors: ELEMS * BATCH <= CAP / 2
     const uint32_t tid = threadIdx.x;
-
-    const uint32_t raw = s.qcount;
+    const uint32_t raw = s.qcount[epoch & 1u];
     const uint32_t nq = raw < (uint32_t)QCAP ? raw : (uint32_t)QCAP;
     const uint32_t count0 = s.count;  // <= CAP/2; only drains and prunes change it
+    if (tid == 0) s.qcount[(epoch + 1u) & 1u] = 0;  // last read one drain ago; visible after the barrier below
+    ++epoch;
     limit = limit < (uint32_t)(CAP / 2) ? limit : (uint32_t)(CAP / 2);
     drain_range(s, 0u, nq, t);
-    if (prune_if_above(s, k, limit, t) > (uint32_t)CAP) {  // uniform; rare
+    if (prune_if_above<false>(s, k, limit, t) > (uint32_t)CAP) {  // uniform; rare
+        __syncthreads();  // everyone has read the count
         if (tid == 0) s.count = count0;
         __syncthreads();
         for (uint32_t b0 = 0; b0 < nq; b0 += BATCH) {
@@ -301,8 +319,6 @@ __device__ TOPLOC_DRAIN_ATTR bool drain(SelectShared<THREADS, CAP, QCAP, Fmt>& s
         }
         (void)prune_if_above(s, k, limit, t);
     }
-    if (tid == 0) s.qcount = 0;
-    __syncthreads();
     return raw > (uint32_t)QCAP;
 }
 
@@ -339,7 +355,8 @@ __device__ __forceinline__ void load_round(u32x4 (&buf)[U], const u32x4* __restr
 // found the queue full retry after the drain (against the new threshold).
 template <int THREADS, int U, int CAP, int QCAP, typename Fmt>
 __device__ __forceinline__ void examine_round(const u32x4 (&buf)[U], uint32_t b, uint32_t v1, uint32_t k,
-                                              SelectShared<THREADS, CAP, QCAP, Fmt>& s, Threshold& t, uint32_t& round)
+                                              SelectShared<THREADS, CAP, QCAP, Fmt>& s, Threshold& t, uint32_t& round,
+                                              uint32_t& epoch)
 {
     constexpr uint32_t QSOFT = QCAP / 2;
     const uint32_t tid = threadIdx.x;
@@ -365,7 +382,7 @@ __device__ __forceinline__ void examine_round(const u32x4 (&buf)[U], uint32_t b,
                 total += (uint32_t)__popcll(want[u]);
             }
             uint32_t first = 0;
-            if (lane_id() == 0) first = atomicAdd(&s.qcount, total);
+            if (lane_id() == 0) first = atomicAdd(&s.qcount[epoch & 1u], total);
             first = __builtin_amdgcn_readfirstlane(first);
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -387,7 +404,7 @@ __device__ __forceinline__ void examine_round(const u32x4 (&buf)[U], uint32_t b,
         ++round;
         if (!f) break;  // no slot at or past the soft limit was handed out: nothing is pending either
         TOPLOC_TICK_BEGIN(drain);
-        const bool again = drain(s, k, TOPLOC_PRUNE_LIMIT(CAP, k), t);
+        const bool again = drain(s, k, TOPLOC_PRUNE_LIMIT(CAP, k), t, epoch);
         TOPLOC_TICK_END(drain, 2);
         if (!again) break;
 #pragma unroll
@@ -433,11 +450,12 @@ __device__ __forceinline__ SelectStart select_topk_from(const u32x4* __restrict_
     const uint32_t k = start.k;
     const uint32_t n_seed = start.n;
     if (tid == 0) {
-        s.qcount = 0; s.count = n_seed; s.eq_count = 0; s.tm = start.t.tm; s.ti = start.t.ti;
+        s.qcount[0] = 0; s.qcount[1] = 0; s.count = n_seed; s.eq_count = 0; s.tm = start.t.tm; s.ti = start.t.ti;
         s.flag[0] = 0; s.flag[1] = 0; s.flag[2] = 0;
     }
     Threshold t = start.t;
     uint32_t round = 0;    // barrier rounds; flag[round % 3] belongs to the current one
+    uint32_t epoch = 0;    // drains so far; qcount[epoch % 2] counts the current pushes
 
     // First threshold: the largest magnitude of every vector of the first round belongs
     // to a distinct real element.  If at least k of those maxima have exponent >= e, then
@@ -462,11 +480,11 @@ __device__ __forceinline__ SelectStart select_topk_from(const u32x4* __restrict_
     TOPLOC_TICK_BEGIN(stream);
     uint32_t base = v0;  // v1 - v0 >= 1
     while (true) {
-        examine_round<THREADS, U>(even, base, v1, k, s, t, round);
+        examine_round<THREADS, U>(even, base, v1, k, s, t, round, epoch);
         base += ROUND;
         if (base >= v1) break;
         load_round<THREADS, U>(even, src, base + ROUND, v1);
-        examine_round<THREADS, U>(odd, base, v1, k, s, t, round);
+        examine_round<THREADS, U>(odd, base, v1, k, s, t, round, epoch);
         base += ROUND;
         if (base >= v1) break;
         load_round<THREADS, U>(odd, src, base + ROUND, v1);
@@ -474,7 +492,8 @@ __device__ __forceinline__ SelectStart select_topk_from(const u32x4* __restrict_
     __syncthreads();
     TOPLOC_TICK_END(stream, 1);
     TOPLOC_TICK_BEGIN(fin);
-    (void)drain(s, k, k, t);  // prunes to exactly k
+    (void)drain(s, k, k, t, epoch);  // prunes to exactly k
+    __syncthreads();
     TOPLOC_TICK_END(fin, 3);
     return SelectStart{k, t, k};
 }
