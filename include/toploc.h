@@ -213,8 +213,10 @@ int toploc_verify_proofs_mixed(const void *d_hidden, uint32_t hidden_dtype, uint
  *   toploc_stream_append        row `token` (0-based position inside the chunk, each
  *                               position at most once per chunk, any order) of every
  *                               sequence: d_step_bf16 [n_seq][hidden]; the flat index of
- *                               channel c is token*hidden + c.  hidden % 8 == 0 and
- *                               chunk_tokens*hidden < 2^32
+ *                               channel c is token*hidden + c.  hidden % 8 == 0,
+ *                               chunk_tokens*hidden < 2^32, d_step_bf16 16-byte aligned (and,
+ *                               because the kernel forms row - token*hidden, not within the
+ *                               first 2*chunk_tokens*hidden bytes of the address space)
  *   toploc_stream_emit          Algorithm 1 steps 2-5 on every sequence's k pairs: proofs,
  *                               status (TOPLOC_CHUNK_SHORT when fewer than k values were
  *                               appended) and optionally the ordered indices, laid out as by
