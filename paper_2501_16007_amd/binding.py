@@ -278,6 +278,27 @@ def toploc_verify_proofs_segments(hidden, row_offsets, proofs, k=128, thresholds
     return res
 
 
+def generation_row_offsets(n_prompt, n_total, chunk_tokens=32):
+    """Row ranges of one sequence as the paper cuts it (Section 5.5): the prompt's activations as one
+    segment, then one segment per `chunk_tokens` generated tokens, the last one ragged."""
+    if not 0 <= n_prompt <= n_total:
+        raise ValueError("need 0 <= n_prompt <= n_total")
+    cuts = [0] if n_prompt == 0 else [0, n_prompt]
+    t = n_prompt
+    while t < n_total:
+        t = min(t + chunk_tokens, n_total)
+        cuts.append(t)
+    return np.asarray(cuts, dtype=np.uint64)
+
+
+def toploc_build_proofs_generation(hidden, n_prompt, k=128, chunk_tokens=32):
+    """Proofs of one sequence's [n_total, H] activations: prefill segment, then 32-token decode segments.
+    Returns (proofs, status, row_offsets); pass row_offsets to toploc_verify_proofs_segments."""
+    off = generation_row_offsets(n_prompt, hidden.shape[0], chunk_tokens)
+    proofs, status = toploc_build_proofs_segments(hidden, off, k=k)
+    return proofs, status, off
+
+
 def toploc_ring_append(ring, step_vec, step):
     """ring [n_seq, chunk_tokens, H] <- step_vec [n_seq, H] at row step mod chunk_tokens."""
     n_seq, chunk_tokens, h = ring.shape

@@ -148,3 +148,20 @@ def test_segments_empty_and_invalid():
         tl.toploc_build_proofs_segments(x, np.array([0, 1, 4], dtype=np.uint64), k=128)   # segment 0 holds 64 < k values
     with pytest.raises(ValueError):
         tl.toploc_build_proofs_segments(x, np.array([0, 9], dtype=np.uint64), k=8)        # past the tensor
+
+
+def test_generation_layout_prefill_plus_decode_segments():
+    """One sequence as the paper cuts it: a 75-token prompt, then 70 generated tokens in 32-token segments."""
+    hidden, n_prompt, n_total, k = 4096, 75, 145, 128
+    x = synth.activations(1, n_total, hidden, 5200, n_outlier=8, device=DEV).reshape(n_total, hidden)
+    proofs, status, off = tl.toploc_build_proofs_generation(x, n_prompt, k=k)
+    assert off.tolist() == [0, 75, 107, 139, 145]
+    res = tl.toploc_verify_proofs_segments(x, off, proofs, k=k)
+    torch.cuda.synchronize()
+    assert not status.cpu().numpy().any() and (tl.results_numpy(res)["accept"] == 1).all()
+    bits = synth.bits_numpy(x)
+    for i in range(len(off) - 1):
+        o_proofs, _ = orc.build(bits[int(off[i]):int(off[i + 1])].reshape(1, -1), k)
+        assert np.array_equal(proofs[i].cpu().numpy(), o_proofs[0]), "segment %d" % i
+    assert tl.generation_row_offsets(0, 64).tolist() == [0, 32, 64]
+    assert tl.generation_row_offsets(10, 10).tolist() == [0, 10]
