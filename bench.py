@@ -235,7 +235,12 @@ def report_config4(args, tl, synth, torch, dev):
                                                                    workspace=ws), args.steps)
         g = tl.results_numpy(results)
         tot = sum(ms.values())
+        # a second, separately labelled pass with tightened mantissa thresholds (the API takes them as
+        # arguments): shows what would separate an fp8 round trip from reordering noise
+        tight = (38, 2, 2)
+        gt = tl.results_numpy(tl.toploc_verify_proofs(rec, proofs, k=k, chunk_tokens=1, thresholds=tight, workspace=ws))
         variants[name] = {
+            "accepted_with_tightened_%d_%d_%d" % tight: int(gt["accept"].sum()),
             "accepted": int(g["accept"].sum()), "rejected": int(n_chunks - g["accept"].sum()),
             "err_exp_max": int(g["err_exp"].max()), "err_exp_mean": float(g["err_exp"].mean()),
             "mant_mean_diff": float(g["mant_sum"].sum()) / max(1, int(g["n_match"].sum())),
