@@ -359,3 +359,37 @@ def test_config5_full_width_one_emission_sampled():
         assert np.array_equal(proofs[selt].cpu().numpy(), o_proofs)
         assert np.array_equal(idx[selt].cpu().numpy().view(np.uint32), o_idx)
         assert_results_equal(g[sel], orc.verify(sample_bits, o_proofs, k), "config 5 full width k=%d" % k)
+
+
+def test_largest_chunk_the_index_space_allows():
+    """One chunk of N = 2^32 - 8 values (8 GiB): flat indices up to 2^32 - 9 must survive the cut into
+    thousands of parts, the merge and the index map.  The oracle's full sort would need minutes and tens
+    of GB here, so the expected top-k is known by construction (zeros, 100 spikes, ties by index) and the
+    expected proof comes from the oracle's own Algorithm 6 and Algorithm 3 on those pairs."""
+    n = (1 << 32) - 8
+    k = 128
+    x = torch.zeros((1, n), dtype=torch.bfloat16, device=DEV)
+    rng = np.random.default_rng(77)
+    pos = np.unique(np.concatenate([rng.integers(1 << 31, n, size=97), [n - 1, n - 8, (1 << 32) - 65536 - 3]]))
+    assert pos.size == 100
+    mags = rng.permutation(np.arange(0x4000, 0x4000 + 100)).astype(np.uint16)          # distinct magnitudes
+    signs = (rng.integers(0, 2, size=100).astype(np.uint16)) << 15
+    vals = torch.from_numpy((mags | signs).view(np.int16).copy()).view(torch.bfloat16).to(DEV)
+    x[0, torch.from_numpy(pos.astype(np.int64)).to(DEV)] = vals
+    order = np.argsort(-mags.astype(np.int64), kind="stable")
+    want_idx = np.concatenate([pos[order], np.arange(28)]).astype(np.uint32)           # then zeros, lowest indices
+    want_val = np.concatenate([(mags | signs)[order], np.zeros(28, dtype=np.uint16)])
+    say("largest chunk: N = 2^32 - 8, parts chosen by the library")
+    proofs, status, idx = tl.toploc_build_proofs(x, k=k, chunk_tokens=1, want_topk=True)
+    res = tl.toploc_verify_proofs(x, proofs, k=k, chunk_tokens=1)
+    t_idx, t_val = tl.toploc_topk(x, k=k, chunk_tokens=1)
+    torch.cuda.synchronize()
+    assert np.array_equal(idx.cpu().numpy().view(np.uint32)[0], want_idx)
+    assert np.array_equal(t_idx.cpu().numpy().view(np.uint32)[0], want_idx)
+    assert np.array_equal(t_val.cpu().numpy().view(np.uint16)[0], want_val)
+    m = orc.find_injective_modulus(want_idx)
+    coef = orc.interpolate(want_idx.astype(np.int64) % m, want_val.astype(np.int64))
+    want_proof = np.concatenate([[m % 65536], coef]).astype("<u2").view(np.uint8)
+    assert int(status[0]) == 0 and np.array_equal(proofs.cpu().numpy()[0], want_proof)
+    g = tl.results_numpy(res)
+    assert g["accept"][0] == 1 and g["n_match"][0] == k and g["mant_sum"][0] == 0 and g["err_exp"][0] == 0
