@@ -393,3 +393,21 @@ def test_largest_chunk_the_index_space_allows():
     assert int(status[0]) == 0 and np.array_equal(proofs.cpu().numpy()[0], want_proof)
     g = tl.results_numpy(res)
     assert g["accept"][0] == 1 and g["n_match"][0] == k and g["mant_sum"][0] == 0 and g["err_exp"][0] == 0
+
+
+def test_many_tiny_chunks():
+    """262144 chunks of 64 values, k = 8: the other end of the size range, every chunk against the oracle."""
+    n_chunks, n, k = 1 << 18, 64, 8
+    g = torch.Generator(device=DEV)
+    g.manual_seed(4242)
+    chunks = torch.randn((n_chunks, n), generator=g, device=DEV, dtype=torch.float32).to(torch.bfloat16)
+    say("many tiny chunks: %d x %d" % (n_chunks, n))
+    bits = synth.bits_numpy(chunks)
+    o_proofs, o_status, o_idx = orc.build(bits, k, want_topk=True)
+    proofs, status, idx = tl.toploc_build_proofs(chunks, k=k, chunk_tokens=1, want_topk=True)
+    res = tl.toploc_verify_proofs(chunks, proofs, k=k, chunk_tokens=1)
+    torch.cuda.synchronize()
+    assert np.array_equal(idx.cpu().numpy().view(np.uint32), o_idx)
+    assert np.array_equal(status.cpu().numpy(), o_status) and np.array_equal(proofs.cpu().numpy(), o_proofs)
+    g_res = tl.results_numpy(res)
+    assert (g_res["accept"] == 1).all() and (g_res["n_match"] == k).all()
