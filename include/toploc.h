@@ -158,7 +158,8 @@ int toploc_topk(const void *d_hidden_bf16, uint64_t n_chunks, const toploc_param
  * proof layout are the same.  Long segments are cut into parts like small batches.
  * d_workspace (required, 16-byte aligned) must hold toploc_segments_workspace_bytes()
  * bytes; the calls copy two small tables into it with hipMemcpyAsync from pageable
- * host memory, which may wait for earlier work of the stream. */
+ * host memory, which may wait for earlier work of the stream (so these two calls, unlike
+ * all others here, are not meant to be captured into a HIP graph). */
 size_t toploc_segments_workspace_bytes(const uint64_t *h_row_offsets, uint64_t n_segments, uint32_t hidden,
                                        uint32_t k);
 int toploc_build_proofs_segments(const void *d_hidden_bf16, const uint64_t *h_row_offsets, uint64_t n_segments,
