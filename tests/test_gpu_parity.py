@@ -265,6 +265,10 @@ def test_config3_full_size_sampled():
     proofs = sampled_parity(x, 128, 32, 203, "config 3")
     # chunk 0 of every sequence is the prefill proof, the rest are decode proofs: all 258 bytes
     assert proofs.shape == (128 * 128, 258)
+    # the result is unique, so a second run under different wave timing gives the same bytes
+    again, _ = tl.toploc_build_proofs(synth.as_chunks(x), k=128, chunk_tokens=1)
+    torch.cuda.synchronize()
+    assert torch.equal(again, proofs)
 
 
 def test_config4_verification_stress_reduced_and_counts():
