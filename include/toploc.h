@@ -22,6 +22,10 @@
  *    TOPLOC_E* code when the call was rejected (nothing was enqueued then).
  *    Data-dependent per-chunk conditions never fail the call; they are reported
  *    per chunk in `d_status` / `toploc_verify_result.status`.
+ *  - Host threads: entry points may be called from several threads at once, each
+ *    on its own stream and buffers.  toploc_set_split and toploc_profile_enable
+ *    set process-wide switches that calls in flight on other threads may or may
+ *    not see yet.
  *
  * Layout of a chunk: `chunk_tokens` consecutive token rows of `hidden` bf16
  * values, row major, so the flat index of (token t, channel c) is t*hidden + c
@@ -244,7 +248,8 @@ int toploc_bench_read(const void *d_hidden_bf16, uint64_t n_chunks, uint64_t chu
  * calling thread's device is bracketed by HIP events on the caller's stream.
  * toploc_profile_read synchronises those events and returns, per kernel slot
  * (TOPLOC_KERNEL_*), the number of launches and their summed duration in
- * milliseconds since the last reset, then resets.  Not thread safe. */
+ * milliseconds since the last reset, then resets.  The list of events is shared by
+ * all threads: one thread reads it, after the others' timed calls have returned. */
 #define TOPLOC_KERNEL_SELECT 0        /* topk alone (toploc_topk)                        */
 #define TOPLOC_KERNEL_PART 1          /* split path: top-k of one part                   */
 #define TOPLOC_KERNEL_BUILD_MERGE 2   /* split path: merge, modulus, interpolation       */

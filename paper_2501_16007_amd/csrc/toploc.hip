@@ -17,6 +17,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdio.h>
+#include <atomic>
+#include <mutex>
 #include <vector>
 
 #include "../../include/toploc.h"
@@ -463,10 +465,12 @@ __global__ __launch_bounds__(kThreads) void read_kernel(const u32x4* __restrict_
 // ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
-static int g_last_hip_error = 0;
-static int g_profile_on = 0;
-static uint32_t g_force_parts = 0;  // toploc_set_split: 0 = choose, n = cut every chunk into n parts
+// Process-wide state: entry points may be called from several host threads at once.
+static std::atomic<int> g_last_hip_error{0};
+static std::atomic<int> g_profile_on{0};
+static std::atomic<uint32_t> g_force_parts{0};  // toploc_set_split: 0 = choose, n = cut every chunk into n parts
 struct ProfRec { int slot; hipEvent_t a, b; };
+static std::mutex g_prof_mutex;
 static std::vector<ProfRec> g_prof;
 
 static bool hip_ok(hipError_t e)
@@ -485,7 +489,10 @@ struct ProfScope {
     }
     ~ProfScope()
     {
-        if (on && hip_ok(hipEventRecord(b, st))) g_prof.push_back({slot, a, b});
+        if (on && hip_ok(hipEventRecord(b, st))) {
+            std::lock_guard<std::mutex> lock(g_prof_mutex);
+            g_prof.push_back({slot, a, b});
+        }
     }
 };
 
@@ -1000,6 +1007,7 @@ int toploc_profile_read(uint32_t* launches, float* total_ms)
     if (!launches || !total_ms) return TOPLOC_EINVAL;
     for (int i = 0; i < TOPLOC_KERNEL_COUNT; ++i) { launches[i] = 0; total_ms[i] = 0.f; }
     int rc = TOPLOC_OK;
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
     for (auto& r : g_prof) {
         float ms = 0.f;
         if (hip_ok(hipEventSynchronize(r.b)) && hip_ok(hipEventElapsedTime(&ms, r.a, r.b))) {

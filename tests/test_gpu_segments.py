@@ -165,3 +165,55 @@ def test_generation_layout_prefill_plus_decode_segments():
         assert np.array_equal(proofs[i].cpu().numpy(), o_proofs[0]), "segment %d" % i
     assert tl.generation_row_offsets(0, 64).tolist() == [0, 32, 64]
     assert tl.generation_row_offsets(10, 10).tolist() == [0, 10]
+
+
+def test_host_threads_on_their_own_streams():
+    """Four host threads call different entry points at once, each on a stream of its own."""
+    import threading
+    k = 128
+    x_fused = synth.activations(40, 32, 1024, 5300, n_outlier=4, device=DEV).reshape(40, 32 * 1024)
+    x_split = synth.activations(2, 32, 8192, 5301, n_outlier=8, device=DEV).reshape(2, 32 * 8192)
+    x_seg = synth.activations(1, 77, 2048, 5302, n_outlier=4, device=DEV).reshape(77, 2048)
+    off = np.array([0, 40, 72, 77], dtype=np.uint64)
+    want = {
+        "fused": orc.build(synth.bits_numpy(x_fused), k)[0],
+        "split": orc.build(synth.bits_numpy(x_split), k)[0],
+        "seg": np.stack([orc.build(synth.bits_numpy(x_seg)[int(off[i]):int(off[i + 1])].reshape(1, -1), k)[0][0]
+                         for i in range(3)]),
+    }
+    want["verify"] = orc.verify(synth.bits_numpy(x_fused), want["fused"], k)
+    proofs_dev = torch.from_numpy(want["fused"]).to(DEV)
+    torch.cuda.synchronize()
+    failures = []
+
+    def worker(name):
+        try:
+            stream = torch.cuda.Stream(device=DEV)
+            with torch.cuda.stream(stream):
+                for rep in range(6):
+                    if name == "fused":
+                        got = tl.toploc_build_proofs(x_fused, k=k, chunk_tokens=1)[0]
+                    elif name == "split":
+                        got = tl.toploc_build_proofs(x_split, k=k, chunk_tokens=1)[0]
+                    elif name == "seg":
+                        got = tl.toploc_build_proofs_segments(x_seg, off, k=k)[0]
+                    else:
+                        got = tl.toploc_verify_proofs(x_fused, proofs_dev, k=k, chunk_tokens=1)
+                    stream.synchronize()
+                    if name == "verify":
+                        g = tl.results_numpy(got)
+                        ok = all(np.array_equal(g[f], want["verify"][f]) for f in FIELDS)
+                    else:
+                        ok = np.array_equal(got.cpu().numpy(), want[name])
+                    if not ok:
+                        failures.append("%s rep %d" % (name, rep))
+        except Exception as e:  # reported by the main thread
+            failures.append("%s: %r" % (name, e))
+
+    say("threads fused/split/seg/verify, 6 calls each")
+    threads = [threading.Thread(target=worker, args=(n,)) for n in ("fused", "split", "seg", "verify")]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not failures, failures
