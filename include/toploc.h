@@ -51,6 +51,7 @@ extern "C" {
 
 #define TOPLOC_PRIME 65497u     /* the field modulus M of Algorithms 3 and 5            */
 #define TOPLOC_MAX_K 512u       /* largest supported top-k parameter                    */
+#define TOPLOC_MAX_K_TOPK 4096u /* largest k of toploc_topk alone (Table 1 looks at k up to 4096) */
 
 /* Precisions (Section 5.6 validates across fp32 and bf16).  An fp32 value enters the
  * polynomial as its 32-bit pattern over GF(TOPLOC_PRIME32); such a proof is 2 + 4k bytes:
@@ -145,7 +146,9 @@ int toploc_verify_proofs(const void *d_hidden_bf16, uint64_t n_chunks, const top
                          toploc_verify_result *d_results, void *d_workspace, size_t workspace_bytes,
                          void *hip_stream);
 
-/* The first step of both algorithms alone (topk(h, k) of Algorithm 1 / 2):
+/* The first step of both algorithms alone (topk(h, k) of Algorithm 1 / 2), for
+ * k <= TOPLOC_MAX_K_TOPK (above TOPLOC_MAX_K at a fraction of the speed: one workgroup
+ * per compute unit):
  *   d_topk_idx   out, device, n_chunks*k uint32, (magnitude desc, index asc)
  *   d_topk_val   out, device, n_chunks*k uint16 bf16 patterns, same order */
 int toploc_topk(const void *d_hidden_bf16, uint64_t n_chunks, const toploc_params *params,

@@ -47,8 +47,12 @@ constexpr int kQcap = TOPLOC_QCAP;        // queue entries (16-byte vectors)
 #endif
 constexpr int kCapSmall = TOPLOC_CAP_SMALL;  // candidate buffer for k <= 128
 constexpr int kCapLarge = 2048;           // candidate buffer for k <= TOPLOC_MAX_K
+constexpr int kCapWide = 16384;           // candidate buffer of the selection alone up to TOPLOC_MAX_K_TOPK (140 KB of LDS:
+                                          // one workgroup per compute unit; an aid for statistics, not a fast path)
 constexpr uint32_t kRoundVecs = kThreads * kLoads;
-static_assert(kCapLarge >= 4 * (int)TOPLOC_MAX_K && kCapSmall >= 4 * 128, "soft limit CAP/2 must leave room above k");
+static_assert(kCapLarge >= 4 * (int)TOPLOC_MAX_K && kCapSmall >= 4 * 128 && kCapWide >= 4 * (int)TOPLOC_MAX_K_TOPK,
+              "soft limit CAP/2 must leave room above k");
+static_assert(kCapWide <= 65536, "prune keeps slot numbers in 16 bits");
 
 // Where a workgroup of a split launch finds its piece.  Fixed chunks need no table:
 // chunk = block / parts, part = block % parts.  Segments come with two tables.
@@ -86,10 +90,10 @@ __device__ __forceinline__ uint64_t chunk_of_block()
 // ---------------------------------------------------------------------------
 // topk(h, k) alone: writes the ordered (index, value) pairs of every chunk
 // ---------------------------------------------------------------------------
-template <int CAP>
-__global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void select_kernel(const u32x4* __restrict__ hidden, uint32_t nvec,
-                                                                            uint32_t k, uint32_t* __restrict__ out_idx,
-                                                                            uint16_t* __restrict__ out_val)
+template <int CAP, int WAVES = TOPLOC_MIN_WAVES>
+__global__ __launch_bounds__(kThreads, WAVES) void select_kernel(const u32x4* __restrict__ hidden, uint32_t nvec,
+                                                                 uint32_t k, uint32_t* __restrict__ out_idx,
+                                                                 uint16_t* __restrict__ out_val)
 {
     __shared__ SelectShared<kThreads, CAP, kQcap> s;
     const uint64_t chunk = chunk_of_block();
@@ -500,9 +504,9 @@ static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 static size_t up16(size_t b) { return (b + 15) & ~(size_t)15; }
 
 // N (values per chunk) when the parameters are usable, else 0
-static uint64_t chunk_len(const toploc_params* p)
+static uint64_t chunk_len(const toploc_params* p, uint32_t max_k = TOPLOC_MAX_K)
 {
-    if (!p || p->k == 0 || p->k > TOPLOC_MAX_K || p->prime != TOPLOC_PRIME) return 0;
+    if (!p || p->k == 0 || p->k > max_k || p->prime != TOPLOC_PRIME) return 0;
     if (p->chunk_tokens == 0 || p->hidden == 0) return 0;
     const uint64_t n = (uint64_t)p->chunk_tokens * p->hidden;
     if (n % 8 != 0 || n >= (1ull << 32) || p->k > n) return 0;
@@ -686,7 +690,7 @@ int toploc_set_split(uint32_t parts_per_chunk)
 int toploc_topk(const void* d_hidden_bf16, uint64_t n_chunks, const toploc_params* params, uint32_t* d_topk_idx,
                 uint16_t* d_topk_val, void* hip_stream)
 {
-    const uint64_t n = chunk_len(params);
+    const uint64_t n = chunk_len(params, TOPLOC_MAX_K_TOPK);
     if (n == 0 || n_chunks >= (1ull << 31)) return TOPLOC_EINVAL;
     if (n_chunks == 0) return TOPLOC_OK;
     if (!d_hidden_bf16 || !d_topk_idx || !d_topk_val || !aligned16(d_hidden_bf16)) return TOPLOC_EINVAL;
@@ -696,8 +700,11 @@ int toploc_topk(const void* d_hidden_bf16, uint64_t n_chunks, const toploc_param
         if (params->k <= 128)
             hipLaunchKernelGGL((select_kernel<kCapSmall>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
                                (const u32x4*)d_hidden_bf16, (uint32_t)(n / 8), params->k, d_topk_idx, d_topk_val);
-        else
+        else if (params->k <= TOPLOC_MAX_K)
             hipLaunchKernelGGL((select_kernel<kCapLarge>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
+                               (const u32x4*)d_hidden_bf16, (uint32_t)(n / 8), params->k, d_topk_idx, d_topk_val);
+        else
+            hipLaunchKernelGGL((select_kernel<kCapWide, 1>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
                                (const u32x4*)d_hidden_bf16, (uint32_t)(n / 8), params->k, d_topk_idx, d_topk_val);
     }
     return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;

@@ -55,12 +55,105 @@ def topk_mismatch(idx_a, idx_b):
     return (~found).sum(dim=1)
 
 
-def proof_to_text(proof):
-    """One proof (uint8 tensor or bytes) as base64 text, e.g. to attach to a response."""
+def proof_to_text(proof, encoding="base64"):
+    """One proof (uint8 tensor or bytes) as base64 or hex text, e.g. to attach to a response."""
     raw = bytes(proof.cpu().numpy().tobytes()) if isinstance(proof, torch.Tensor) else bytes(proof)
+    if encoding == "hex":
+        return raw.hex()
+    if encoding != "base64":
+        raise ValueError("encoding is 'base64' or 'hex'")
     return base64.b64encode(raw).decode("ascii")
 
 
-def proof_from_text(text, device="cpu"):
-    raw = base64.b64decode(text.encode("ascii"))
+def proof_from_text(text, device="cpu", encoding="base64"):
+    if encoding == "hex":
+        raw = bytes.fromhex(text)
+    elif encoding == "base64":
+        raw = base64.b64decode(text.encode("ascii"), validate=True)
+    else:
+        raise ValueError("encoding is 'base64' or 'hex'")
     return torch.from_numpy(np.frombuffer(raw, dtype=np.uint8).copy()).to(device)
+
+
+# Columns of Table 1 (signed deviation d of the 8-bit exponent field) and of its appendix
+# twin (|d| only).  The table's ranges share their end points; here 10 belongs to "3..10"
+# and 100 to ">=100".
+EXPONENT_DEVIATION_COLUMNS = ("0", "-1", "+1", "-2", "+2", "-10..-3", "+3..+10", "10<|d|<100", "|d|>=100")
+
+
+def _exponent(chunks, idx):
+    bits = chunks.view(torch.int16).to(torch.int64) & 0xFFFF
+    return (torch.gather(bits, 1, idx.to(torch.int64) & 0xFFFFFFFF) >> 7) & 0xFF
+
+
+def exponent_deviation_counts(chunks_a, chunks_b, k, both_only=False):
+    """Table 1 for one k over [n_chunks, N] bf16 chunks: at the top-k positions of `chunks_a`
+    (the library's toploc_topk, so k may reach 4096), d = exponent(chunks_b) - exponent(chunks_a),
+    counted per column of EXPONENT_DEVIATION_COLUMNS.  both_only: only positions that are also among
+    the top-k of `chunks_b`, |d| in place of d (the appendix table: its negative columns stay empty).
+    Returns {column: count}."""
+    idx_a, _ = binding.toploc_topk(chunks_a, k=k, chunk_tokens=1)
+    d = _exponent(chunks_b, idx_a) - _exponent(chunks_a, idx_a)
+    if both_only:
+        idx_b, _ = binding.toploc_topk(chunks_b, k=k, chunk_tokens=1)
+        a = idx_a.to(torch.int64) & 0xFFFFFFFF
+        bs, _ = torch.sort(idx_b.to(torch.int64) & 0xFFFFFFFF, dim=1)
+        pos = torch.searchsorted(bs, a).clamp(max=k - 1)
+        d = d.abs()[torch.gather(bs, 1, pos) == a]
+    d = d.reshape(-1)
+    ad = d.abs()
+    cols = (d == 0, d == -1, d == 1, d == -2, d == 2, (d <= -3) & (d >= -10), (d >= 3) & (d <= 10),
+            (ad > 10) & (ad < 100), ad >= 100)
+    return {name: int(c.sum().item()) for name, c in zip(EXPONENT_DEVIATION_COLUMNS, cols)}
+
+
+def topk_overlap_by_k(chunks_a, chunks_b, ks=(64, 128, 256, 512, 1024, 2048, 4096)):
+    """{k: (mean, worst) share of the top-k positions of chunks_a that are also top-k positions of
+    chunks_b}: how stable the selected set is under the difference between the two tensors."""
+    out = {}
+    for k in ks:
+        ia, _ = binding.toploc_topk(chunks_a, k=k, chunk_tokens=1)
+        ib, _ = binding.toploc_topk(chunks_b, k=k, chunk_tokens=1)
+        share = 1.0 - topk_mismatch(ia, ib).to(torch.float64) / k
+        out[int(k)] = (float(share.mean().item()), float(share.min().item()))
+    return out
+
+
+def decisions_under(results, thresholds):
+    """The accept bit every record would get under other thresholds (t_exp, t_mean, t_median): the
+    rule of Algorithm 2 applied again to the stored statistics, so that one verify pass serves a
+    whole sweep.  Malformed records stay rejected.  Returns a bool array."""
+    r = binding.results_numpy(results) if isinstance(results, torch.Tensor) else results
+    t_exp, t_mean, t_median = thresholds
+    n = r["n_match"].astype(np.int64)
+    reject = r["err_exp"].astype(np.int64) > t_exp
+    reject |= (n > 0) & (r["mant_sum"].astype(np.int64) > t_mean * n)
+    reject |= (n > 0) & (r["mant_median"].astype(np.int64) > t_median)
+    reject |= r["status"] != binding.CHUNK_OK
+    return ~reject
+
+
+def threshold_sweep(honest, tampered, grid):
+    """For every (t_exp, t_mean, t_median) of `grid`: the share of honest records rejected and of
+    tampered records accepted.  Returns a list of (thresholds, false_reject, false_accept)."""
+    rows = []
+    for thr in grid:
+        fr = 1.0 - float(decisions_under(honest, thr).mean()) if len(honest) else 0.0
+        fa = float(decisions_under(tampered, thr).mean()) if len(tampered) else 0.0
+        rows.append((tuple(thr), fr, fa))
+    return rows
+
+
+def separation(honest, tampered):
+    """Per statistic, the worst honest value and the best tampered value (the two numbers the paper
+    reads its thresholds from, Section 5.2 with Tables 2-5): a threshold between them separates the
+    two sets on that statistic alone.  Returns {statistic: (honest_max, tampered_min)}."""
+    def stats(res):
+        r = binding.results_numpy(res) if isinstance(res, torch.Tensor) else res
+        r = r[r["status"] == binding.CHUNK_OK]
+        mean = r["mant_sum"] / np.maximum(r["n_match"], 1)
+        return {"exp_mismatch": r["err_exp"].astype(np.float64), "mant_mean": mean.astype(np.float64),
+                "mant_median": r["mant_median"].astype(np.float64)}
+    h, t = stats(honest), stats(tampered)
+    return {name: (float(h[name].max()) if h[name].size else float("nan"),
+                   float(t[name].min()) if t[name].size else float("nan")) for name in h}

@@ -415,3 +415,27 @@ def test_many_tiny_chunks():
     assert np.array_equal(status.cpu().numpy(), o_status) and np.array_equal(proofs.cpu().numpy(), o_proofs)
     g_res = tl.results_numpy(res)
     assert (g_res["accept"] == 1).all() and (g_res["n_match"] == k).all()
+
+
+@pytest.mark.parametrize("k", [513, 1024, 4096])
+def test_topk_alone_beyond_the_proof_limit(k):
+    """toploc_topk serves the k range of Table 1 (up to 4096); the proof calls stop at 512."""
+    say("wide topk k=%d: activations, ties, k = N, ragged length" % k)
+    cases = [
+        random_chunks(3, 4096, 32, 900 + k),                              # 131072 values, outliers
+        random_chunks(2, 4096 // 32 * 5, 32, 901 + k),                    # 20480 values: a few rounds
+        random_chunks(2, (k + 7) // 8, 8, 902 + k),                       # N = k rounded up to 8: nearly everything
+    ]
+    rng = np.random.default_rng(903 + k)
+    vals = np.array([0x3F80, 0xBF80, 0x4000, 0x0000, 0x8000], dtype=np.uint16)
+    cases.append(synth.from_bits(vals[rng.integers(0, len(vals), size=(2, 40000))], DEV))   # heavy ties
+    for x in cases:
+        bits = synth.bits_numpy(x)
+        idx, val = tl.toploc_topk(x, k=k, chunk_tokens=1)
+        torch.cuda.synchronize()
+        for c in range(x.shape[0]):
+            oi, ov = orc.topk(bits[c], k)
+            assert np.array_equal(idx[c].cpu().numpy().view(np.uint32), oi), "indices, N=%d chunk %d" % (x.shape[1], c)
+            assert np.array_equal(val[c].cpu().numpy().view(np.uint16), ov), "values, N=%d chunk %d" % (x.shape[1], c)
+    with pytest.raises(tl.ToplocError):
+        tl.toploc_topk(cases[0], k=4097, chunk_tokens=1)

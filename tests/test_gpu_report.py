@@ -57,3 +57,66 @@ def test_summaries_topk_mismatch_and_text_codec():
     assert report.topk_mismatch(idx, idx).sum().item() == 0
     text = report.proof_to_text(proofs[3])
     assert torch.equal(report.proof_from_text(text, DEV), proofs[3]) and len(text) == 344   # 258 bytes in base64
+    hexed = report.proof_to_text(proofs[3], encoding="hex")
+    assert len(hexed) == 516 and torch.equal(report.proof_from_text(hexed, DEV, encoding="hex"), proofs[3])
+
+
+def _exp(bits):
+    return ((bits.astype(np.int64) >> 7) & 0xFF)
+
+
+def _bin(d):
+    ad = np.abs(d)
+    cols = (d == 0, d == -1, d == 1, d == -2, d == 2, (d <= -3) & (d >= -10), (d >= 3) & (d <= 10),
+            (ad > 10) & (ad < 100), ad >= 100)
+    return {name: int(c.sum()) for name, c in zip(report.EXPONENT_DEVIATION_COLUMNS, cols)}
+
+
+@pytest.mark.parametrize("k", [128, 1024])
+def test_exponent_deviation_table_and_overlap_against_the_oracles_topk(k):
+    """Table 1's counting on a perturbed recomputation, checked against the same counting over the
+    oracle's top-k positions."""
+    x = synth.activations(4, 32, 2048, 8300, n_outlier=8, device=DEV).reshape(4, -1)
+    y = synth.perturb_relative(x, 2.0 ** -5, 8301)          # large enough to move exponents near powers of two
+    xb, yb = synth.bits_numpy(x), synth.bits_numpy(y)
+    got = report.exponent_deviation_counts(x, y, k)
+    got_both = report.exponent_deviation_counts(x, y, k, both_only=True)
+    over = report.topk_overlap_by_k(x, y, ks=(k,))[k]
+    d_all, d_both, shares = [], [], []
+    for c in range(4):
+        ia, _ = orc.topk(xb[c], k)
+        ib, _ = orc.topk(yb[c], k)
+        d = _exp(yb[c][ia]) - _exp(xb[c][ia])
+        keep = np.isin(ia, ib)
+        d_all.append(d)
+        d_both.append(np.abs(d[keep]))
+        shares.append(keep.mean())
+    assert got == _bin(np.concatenate(d_all))
+    assert got_both == _bin(np.concatenate(d_both))
+    assert sum(got.values()) == 4 * k and got["0"] > 0.8 * 4 * k and got["-1"] + got["+1"] > 0
+    assert got_both["-1"] == 0 and got_both["-2"] == 0
+    assert abs(over[0] - np.mean(shares)) < 1e-12 and abs(over[1] - np.min(shares)) < 1e-12
+
+
+def test_threshold_sweep_on_honest_and_tampered_recomputations():
+    """One verify pass per recomputation serves every threshold triple: the re-decided accept bits equal the
+    kernel's own under the same thresholds, and the paper's triple separates small numeric noise from
+    activations of another input (Section 5.2; Tables 2 and 3)."""
+    x = synth.config2(DEV, n_seq=2, n_tok=256)
+    chunks = synth.as_chunks(x)
+    proofs, _ = tl.toploc_build_proofs(chunks, k=128, chunk_tokens=1)
+    honest_in = synth.as_chunks(synth.perturb_relative(x, 2.0 ** -7, 8400))
+    tampered_in = synth.as_chunks(synth.activations(2, 256, 4096, 8401, n_outlier=8, device=DEV))
+    honest = tl.results_numpy(tl.toploc_verify_proofs(honest_in, proofs, k=128, chunk_tokens=1))
+    tampered = tl.results_numpy(tl.toploc_verify_proofs(tampered_in, proofs, k=128, chunk_tokens=1))
+    for thr in ((38, 10, 8), (0, 0, 0), (5, 2, 1), (128, 127, 127)):
+        for inp, rec in ((honest_in, honest), (tampered_in, tampered)):
+            kernel = tl.results_numpy(tl.toploc_verify_proofs(inp, proofs, k=128, chunk_tokens=1, thresholds=thr))
+            assert np.array_equal(report.decisions_under(rec, thr), kernel["accept"] == 1), thr
+    rows = report.threshold_sweep(honest, tampered, [(38, 10, 8), (0, 0, 0), (128, 127, 127)])
+    assert rows[0] == ((38, 10, 8), 0.0, 0.0)               # the paper's triple: no false reject, no false accept
+    assert rows[1][1] > 0.9 and rows[1][2] == 0.0            # zero tolerance rejects honest noise too
+    assert rows[2][1] == 0.0                                 # nothing honest fails the loosest triple
+    sep = report.separation(honest, tampered)
+    assert sep["exp_mismatch"][0] <= 38 < sep["exp_mismatch"][1]
+    assert sep["mant_mean"][0] <= 10 and sep["mant_median"][0] <= 8
