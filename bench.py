@@ -166,6 +166,16 @@ def main():
         cdt = time.perf_counter() - t0
         assert np.array_equal(proofs[sel].cpu().numpy(), o_proofs), "GPU proofs differ from the oracle on the sample"
         assert bool((o_res["accept"] == 1).all())
+        # the same oracle on one core, on the first chunks of the sample (about as long again)
+        n1 = max(1, ns // max(1, cores))
+        t0 = time.perf_counter()
+        if f32:
+            p1, _ = orc.build32(sample[:n1], k, n_threads=1)
+            orc.verify_mixed(sample[:n1], orc.F32, p1, orc.F32, k, n_threads=1)
+        else:
+            p1, _ = orc.build(sample[:n1], k, n_threads=1)
+            orc.verify(sample[:n1], p1, k, n_threads=1)
+        cdt1 = time.perf_counter() - t0
         cpu = {
             "value": 2 * sample.size * eb / cdt / 1e9,
             "unit": "GB/s",
@@ -174,6 +184,8 @@ def main():
             "sample": "%d of %d chunks (every %d-th), build + verify, %.1f s wall" % (
                 ns, n_chunks, max(1, n_chunks // ns), cdt),
             "chunks_per_s": ns / cdt,
+            "single_core": {"value": 2 * sample[:n1].size * eb / cdt1 / 1e9, "unit": "GB/s",
+                            "chunks_per_s": n1 / cdt1, "sample": "%d chunks, %.1f s wall" % (n1, cdt1)},
         }
 
     out = {

@@ -439,3 +439,29 @@ def test_topk_alone_beyond_the_proof_limit(k):
             assert np.array_equal(val[c].cpu().numpy().view(np.uint16), ov), "values, N=%d chunk %d" % (x.shape[1], c)
     with pytest.raises(tl.ToplocError):
         tl.toploc_topk(cases[0], k=4097, chunk_tokens=1)
+
+
+def test_no_injective_modulus_and_a_deep_search():
+    """Algorithm 6 fails only when every candidate sees two congruent indices: 385 top positions whose
+    differences cover [32769, 65536] do that (k = 512).  Status, the zeroed proof and what a verifier
+    makes of it must equal the oracle's; a neighbour set sends the search hundreds of candidates deep."""
+    k, n = 512, 32 * 4096
+    cover = np.concatenate([np.arange(256), 32769 + 256 * np.arange(129)])
+    rng = np.random.default_rng(950)
+    bits = (rng.integers(0x3000, 0x3800, size=(3, n)).astype(np.uint16)
+            | (rng.integers(0, 2, size=(3, n)).astype(np.uint16) << 15))        # bulk: magnitudes below 0x3800
+    big = lambda count: (rng.integers(0x4000, 0x4400, size=count).astype(np.uint16)
+                         | (rng.integers(0, 2, size=count).astype(np.uint16) << 15))
+    bits[0, cover] = big(cover.size)                 # chunk 0: no modulus (the other 127 entries come from the bulk)
+    fewer = np.delete(cover, 255)
+    bits[1, fewer] = big(fewer.size)                 # chunk 1: a deep search; chunk 2: plain
+    say("no injective modulus: k=512, N=%d, covering set of %d indices" % (n, cover.size))
+    chunks = synth.from_bits(bits, DEV)
+    o_proofs, o_status, o_idx = orc.build(bits, k, want_topk=True)
+    assert o_status.tolist() == [1, 0, 0] and not o_proofs[0].any()
+    assert set(cover.tolist()) <= set(o_idx[0].tolist())
+    g_proofs, g_status, g_idx = gpu_build(chunks, k)
+    assert np.array_equal(g_idx, o_idx) and np.array_equal(g_status, o_status) and np.array_equal(g_proofs, o_proofs)
+    m_deep = int(o_proofs[1, 0]) | (int(o_proofs[1, 1]) << 8)
+    assert 32769 <= m_deep < 65536 - 200
+    assert_results_equal(gpu_verify(chunks, o_proofs, k), orc.verify(bits, o_proofs, k), "no modulus")

@@ -281,6 +281,29 @@ def test_modulus_failure_when_no_candidate_works():
         orc.find_injective_modulus(np.array([7, 7], dtype=np.uint32), M=P)
 
 
+def covering_index_set():
+    """385 distinct indices whose pairwise differences include every m in [32769, 65536]:
+    (32769 + 256 j) - i = m has a solution with 0 <= i < 256, 0 <= j <= 128 for each such m,
+    so two of the indices are congruent modulo every candidate of Algorithm 6."""
+    return np.concatenate([np.arange(256), 32769 + 256 * np.arange(129)]).astype(np.uint32)
+
+
+def test_modulus_failure_with_distinct_indices_and_a_deep_search():
+    idx = covering_index_set()
+    assert len(set(idx.tolist())) == idx.size
+    diffs = set(int(a) - int(b) for a in idx[256:] for b in idx[:256])
+    assert all(m in diffs for m in range(32769, 65537))
+    for p in (0, P):
+        with pytest.raises(ValueError):
+            orc.find_injective_modulus(idx, M=p)
+    # without index 255 only the candidates 32769 + 256 j - 255 lose their colliding pair ... unless another
+    # pair collides there too: brute force says which candidate the search must stop at
+    fewer = np.delete(idx, 255)
+    want = next(m for m in range(65536, 32768, -1) if _is_injective(fewer, m, P))
+    assert want < 65536 - 200                                   # hundreds of candidates deep
+    assert orc.find_injective_modulus(fewer, M=P) == want
+
+
 # ---------------------------------------------------------------------------
 # P4: Table 7 -- printed values, closed form, Monte Carlo of the oracle
 # ---------------------------------------------------------------------------
