@@ -532,8 +532,9 @@ struct FixedPlan { uint32_t parts; uint32_t part_vecs; };
 static FixedPlan plan_fixed(uint64_t n_chunks, uint64_t nvec)
 {
     uint64_t pv;
-    if (g_force_parts) {
-        pv = (nvec + g_force_parts - 1) / g_force_parts;
+    const uint64_t forced = g_force_parts.load();  // read once: another thread may change it
+    if (forced) {
+        pv = (nvec + forced - 1) / forced;
         pv = pv ? pv : 1;
     } else {
         const uint64_t want = n_chunks < kTargetGroups ? kTargetGroups / n_chunks : 1;  // parts per chunk
@@ -548,8 +549,9 @@ static FixedPlan plan_fixed(uint64_t n_chunks, uint64_t nvec)
 // vectors per part for segments: `total_vecs` vectors in `n_units` segments, the longest of `max_unit_vecs`
 static uint64_t pick_part_vecs(uint64_t total_vecs, uint64_t max_unit_vecs, uint64_t n_units)
 {
-    if (g_force_parts) {
-        const uint64_t pv = (max_unit_vecs + g_force_parts - 1) / g_force_parts;
+    const uint64_t forced = g_force_parts.load();  // read once: another thread may change it
+    if (forced) {
+        const uint64_t pv = (max_unit_vecs + forced - 1) / forced;
         return pv ? pv : 1;
     }
     const uint64_t groups = n_units > kTargetGroups ? n_units : kTargetGroups;

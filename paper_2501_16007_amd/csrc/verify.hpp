@@ -21,6 +21,10 @@
 #include "interp.hpp"
 #include "select.hpp"
 
+#ifndef TOPLOC_HORNER_LANES
+#define TOPLOC_HORNER_LANES 2
+#endif
+
 namespace toploc {
 
 template <int KMAX, bool WIDE = false>
@@ -86,10 +90,25 @@ __device__ __forceinline__ void verify_tail(VerifyShared<KMAX, WIDE>& vs, const 
     static_assert(WIDE == (Fmt::ELEMS == 4), "an fp32 validator keeps err_m as a list");
     const uint32_t tid = threadIdx.x;
     const uint32_t m = vs.m;
-    for (uint32_t j = tid; j < k; j += THREADS) {
+    // With lanes to spare two lanes share a point: P(x) = E(x^2) + x O(x^2), the even and the odd
+    // coefficients as two Horner chains of half the length (the chain is the tail's critical path).
+    constexpr int L = (2 * KMAX <= THREADS && TOPLOC_HORNER_LANES == 2) ? 2 : 1;
+    const uint32_t h = (L == 2) ? (tid & 1u) : 0u;
+    for (uint32_t j = tid / L; j < k; j += THREADS / L) {
         const uint32_t x = F::from_residue(cand_idx[j] % m);
-        uint32_t acc = vs.coef[k - 1];
-        for (int i = (int)k - 2; i >= 0; --i) acc = F::muladdmod(acc, x, vs.coef[i]);
+        uint32_t acc;
+        if (L == 2) {
+            const uint32_t x2 = F::mulmod(x, x);
+            const int terms = (int)((k - h + 1u) / 2u);   // coefficients h, h + 2, ...
+            acc = 0;
+            for (int i = terms - 1; i >= 0; --i) acc = F::muladdmod(acc, x2, vs.coef[2 * i + (int)h]);
+            const uint32_t odd = __shfl_xor(acc, 1);      // the partner's chain
+            acc = F::muladdmod(odd, x, acc);              // meaningful in the even lane
+            if (h) continue;
+        } else {
+            acc = vs.coef[k - 1];
+            for (int i = (int)k - 2; i >= 0; --i) acc = F::muladdmod(acc, x, vs.coef[i]);
+        }
         const uint32_t v = cand_bits[j];
         uint32_t e_p, m_p, e_v, m_v;
         extract_proof_bits<F, Fmt>(acc, e_p, m_p);
