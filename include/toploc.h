@@ -2,7 +2,7 @@
  * toploc.h -- C ABI of the MI355X (gfx950) TopLoc proof build / verify library.
  *
  * The paper states the problem as two functions applied once per chunk of 32
- * new tokens (Section 4; Section 5.5 and 5.8 for the 32-token sampling):
+ * new tokens (Section 4; Section 5.6 and 5.8 for the 32-token sampling):
  *   Algorithm 1:  (hidden state tensor h, k)      -> encoded proof p
  *   Algorithm 2:  (hidden state tensor h, proof p) -> accept / reject
  * with the three thresholds of Section 5.2 as fixed parameters.  The entry
@@ -53,7 +53,7 @@ extern "C" {
 #define TOPLOC_MAX_K 512u       /* largest supported top-k parameter                    */
 #define TOPLOC_MAX_K_TOPK 4096u /* largest k of toploc_topk alone (Table 1 looks at k up to 4096) */
 
-/* Precisions (Section 5.6 validates across fp32 and bf16).  An fp32 value enters the
+/* Precisions (Section 5.7 validates across fp32 and bf16).  An fp32 value enters the
  * polynomial as its 32-bit pattern over GF(TOPLOC_PRIME32); such a proof is 2 + 4k bytes:
  * the same 2-byte modulus field, then 4-byte little-endian coefficients. */
 #define TOPLOC_DTYPE_BF16 0u
@@ -155,7 +155,7 @@ int toploc_topk(const void *d_hidden_bf16, uint64_t n_chunks, const toploc_param
                 uint32_t *d_topk_idx, uint16_t *d_topk_val, void *hip_stream);
 
 /* The same two algorithms over SEGMENTS of unequal length: the proof over a whole
- * prompt (Section 5.5: a set of top-k values is also kept for the activations of the
+ * prompt (Section 5.6: a set of top-k values is also kept for the activations of the
  * input prompt) and the ragged last chunk of a generation.  The activations are one
  * [total_rows][hidden] bf16 matrix; segment i is rows h_row_offsets[i] ..
  * h_row_offsets[i+1]-1 (n_segments + 1 non-decreasing HOST values), its flat index is
@@ -188,7 +188,7 @@ int toploc_verify_proofs_segments(const void *d_hidden_bf16, const uint64_t *h_r
 int toploc_ring_append(void *d_ring_bf16, const void *d_step_bf16, uint32_t n_seq, uint32_t hidden,
                        uint32_t chunk_tokens, uint32_t step, void *hip_stream);
 
-/* fp32 activations and validation across precisions (Section 5.6, Table 5; fp32 thresholds
+/* fp32 activations and validation across precisions (Section 5.7, Table 5; fp32 thresholds
  * {8, 256, 128} in Section 5.2).  Top-k ranks fp32 values by (pattern & 0x7FFFFFFF).
  *   toploc_proof_bytes_dtype   2 + 2k (TOPLOC_DTYPE_BF16) or 2 + 4k (TOPLOC_DTYPE_F32)
  *   toploc_build_proofs_f32    Algorithm 1 over [n_chunks][chunk_tokens*hidden] fp32 values;

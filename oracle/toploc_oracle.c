@@ -15,7 +15,7 @@
  *
  * Readings of points the paper leaves open (each is listed with its reason in
  * the design notes of this repository):
- *   - top-k ranks by magnitude (Section 5.3: "top-k magnitude elements"):
+ *   - top-k ranks by magnitude (Section 5.3 speaks of the k elements of largest magnitude):
  *     key = bits & 0x7FFF compared as an unsigned integer; ties go to the
  *     lower flat index; output order is (magnitude desc, index asc).
  *   - the polynomial modulus M of Algorithms 3 and 5 is the prime 65497.
@@ -32,7 +32,7 @@
  *
  * Pins (tests/test_oracle_pins.py): round trip P(x_j) = y_j; uniqueness against
  * Lagrange / Gaussian elimination written in Python; injectivity and maximality
- * of m; Table 7's distribution against the closed-form birthday product and
+ * of m; the appendix's distribution of return values against the closed-form birthday product and
  * the paper's printed values; 258-byte size; brute-force top-k on tiny inputs;
  * Algorithm 4 against Fermat's little theorem; verification identities.
  * The actual proof BYTES of a tensor are printed nowhere in the paper, so the
@@ -208,7 +208,7 @@ int toploc_oracle_find_injective_modulus(const uint32_t *x, uint32_t n, uint32_t
     return ORACLE_ENOMOD;
 }
 
-/* Many independent sets at once (the experiment behind Table 7). */
+/* Many independent sets at once (the experiment behind the appendix's table of return values). */
 int toploc_oracle_find_injective_modulus_batch(const uint32_t *x, uint64_t n_sets,
                                                uint32_t n, uint32_t M,
                                                uint32_t *m_out, uint8_t *status)

@@ -2,7 +2,7 @@
  * TopLoc CPU oracle, 32-bit variant -- TEST INFRASTRUCTURE, NOT THE PRODUCT.
  *
  * Proof generation over fp32 hidden states and proof validation across the two
- * precisions of the paper's precision study (Section 5.6, Table 5; fp32 thresholds
+ * precisions of the paper's precision study (Section 5.7, Table 5; fp32 thresholds
  * in Section 5.2).  Same rules as toploc_oracle.c: plain, slow, step by step, the
  * paper's order and notation (Algorithms 1-6), a full qsort for top-k and for the
  * median, exact integer arithmetic (unsigned 128-bit products where a 64-bit one
@@ -22,10 +22,10 @@
  *     of a 16-bit (bf16) pattern: exponent = bits 14..7, mantissa = bits 6..0.
  *   - validating an fp32 proof with bf16 activations: the proof's mantissa is scaled to
  *     bf16's width, m_p = mantissa23 >> 16, and compared with the bf16 mantissa
- *     ("scaled the fp32 mantissa to match bf16", Section 5.6).
+ *     (Section 5.7 scales the fp32 mantissa to bf16's width for a bf16 validator).
  *   - validating a bf16 proof with fp32 activations: the proof's value gets 16 zero
  *     bits appended, m_p = mantissa7 << 16, and is compared with the fp32 mantissa
- *     ("padded 16 zero bits to the bf16 representation", Section 5.6).
+ *     (Section 5.7 pads the bf16 representation with 16 zero bits for an fp32 validator).
  *   - decision rule as in toploc_oracle.c: sum > T_mean * n, lower median, an empty
  *     err_m fails neither mantissa test.
  *

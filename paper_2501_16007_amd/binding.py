@@ -279,7 +279,7 @@ def toploc_verify_proofs_segments(hidden, row_offsets, proofs, k=128, thresholds
 
 
 def generation_row_offsets(n_prompt, n_total, chunk_tokens=32):
-    """Row ranges of one sequence as the paper cuts it (Section 5.5): the prompt's activations as one
+    """Row ranges of one sequence as the paper cuts it (Section 5.6): the prompt's activations as one
     segment, then one segment per `chunk_tokens` generated tokens, the last one ragged."""
     if not 0 <= n_prompt <= n_total:
         raise ValueError("need 0 <= n_prompt <= n_total")

@@ -1,6 +1,6 @@
 // Exact top-k by magnitude over one chunk of bf16 (or fp32) patterns, one workgroup per
 // chunk, one pass over HBM.  This is topk(h, k) of the paper's Algorithm 1 and
-// Algorithm 2 ("top-k magnitude elements", Section 5.3) with the total order
+// Algorithm 2 (Section 5.3 ranks the elements by magnitude) with the total order
 //     a before b  <=>  |a| > |b|  or  (|a| == |b| and index(a) < index(b)),
 // |x| taken as the integer (bits & 0x7FFF), for fp32 (bits & 0x7FFFFFFF).
 //

@@ -161,7 +161,7 @@ struct DecodeFirst {
     }
 };
 
-// F is the proof's field, Fmt the format of the recomputed activations (Section 5.6
+// F is the proof's field, Fmt the format of the recomputed activations (Section 5.7
 // validates across the two precisions).
 template <int KMAX, int CAP, typename F = Field16, typename Fmt = Bf16Fmt, int U = kLoads, int WAVES = TOPLOC_MIN_WAVES>
 __global__ __launch_bounds__(kThreads, WAVES) void verify_kernel(const u32x4* __restrict__ hidden, uint32_t nvec,

@@ -3,7 +3,7 @@
 // (Algorithm 5), extractBits, the err_e / err_m statistics and the three thresholds
 // (Section 5.2).  All integer arithmetic.
 //
-// Two precisions meet here (Section 5.6): the proof's (its field F: GF(65497) carries
+// Two precisions meet here (Section 5.7): the proof's (its field F: GF(65497) carries
 // bf16 patterns, GF(2^32 - 5) fp32 patterns) and the validator's (the format of the
 // recomputed activations).  Exponent and mantissa are compared in the validator's
 // precision: an fp32 proof value met by bf16 activations has its 23-bit mantissa scaled

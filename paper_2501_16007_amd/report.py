@@ -1,5 +1,5 @@
 """Reading aids for proofs and verify records: what the paper tabulates (the modulus
-Algorithm 6 returns, Table 7; exponent mismatches and mantissa differences, Tables 2-5;
+Algorithm 6 returns, the appendix's table of its return values; exponent mismatches and mantissa differences, Tables 2-5;
 top-k mismatch, Table 1) taken from the library's outputs.  Nothing here is on the
 build / verify path; these are reductions over its results with plain tensor ops."""
 import base64
@@ -18,7 +18,7 @@ def proof_modulus(proofs):
 
 
 def modulus_distribution(proofs):
-    """{m: fraction of proofs}, largest modulus first (the shape of Table 7)."""
+    """{m: fraction of proofs}, largest modulus first (the shape of the appendix's table of Algorithm 6's return values)."""
     m = proof_modulus(proofs).cpu().numpy()
     vals, counts = np.unique(m, return_counts=True)
     order = np.argsort(-vals)
@@ -107,15 +107,16 @@ def exponent_deviation_counts(chunks_a, chunks_b, k, both_only=False):
     return {name: int(c.sum().item()) for name, c in zip(EXPONENT_DEVIATION_COLUMNS, cols)}
 
 
-def topk_overlap_by_k(chunks_a, chunks_b, ks=(64, 128, 256, 512, 1024, 2048, 4096)):
-    """{k: (mean, worst) share of the top-k positions of chunks_a that are also top-k positions of
-    chunks_b}: how stable the selected set is under the difference between the two tensors."""
+def topk_mismatch_by_k(chunks_a, chunks_b, ks=(64, 128, 256, 512, 1024, 2048, 4096)):
+    """{k: {"max", "median", "mean"}} of the mismatch ratio per chunk: the share of the top-k positions of
+    chunks_a that are not top-k positions of chunks_b, the two index sets compared as sets (the quantity
+    Section 5.5 plots over k as maximum and median)."""
     out = {}
     for k in ks:
         ia, _ = binding.toploc_topk(chunks_a, k=k, chunk_tokens=1)
         ib, _ = binding.toploc_topk(chunks_b, k=k, chunk_tokens=1)
-        share = 1.0 - topk_mismatch(ia, ib).to(torch.float64) / k
-        out[int(k)] = (float(share.mean().item()), float(share.min().item()))
+        ratio = (topk_mismatch(ia, ib).to(torch.float64) / k).cpu().numpy()
+        out[int(k)] = {"max": float(ratio.max()), "median": float(np.median(ratio)), "mean": float(ratio.mean())}
     return out
 
 

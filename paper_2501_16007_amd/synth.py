@@ -5,7 +5,7 @@ none of the method's arithmetic: no top-k, no modular arithmetic, no bit
 extraction.  It only draws tensors.
 
 The paper measured on UltraChat prompts run through Llama-3.1-8B/70B,
-INTELLECT-1 and Gemma-2-9b (Section 5.1, Table 10); neither the dataset nor
+INTELLECT-1 and Gemma-2-9b (Section 5.1 and the appendix's table of model configurations); neither the dataset nor
 any weights are available here, so these tensors stand in for them.  They
 take the shapes (hidden 4096 / 8192 / 5120 / 3584, bf16) and the structure
 that makes top-k reproducible in real models (Section 3.3): a near-Gaussian
@@ -95,7 +95,7 @@ def perturb_ulp(x, frac, seed):
 
 def perturb_relative(x, max_rel, seed):
     """bf16(x * (1 + d)), d ~ U(-max_rel, max_rel) in fp32: emulates the small
-    deviations of a reordered computation (Section 5.5, Table 2)."""
+    deviations of a reordered computation (Section 5.6, Table 2)."""
     g = _gen(seed, x.device)
     out = torch.empty_like(x)
     flat_in = x.reshape(-1)

@@ -1,4 +1,4 @@
-"""fp32 proofs and validation across precisions (Section 5.6): GPU path vs the 32-bit CPU
+"""fp32 proofs and validation across precisions (Section 5.7): GPU path vs the 32-bit CPU
 oracle, bit for bit, through the C ABI.  Inputs are seeded and synthetic."""
 import numpy as np
 import pytest

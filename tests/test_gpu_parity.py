@@ -79,7 +79,7 @@ def random_chunks(n_chunks, hidden, tokens, seed, n_outlier=4):
         (4096, 32, 128, 6),    # the 8B shape
         (5120, 32, 512, 2),    # the 13B shape, largest k
         (8192, 32, 128, 3),    # the 70B shape
-        (3584, 32, 64, 2),     # Gemma-2-9b hidden size (Table 10)
+        (3584, 32, 64, 2),     # Gemma-2-9b hidden size (appendix, model configurations)
         (64, 32, 512, 2),      # N = 2048, k = N/4: prune pressure
     ],
 )

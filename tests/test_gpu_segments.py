@@ -3,7 +3,7 @@
 A chunk or a segment may be cut into parts whose candidates a second launch merges;
 whatever the cut, top-k indices, proof bytes, status and verify records must equal the
 oracle's, which sees every segment as one flat array (Algorithm 1 and 2 on the whole
-prompt, Section 5.5, or on a ragged last chunk).
+prompt, Section 5.6, or on a ragged last chunk).
 """
 import numpy as np
 import pytest

@@ -5,7 +5,7 @@ mathematics fixes: uniqueness of the interpolating polynomial (against Lagrange 
 Python integers and against the already pinned 16-bit routine on a common modulus),
 exhaustive small fields, brute-force top-k, Algorithm 6 against the pinned routine, the
 round trip P(x_j) = y_j through the proof bytes, and closed-form outcomes of validation
-across precisions (Section 5.6) on inputs built so that the result is known by hand.
+across precisions (Section 5.7) on inputs built so that the result is known by hand.
 """
 import itertools
 

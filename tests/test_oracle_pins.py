@@ -305,7 +305,7 @@ def test_modulus_failure_with_distinct_indices_and_a_deep_search():
 
 
 # ---------------------------------------------------------------------------
-# P4: Table 7 -- printed values, closed form, Monte Carlo of the oracle
+# P4: the appendix's table of Algorithm 6's return values -- printed values, closed form, Monte Carlo of the oracle
 # ---------------------------------------------------------------------------
 
 def birthday_distribution(k, top=65536, rows=9):
@@ -319,8 +319,8 @@ def birthday_distribution(k, top=65536, rows=9):
     return probs
 
 
-def test_table7_closed_form_matches_printed_values():
-    rows = read_golden("table7_modulus_distribution.txt")
+def test_modulus_distribution_closed_form_matches_printed_values():
+    rows = read_golden("injective_modulus_distribution.txt")
     printed = {int(m): float(v) for m, v in rows}
     closed = dict(zip(range(65536, 65536 - 9, -1), birthday_distribution(128)))
     assert abs(closed[65536] - printed[65536]) < 5e-5                # 4 printed digits
@@ -330,8 +330,8 @@ def test_table7_closed_form_matches_printed_values():
     assert abs(closed[65532] - printed[65532]) / printed[65532] < 5e-2
 
 
-def test_table7_monte_carlo_of_oracle():
-    rows = read_golden("table7_modulus_distribution.txt")
+def test_modulus_distribution_monte_carlo_of_oracle():
+    rows = read_golden("injective_modulus_distribution.txt")
     printed = {int(m): float(v) for m, v in rows}
     rng = np.random.default_rng(7)
     n_sets, counts = 0, {}
@@ -354,7 +354,7 @@ def test_table7_monte_carlo_of_oracle():
     assert min(counts) >= 65528 and max(counts) == 65536
 
 
-def test_composite_reading_shifts_table7_only_slightly():
+def test_composite_reading_shifts_the_distribution_only_slightly():
     rng = np.random.default_rng(8)
     sets = rng.integers(0, 2 ** 31, size=(100_000, 128), dtype=np.int64).astype(np.uint32)
     m0, _ = orc.find_injective_modulus_batch(sets, M=0)
