@@ -229,6 +229,17 @@ int toploc_verify_proofs_mixed(const void *d_hidden, uint32_t hidden_dtype, uint
  *                               status (TOPLOC_CHUNK_SHORT when fewer than k values were
  *                               appended) and optionally the ordered indices, laid out as by
  *                               toploc_build_proofs; then empties the states
+ *   toploc_stream_append_rows   the same for a serving loop with continuous batching, where a
+ *                               step carries rows of any subset of the sequences, each at its
+ *                               own position: row r of d_step_bf16 [n_rows][hidden] enters the
+ *                               state of sequence d_slots[r] (< n_slots) as token d_tokens[r]
+ *                               (< chunk_tokens); d_slots, d_tokens: device, n_rows uint32.
+ *                               The slots of one call must be distinct; a row whose slot or
+ *                               token is out of range is skipped
+ *   toploc_stream_emit_rows     emission for the sequences d_slots[0..n_rows): output row r
+ *                               (proof, status, indices) belongs to sequence d_slots[r], whose
+ *                               state is emptied; an out-of-range slot reads as an empty state
+ *                               (TOPLOC_CHUNK_SHORT).  Slots must be distinct
  * d_state is 16-byte aligned device memory owned by the caller; calls on one state must
  * be ordered on one stream. */
 size_t toploc_stream_state_bytes(uint32_t n_seq, uint32_t k);
@@ -237,6 +248,11 @@ int toploc_stream_append(void *d_state, const void *d_step_bf16, uint32_t n_seq,
                          uint32_t token, uint32_t k, void *hip_stream);
 int toploc_stream_emit(void *d_state, uint32_t n_seq, uint32_t k, uint8_t *d_proofs, uint8_t *d_status,
                        uint32_t *d_topk_idx_opt, void *hip_stream);
+int toploc_stream_append_rows(void *d_state, uint32_t n_slots, const void *d_step_bf16, const uint32_t *d_slots,
+                              const uint32_t *d_tokens, uint32_t n_rows, uint32_t hidden, uint32_t chunk_tokens,
+                              uint32_t k, void *hip_stream);
+int toploc_stream_emit_rows(void *d_state, uint32_t n_slots, const uint32_t *d_slots, uint32_t n_rows, uint32_t k,
+                            uint8_t *d_proofs, uint8_t *d_status, uint32_t *d_topk_idx_opt, void *hip_stream);
 
 /* Measurement aid, not part of the method: reads n_chunks * chunk_values bf16
  * values with the access pattern of the selection kernel (one workgroup per
@@ -261,8 +277,8 @@ int toploc_bench_read(const void *d_hidden_bf16, uint64_t n_chunks, uint64_t chu
 #define TOPLOC_KERNEL_VERIFY 5        /* fused verify kernel                             */
 #define TOPLOC_KERNEL_RING 6          /* ring append kernel                              */
 #define TOPLOC_KERNEL_READ 7          /* toploc_bench_read                               */
-#define TOPLOC_KERNEL_STREAM_APPEND 8 /* toploc_stream_append                            */
-#define TOPLOC_KERNEL_STREAM_EMIT 9   /* toploc_stream_emit                              */
+#define TOPLOC_KERNEL_STREAM_APPEND 8 /* toploc_stream_append, toploc_stream_append_rows  */
+#define TOPLOC_KERNEL_STREAM_EMIT 9   /* toploc_stream_emit, toploc_stream_emit_rows      */
 #define TOPLOC_KERNEL_COUNT 10
 int toploc_profile_enable(int on);
 int toploc_profile_read(uint32_t *launches /*[TOPLOC_KERNEL_COUNT]*/, float *total_ms /*[TOPLOC_KERNEL_COUNT]*/);

@@ -56,6 +56,8 @@ EXPORTS = (
     "toploc_stream_reset",
     "toploc_stream_append",
     "toploc_stream_emit",
+    "toploc_stream_append_rows",
+    "toploc_stream_emit_rows",
     "toploc_ring_append",
     "toploc_bench_read",
     "toploc_profile_enable",
@@ -120,6 +122,8 @@ def lib():
         L.toploc_stream_reset.argtypes = [P, c.c_uint32, c.c_uint32, P]
         L.toploc_stream_append.argtypes = [P, P, c.c_uint32, c.c_uint32, c.c_uint32, c.c_uint32, c.c_uint32, P]
         L.toploc_stream_emit.argtypes = [P, c.c_uint32, c.c_uint32, P, P, P, P]
+        L.toploc_stream_append_rows.argtypes = [P, c.c_uint32, P, P, P, c.c_uint32, c.c_uint32, c.c_uint32, c.c_uint32, P]
+        L.toploc_stream_emit_rows.argtypes = [P, c.c_uint32, P, c.c_uint32, c.c_uint32, P, P, P, P]
         L.toploc_bench_read.argtypes = [P, c.c_uint64, c.c_uint64, P, P]
         L.toploc_profile_enable.argtypes = [c.c_int]
         L.toploc_profile_read.argtypes = [c.POINTER(c.c_uint32), c.POINTER(c.c_float)]
@@ -414,6 +418,51 @@ def toploc_stream_emit(state, n_seq, k=128, want_topk=False, out=None):
                                   idx.data_ptr() if want_topk else None, _stream(state))
     if rc != OK:
         raise ToplocError(rc, "toploc_stream_emit")
+    return (proofs, status, idx) if want_topk else (proofs, status)
+
+
+def _u32_device(values, device, what):
+    """A list, numpy array or tensor of non-negative integers as a contiguous int32 device tensor (uint32 bits)."""
+    if isinstance(values, torch.Tensor):
+        t = values.to(device=device, dtype=torch.int32)
+    else:
+        t = torch.from_numpy(np.ascontiguousarray(values, dtype=np.uint32).view(np.int32)).to(device)
+    if t.dim() != 1:
+        raise ValueError(what + " must be one-dimensional")
+    return t.contiguous()
+
+
+def toploc_stream_append_rows(state, n_slots, step_vec, slots, tokens, k=128, chunk_tokens=32):
+    """Continuous batching: row r of step_vec [n_rows, H] bf16 is token tokens[r] of sequence slots[r]."""
+    if step_vec.dtype != torch.bfloat16 or not step_vec.is_cuda or not step_vec.is_contiguous() or step_vec.dim() != 2:
+        raise ValueError("step_vec must be a contiguous [n_rows, H] bf16 tensor on the GPU")
+    n_rows, h = step_vec.shape
+    slots = _u32_device(slots, step_vec.device, "slots")
+    tokens = _u32_device(tokens, step_vec.device, "tokens")
+    if slots.numel() != n_rows or tokens.numel() != n_rows:
+        raise ValueError("one slot and one token per row")
+    if state.numel() < toploc_stream_state_bytes(n_slots, k):
+        raise ValueError("state too small for n_slots sequences")
+    rc = lib().toploc_stream_append_rows(state.data_ptr(), n_slots, step_vec.data_ptr(), slots.data_ptr(),
+                                         tokens.data_ptr(), n_rows, h, chunk_tokens, k, _stream(step_vec))
+    if rc != OK:
+        raise ToplocError(rc, "toploc_stream_append_rows")
+
+
+def toploc_stream_emit_rows(state, n_slots, slots, k=128, want_topk=False):
+    """Proofs of the sequences `slots` (output row r belongs to slots[r]); empties their states."""
+    dev = state.device
+    slots = _u32_device(slots, dev, "slots")
+    n_rows = slots.numel()
+    proofs = torch.empty((n_rows, 2 + 2 * k), dtype=torch.uint8, device=dev)
+    status = torch.empty(n_rows, dtype=torch.uint8, device=dev)
+    idx = torch.empty((n_rows, k), dtype=torch.int32, device=dev) if want_topk else None
+    if state.numel() < toploc_stream_state_bytes(n_slots, k):
+        raise ValueError("state too small for n_slots sequences")
+    rc = lib().toploc_stream_emit_rows(state.data_ptr(), n_slots, slots.data_ptr(), n_rows, k, proofs.data_ptr(),
+                                       status.data_ptr(), idx.data_ptr() if want_topk else None, _stream(state))
+    if rc != OK:
+        raise ToplocError(rc, "toploc_stream_emit_rows")
     return (proofs, status, idx) if want_topk else (proofs, status)
 
 

@@ -358,14 +358,27 @@ struct StreamSeed {
 // seeded with the pairs and the threshold the sequence holds.  `row_base` is the
 // sequence's row pointer moved back by v0 vectors, so that vector v0 + j of the
 // selection is vector j of the row and flat indices come out as token*hidden + channel.
+// With `slots` (continuous batching: the rows of a step belong to any subset of the
+// sequences, each at its own position) row r goes to sequence slots[r] as token tokens[r];
+// a row whose slot or token is out of range is skipped.
 template <int CAP>
 __global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void stream_append_kernel(char* __restrict__ state, size_t stride,
                                                                                    const u32x4* __restrict__ step_vec,
-                                                                                   uint32_t hvec, uint32_t v0, uint32_t k)
+                                                                                   uint32_t hvec, uint32_t v0, uint32_t k,
+                                                                                   const uint32_t* __restrict__ slots,
+                                                                                   const uint32_t* __restrict__ tokens,
+                                                                                   uint32_t n_slots, uint32_t chunk_tokens)
 {
     __shared__ SelectShared<kThreads, CAP, kQcap> s;
     const uint32_t tid = threadIdx.x;
-    char* st = state + (size_t)blockIdx.x * stride;
+    uint32_t seq = blockIdx.x;
+    if (slots) {  // uniform
+        seq = slots[blockIdx.x];
+        const uint32_t token = tokens[blockIdx.x];
+        if (seq >= n_slots || token >= chunk_tokens) return;
+        v0 = token * hvec;
+    }
+    char* st = state + (size_t)seq * stride;
     StreamHeader* hdr = reinterpret_cast<StreamHeader*>(st);
     uint32_t* g_idx = reinterpret_cast<uint32_t*>(st + sizeof(StreamHeader));
     uint16_t* g_bits = reinterpret_cast<uint16_t*>(st + sizeof(StreamHeader) + stream_idx_bytes(k));
@@ -385,7 +398,8 @@ __global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void stream_append_kern
 template <int THREADS, int KMAX, int CAP>
 __global__ __launch_bounds__(THREADS) void stream_emit_kernel(char* __restrict__ state, size_t stride, uint32_t k,
                                                               uint8_t* __restrict__ proofs, uint8_t* __restrict__ status,
-                                                              uint32_t* __restrict__ out_idx)
+                                                              uint32_t* __restrict__ out_idx,
+                                                              const uint32_t* __restrict__ slots, uint32_t n_slots)
 {
     static_assert(KMAX <= THREADS, "one pair per lane is carried across the phase change");
     __shared__ union EmitShared {
@@ -394,15 +408,17 @@ __global__ __launch_bounds__(THREADS) void stream_emit_kernel(char* __restrict__
     } sh;
     __shared__ uint32_t coef[KMAX];
     const uint32_t tid = threadIdx.x;
-    const uint64_t seq = blockIdx.x;
-    char* st = state + seq * stride;
+    const uint64_t seq = blockIdx.x;  // output row; with `slots` the state of sequence slots[seq]
+    const uint64_t owner = slots ? slots[seq] : seq;
+    const bool known = owner < n_slots;  // uniform
+    char* st = state + (known ? owner : 0) * stride;
     StreamHeader* hdr = reinterpret_cast<StreamHeader*>(st);
     const uint32_t* g_idx = reinterpret_cast<const uint32_t*>(st + sizeof(StreamHeader));
     const uint16_t* g_bits = reinterpret_cast<const uint16_t*>(st + sizeof(StreamHeader) + stream_idx_bytes(k));
-    const uint32_t count = hdr->count;
+    const uint32_t count = known ? hdr->count : 0u;
     uint16_t* proof = reinterpret_cast<uint16_t*>(proofs + seq * (2 + 2 * (uint64_t)k));
     __syncthreads();  // every lane has read the header
-    if (tid == 0) *hdr = StreamHeader{0u, 0, 0xFFFFFFFFu, 0u};
+    if (tid == 0 && known) *hdr = StreamHeader{0u, 0, 0xFFFFFFFFu, 0u};
     if (count < k) {  // uniform
         for (uint32_t j = tid; j <= k; j += THREADS) proof[j] = 0;
         if (out_idx)
@@ -942,10 +958,41 @@ int toploc_stream_append(void* d_state, const void* d_step_bf16, uint32_t n_seq,
         ProfScope ps(TOPLOC_KERNEL_STREAM_APPEND, st);
         if (k <= 128)
             hipLaunchKernelGGL((stream_append_kernel<kCapSmall>), dim3(n_seq), dim3(kThreads), 0, st, (char*)d_state,
-                               stream_stride(k), (const u32x4*)d_step_bf16, hvec, token * hvec, k);
+                               stream_stride(k), (const u32x4*)d_step_bf16, hvec, token * hvec, k, nullptr, nullptr, n_seq,
+                               chunk_tokens);
         else
             hipLaunchKernelGGL((stream_append_kernel<kCapLarge>), dim3(n_seq), dim3(kThreads), 0, st, (char*)d_state,
-                               stream_stride(k), (const u32x4*)d_step_bf16, hvec, token * hvec, k);
+                               stream_stride(k), (const u32x4*)d_step_bf16, hvec, token * hvec, k, nullptr, nullptr, n_seq,
+                               chunk_tokens);
+    }
+    return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
+}
+
+int toploc_stream_append_rows(void* d_state, uint32_t n_slots, const void* d_step_bf16, const uint32_t* d_slots,
+                              const uint32_t* d_tokens, uint32_t n_rows, uint32_t hidden, uint32_t chunk_tokens,
+                              uint32_t k, void* hip_stream)
+{
+    if (k == 0 || k > TOPLOC_MAX_K || hidden == 0 || hidden % 8 != 0 || chunk_tokens == 0) return TOPLOC_EINVAL;
+    const uint64_t chunk_values = (uint64_t)chunk_tokens * hidden;
+    if (chunk_values >= (1ull << 32)) return TOPLOC_EINVAL;
+    if (n_rows == 0) return TOPLOC_OK;
+    if (!d_state || !d_step_bf16 || !d_slots || !d_tokens || n_slots == 0) return TOPLOC_EINVAL;
+    if (!aligned16(d_state) || !aligned16(d_step_bf16)) return TOPLOC_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(d_slots) & 3u) != 0 || (reinterpret_cast<uintptr_t>(d_tokens) & 3u) != 0)
+        return TOPLOC_EINVAL;
+    if (reinterpret_cast<uintptr_t>(d_step_bf16) < chunk_values * 2) return TOPLOC_EINVAL;  // the kernel forms row - v0
+    hipStream_t st = (hipStream_t)hip_stream;
+    const uint32_t hvec = hidden / 8;
+    {
+        ProfScope ps(TOPLOC_KERNEL_STREAM_APPEND, st);
+        if (k <= 128)
+            hipLaunchKernelGGL((stream_append_kernel<kCapSmall>), dim3(n_rows), dim3(kThreads), 0, st, (char*)d_state,
+                               stream_stride(k), (const u32x4*)d_step_bf16, hvec, 0u, k, d_slots, d_tokens, n_slots,
+                               chunk_tokens);
+        else
+            hipLaunchKernelGGL((stream_append_kernel<kCapLarge>), dim3(n_rows), dim3(kThreads), 0, st, (char*)d_state,
+                               stream_stride(k), (const u32x4*)d_step_bf16, hvec, 0u, k, d_slots, d_tokens, n_slots,
+                               chunk_tokens);
     }
     return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
 }
@@ -962,10 +1009,31 @@ int toploc_stream_emit(void* d_state, uint32_t n_seq, uint32_t k, uint8_t* d_pro
         ProfScope ps(TOPLOC_KERNEL_STREAM_EMIT, st);
         if (k <= 128)
             hipLaunchKernelGGL((stream_emit_kernel<256, 128, kCapSmall>), dim3(n_seq), dim3(256), 0, st, (char*)d_state,
-                               stream_stride(k), k, d_proofs, d_status, d_topk_idx_opt);
+                               stream_stride(k), k, d_proofs, d_status, d_topk_idx_opt, nullptr, n_seq);
         else
             hipLaunchKernelGGL((stream_emit_kernel<1024, 512, kCapLarge>), dim3(n_seq), dim3(1024), 0, st, (char*)d_state,
-                               stream_stride(k), k, d_proofs, d_status, d_topk_idx_opt);
+                               stream_stride(k), k, d_proofs, d_status, d_topk_idx_opt, nullptr, n_seq);
+    }
+    return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
+}
+
+int toploc_stream_emit_rows(void* d_state, uint32_t n_slots, const uint32_t* d_slots, uint32_t n_rows, uint32_t k,
+                            uint8_t* d_proofs, uint8_t* d_status, uint32_t* d_topk_idx_opt, void* hip_stream)
+{
+    if (k == 0 || k > TOPLOC_MAX_K) return TOPLOC_EINVAL;
+    if (n_rows == 0) return TOPLOC_OK;
+    if (!d_state || !d_slots || !d_proofs || !d_status || n_slots == 0 || !aligned16(d_state)) return TOPLOC_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(d_proofs) & 1u) != 0 || (reinterpret_cast<uintptr_t>(d_slots) & 3u) != 0)
+        return TOPLOC_EINVAL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    {
+        ProfScope ps(TOPLOC_KERNEL_STREAM_EMIT, st);
+        if (k <= 128)
+            hipLaunchKernelGGL((stream_emit_kernel<256, 128, kCapSmall>), dim3(n_rows), dim3(256), 0, st, (char*)d_state,
+                               stream_stride(k), k, d_proofs, d_status, d_topk_idx_opt, d_slots, n_slots);
+        else
+            hipLaunchKernelGGL((stream_emit_kernel<1024, 512, kCapLarge>), dim3(n_rows), dim3(1024), 0, st, (char*)d_state,
+                               stream_stride(k), k, d_proofs, d_status, d_topk_idx_opt, d_slots, n_slots);
     }
     return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
 }

@@ -147,3 +147,61 @@ def test_stream_window_captured_in_a_graph_replays_like_eager():
         bits = synth.bits_numpy(static.transpose(0, 1).contiguous()).reshape(n_seq, -1)
         o_proofs, _ = orc.build(bits[:8], k)
         assert np.array_equal(replayed[:8].cpu().numpy(), o_proofs)
+
+
+def test_continuous_batching_against_the_oracle_per_sequence():
+    """Sequences join and leave a running batch at different steps; every proof the prover cuts (full
+    32-token chunks, ragged tails, the prompt) equals the oracle's on the rows that went into it."""
+    from paper_2501_16007_amd.online import OnlineProver
+    hidden, k, n_slots = 1024, 128, 6
+    plan = {0: (0, 70), 1: (3, 33), 2: (10, 64), 3: (10, 5), 4: (40, 100), 5: (41, 32)}   # slot: (first step, tokens)
+    rows = {s: synth.activations(1, n, hidden, 6100 + s, n_outlier=4, device=DEV).reshape(n, hidden)
+            for s, (_, n) in plan.items()}
+    say("continuous batching: %d slots, lengths %s" % (n_slots, [n for _, n in plan.values()]))
+    prover = OnlineProver(n_slots, hidden, k=k, device=DEV)
+    got = {s: [] for s in plan}
+    for step in range(150):
+        active = [s for s, (t0, n) in plan.items() if t0 <= step < t0 + n]
+        if active:
+            batch = torch.stack([rows[s][step - plan[s][0]] for s in active])
+            out = prover.append(batch, active)
+            if out is not None:
+                for s, p, st in zip(out[0].tolist(), out[1].cpu().numpy(), out[2].cpu().numpy()):
+                    got[s].append((p, int(st)))
+        ended = [s for s, (t0, n) in plan.items() if step == t0 + n - 1]
+        out = prover.finish(ended) if ended else None
+        if out is not None:
+            for s, p, st in zip(out[0].tolist(), out[1].cpu().numpy(), out[2].cpu().numpy()):
+                got[s].append((p, int(st)))
+    assert not prover.rows.any()
+    for s, (_, n) in plan.items():
+        bits = synth.bits_numpy(rows[s])
+        cuts = list(range(0, n, 32)) + [n]
+        assert len(got[s]) == len(cuts) - 1, "slot %d: %d proofs" % (s, len(got[s]))
+        for c, (p, st) in enumerate(got[s]):
+            o_proofs, o_status = orc.build(bits[cuts[c]:cuts[c + 1]].reshape(1, -1), k)
+            assert st == int(o_status[0]) and np.array_equal(p, o_proofs[0]), "slot %d chunk %d" % (s, c)
+    # the prompt's proof is the segment call on the prompt's rows
+    p, st = prover.prefill(rows[4][:75])
+    o_proofs, _ = orc.build(synth.bits_numpy(rows[4][:75]).reshape(1, -1), k)
+    assert int(st) == 0 and np.array_equal(p.cpu().numpy(), o_proofs[0])
+
+
+def test_indexed_stream_calls_skip_rows_that_are_out_of_range():
+    hidden, k = 256, 16
+    state = tl.toploc_stream_new_state(3, k, DEV)
+    x = synth.activations(1, 4, hidden, 6200, n_outlier=2, device=DEV).reshape(4, hidden)
+    # rows 1 and 3 name a slot / a token that do not exist: they must leave every state alone
+    tl.toploc_stream_append_rows(state, 3, x, [2, 7, 0, 1], [0, 0, 5, 32], k=k)
+    proofs, status, idx = tl.toploc_stream_emit_rows(state, 3, [0, 1, 2, 9], k=k, want_topk=True)
+    torch.cuda.synchronize()
+    bits = synth.bits_numpy(x)
+    o2, s2, i2 = orc.build(bits[0:1], k, want_topk=True)                   # slot 2: row 0 as token 0
+    o0, s0, i0 = orc.build(bits[2:3], k, want_topk=True)                   # slot 0: row 2 as token 5
+    assert status.cpu().numpy().tolist() == [0, tl.CHUNK_SHORT, 0, tl.CHUNK_SHORT]
+    assert np.array_equal(proofs[2].cpu().numpy(), o2[0]) and np.array_equal(idx[2].cpu().numpy().view(np.uint32), i2[0])
+    assert np.array_equal(idx[0].cpu().numpy().view(np.uint32), i0[0] + 5 * hidden)
+    assert not proofs[1].any() and not proofs[3].any()
+    # emission emptied the states
+    _, status = tl.toploc_stream_emit_rows(state, 3, [0, 1, 2], k=k)
+    assert status.cpu().numpy().tolist() == [tl.CHUNK_SHORT] * 3
