@@ -23,6 +23,7 @@
 
 #include "gf32.hpp"
 #include "gf65497.hpp"
+#include "ticks.hpp"
 
 namespace toploc {
 
@@ -92,6 +93,7 @@ __device__ __forceinline__ void interpolate(InterpShared<KMAX, F>& s, uint32_t k
     const uint32_t n_giant = (k + kBaby - 1u) / kBaby;
 
     // ---- W(X) = prod (X - x_j): pairwise products of monic polynomials ----
+    TOPLOC_TICK_BEGIN(tree);
     E* src = s.pa;
     E* dst = s.pb;
     for (uint32_t j = tid; j < k; j += THREADS) src[j] = (E)F::neg(s.xs[j]);
@@ -124,6 +126,8 @@ __device__ __forceinline__ void interpolate(InterpShared<KMAX, F>& s, uint32_t k
         E* tmp = src; src = dst; dst = tmp;
     }
     const E* W = src;  // W_0..W_{k-1}; W_k = 1
+    TOPLOC_TICK_END(tree, 7);
+    TOPLOC_TICK_BEGIN(tables);
     // ---- W'(X) coefficients: wder_r = (r+1) W_{r+1}; power tables of every point ----
     for (uint32_t r = tid; r < k; r += THREADS)
         s.wder[r] = (E)F::mulmod(r + 1, r + 1 == k ? 1u : (uint32_t)W[r + 1]);
@@ -154,6 +158,8 @@ __device__ __forceinline__ void interpolate(InterpShared<KMAX, F>& s, uint32_t k
         }
     }
     __syncthreads();
+    TOPLOC_TICK_END(tables, 8);
+    TOPLOC_TICK_BEGIN(denom);
     // ---- d_j = sum_r1 x_j^(16 r1) * (sum_r0 W'_(16 r1 + r0) x_j^r0); a_j = y_j / d_j; G <- a_j G ----
 #pragma unroll
     for (int i = 0; i < PPT; ++i) {
@@ -185,6 +191,8 @@ __device__ __forceinline__ void interpolate(InterpShared<KMAX, F>& s, uint32_t k
         }
     }
     __syncthreads();
+    TOPLOC_TICK_END(denom, 9);
+    TOPLOC_TICK_BEGIN(sums);
     // ---- S_r = sum_j (a_j x_j^(16 r1)) x_j^r0, r = 16 r1 + r0; lane h takes j = h mod L ----
     for (uint32_t r = tid / L; r < k; r += THREADS / L) {
         const E* arow = &s.u.pw.G[(r / kBaby) * KMAX];
@@ -197,6 +205,8 @@ __device__ __forceinline__ void interpolate(InterpShared<KMAX, F>& s, uint32_t k
         if (h == 0) s.S[r] = (E)v;
     }
     __syncthreads();
+    TOPLOC_TICK_END(sums, 10);
+    TOPLOC_TICK_BEGIN(coefs);
     // ---- c_i = sum_{r=0}^{k-1-i} W_{i+1+r} S_r, lane h takes r = h mod L ----
     for (uint32_t i = tid / L; i < k; i += THREADS / L) {
         Acc acc;
@@ -209,6 +219,7 @@ __device__ __forceinline__ void interpolate(InterpShared<KMAX, F>& s, uint32_t k
         if (h == 0) coef_out[i] = c;
     }
     __syncthreads();
+    TOPLOC_TICK_END(coefs, 11);
 }
 
 // Remaining steps of Algorithm 1 for one chunk whose top-k pairs sit in s.idx / s.ys
@@ -223,7 +234,9 @@ __device__ __forceinline__ void finish_proof(InterpShared<KMAX, F>& s, uint32_t*
     for (uint32_t w = tid; w < 2048; w += THREADS) s.u.bitmap[w] = 0;
     if (tid == 0) { s.collide[0] = 0; s.collide[1] = 0; }
     __syncthreads();
+    TOPLOC_TICK_BEGIN(modulus);
     const uint32_t m = find_modulus<THREADS>(s, k);
+    TOPLOC_TICK_END(modulus, 6);
     if (m == 0) {  // uniform
         for (uint32_t j = tid; j <= k * F::WORDS; j += THREADS) proof[j] = 0;
         if (tid == 0) *status = 1;  // TOPLOC_CHUNK_NO_MODULUS
