@@ -189,7 +189,13 @@ __global__ __launch_bounds__(kThreads, WAVES) void verify_kernel(const u32x4* __
 // generations (the 8B shape's 4096 chunks of 256 KB) spends a larger share of each
 // workgroup's life outside the streaming loop and gains more from a sixth resident
 // workgroup per compute unit, which 3 loads per lane leave registers for.
-constexpr int kLoadsShort = 3, kWavesShort = 6;
+#ifndef TOPLOC_LOADS_SHORT
+#define TOPLOC_LOADS_SHORT 3
+#endif
+#ifndef TOPLOC_WAVES_SHORT
+#define TOPLOC_WAVES_SHORT 6
+#endif
+constexpr int kLoadsShort = TOPLOC_LOADS_SHORT, kWavesShort = TOPLOC_WAVES_SHORT;
 constexpr uint64_t kShortLaunchGroups = 6 * 5 * 256;  // fewer than about six generations
 
 // ---------------------------------------------------------------------------
