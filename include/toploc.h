@@ -201,13 +201,30 @@ int toploc_ring_append(void *d_ring_bf16, const void *d_step_bf16, uint32_t n_se
  *                              (>> 16) for a bf16 validator, a bf16 proof's value gets 16 zero
  *                              bits appended for an fp32 validator.  Thresholds are the caller's
  *                              (the paper uses the validator's precision's).
- * Both run as one fused launch per call and need no workspace. */
+ * Both run as one fused launch per call and need no workspace.
+ *   toploc_build_proofs_segments_f32, toploc_verify_proofs_segments_mixed
+ *                              the same two over segments of unequal length (the whole prompt,
+ *                              a ragged last chunk), arguments as toploc_build_proofs_segments /
+ *                              toploc_verify_proofs_segments; d_workspace must hold
+ *                              toploc_segments_workspace_bytes_dtype(..., hidden_dtype) bytes
+ *                              (candidates carry 4-byte patterns when the activations are fp32) */
 size_t toploc_proof_bytes_dtype(uint32_t k, uint32_t dtype);
 int toploc_build_proofs_f32(const void *d_hidden_f32, uint64_t n_chunks, const toploc_params *params, uint8_t *d_proofs,
                             uint8_t *d_status, uint32_t *d_topk_idx_opt, void *hip_stream);
 int toploc_verify_proofs_mixed(const void *d_hidden, uint32_t hidden_dtype, uint64_t n_chunks, const toploc_params *params,
                                const uint8_t *d_proofs, uint32_t proof_dtype, const toploc_thresholds *thresholds,
                                toploc_verify_result *d_results, void *hip_stream);
+size_t toploc_segments_workspace_bytes_dtype(const uint64_t *h_row_offsets, uint64_t n_segments, uint32_t hidden,
+                                             uint32_t k, uint32_t hidden_dtype);
+int toploc_build_proofs_segments_f32(const void *d_hidden_f32, const uint64_t *h_row_offsets, uint64_t n_segments,
+                                     uint32_t hidden, uint32_t k, uint8_t *d_proofs, uint8_t *d_status,
+                                     uint32_t *d_topk_idx_opt, void *d_workspace, size_t workspace_bytes,
+                                     void *hip_stream);
+int toploc_verify_proofs_segments_mixed(const void *d_hidden, uint32_t hidden_dtype, const uint64_t *h_row_offsets,
+                                        uint64_t n_segments, uint32_t hidden, uint32_t k, const uint8_t *d_proofs,
+                                        uint32_t proof_dtype, const toploc_thresholds *thresholds,
+                                        toploc_verify_result *d_results, void *d_workspace, size_t workspace_bytes,
+                                        void *hip_stream);
 
 /* Online path without the ring (a design of this build; the paper's provider keeps the
  * last hidden states, Table 6, only to take their top-k when the proof is cut).  Per

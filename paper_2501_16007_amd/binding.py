@@ -52,6 +52,9 @@ EXPORTS = (
     "toploc_proof_bytes_dtype",
     "toploc_build_proofs_f32",
     "toploc_verify_proofs_mixed",
+    "toploc_segments_workspace_bytes_dtype",
+    "toploc_build_proofs_segments_f32",
+    "toploc_verify_proofs_segments_mixed",
     "toploc_stream_state_bytes",
     "toploc_stream_reset",
     "toploc_stream_append",
@@ -117,6 +120,11 @@ def lib():
         L.toploc_build_proofs_f32.argtypes = [P, c.c_uint64, c.POINTER(Params), P, P, P, P]
         L.toploc_verify_proofs_mixed.argtypes = [P, c.c_uint32, c.c_uint64, c.POINTER(Params), P, c.c_uint32,
                                                  c.POINTER(Thresholds), P, P]
+        L.toploc_segments_workspace_bytes_dtype.argtypes = [P, c.c_uint64, c.c_uint32, c.c_uint32, c.c_uint32]
+        L.toploc_segments_workspace_bytes_dtype.restype = c.c_size_t
+        L.toploc_build_proofs_segments_f32.argtypes = [P, P, c.c_uint64, c.c_uint32, c.c_uint32, P, P, P, P, c.c_size_t, P]
+        L.toploc_verify_proofs_segments_mixed.argtypes = [P, c.c_uint32, P, c.c_uint64, c.c_uint32, c.c_uint32, P, c.c_uint32,
+                                                          c.POINTER(Thresholds), P, P, c.c_size_t, P]
         L.toploc_stream_state_bytes.argtypes = [c.c_uint32, c.c_uint32]
         L.toploc_stream_state_bytes.restype = c.c_size_t
         L.toploc_stream_reset.argtypes = [P, c.c_uint32, c.c_uint32, P]
@@ -369,6 +377,62 @@ def toploc_verify_proofs_mixed(hidden, proofs, proof_dtype, k=128, chunk_tokens=
                                           ctypes.byref(t), res.data_ptr(), _stream(hidden))
     if rc != OK:
         raise ToplocError(rc, "toploc_verify_proofs_mixed")
+    return res
+
+
+def _segments_any(hidden, row_offsets):
+    """[total_rows, H] bf16 or fp32 device tensor and row offsets -> (offsets uint64, n_segments, H, dtype code)."""
+    if hidden.dtype not in (torch.bfloat16, torch.float32) or not hidden.is_cuda or not hidden.is_contiguous() or \
+            hidden.dim() != 2:
+        raise ValueError("hidden must be a contiguous [total_rows, H] bf16 or fp32 tensor on the GPU")
+    off = np.ascontiguousarray(row_offsets, dtype=np.uint64)
+    if off.ndim != 1 or off.size < 1 or int(off[-1]) > hidden.shape[0]:
+        raise ValueError("row_offsets must be a 1-D array of n_segments + 1 row numbers inside the tensor")
+    return off, off.size - 1, hidden.shape[1], (DTYPE_F32 if hidden.dtype == torch.float32 else DTYPE_BF16)
+
+
+def toploc_segments_workspace_bytes_dtype(row_offsets, hidden_size, k, hidden_dtype):
+    off = np.ascontiguousarray(row_offsets, dtype=np.uint64)
+    return int(lib().toploc_segments_workspace_bytes_dtype(off.ctypes.data_as(ctypes.c_void_p), off.size - 1, hidden_size,
+                                                           k, hidden_dtype))
+
+
+def toploc_build_proofs_segments_f32(hidden, row_offsets, k=128, want_topk=False):
+    """Algorithm 1 over segments of fp32 rows. Returns (proofs uint8 [n_segments, 2+4k], status[, idx])."""
+    off, n_seg, h, dt = _segments_any(hidden, row_offsets)
+    if dt != DTYPE_F32:
+        raise ValueError("hidden must be fp32")
+    dev = hidden.device
+    proofs = torch.empty((n_seg, 2 + 4 * k), dtype=torch.uint8, device=dev)
+    status = torch.empty(n_seg, dtype=torch.uint8, device=dev)
+    idx = torch.empty((n_seg, k), dtype=torch.int32, device=dev) if want_topk else None
+    ws = torch.empty(max(16, toploc_segments_workspace_bytes_dtype(off, h, k, dt)), dtype=torch.uint8, device=dev)
+    rc = lib().toploc_build_proofs_segments_f32(
+        hidden.data_ptr(), off.ctypes.data_as(ctypes.c_void_p), n_seg, h, k, proofs.data_ptr(), status.data_ptr(),
+        idx.data_ptr() if want_topk else None, ws.data_ptr(), ws.numel(), _stream(hidden))
+    if rc != OK:
+        raise ToplocError(rc, "toploc_build_proofs_segments_f32")
+    return (proofs, status, idx) if want_topk else (proofs, status)
+
+
+def toploc_verify_proofs_segments_mixed(hidden, row_offsets, proofs, proof_dtype, k=128, thresholds=None):
+    """Algorithm 2 over segments with bf16 or fp32 activations and bf16 or fp32 proofs; thresholds default to
+    the paper's for the validator's precision. Returns a uint8 device tensor [n_segments, 20]."""
+    off, n_seg, h, dt = _segments_any(hidden, row_offsets)
+    pb = 2 + (4 if proof_dtype == DTYPE_F32 else 2) * k
+    if proofs.dtype != torch.uint8 or not proofs.is_cuda or not proofs.is_contiguous() or proofs.numel() != n_seg * pb:
+        raise ValueError("proofs must be a contiguous uint8 device tensor of n_segments proofs of proof_dtype")
+    if thresholds is None:
+        thresholds = F32_THRESHOLDS if dt == DTYPE_F32 else BF16_THRESHOLDS
+    t = Thresholds(*thresholds)
+    res = torch.empty((n_seg, RESULT_DTYPE.itemsize), dtype=torch.uint8, device=hidden.device)
+    ws = torch.empty(max(16, toploc_segments_workspace_bytes_dtype(off, h, k, dt)), dtype=torch.uint8,
+                     device=hidden.device)
+    rc = lib().toploc_verify_proofs_segments_mixed(
+        hidden.data_ptr(), dt, off.ctypes.data_as(ctypes.c_void_p), n_seg, h, k, proofs.data_ptr(), proof_dtype,
+        ctypes.byref(t), res.data_ptr(), ws.data_ptr(), ws.numel(), _stream(hidden))
+    if rc != OK:
+        raise ToplocError(rc, "toploc_verify_proofs_segments_mixed")
     return res
 
 

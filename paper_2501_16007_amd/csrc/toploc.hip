@@ -202,12 +202,12 @@ constexpr uint64_t kShortLaunchGroups = 6 * 5 * 256;  // fewer than about six ge
 // Split path, first launch: top-k of one part.  Writes k candidate slots per part,
 // the unused ones (part shorter than k values) padded with index 0xFFFFFFFF.
 // ---------------------------------------------------------------------------
-template <int CAP>
+template <int CAP, typename Fmt = Bf16Fmt>
 __global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void part_kernel(const u32x4* __restrict__ hidden, Layout lay,
                                                                           uint32_t k, uint32_t* __restrict__ c_idx,
-                                                                          uint16_t* __restrict__ c_bits)
+                                                                          typename Fmt::bits_t* __restrict__ c_bits)
 {
-    __shared__ SelectShared<kThreads, CAP, kQcap> s;
+    __shared__ SelectShared<kThreads, CAP, kQcap, Fmt> s;
     const uint32_t tid = threadIdx.x;
     const uint64_t slot = blockIdx.x;
     const u32x4* src;
@@ -225,12 +225,12 @@ __global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void part_kernel(const 
         v1 = v0 + lay.part_vecs < lay.nvec ? v0 + lay.part_vecs : lay.nvec;
         if (v0 > v1) v0 = v1;
     }
-    const uint32_t have = (v1 - v0) * 8u;
+    const uint32_t have = (v1 - v0) * (uint32_t)Fmt::ELEMS;
     const uint32_t k_eff = have < k ? have : k;
-    if (k_eff) select_topk<kThreads, kLoads, CAP, kQcap>(src, v0, v1, k_eff, s);
+    if (k_eff) select_topk<kThreads, kLoads>(src, v0, v1, k_eff, s);
     for (uint32_t t = tid; t < k; t += kThreads) {
         c_idx[slot * k + t] = t < k_eff ? s.cand_idx[t] : 0xFFFFFFFFu;
-        c_bits[slot * k + t] = t < k_eff ? s.cand_bits[t] : (uint16_t)0;
+        c_bits[slot * k + t] = t < k_eff ? s.cand_bits[t] : (typename Fmt::bits_t)0;
     }
 }
 
@@ -251,16 +251,16 @@ __device__ __forceinline__ void merge_range(const Layout& lay, uint64_t unit, ui
 // Split path, second launch of a build: top-k of the candidates, then the rest of
 // Algorithm 1 (interp.hpp).
 // ---------------------------------------------------------------------------
-template <int THREADS, int KMAX, int CAP>
+template <int THREADS, int KMAX, int CAP, typename F = Field16, typename Fmt = Bf16Fmt>
 __global__ __launch_bounds__(THREADS) void build_merge_kernel(Layout lay, uint32_t k, const uint32_t* __restrict__ c_idx,
-                                                              const uint16_t* __restrict__ c_bits,
+                                                              const typename Fmt::bits_t* __restrict__ c_bits,
                                                               uint8_t* __restrict__ proofs, uint8_t* __restrict__ status,
                                                               uint32_t* __restrict__ out_idx)
 {
     static_assert(KMAX <= THREADS, "one pair per lane is carried across the phase change");
     __shared__ union MergeShared {
-        SelectShared<THREADS, CAP, 1> sel;
-        InterpShared<KMAX> itp;
+        SelectShared<THREADS, CAP, 1, Fmt> sel;
+        InterpShared<KMAX, F> itp;
     } sh;
     __shared__ uint32_t coef[KMAX];
     const uint32_t tid = threadIdx.x;
@@ -278,32 +278,32 @@ __global__ __launch_bounds__(THREADS) void build_merge_kernel(Layout lay, uint32
     __syncthreads();
     if (tid < k) {
         sh.itp.idx[tid] = my_idx;
-        sh.itp.ys[tid] = (uint16_t)(my_y >= kPrime ? my_y - kPrime : my_y);
+        sh.itp.ys[tid] = (typename F::elem_t)F::from_pattern(my_y);
     }
-    finish_proof<THREADS>(sh.itp, coef, k, reinterpret_cast<uint16_t*>(proofs + unit * (2 + 2 * (uint64_t)k)),
-                                status + unit);
+    finish_proof<THREADS>(sh.itp, coef, k,
+                          reinterpret_cast<uint16_t*>(proofs + unit * (2 + 2 * (uint64_t)F::WORDS * k)), status + unit);
 }
 
 // ---------------------------------------------------------------------------
 // Split path, second launch of a verify: top-k of the candidates, then the rest of
 // Algorithm 2 (verify.hpp).
 // ---------------------------------------------------------------------------
-template <int THREADS, int KMAX, int CAP>
+template <int THREADS, int KMAX, int CAP, typename F = Field16, typename Fmt = Bf16Fmt>
 __global__ __launch_bounds__(THREADS) void verify_merge_kernel(Layout lay, uint32_t k, const uint32_t* __restrict__ c_idx,
-                                                               const uint16_t* __restrict__ c_bits,
+                                                               const typename Fmt::bits_t* __restrict__ c_bits,
                                                                const uint8_t* __restrict__ proofs, toploc_thresholds thr,
                                                                toploc_verify_result* __restrict__ results)
 {
-    __shared__ SelectShared<THREADS, CAP, 1> s;
-    __shared__ VerifyShared<KMAX> vs;
+    __shared__ SelectShared<THREADS, CAP, 1, Fmt> s;
+    __shared__ VerifyShared<KMAX, Fmt::ELEMS == 4> vs;
     const uint64_t unit = blockIdx.x;
-    const uint16_t* proof = reinterpret_cast<const uint16_t*>(proofs + unit * (2 + 2 * (uint64_t)k));
-    if (!verify_decode<THREADS, Field16>(vs, proof, k, results + unit)) return;
+    const uint16_t* proof = reinterpret_cast<const uint16_t*>(proofs + unit * (2 + 2 * (uint64_t)F::WORDS * k));
+    if (!verify_decode<THREADS, F>(vs, proof, k, results + unit)) return;
     uint64_t first;
     uint32_t n_parts;
     merge_range(lay, unit, first, n_parts);
     merge_topk(c_idx + first * k, c_bits + first * k, n_parts * k, k, s);
-    verify_tail<THREADS, Field16, Bf16Fmt>(vs, s.cand_idx, s.cand_bits, k, thr, results + unit);
+    verify_tail<THREADS, F, Fmt>(vs, s.cand_idx, s.cand_bits, k, thr, results + unit);
 }
 
 // ---------------------------------------------------------------------------
@@ -580,16 +580,24 @@ static uint64_t pick_part_vecs(uint64_t total_vecs, uint64_t max_unit_vecs, uint
     return clamp_part_vecs((total_vecs + groups - 1) / groups);
 }
 
-// candidate arrays for `slots` parts: [slots*k] uint32 then [slots*k] uint16, each 16-byte aligned
-static size_t cand_bytes(uint64_t slots, uint32_t k)
+// candidate arrays for `slots` parts: [slots*k] uint32 indices, then [slots*k] patterns of
+// `bits_size` bytes (2: bf16, 4: fp32), each array 16-byte aligned
+static size_t cand_bytes(uint64_t slots, uint32_t k, size_t bits_size = sizeof(uint16_t))
 {
-    return up16((size_t)slots * k * sizeof(uint32_t)) + up16((size_t)slots * k * sizeof(uint16_t));
+    return up16((size_t)slots * k * sizeof(uint32_t)) + up16((size_t)slots * k * bits_size);
 }
+static size_t bits_size_of(uint32_t dtype) { return dtype == TOPLOC_DTYPE_F32 ? sizeof(uint32_t) : sizeof(uint16_t); }
 
 static void launch_part(hipStream_t st, const void* d_hidden, const Layout& lay, uint64_t slots, uint32_t k, uint32_t* c_idx,
-                        uint16_t* c_bits)
+                        void* c_bits_any, uint32_t hidden_dtype = TOPLOC_DTYPE_BF16)
 {
     ProfScope ps(TOPLOC_KERNEL_PART, st);
+    if (hidden_dtype == TOPLOC_DTYPE_F32) {  // k <= TOPLOC_MAX_K_F32
+        hipLaunchKernelGGL((part_kernel<kCapSmall, F32Fmt>), dim3((uint32_t)slots), dim3(kThreads), 0, st,
+                           (const u32x4*)d_hidden, lay, k, c_idx, (uint32_t*)c_bits_any);
+        return;
+    }
+    uint16_t* c_bits = (uint16_t*)c_bits_any;
     if (k <= 128)
         hipLaunchKernelGGL((part_kernel<kCapSmall>), dim3((uint32_t)slots), dim3(kThreads), 0, st, (const u32x4*)d_hidden, lay,
                            k, c_idx, c_bits);
@@ -599,9 +607,16 @@ static void launch_part(hipStream_t st, const void* d_hidden, const Layout& lay,
 }
 
 static void launch_build_merge(hipStream_t st, const Layout& lay, uint64_t units, uint32_t k, const uint32_t* c_idx,
-                               const uint16_t* c_bits, uint8_t* d_proofs, uint8_t* d_status, uint32_t* d_topk_idx_opt)
+                               const void* c_bits_any, uint8_t* d_proofs, uint8_t* d_status, uint32_t* d_topk_idx_opt,
+                               uint32_t dtype = TOPLOC_DTYPE_BF16)
 {
     ProfScope ps(TOPLOC_KERNEL_BUILD_MERGE, st);
+    if (dtype == TOPLOC_DTYPE_F32) {  // k <= TOPLOC_MAX_K_F32
+        hipLaunchKernelGGL((build_merge_kernel<256, 128, kCapSmall, Field32, F32Fmt>), dim3((uint32_t)units), dim3(256), 0, st,
+                           lay, k, c_idx, (const uint32_t*)c_bits_any, d_proofs, d_status, d_topk_idx_opt);
+        return;
+    }
+    const uint16_t* c_bits = (const uint16_t*)c_bits_any;
     if (k <= 128)
         hipLaunchKernelGGL((build_merge_kernel<256, 128, kCapSmall>), dim3((uint32_t)units), dim3(256), 0, st, lay, k, c_idx,
                            c_bits, d_proofs, d_status, d_topk_idx_opt);
@@ -611,10 +626,28 @@ static void launch_build_merge(hipStream_t st, const Layout& lay, uint64_t units
 }
 
 static void launch_verify_merge(hipStream_t st, const Layout& lay, uint64_t units, uint32_t k, const uint32_t* c_idx,
-                                const uint16_t* c_bits, const uint8_t* d_proofs, const toploc_thresholds& thr,
-                                toploc_verify_result* d_results)
+                                const void* c_bits_any, const uint8_t* d_proofs, const toploc_thresholds& thr,
+                                toploc_verify_result* d_results, uint32_t hidden_dtype = TOPLOC_DTYPE_BF16,
+                                uint32_t proof_dtype = TOPLOC_DTYPE_BF16)
 {
     ProfScope ps(TOPLOC_KERNEL_VERIFY_MERGE, st);
+    const dim3 grid((uint32_t)units), block(256);
+    if (hidden_dtype == TOPLOC_DTYPE_F32 && proof_dtype == TOPLOC_DTYPE_F32) {
+        hipLaunchKernelGGL((verify_merge_kernel<256, 128, kCapSmall, Field32, F32Fmt>), grid, block, 0, st, lay, k, c_idx,
+                           (const uint32_t*)c_bits_any, d_proofs, thr, d_results);
+        return;
+    }
+    if (hidden_dtype == TOPLOC_DTYPE_F32) {  // bf16 proof, fp32 validator
+        hipLaunchKernelGGL((verify_merge_kernel<256, 128, kCapSmall, Field16, F32Fmt>), grid, block, 0, st, lay, k, c_idx,
+                           (const uint32_t*)c_bits_any, d_proofs, thr, d_results);
+        return;
+    }
+    const uint16_t* c_bits = (const uint16_t*)c_bits_any;
+    if (proof_dtype == TOPLOC_DTYPE_F32) {   // fp32 proof, bf16 validator
+        hipLaunchKernelGGL((verify_merge_kernel<256, 128, kCapSmall, Field32, Bf16Fmt>), grid, block, 0, st, lay, k, c_idx,
+                           c_bits, d_proofs, thr, d_results);
+        return;
+    }
     if (k <= 128)
         hipLaunchKernelGGL((verify_merge_kernel<256, 128, kCapSmall>), dim3((uint32_t)units), dim3(256), 0, st, lay, k, c_idx,
                            c_bits, d_proofs, thr, d_results);
@@ -629,11 +662,12 @@ struct SegPlan {
     std::vector<SegDesc> segs;
     bool ok = false;
 };
-static SegPlan plan_segments(const uint64_t* h_row_offsets, uint64_t n_segments, uint32_t hidden, uint32_t k)
+static SegPlan plan_segments(const uint64_t* h_row_offsets, uint64_t n_segments, uint32_t hidden, uint32_t k,
+                             uint32_t hidden_dtype = TOPLOC_DTYPE_BF16, uint32_t k_max = TOPLOC_MAX_K)
 {
     SegPlan pl;
-    if (!h_row_offsets || hidden == 0 || hidden % 8 != 0 || k == 0 || k > TOPLOC_MAX_K || n_segments >= (1ull << 31)) return pl;
-    const uint64_t hv = hidden / 8;
+    if (!h_row_offsets || hidden == 0 || hidden % 8 != 0 || k == 0 || k > k_max || n_segments >= (1ull << 31)) return pl;
+    const uint64_t hv = hidden / (hidden_dtype == TOPLOC_DTYPE_F32 ? 4 : 8);  // 16-byte vectors per row
     uint64_t max_vecs = 0;
     for (uint64_t i = 0; i < n_segments; ++i) {
         if (h_row_offsets[i + 1] < h_row_offsets[i]) return pl;
@@ -663,19 +697,21 @@ static SegPlan plan_segments(const uint64_t* h_row_offsets, uint64_t n_segments,
     return pl;
 }
 
-static size_t seg_workspace_bytes(const SegPlan& pl, uint32_t k)
+static size_t seg_workspace_bytes(const SegPlan& pl, uint32_t k, size_t bits_size = sizeof(uint16_t))
 {
-    return cand_bytes(pl.parts.size(), k) + up16(pl.parts.size() * sizeof(PartDesc)) + up16(pl.segs.size() * sizeof(SegDesc));
+    return cand_bytes(pl.parts.size(), k, bits_size) + up16(pl.parts.size() * sizeof(PartDesc)) +
+           up16(pl.segs.size() * sizeof(SegDesc));
 }
 
 // copies the tables behind the candidate arrays and fills the layout
+template <typename Bits>
 static bool stage_segments(const SegPlan& pl, uint32_t k, void* d_workspace, hipStream_t st, Layout& lay, uint32_t*& c_idx,
-                           uint16_t*& c_bits)
+                           Bits*& c_bits)
 {
     char* w = (char*)d_workspace;
     c_idx = (uint32_t*)w;
-    c_bits = (uint16_t*)(w + up16(pl.parts.size() * (size_t)k * sizeof(uint32_t)));
-    char* t_parts = w + cand_bytes(pl.parts.size(), k);
+    c_bits = (Bits*)(w + up16(pl.parts.size() * (size_t)k * sizeof(uint32_t)));
+    char* t_parts = w + cand_bytes(pl.parts.size(), k, sizeof(Bits));
     char* t_segs = t_parts + up16(pl.parts.size() * sizeof(PartDesc));
     if (!hip_ok(hipMemcpyAsync(t_parts, pl.parts.data(), pl.parts.size() * sizeof(PartDesc), hipMemcpyHostToDevice, st)))
         return false;
@@ -928,6 +964,79 @@ int toploc_verify_proofs_mixed(const void* d_hidden, uint32_t hidden_dtype, uint
             hipLaunchKernelGGL((verify_kernel<128, kCapSmall, Field32, Bf16Fmt>), grid, block, 0, st, h, (uint32_t)(n / 8), k,
                                d_proofs, *thresholds, d_results);
     }
+    return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
+}
+
+// k limit and table plan of the segment calls that involve fp32
+static SegPlan plan_segments_mixed(const uint64_t* h_row_offsets, uint64_t n_segments, uint32_t hidden, uint32_t k,
+                                   uint32_t hidden_dtype, uint32_t proof_dtype)
+{
+    if (hidden_dtype > TOPLOC_DTYPE_F32 || proof_dtype > TOPLOC_DTYPE_F32) return SegPlan();
+    const bool any32 = hidden_dtype == TOPLOC_DTYPE_F32 || proof_dtype == TOPLOC_DTYPE_F32;
+    return plan_segments(h_row_offsets, n_segments, hidden, k, hidden_dtype, any32 ? TOPLOC_MAX_K_F32 : TOPLOC_MAX_K);
+}
+
+size_t toploc_segments_workspace_bytes_dtype(const uint64_t* h_row_offsets, uint64_t n_segments, uint32_t hidden,
+                                             uint32_t k, uint32_t hidden_dtype)
+{
+    const SegPlan pl = plan_segments_mixed(h_row_offsets, n_segments, hidden, k, hidden_dtype, hidden_dtype);
+    if (!pl.ok || n_segments == 0) return 0;
+    return seg_workspace_bytes(pl, k, bits_size_of(hidden_dtype));
+}
+
+int toploc_build_proofs_segments_f32(const void* d_hidden_f32, const uint64_t* h_row_offsets, uint64_t n_segments,
+                                     uint32_t hidden, uint32_t k, uint8_t* d_proofs, uint8_t* d_status,
+                                     uint32_t* d_topk_idx_opt, void* d_workspace, size_t workspace_bytes,
+                                     void* hip_stream)
+{
+    const SegPlan pl = plan_segments_mixed(h_row_offsets, n_segments, hidden, k, TOPLOC_DTYPE_F32, TOPLOC_DTYPE_F32);
+    if (!pl.ok) return TOPLOC_EINVAL;
+    if (n_segments == 0) return TOPLOC_OK;
+    if (!d_hidden_f32 || !d_proofs || !d_status || !d_workspace || !aligned16(d_hidden_f32) || !aligned16(d_workspace))
+        return TOPLOC_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(d_proofs) & 1u) != 0) return TOPLOC_EINVAL;
+    if (workspace_bytes < seg_workspace_bytes(pl, k, sizeof(uint32_t))) return TOPLOC_EWORKSPACE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    Layout lay;
+    uint32_t* c_idx;
+    uint32_t* c_bits;
+    if (!stage_segments(pl, k, d_workspace, st, lay, c_idx, c_bits)) return TOPLOC_EHIP;
+    launch_part(st, d_hidden_f32, lay, pl.parts.size(), k, c_idx, c_bits, TOPLOC_DTYPE_F32);
+    if (!hip_ok(hipGetLastError())) return TOPLOC_EHIP;
+    launch_build_merge(st, lay, n_segments, k, c_idx, c_bits, d_proofs, d_status, d_topk_idx_opt, TOPLOC_DTYPE_F32);
+    return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
+}
+
+int toploc_verify_proofs_segments_mixed(const void* d_hidden, uint32_t hidden_dtype, const uint64_t* h_row_offsets,
+                                        uint64_t n_segments, uint32_t hidden, uint32_t k, const uint8_t* d_proofs,
+                                        uint32_t proof_dtype, const toploc_thresholds* thresholds,
+                                        toploc_verify_result* d_results, void* d_workspace, size_t workspace_bytes,
+                                        void* hip_stream)
+{
+    const SegPlan pl = plan_segments_mixed(h_row_offsets, n_segments, hidden, k, hidden_dtype, proof_dtype);
+    if (!pl.ok || !thresholds) return TOPLOC_EINVAL;
+    if (n_segments == 0) return TOPLOC_OK;
+    if (!d_hidden || !d_proofs || !d_results || !d_workspace || !aligned16(d_hidden) || !aligned16(d_workspace))
+        return TOPLOC_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(d_proofs) & 1u) != 0 || (reinterpret_cast<uintptr_t>(d_results) & 3u) != 0)
+        return TOPLOC_EINVAL;
+    if (workspace_bytes < seg_workspace_bytes(pl, k, bits_size_of(hidden_dtype))) return TOPLOC_EWORKSPACE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    Layout lay;
+    uint32_t* c_idx;
+    void* c_bits;
+    if (hidden_dtype == TOPLOC_DTYPE_F32) {
+        uint32_t* b32;
+        if (!stage_segments(pl, k, d_workspace, st, lay, c_idx, b32)) return TOPLOC_EHIP;
+        c_bits = b32;
+    } else {
+        uint16_t* b16;
+        if (!stage_segments(pl, k, d_workspace, st, lay, c_idx, b16)) return TOPLOC_EHIP;
+        c_bits = b16;
+    }
+    launch_part(st, d_hidden, lay, pl.parts.size(), k, c_idx, c_bits, hidden_dtype);
+    if (!hip_ok(hipGetLastError())) return TOPLOC_EHIP;
+    launch_verify_merge(st, lay, n_segments, k, c_idx, c_bits, d_proofs, *thresholds, d_results, hidden_dtype, proof_dtype);
     return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
 }
 

@@ -150,3 +150,74 @@ def test_f32_full_size_sampled():
     o_proofs, o_status, o_idx = orc.build32(synth.bits_numpy(chunks[selt]), 128, want_topk=True)
     assert np.array_equal(proofs[selt].cpu().numpy(), o_proofs)
     assert np.array_equal(idx[selt].cpu().numpy().view(np.uint32), o_idx)
+
+
+def _to_bf16_model(x32):
+    """What a bf16 run of the same model would hold: the fp32 activations rounded to bf16."""
+    return x32.to(torch.bfloat16)
+
+
+@pytest.mark.parametrize("hidden,rows,k,parts", [
+    (4096, [100, 32, 32, 7], 128, 0),      # prompt, two full chunks, a ragged last chunk
+    (1024, [64, 9, 33, 1], 64, 0),
+    (8, [1, 2, 5], 8, 0),                  # the smallest rows: two vectors each
+    (4096, [300, 5], 128, 5),              # forced cuts: parts of unequal length, ties across borders by chance
+    (5120, [40, 32], 32, 1),
+])
+def test_f32_segments_build_and_the_four_precision_pairs(hidden, rows, k, parts):
+    """Segments of unequal length with fp32 activations: proofs, status, indices and the verify records of all
+    four validator/proof precision pairs equal the oracle's, which sees every segment as one flat array."""
+    total = int(sum(rows))
+    say("f32 segments H=%d rows=%s k=%d parts=%d" % (hidden, rows, k, parts))
+    x32 = synth.activations(1, total, hidden, 9300 + hidden + k, n_outlier=min(8, hidden), device=DEV,
+                            dtype=torch.float32).reshape(total, hidden)
+    x16 = _to_bf16_model(x32)
+    off = np.concatenate([[0], np.cumsum(rows)]).astype(np.uint64)
+    b32, b16 = synth.bits_numpy(x32), synth.bits_numpy(x16)
+    try:
+        tl.toploc_set_split(parts)
+        proofs32, status32, idx32 = tl.toploc_build_proofs_segments_f32(x32, off, k=k, want_topk=True)
+        proofs16, status16 = tl.toploc_build_proofs_segments(x16, off, k=k)
+        torch.cuda.synchronize()
+        o32 = np.zeros((len(rows), 2 + 4 * k), dtype=np.uint8)
+        o16 = np.zeros((len(rows), 2 + 2 * k), dtype=np.uint8)
+        for i in range(len(rows)):
+            a, b = int(off[i]), int(off[i + 1])
+            p, st, ix = orc.build32(b32[a:b].reshape(1, -1), k, want_topk=True)
+            assert np.array_equal(idx32[i].cpu().numpy().view(np.uint32), ix[0]), "segment %d indices" % i
+            assert int(status32[i]) == int(st[0]) and np.array_equal(proofs32[i].cpu().numpy(), p[0]), "segment %d" % i
+            o32[i] = p[0]
+            o16[i] = orc.build(b16[a:b].reshape(1, -1), k)[0][0]
+        assert np.array_equal(proofs16.cpu().numpy(), o16)
+        # a recomputation that differs a little, in both precisions
+        r32 = x32 * (1.0 + 2.0 ** -12 * torch.sin(torch.arange(hidden, device=DEV, dtype=torch.float32)))
+        r16 = _to_bf16_model(r32)
+        for rec, rbits, h_dt in ((r32, synth.bits_numpy(r32), orc.F32), (r16, synth.bits_numpy(r16), orc.BF16)):
+            for p_np, p_dt in ((o32, orc.F32), (o16, orc.BF16)):
+                res = tl.toploc_verify_proofs_segments_mixed(rec, off, torch.from_numpy(p_np).to(DEV), p_dt, k=k)
+                torch.cuda.synchronize()
+                g = tl.results_numpy(res)
+                for i in range(len(rows)):
+                    a, b = int(off[i]), int(off[i + 1])
+                    o = orc.verify_mixed(rbits[a:b].reshape(1, -1), h_dt, p_np[i:i + 1], p_dt, k)
+                    for f in FIELDS:
+                        assert g[f][i] == o[f][0], "validator %d proof %d segment %d field %s: gpu %s oracle %s" % (
+                            h_dt, p_dt, i, f, g[f][i], o[f][0])
+    finally:
+        tl.toploc_set_split(0)
+
+
+def test_f32_segments_equal_fixed_chunks_and_reject_bad_arguments():
+    x = f32_chunks(4, 1024, 32, 9400).reshape(4 * 32, 1024)
+    off = np.arange(5, dtype=np.uint64) * 32
+    p_seg, s_seg, i_seg = tl.toploc_build_proofs_segments_f32(x, off, k=128, want_topk=True)
+    p_fix, s_fix, i_fix = tl.toploc_build_proofs_f32(x.reshape(4, -1), k=128, chunk_tokens=1, want_topk=True)
+    torch.cuda.synchronize()
+    assert torch.equal(p_seg, p_fix) and torch.equal(s_seg, s_fix) and torch.equal(i_seg, i_fix)
+    with pytest.raises(tl.ToplocError):
+        tl.toploc_build_proofs_segments_f32(x, off, k=129)                       # k above the fp32 limit
+    with pytest.raises(tl.ToplocError):
+        tl.toploc_verify_proofs_segments_mixed(x.to(torch.bfloat16), off,
+                                               torch.zeros((4, 2 + 4 * 256), dtype=torch.uint8, device=DEV), orc.F32, k=256)
+    assert tl.toploc_segments_workspace_bytes_dtype(off, 1024, 128, tl.DTYPE_F32) > \
+        tl.toploc_segments_workspace_bytes_dtype(off, 1024, 128, tl.DTYPE_BF16) > 0
