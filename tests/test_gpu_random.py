@@ -101,6 +101,18 @@ def test_random_case(seed):
     p_st, s_st = tl.toploc_stream_emit(state, n_chunks, k=k)
     torch.cuda.synchronize()
     assert np.array_equal(p_st.cpu().numpy(), o_proofs) and np.array_equal(s_st.cpu().numpy(), o_status), what + ": stream"
+    # the same rows through the indexed calls: slots in a random order, each row at its own token
+    state = tl.toploc_stream_new_state(n_chunks + 2, k, DEV)
+    slot_of = rng.permutation(n_chunks + 2)[:n_chunks]            # chunk c lives in slot slot_of[c]
+    step = max(1, n_chunks // 2)                                   # a few rows per call, distinct slots in each
+    for t in range(tokens):
+        for c0 in range(0, n_chunks, step):
+            cs = list(range(c0, min(n_chunks, c0 + step)))
+            tl.toploc_stream_append_rows(state, n_chunks + 2, rows[t][cs].contiguous(), slot_of[cs],
+                                         np.full(len(cs), t), k=k, chunk_tokens=tokens)
+    p_ix, s_ix = tl.toploc_stream_emit_rows(state, n_chunks + 2, slot_of, k=k)
+    torch.cuda.synchronize()
+    assert np.array_equal(p_ix.cpu().numpy(), o_proofs) and np.array_equal(s_ix.cpu().numpy(), o_status), what + ": rows"
 
 
 @pytest.mark.parametrize("seed", range(max(12, N_CASES // 3)))
@@ -139,3 +151,18 @@ def test_random_case_f32(seed):
         g = tl.toploc_verify_proofs_mixed(synth.from_bits(h_bits, DEV), torch.from_numpy(p).to(DEV), p_dt, k=k, chunk_tokens=1)
         torch.cuda.synchronize()
         compare(tl.results_numpy(g), o, what + " validator %d proof %d" % (h_dt, p_dt))
+    # whole chunks as segments of one fp32 matrix, cut into a random number of parts
+    if hidden % 8 == 0:
+        off = np.arange(n_chunks + 1, dtype=np.uint64) * tokens
+        parts = int(rng.choice([0, 1, 2, 5]))
+        try:
+            tl.toploc_set_split(parts)
+            p_seg, s_seg = tl.toploc_build_proofs_segments_f32(chunks.reshape(n_chunks * tokens, hidden), off, k=k)
+            r_seg = tl.toploc_verify_proofs_segments_mixed(synth.from_bits(rec_bits, DEV).reshape(n_chunks * tokens, hidden),
+                                                           off, torch.from_numpy(o_proofs).to(DEV), orc.F32, k=k)
+            torch.cuda.synchronize()
+        finally:
+            tl.toploc_set_split(0)
+        assert np.array_equal(p_seg.cpu().numpy(), o_proofs) and np.array_equal(s_seg.cpu().numpy(), o_status), \
+            what + ": segments, parts=%d" % parts
+        compare(tl.results_numpy(r_seg), orc.verify_mixed(rec_bits, orc.F32, o_proofs, orc.F32, k), what + " segments")
