@@ -251,3 +251,72 @@ def test_malformed_proofs():
     bad[0, 0], bad[0, 1] = 0x00, 0x40                                      # m = 16384
     res = orc.verify_mixed(bits, orc.F32, bad, orc.F32, 16)
     assert res["status"][0] == orc.EMALFORMED and res["accept"][0] == 0
+
+
+def brute_verify_mixed(bits, h_dtype, proof, p_dtype, thresholds):
+    """Algorithm 2 across precisions on one small chunk in Python integers: decode, top-k by repeated
+    arg-max, the polynomial by its definition (sum of c_d x^d), fields by shifts, the mantissa brought to
+    the validator's width, sorted lower median."""
+    width = 4 if p_dtype == orc.F32 else 2
+    M = P32 if p_dtype == orc.F32 else 65497
+    m = int(proof[0]) | (int(proof[1]) << 8)
+    m = m if m else 65536
+    k = (len(proof) - 2) // width
+    c = [int.from_bytes(bytes(proof[2 + width * j: 2 + width * (j + 1)].tolist()), "little") for j in range(k)]
+    mask = 0x7FFFFFFF if h_dtype == orc.F32 else 0x7FFF
+    err_e, err_m = 0, []
+    for i in brute_topk(bits, k, mask):
+        x = (i % m) % M
+        val = sum(cd * pow(x, d, M) for d, cd in enumerate(c)) % M
+        if p_dtype == orc.F32:
+            e_p, m_p = (val >> 23) & 0xFF, val & 0x7FFFFF
+        else:
+            e_p, m_p = (val >> 7) & 0xFF, val & 0x7F
+        v = int(bits[i])
+        if h_dtype == orc.F32:
+            e_v, m_v = (v >> 23) & 0xFF, v & 0x7FFFFF
+        else:
+            e_v, m_v = (v >> 7) & 0xFF, v & 0x7F
+        if p_dtype == orc.F32 and h_dtype == orc.BF16:
+            m_p >>= 16                                   # 23 bits scaled to 7
+        if p_dtype == orc.BF16 and h_dtype == orc.F32:
+            m_p <<= 16                                   # 16 zero bits appended
+        if e_p == e_v:
+            err_m.append(abs(m_p - m_v))
+        else:
+            err_e += 1
+    n = len(err_m)
+    median = sorted(err_m)[(n - 1) // 2] if n else 0
+    t_exp, t_mean, t_median = thresholds
+    reject = err_e > t_exp or (n > 0 and (sum(err_m) > t_mean * n or median > t_median))
+    return {"err_exp": err_e, "n_match": n, "mant_sum": sum(err_m), "mant_median": median, "accept": 0 if reject else 1}
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_validation_equals_brute_force_in_all_four_precision_pairs(seed):
+    rng = np.random.default_rng(5200 + seed)
+    n = int(rng.choice([32, 96, 256]))
+    k = int(rng.choice([4, 12, 25]))
+    x = (rng.standard_normal(n) * 3.0).astype(np.float32)
+    b32 = x.view(np.uint32).copy()
+    b16 = (b32 >> 16).astype(np.uint16)
+    p32, st32 = orc.build32(b32[None, :], k)
+    p16, st16 = orc.build(b16[None, :], k)
+    assert st32[0] == 0 and st16[0] == 0
+    # a recomputation: low mantissa bits move everywhere, a few exponents step, a few entries change hands
+    r32 = b32.copy()
+    r32 ^= rng.integers(0, 1 << 19, size=n, dtype=np.uint64).astype(np.uint32) * (rng.random(n) < 0.6)
+    step = rng.choice(n, size=max(1, n // 16), replace=False)
+    r32[step] += np.uint32(1 << 23)
+    swap = rng.choice(n, size=2, replace=False)
+    r32[swap] = r32[swap[::-1]]
+    r16 = (r32 >> 16).astype(np.uint16)
+    for rbits, h_dt in ((r32, orc.F32), (r16, orc.BF16)):
+        for proof, p_dt in ((p32[0], orc.F32), (p16[0], orc.BF16)):
+            hi = 1 << 18 if h_dt == orc.F32 else 12
+            thresholds = (int(rng.integers(0, k)), int(rng.integers(0, hi)), int(rng.integers(0, hi)))
+            got = orc.verify_mixed(rbits[None, :], h_dt, proof[None, :], p_dt, k, thresholds=thresholds)[0]
+            want = brute_verify_mixed(rbits, h_dt, proof, p_dt, thresholds)
+            for f, v in want.items():
+                assert int(got[f]) == v, (h_dt, p_dt, f, int(got[f]), v)
+            assert got["status"] == 0 and want["err_exp"] + want["n_match"] == k

@@ -456,6 +456,53 @@ def test_threshold_strictness_and_median_rule():
     assert orc.decide(4, [], (3, 0, 0))["accept"] == 0
 
 
+def brute_verify(bits, proof, thresholds):
+    """Algorithm 2 on one small chunk in Python integers: decode, top-k by repeated arg-max, the
+    polynomial evaluated by its definition (sum of c_d x^d, no Horner), fields by shifts, sorted median."""
+    m, c = decode(proof)
+    k = len(c)
+    err_e, err_m = 0, []
+    for i in brute_topk([int(b) for b in bits], k):
+        x = (i % m) % P
+        val = poly_eval(c, x, P)
+        e_p, m_p = (val >> 7) & 0xFF, val & 0x7F
+        e_v, m_v = (int(bits[i]) >> 7) & 0xFF, int(bits[i]) & 0x7F
+        if e_p == e_v:
+            err_m.append(abs(m_p - m_v))
+        else:
+            err_e += 1
+    n = len(err_m)
+    median = sorted(err_m)[(n - 1) // 2] if n else 0
+    t_exp, t_mean, t_median = thresholds
+    reject = err_e > t_exp or (n > 0 and (sum(err_m) > t_mean * n or median > t_median))
+    return {"err_exp": err_e, "n_match": n, "mant_sum": sum(err_m), "mant_median": median, "accept": 0 if reject else 1}
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_verify_equals_brute_force_on_small_perturbed_chunks(seed):
+    """The whole of Algorithm 2 on inputs where exponents match for some entries and not for others, mantissas
+    differ by several steps, the selected set changes and thresholds sit near the statistics."""
+    rng = np.random.default_rng(2400 + seed)
+    n = int(rng.choice([64, 200, 512]))
+    k = int(rng.choice([4, 16, 33]))
+    h = random_chunk(rng, n)[None, :].copy()
+    proofs, status = orc.build(h, k)
+    assert status[0] == 0
+    h2 = h.copy()
+    touch = rng.random(n) < 0.5
+    delta = rng.integers(-12, 13, size=n)
+    mag = (h2[0].astype(np.int64) & 0x7FFF) + np.where(touch, delta, 0)        # crosses binades now and then
+    h2[0] = (h2[0] & 0x8000) | np.clip(mag, 0, 0x7F7F).astype(np.uint16)
+    swap = rng.choice(n, size=3, replace=False)                                # a few entries change hands
+    h2[0, swap] = h2[0, swap[::-1]]
+    thresholds = (int(rng.integers(0, k)), int(rng.integers(0, 12)), int(rng.integers(0, 12)))
+    got = orc.verify(h2, proofs, k, thresholds=thresholds)[0]
+    want = brute_verify(h2[0], proofs[0], thresholds)
+    for f, v in want.items():
+        assert int(got[f]) == v, (f, int(got[f]), v)
+    assert got["status"] == 0 and want["n_match"] > 0 and want["err_exp"] + want["n_match"] == k
+
+
 def test_independent_tensor_is_rejected_and_statistics_are_in_range():
     rng = np.random.default_rng(24)
     hidden, k = 512, 128
