@@ -80,7 +80,7 @@ def brute_topk(bits, k):
 
 
 def decode(proof):
-    m = proof[0] | (proof[1] << 8)
+    m = int(proof[0]) | (int(proof[1]) << 8)
     m = m if m else 65536
     c = [int(proof[2 + 2 * j]) | (int(proof[3 + 2 * j]) << 8) for j in range((len(proof) - 2) // 2)]
     return m, c
@@ -391,6 +391,29 @@ def test_proof_round_trip(hidden, k):
 # P8: verification identities and the strictness of the three thresholds
 # ---------------------------------------------------------------------------
 
+@pytest.mark.parametrize("seed", range(10))
+def test_build_equals_brute_force_on_small_chunks(seed):
+    """The whole of Algorithm 1 on small chunks: the bytes are the largest injective modulus found by trying
+    every candidate, followed by the Lagrange-sum coefficients through the arg-max top-k, all in Python."""
+    rng = np.random.default_rng(2300 + seed)
+    n = int(rng.choice([16, 64, 300]))
+    k = int(rng.choice([1, 3, 8, 12]))
+    h = random_chunk(rng, n)
+    if seed % 3 == 0:
+        h[rng.integers(0, n, size=n // 2)] = h[0]                       # ties at the boundary
+    if seed % 4 == 1:
+        h = np.concatenate([h, np.zeros(70000, dtype=np.uint16)])        # indices beyond 65536 among the ...
+        h[[65541, 69999, 5]] = np.uint16(0x7F00)                         # ... top-k: 5 and 65541 collide mod 65536
+    proofs, status, idx = orc.build(h[None, :], k, want_topk=True)
+    top = brute_topk([int(b) for b in h], k)
+    assert status[0] == 0 and idx[0].tolist() == top
+    m = next(c for c in range(65536, 32768, -1) if _is_injective(np.array(top), c, P))
+    want = lagrange_coeffs([(i % m) % P for i in top], [int(h[i]) % P for i in top], P)
+    got_m, got_c = decode(proofs[0])
+    assert got_m == m and got_c == want
+    assert len(proofs[0]) == 2 + 2 * k
+
+
 def test_self_verify_accepts_with_zero_statistics():
     rng = np.random.default_rng(21)
     h = np.stack([random_chunk(rng, 32 * 512, hidden=512) for _ in range(4)])
@@ -486,8 +509,13 @@ def test_verify_equals_brute_force_on_small_perturbed_chunks(seed):
     n = int(rng.choice([64, 200, 512]))
     k = int(rng.choice([4, 16, 33]))
     h = random_chunk(rng, n)[None, :].copy()
+    if seed % 4 == 1:      # indices 5 and 65541 collide mod 65536: the proof then carries a smaller modulus
+        h = np.concatenate([h, np.zeros((1, 70000), dtype=np.uint16)], axis=1)
+        h[0, [65541 + n, 5, 69999]] = np.uint16(0x7E00)
+        h[0, 65541] = np.uint16(0x7E40)
+        n = h.shape[1]
     proofs, status = orc.build(h, k)
-    assert status[0] == 0
+    assert status[0] == 0 and (seed % 4 != 1 or decode(proofs[0])[0] < 65536)
     h2 = h.copy()
     touch = rng.random(n) < 0.5
     delta = rng.integers(-12, 13, size=n)
