@@ -124,6 +124,18 @@ def test_thresholds_and_malformed_proofs_in_the_32_bit_field():
     assert o["status"].tolist() == [tl.CHUNK_MALFORMED, tl.CHUNK_MALFORMED, tl.CHUNK_OK]
 
 
+def test_decode_edges_in_the_32_bit_field():
+    chunks = f32_chunks(4, 64, 32, 7300)
+    bits = synth.bits_numpy(chunks)
+    proofs, _ = orc.build32(bits, 16)
+    for c, field in ((0, 32768), (1, 32769)):
+        proofs[c, 0], proofs[c, 1] = field & 0xFF, field >> 8
+    for c, coef in ((2, orc.PRIME32 - 1), (3, orc.PRIME32)):
+        proofs[c, 2 + 4 * 15: 6 + 4 * 15] = np.frombuffer(int(coef).to_bytes(4, "little"), dtype=np.uint8)
+    o = check_verify(chunks, proofs, orc.F32, 16, "decode edges")
+    assert o["status"].tolist() == [tl.CHUNK_MALFORMED, 0, 0, tl.CHUNK_MALFORMED]
+
+
 def test_f32_arguments_are_checked():
     x = torch.zeros((1, 32 * 64), dtype=torch.float32, device=DEV)
     with pytest.raises(tl.ToplocError):

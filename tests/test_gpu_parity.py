@@ -465,3 +465,32 @@ def test_no_injective_modulus_and_a_deep_search():
     m_deep = int(o_proofs[1, 0]) | (int(o_proofs[1, 1]) << 8)
     assert 32769 <= m_deep < 65536 - 200
     assert_results_equal(gpu_verify(chunks, o_proofs, k), orc.verify(bits, o_proofs, k), "no modulus")
+
+
+def test_decode_edges_and_the_zero_modulus_field():
+    """The ends of the two decode ranges (m = 2^15 out, 2^15 + 1 in; coefficient p - 1 in, p out) and a
+    proof whose modulus field is 0 (m = 65536) over a chunk with top-k positions beyond 65535."""
+    chunks = random_chunks(6, 256, 32, 960)
+    bits = synth.bits_numpy(chunks)
+    proofs, _ = orc.build(bits, 16)
+    for c, field in ((0, 32768), (1, 32769)):
+        proofs[c, 0], proofs[c, 1] = field & 0xFF, field >> 8
+    for c, coef in ((2, 65496), (3, 65497)):
+        proofs[c, 2 + 2 * 15], proofs[c, 3 + 2 * 15] = coef & 0xFF, coef >> 8
+    g = gpu_verify(chunks, proofs, 16)
+    assert_results_equal(g, orc.verify(bits, proofs, 16), "decode edges")
+    assert g["status"].tolist() == [tl.CHUNK_MALFORMED, 0, 0, tl.CHUNK_MALFORMED, 0, 0]
+    n, k = 66000, 6
+    h = np.full((2, n), 0x1000, dtype=np.uint16)
+    big = [65535, 65540, 3, 40000, 65999, 100]
+    h[0, big] = np.uint16(0x4500) + np.arange(6, dtype=np.uint16)
+    h[1, [5, 65541, 7, 8, 9, 10]] = np.uint16(0x4500) + np.arange(6, dtype=np.uint16)     # 5 and 65541 collide
+    say("zero modulus field: N=%d k=%d" % (n, k))
+    o_proofs, o_status, o_idx = orc.build(h, k, want_topk=True)
+    assert o_proofs[0, 0] == 0 and o_proofs[0, 1] == 0 and (o_proofs[1, 0] != 0 or o_proofs[1, 1] != 0)
+    x = synth.from_bits(h, DEV)
+    g_proofs, g_status, g_idx = gpu_build(x, k)
+    assert np.array_equal(g_idx, o_idx) and np.array_equal(g_status, o_status) and np.array_equal(g_proofs, o_proofs)
+    g = gpu_verify(x, o_proofs, k)
+    assert_results_equal(g, orc.verify(h, o_proofs, k), "zero field")
+    assert (g["accept"] == 1).all() and (g["mant_sum"] == 0).all() and (g["n_match"] == k).all()

@@ -251,6 +251,24 @@ def test_malformed_proofs():
     bad[0, 0], bad[0, 1] = 0x00, 0x40                                      # m = 16384
     res = orc.verify_mixed(bits, orc.F32, bad, orc.F32, 16)
     assert res["status"][0] == orc.EMALFORMED and res["accept"][0] == 0
+    # the edges: m = 2^15 is out, 2^15 + 1 is in; a coefficient M - 1 is in, M is out
+    for field, want in ((32768, orc.EMALFORMED), (32769, 0)):
+        edge = p.copy()
+        edge[0, 0], edge[0, 1] = field & 0xFF, field >> 8
+        assert orc.verify_mixed(bits, orc.F32, edge, orc.F32, 16)["status"][0] == want, field
+    for coef, want in ((P32 - 1, 0), (P32, orc.EMALFORMED)):
+        edge = p.copy()
+        edge[0, 2 + 4 * 15: 6 + 4 * 15] = np.frombuffer(int(coef).to_bytes(4, "little"), dtype=np.uint8)
+        assert orc.verify_mixed(bits, orc.F32, edge, orc.F32, 16)["status"][0] == want, coef
+    # a field of 0 stands for 65536: positions 65535 and 65540 do not collide there
+    n, k = 66000, 6
+    b = np.full(n, 0x3C000000, dtype=np.uint32)
+    big = [65535, 65540, 3, 40000, 65999, 100]
+    b[big] = np.uint32(0x45000000) + np.arange(6, dtype=np.uint32) * np.uint32(0x10001)
+    proofs, status = orc.build32(b[None, :], k)
+    assert status[0] == 0 and proofs[0, 0] == 0 and proofs[0, 1] == 0
+    res = orc.verify_mixed(b[None, :], orc.F32, proofs, orc.F32, k)
+    assert res["err_exp"][0] == 0 and res["mant_sum"][0] == 0 and res["n_match"][0] == k
 
 
 def brute_verify_mixed(bits, h_dtype, proof, p_dtype, thresholds):
@@ -320,3 +338,54 @@ def test_validation_equals_brute_force_in_all_four_precision_pairs(seed):
             for f, v in want.items():
                 assert int(got[f]) == v, (h_dt, p_dt, f, int(got[f]), v)
             assert got["status"] == 0 and want["err_exp"] + want["n_match"] == k
+
+
+def test_thresholds_are_strict_and_the_search_reaches_its_last_candidate():
+    """Equality with a threshold accepts, one more rejects (Algorithm 2 compares with '>'), for each of the
+    three statistics; Algorithm 6's range ends at 2^15 + 1 inclusive."""
+    bits = f32_chunks(1, 4096, 31)
+    k = 128
+    proofs, _ = orc.build32(bits, k)
+    idx, _ = orc.topk32(bits[0], k, orc.F32)
+    rec = bits.copy()
+    for i in idx[:64]:
+        rec[0, i] ^= np.uint32(1 << 4)                 # 64 entries differ by 16, 64 by 0: sum = 8 k, lower median 0
+    for i in idx[64:67]:
+        rec[0, i] ^= np.uint32(1 << 23)                # three binade steps: err_e = 3, their mantissas drop out
+    base = orc.verify_mixed(rec, orc.F32, proofs, orc.F32, k, thresholds=(3, 1 << 20, 1 << 20))[0]
+    assert base["err_exp"] == 3 and base["n_match"] == k - 3 and base["mant_sum"] == 64 * 16 and base["accept"] == 1
+    assert orc.verify_mixed(rec, orc.F32, proofs, orc.F32, k, thresholds=(2, 1 << 20, 1 << 20))[0]["accept"] == 0
+    rec = bits.copy()
+    for i in idx[:96]:
+        rec[0, i] ^= np.uint32(1 << 4)                 # 96 * 16 = 1536 = 12 * 128: mean exactly 12, median 16
+    assert orc.verify_mixed(rec, orc.F32, proofs, orc.F32, k, thresholds=(0, 12, 16))[0]["accept"] == 1
+    assert orc.verify_mixed(rec, orc.F32, proofs, orc.F32, k, thresholds=(0, 11, 16))[0]["accept"] == 0
+    assert orc.verify_mixed(rec, orc.F32, proofs, orc.F32, k, thresholds=(0, 12, 15))[0]["accept"] == 0
+    # the smallest candidate: differences cover 32770..65537, nothing that 32769 divides
+    low = np.concatenate([np.arange(256), 32770 + 255 + 256 * np.arange(128)]).astype(np.uint32)
+    assert orc.find_injective_modulus32(low) == 32769 == orc.find_injective_modulus(low, M=0)
+    cover = np.concatenate([np.arange(256), 32769 + 256 * np.arange(129)]).astype(np.uint32)
+    with pytest.raises(ValueError):
+        orc.find_injective_modulus32(cover)
+
+
+def test_validation_maps_indices_with_the_proofs_modulus():
+    """Top-k positions 5 and 65541 collide modulo 65536, so the proof carries a smaller modulus; a validator
+    that mapped indices with anything else would evaluate the polynomial at the wrong points."""
+    rng = np.random.default_rng(41)
+    n, k = 70000, 8
+    b32 = (rng.standard_normal(n) * 0.01).astype(np.float32).view(np.uint32).copy()
+    big = [5, 65541, 69999, 40000, 123, 65536 + 123 + 7, 33000, 1]
+    b32[big] = (np.float32(100.0) + np.arange(8, dtype=np.float32)).view(np.uint32)
+    for bits, dt, build in ((b32, orc.F32, orc.build32), ((b32 >> 16).astype(np.uint16), orc.BF16, orc.build)):
+        proofs, status = build(bits[None, :], k)
+        m = int(proofs[0, 0]) | (int(proofs[0, 1]) << 8)
+        assert status[0] == 0 and 32769 <= m < 65536
+        rec = bits.copy()
+        rec[big[:4]] ^= rec.dtype.type(1)                                  # four low mantissa bits move
+        for h_dt, rbits in ((dt, rec),):
+            got = orc.verify_mixed(rbits[None, :], h_dt, proofs, dt, k)[0]
+            want = brute_verify_mixed(rbits, h_dt, proofs[0], dt, (8, 256, 128) if h_dt == orc.F32 else (38, 10, 8))
+            assert want["err_exp"] == 0 and want["mant_sum"] == 4
+            for f, v in want.items():
+                assert int(got[f]) == v, (dt, f, int(got[f]), v)

@@ -298,6 +298,11 @@ def test_modulus_failure_with_distinct_indices_and_a_deep_search():
             orc.find_injective_modulus(idx, M=p)
     # without index 255 only the candidates 32769 + 256 j - 255 lose their colliding pair ... unless another
     # pair collides there too: brute force says which candidate the search must stop at
+    # the smallest candidate, 2^15 + 1, is part of the range: a set whose differences cover 32770..65537 and
+    # nothing that 32769 divides is injective there and nowhere above
+    low = np.concatenate([np.arange(256), 32770 + 255 + 256 * np.arange(128)]).astype(np.uint32)
+    assert all(not _is_injective(low, m, P) for m in range(32770, 65537)) and _is_injective(low, 32769, P)
+    assert orc.find_injective_modulus(low, M=P) == 32769 and orc.find_injective_modulus(low, M=0) == 32769
     fewer = np.delete(idx, 255)
     want = next(m for m in range(65536, 32768, -1) if _is_injective(fewer, m, P))
     assert want < 65536 - 200                                   # hundreds of candidates deep
@@ -556,6 +561,32 @@ def test_malformed_proofs_are_rejected_not_crashed():
     assert r["status"] == orc.EMALFORMED and r["accept"] == 0
     ok = orc.verify(h, proofs, 16)[0]
     assert ok["status"] == 0 and ok["accept"] == 1
+    # the edges of the two ranges: m = 2^15 is out, 2^15 + 1 is in; a coefficient p - 1 is in, p is out
+    for field, want in ((32768, orc.EMALFORMED), (32769, 0)):
+        edge = proofs.copy()
+        edge[0, 0], edge[0, 1] = field & 0xFF, field >> 8
+        assert orc.verify(h, edge, 16)[0]["status"] == want, field
+    for coef, want in ((P - 1, 0), (P, orc.EMALFORMED)):
+        edge = proofs.copy()
+        edge[0, 2 + 2 * 15], edge[0, 3 + 2 * 15] = coef & 0xFF, coef >> 8          # the last coefficient
+        assert orc.verify(h, edge, 16)[0]["status"] == want, coef
+
+
+def test_modulus_field_zero_stands_for_65536():
+    """Top-k positions 65535 and 65540 (residues 65535 and 4) are distinct modulo 65536, so the search stops at
+    its first candidate and the 2-byte field holds 0; a validator reading that 0 as anything but 65536 would
+    evaluate the polynomial at other points and could not reproduce all-zero statistics."""
+    n, k = 66000, 6
+    h = np.full(n, 0x1000, dtype=np.uint16)
+    big = [65535, 65540, 3, 40000, 65999, 100]
+    h[big] = np.uint16(0x4500) + np.arange(6, dtype=np.uint16)
+    proofs, status, idx = orc.build(h[None, :], k, want_topk=True)
+    assert status[0] == 0 and sorted(idx[0].tolist()) == sorted(big)
+    assert proofs[0, 0] == 0 and proofs[0, 1] == 0
+    res = orc.verify(h[None, :], proofs, k)[0]
+    assert res["err_exp"] == 0 and res["n_match"] == k and res["mant_sum"] == 0 and res["accept"] == 1
+    m, c = decode(proofs[0])
+    assert m == 65536 and all(poly_eval(c, (i % 65536) % P, P) == int(h[i]) for i in big)
 
 
 def test_thread_count_does_not_change_results():
