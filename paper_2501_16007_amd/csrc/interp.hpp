@@ -25,6 +25,10 @@
 #include "gf65497.hpp"
 #include "ticks.hpp"
 
+#ifndef TOPLOC_TREE_LEAF
+#define TOPLOC_TREE_LEAF 16   // 16: leaves of 16 points built by lane groups; 1: the plain tree from single points
+#endif
+
 namespace toploc {
 
 constexpr uint32_t kModHigh = 65536u;
@@ -96,9 +100,35 @@ __device__ __forceinline__ void interpolate(InterpShared<KMAX, F>& s, uint32_t k
     TOPLOC_TICK_BEGIN(tree);
     E* src = s.pa;
     E* dst = s.pb;
+#if TOPLOC_TREE_LEAF == 16
+    // Leaves of 16 points, one lane per point: the 16 lanes of a group hold the coefficients
+    // c_0..c_15 of the running product and multiply it by (X - x_s) sixteen times,
+    // c_i <- c_{i-1} - x_s c_i (the coefficient 1 of the highest power is implied, as in the
+    // levels above).  This replaces the four lowest levels, whose cost is all overhead.
+    static_assert(KMAX <= THREADS && KMAX % 16 == 0, "one lane per point, whole groups");
+    if (tid < ((k + 15u) & ~15u)) {  // whole groups of 16 lanes; a group never straddles a wave
+        const uint32_t g0 = tid & ~15u, i = tid & 15u;
+        const uint32_t cnt = (k - g0) < 16u ? (k - g0) : 16u;  // points of this group
+        const uint32_t x = tid < k ? (uint32_t)s.xs[tid] : 0u;
+        const int lane0 = (int)(__lane_id() & ~15u);
+        uint32_t c = (i == 0u) ? 1u : 0u;  // the polynomial 1
+#pragma unroll
+        for (uint32_t step = 0; step < 16u; ++step) {
+            const uint32_t xs = __shfl(x, lane0 + (int)step);
+            uint32_t below = __shfl_up(c, 1);
+            if (i == 0u) below = 0u;
+            const uint32_t next = F::submod(below, F::mulmod(xs, c));
+            if (step < cnt) c = next;
+        }
+        if (i < cnt) src[tid] = (E)c;
+    }
+    __syncthreads();
+    for (uint32_t d = 16u; d < k; d <<= 1) {
+#else
     for (uint32_t j = tid; j < k; j += THREADS) src[j] = (E)F::neg(s.xs[j]);
     __syncthreads();
     for (uint32_t d = 1; d < k; d <<= 1) {
+#endif
         for (uint32_t o = tid / L; o < k; o += THREADS / L) {
             const uint32_t start = o & ~(2u * d - 1u);
             const uint32_t t = o - start;
