@@ -149,14 +149,14 @@ __global__ __launch_bounds__(kThreads, WAVES) void build_kernel(const u32x4* __r
 template <typename F, int KMAX, bool WIDE>
 struct DecodeFirst {
     VerifyShared<KMAX, WIDE>& vs;
-    const uint16_t* proof;
+    const ProofWords<kThreads, KMAX>& words;  // read from global memory before the chunk's first loads
     uint32_t k;
     toploc_verify_result* result;
     bool* ok;
     template <typename Shared>
     __device__ __forceinline__ SelectStart seed(Shared&) const
     {
-        *ok = verify_decode<kThreads, F>(vs, proof, k, result);
+        *ok = verify_decode<kThreads, F>(vs, words, k, result);
         return SelectStart{0u, Threshold{0, 0xFFFFFFFFu}, k};
     }
 };
@@ -173,10 +173,12 @@ __global__ __launch_bounds__(kThreads, WAVES) void verify_kernel(const u32x4* __
     __shared__ VerifyShared<KMAX, Fmt::ELEMS == 4> vs;
     const uint64_t chunk = chunk_of_block();
     const uint16_t* proof = reinterpret_cast<const uint16_t*>(proofs + chunk * (2 + 2 * (uint64_t)F::WORDS * k));
-    // decode(p) runs once the chunk's first loads are in flight; a malformed proof has its record
-    // written there and the selection's result is dropped
+    // The proof's words are requested first and the chunk's first loads right behind them; decode(p)
+    // runs while those are in flight.  A malformed proof has its record written there and the
+    // selection's result is dropped
     bool ok = true;
-    const DecodeFirst<F, KMAX, Fmt::ELEMS == 4> first{vs, proof, k, results + chunk, &ok};
+    const ProofWords<kThreads, KMAX> words = verify_load_proof<kThreads, F, KMAX>(proof, k);
+    const DecodeFirst<F, KMAX, Fmt::ELEMS == 4> first{vs, words, k, results + chunk, &ok};
     (void)select_topk_from<kThreads, U>(hidden + chunk * nvec, 0u, nvec, s, first);  // order is irrelevant here
     if (!ok) return;  // uniform
     TOPLOC_TICK_BEGIN(tail);

@@ -35,23 +35,51 @@ struct VerifyShared {
     uint32_t err_e, mant_sum, bad, m, n_match, median;
 };
 
+// The words of a proof as the lanes read them from global memory: issued early (before the
+// chunk's first loads, which return in order behind them), used by verify_decode.
+template <int THREADS, int KMAX>
+struct ProofWords {
+    static constexpr int PER_LANE = (KMAX + THREADS - 1) / THREADS;
+    uint32_t mf;            // the 2-byte modulus field
+    uint32_t c[PER_LANE];   // coefficients tid, tid + THREADS, ..
+};
+
+template <int THREADS, typename F, int KMAX>
+__device__ __forceinline__ ProofWords<THREADS, KMAX> verify_load_proof(const uint16_t* __restrict__ proof, uint32_t k)
+{
+    ProofWords<THREADS, KMAX> w;
+    w.mf = proof[0];
+#pragma unroll
+    for (int i = 0; i < ProofWords<THREADS, KMAX>::PER_LANE; ++i) {
+        const uint32_t j = threadIdx.x + i * THREADS;
+        uint32_t c = 0;
+        if (j < k) {
+            c = proof[1 + j * F::WORDS];
+            if (F::WORDS == 2) c |= (uint32_t)proof[2 + j * F::WORDS] << 16;
+        }
+        w.c[i] = c;
+    }
+    return w;
+}
+
 // decode(p): coefficients and modulus into LDS.  Returns false (uniformly) for a
 // malformed proof, after writing its result record.  All threads call; ends with a barrier.
 template <int THREADS, typename F, int KMAX, bool WIDE>
-__device__ __forceinline__ bool verify_decode(VerifyShared<KMAX, WIDE>& vs, const uint16_t* __restrict__ proof, uint32_t k,
+__device__ __forceinline__ bool verify_decode(VerifyShared<KMAX, WIDE>& vs, const ProofWords<THREADS, KMAX>& w, uint32_t k,
                                               toploc_verify_result* __restrict__ result)
 {
     const uint32_t tid = threadIdx.x;
     if (tid == 0) { vs.err_e = 0; vs.mant_sum = 0; vs.bad = 0; vs.n_match = 0; vs.median = 0; }
     for (uint32_t b = tid; b < 128; b += THREADS) vs.hist_d[b] = 0;
     __syncthreads();
-    const uint32_t mf = proof[0];
-    const uint32_t m = mf ? mf : kModHigh;   // the 2-byte field stores m mod 65536
-    for (uint32_t j = tid; j < k; j += THREADS) {
-        uint32_t c = proof[1 + j * F::WORDS];
-        if (F::WORDS == 2) c |= (uint32_t)proof[2 + j * F::WORDS] << 16;
-        vs.coef[j] = c;
-        if (c >= F::P) vs.bad = 1u;
+    const uint32_t m = w.mf ? w.mf : kModHigh;   // the 2-byte field stores m mod 65536
+#pragma unroll
+    for (int i = 0; i < ProofWords<THREADS, KMAX>::PER_LANE; ++i) {
+        const uint32_t j = tid + i * THREADS;
+        if (j < k) {
+            vs.coef[j] = w.c[i];
+            if (w.c[i] >= F::P) vs.bad = 1u;
+        }
     }
     if (tid == 0) {
         vs.m = m;
@@ -67,6 +95,13 @@ __device__ __forceinline__ bool verify_decode(VerifyShared<KMAX, WIDE>& vs, cons
         return false;
     }
     return true;
+}
+
+template <int THREADS, typename F, int KMAX, bool WIDE>
+__device__ __forceinline__ bool verify_decode(VerifyShared<KMAX, WIDE>& vs, const uint16_t* __restrict__ proof, uint32_t k,
+                                              toploc_verify_result* __restrict__ result)
+{
+    return verify_decode<THREADS, F>(vs, verify_load_proof<THREADS, F, KMAX>(proof, k), k, result);
 }
 
 // extractBits of a proof value (a pattern of the field's precision), expressed in the
