@@ -44,9 +44,9 @@ struct InterpShared {
     E ys[KMAX];               // pattern mod p
     E pa[KMAX + 2];           // product tree ping
     E pb[KMAX + 2];           // product tree pong
-    E wder[KMAX];             // coefficients of W'
+    alignas(16) E wder[KMAX]; // coefficients of W' (read 16 at a time)
     E S[KMAX];
-    union {
+    alignas(16) union {
         uint32_t bitmap[2048];                    // modulus search: one bit per residue below 65536
         struct {
             E B[KMAX * 16];                       // B[j][r0] = x_j^r0
@@ -55,6 +55,44 @@ struct InterpShared {
     } u;
     uint32_t collide[2];
 };
+
+// Sixteen consecutive field elements from LDS (16-byte aligned) into registers with
+// 16-byte loads: 2 loads for 16-bit elements, 4 for 32-bit ones, instead of 16.
+template <typename E>
+__device__ __forceinline__ void load16(const E* p, uint32_t (&out)[16])
+{
+    typedef uint32_t vec4 __attribute__((ext_vector_type(4)));
+    const vec4* v = reinterpret_cast<const vec4*>(p);
+    if (sizeof(E) == 2) {
+        const vec4 a = v[0], b = v[1];
+        const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { out[2 * i] = w[i] & 0xFFFFu; out[2 * i + 1] = w[i] >> 16; }
+    } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const vec4 a = v[q];
+            out[4 * q] = a.x; out[4 * q + 1] = a.y; out[4 * q + 2] = a.z; out[4 * q + 3] = a.w;
+        }
+    }
+}
+
+template <typename E>
+__device__ __forceinline__ void store16(E* p, const uint32_t (&in)[16])
+{
+    typedef uint32_t vec4 __attribute__((ext_vector_type(4)));
+    vec4* v = reinterpret_cast<vec4*>(p);
+    if (sizeof(E) == 2) {
+        uint32_t w[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) w[i] = in[2 * i] | (in[2 * i + 1] << 16);
+        v[0] = vec4{w[0], w[1], w[2], w[3]};
+        v[1] = vec4{w[4], w[5], w[6], w[7]};
+    } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[q] = vec4{in[4 * q], in[4 * q + 1], in[4 * q + 2], in[4 * q + 3]};
+    }
+}
 
 // Algorithm 6 with the residues compared in the form Algorithms 3 and 5 consume them,
 // (i mod m) mod p: the largest m in [2^15+1, 65536] for which the k points are
@@ -167,12 +205,14 @@ __device__ __forceinline__ void interpolate(InterpShared<KMAX, F>& s, uint32_t k
         if (j < k) {
             const uint32_t x = s.xs[j];
             if (L == 1 || h == 0) {   // baby steps 1, x, .., x^15
+                uint32_t pw[kBaby];
                 uint32_t p = 1u;
 #pragma unroll
                 for (uint32_t r0 = 0; r0 < kBaby; ++r0) {
-                    s.u.pw.B[j * kBaby + r0] = (E)p;
+                    pw[r0] = p;
                     p = F::mulmod(p, x);
                 }
+                store16(&s.u.pw.B[j * kBaby], pw);
             }
             if (L == 1 || h == 1) {   // giant steps 1, x^16, x^32, ..
                 uint32_t x16 = F::mulmod(x, x);
@@ -196,15 +236,16 @@ __device__ __forceinline__ void interpolate(InterpShared<KMAX, F>& s, uint32_t k
         const uint32_t j = (tid + i * THREADS) / L;
         if (j < k) {
             uint32_t brow[kBaby];
-#pragma unroll
-            for (uint32_t r0 = 0; r0 < kBaby; ++r0) brow[r0] = s.u.pw.B[j * kBaby + r0];
+            load16(&s.u.pw.B[j * kBaby], brow);
             Acc dacc;   // sum over r1 of (inner sum mod p) * x_j^(16 r1)
             for (uint32_t r1 = h; r1 < n_giant; r1 += L) {
                 const uint32_t rbase = r1 * kBaby;
+                uint32_t wrow[kBaby];   // the same 16 coefficients for every lane: a broadcast read
+                load16(&s.wder[rbase], wrow);
                 Acc acc;
 #pragma unroll
                 for (uint32_t r0 = 0; r0 < kBaby; ++r0)
-                    if (rbase + r0 < k) acc.mac(s.wder[rbase + r0], brow[r0]);
+                    if (rbase + r0 < k) acc.mac(wrow[r0], brow[r0]);
                 dacc.mac(acc.reduce(), s.u.pw.G[r1 * KMAX + j]);
             }
             uint32_t d = dacc.reduce();
