@@ -40,7 +40,7 @@ struct InterpShared {
     static_assert(KMAX % 16 == 0, "giant steps cover 16 powers each");
     typedef typename F::elem_t E;
     uint32_t idx[KMAX];       // top-k flat indices
-    E xs[KMAX];               // (idx mod m) mod p
+    alignas(16) E xs[KMAX];   // (idx mod m) mod p (read 16 at a time)
     E ys[KMAX];               // pattern mod p
     E pa[KMAX + 2];           // product tree ping
     E pb[KMAX + 2];           // product tree pong
@@ -147,15 +147,14 @@ __device__ __forceinline__ void interpolate(InterpShared<KMAX, F>& s, uint32_t k
     if (tid < ((k + 15u) & ~15u)) {  // whole groups of 16 lanes; a group never straddles a wave
         const uint32_t g0 = tid & ~15u, i = tid & 15u;
         const uint32_t cnt = (k - g0) < 16u ? (k - g0) : 16u;  // points of this group
-        const uint32_t x = tid < k ? (uint32_t)s.xs[tid] : 0u;
-        const int lane0 = (int)(__lane_id() & ~15u);
+        uint32_t xg[16];                   // the group's points: the same two LDS loads for its 16 lanes
+        load16(&s.xs[g0], xg);
         uint32_t c = (i == 0u) ? 1u : 0u;  // the polynomial 1
 #pragma unroll
         for (uint32_t step = 0; step < 16u; ++step) {
-            const uint32_t xs = __shfl(x, lane0 + (int)step);
-            uint32_t below = __shfl_up(c, 1);
-            if (i == 0u) below = 0u;
-            const uint32_t next = F::submod(below, F::mulmod(xs, c));
+            // c_{i-1} from the lane below inside the row of 16 (DPP row_shr:1; lane 0 of a row gets 0)
+            const uint32_t below = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)c, 0x111, 0xF, 0xF, false);
+            const uint32_t next = F::submod(below, F::mulmod(xg[step], c));
             if (step < cnt) c = next;
         }
         if (i < cnt) src[tid] = (E)c;
