@@ -112,6 +112,25 @@ struct SelectShared {
 
 __device__ __forceinline__ uint32_t lane_id() { return __lane_id(); }
 
+// Inclusive prefix sum over the 64 lanes of a wave with DPP adds: four shifts inside the
+// rows of 16 lanes, then lane 15 of rows 0 and 2 into rows 1 and 3, then lane 31 into rows 2
+// and 3.  Lanes without a source add 0.  No LDS round trip, unlike the shuffle form.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_or_zero(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xF, false);
+}
+__device__ __forceinline__ uint32_t wave_prefix_sum(uint32_t v)
+{
+    v += dpp_or_zero<0x111, 0xF>(v);  // row_shr:1
+    v += dpp_or_zero<0x112, 0xF>(v);  // row_shr:2
+    v += dpp_or_zero<0x114, 0xF>(v);  // row_shr:4
+    v += dpp_or_zero<0x118, 0xF>(v);  // row_shr:8
+    v += dpp_or_zero<0x142, 0xA>(v);  // row_bcast:15
+    v += dpp_or_zero<0x143, 0xC>(v);  // row_bcast:31
+    return v;
+}
+
 // Suffix search over a histogram held 'BPL' bins per lane by one wave: returns the
 // bin b (scanning from the highest bin down) at which the running count
 // above0 + sum_{b' > b} hist[b'] first reaches k when hist[b] is added, and that
@@ -125,13 +144,10 @@ __device__ __forceinline__ void find_bin(const uint32_t* hist, uint32_t above0, 
     uint32_t t = 0;
 #pragma unroll
     for (int b = 0; b < BPL; ++b) { own[b] = hist[lane * BPL + b]; t += own[b]; }
-    uint32_t v = t;  // inclusive suffix sum over lanes
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        uint32_t o = __shfl_down(v, d);
-        if (lane + d < 64) v += o;
-    }
-    uint32_t a = above0 + (v - t);
+    // entries in the lanes above this one: the wave's total minus the inclusive prefix sum
+    const uint32_t incl = wave_prefix_sum(t);
+    const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+    uint32_t a = above0 + (total - incl);
     uint32_t fbin = 0, fabove = 0;
     bool found = false;
 #pragma unroll
@@ -139,10 +155,10 @@ __device__ __forceinline__ void find_bin(const uint32_t* hist, uint32_t above0, 
         if (!found && a < k && a + own[b] >= k) { found = true; fbin = lane * BPL + b; fabove = a; }
         a += own[b];
     }
-    uint64_t mask = __ballot(found);
-    int src = mask ? (__ffsll((long long)mask) - 1) : 0;
-    bin = __shfl(fbin, src);
-    above = __shfl(fabove, src);
+    const uint64_t mask = __ballot(found);
+    const int src = mask ? (__ffsll((long long)mask) - 1) : 0;  // uniform
+    bin = (uint32_t)__builtin_amdgcn_readlane((int)fbin, src);
+    above = (uint32_t)__builtin_amdgcn_readlane((int)fabove, src);
 }
 
 // the threshold element as the lanes carry it

@@ -179,21 +179,16 @@ __device__ __forceinline__ void verify_tail(VerifyShared<KMAX, WIDE>& vs, const 
         // |err_m| and its lower median from the histogram: the smallest d whose
         // cumulative count reaches floor((n-1)/2) + 1
         const uint32_t h0 = vs.hist_d[2 * tid], h1 = vs.hist_d[2 * tid + 1];
-        uint32_t v = h0 + h1;  // inclusive prefix sum over lanes
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const uint32_t o = __shfl_up(v, d);
-            if ((int)tid >= d) v += o;
-        }
-        n = __shfl(v, 63);
+        const uint32_t v = wave_prefix_sum(h0 + h1);  // inclusive prefix sum over lanes
+        n = (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
         const uint32_t target = n ? (n - 1) / 2 + 1 : 0;
         const uint32_t before = v - h0 - h1;
         med = 0xFFFFFFFFu;
         if (n && before < target && before + h0 >= target) med = 2 * tid;
         else if (n && before + h0 < target && v >= target) med = 2 * tid + 1;
         const uint64_t mask = __ballot(med != 0xFFFFFFFFu);
-        const int srcl = mask ? (__ffsll((long long)mask) - 1) : 0;
-        med = __shfl(med, srcl);
+        const int srcl = mask ? (__ffsll((long long)mask) - 1) : 0;  // uniform
+        med = (uint32_t)__builtin_amdgcn_readlane((int)med, srcl);
     } else {
         n = 0;
     }
