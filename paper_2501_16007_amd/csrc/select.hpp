@@ -115,6 +115,7 @@ __device__ __forceinline__ uint32_t lane_id() { return __lane_id(); }
 // Inclusive prefix sum over the 64 lanes of a wave with DPP adds: four shifts inside the
 // rows of 16 lanes, then lane 15 of rows 0 and 2 into rows 1 and 3, then lane 31 into rows 2
 // and 3.  Lanes without a source add 0.  No LDS round trip, unlike the shuffle form.
+// Every lane of the wave must be active (the callers run it in whole waves only).
 template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ uint32_t dpp_or_zero(uint32_t v)
 {
