@@ -44,6 +44,28 @@ def summarize_results(results):
     }
 
 
+def error_statistics_row(chunks_gen, chunks_val, k=128, thresholds=binding.BF16_THRESHOLDS):
+    """One row of the paper's error-statistics tables (Tables 2-5): proofs built from `chunks_gen`
+    [n_chunks, N] are validated against `chunks_val`.  Worst case over the chunks as Table 2 prints it
+    (for a pair that should pass) and best case as Tables 3 and 4 print it (for a pair that should fail)."""
+    proofs, status, idx_gen = binding.toploc_build_proofs(chunks_gen, k=k, chunk_tokens=1, want_topk=True)
+    idx_val, _ = binding.toploc_topk(chunks_val, k=k, chunk_tokens=1)
+    r = binding.results_numpy(binding.toploc_verify_proofs(chunks_val, proofs, k=k, chunk_tokens=1, thresholds=thresholds))
+    miss = topk_mismatch(idx_gen, idx_val).cpu().numpy()
+    mean = r["mant_sum"] / np.maximum(r["n_match"], 1)
+    some = r["n_match"] > 0                           # the paper prints "-" where nothing matched
+    return {
+        "chunks": int(r.size), "accepted": int(r["accept"].sum()), "unbuilt": int((status != 0).sum().item()),
+        "topk_mismatch_max": int(miss.max()), "topk_mismatch_max_pct": 100.0 * float(miss.max()) / k,
+        "exp_mismatch_max": int(r["err_exp"].max()), "exp_mismatch_max_pct": 100.0 * float(r["err_exp"].max()) / k,
+        "exp_mismatch_min": int(r["err_exp"].min()),
+        "mant_mean_max": float(mean[some].max()) if some.any() else None,
+        "mant_mean_min": float(mean[some].min()) if some.any() else None,
+        "mant_median_max": int(r["mant_median"][some].max()) if some.any() else None,
+        "mant_median_min": int(r["mant_median"][some].min()) if some.any() else None,
+    }
+
+
 def topk_mismatch(idx_a, idx_b):
     """Per chunk, how many of the k indices of idx_a are missing from idx_b (Table 1's top-k
     mismatch); both are [n_chunks, k] index tensors as the build calls export them."""

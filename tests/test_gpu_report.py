@@ -123,3 +123,31 @@ def test_threshold_sweep_on_honest_and_tampered_recomputations():
     sep = report.separation(honest, tampered)
     assert sep["exp_mismatch"][0] <= 38 < sep["exp_mismatch"][1]
     assert sep["mant_mean"][0] <= 10 and sep["mant_median"][0] <= 8
+
+
+def test_error_statistics_row_against_the_oracle():
+    """The row of Tables 2-5 for an honest pair (small numeric noise) and for a tampered pair (another
+    input), each statistic checked against the same reduction over the oracle's records and top-k."""
+    x = synth.activations(8, 32, 2048, 8500, n_outlier=8, device=DEV).reshape(8, -1)
+    honest = synth.perturb_relative(x, 2.0 ** -7, 8501)
+    other = synth.activations(8, 32, 2048, 8502, n_outlier=8, device=DEV).reshape(8, -1)
+    k = 128
+    xb = synth.bits_numpy(x)
+    o_proofs, _, o_idx = orc.build(xb, k, want_topk=True)
+    for val, should_pass in ((honest, True), (other, False)):
+        row = report.error_statistics_row(x, val, k=k)
+        vb = synth.bits_numpy(val)
+        o = orc.verify(vb, o_proofs, k)
+        miss = [len(set(o_idx[c].tolist()) - set(orc.topk(vb[c], k)[0].tolist())) for c in range(8)]
+        assert row["chunks"] == 8 and row["accepted"] == int(o["accept"].sum()) == (8 if should_pass else 0)
+        assert row["topk_mismatch_max"] == max(miss) and row["exp_mismatch_max"] == int(o["err_exp"].max())
+        assert row["exp_mismatch_min"] == int(o["err_exp"].min())
+        some = o["n_match"] > 0
+        if some.any():
+            mean = o["mant_sum"][some] / o["n_match"][some]
+            assert abs(row["mant_mean_max"] - mean.max()) < 1e-12 and abs(row["mant_mean_min"] - mean.min()) < 1e-12
+            assert row["mant_median_max"] == int(o["mant_median"][some].max())
+        if should_pass:
+            assert row["exp_mismatch_max"] <= 38 and row["mant_mean_max"] <= 10 and row["mant_median_max"] <= 8
+        else:
+            assert row["exp_mismatch_min"] > 38      # the best case of a wrong input is still far above T_exp
