@@ -180,3 +180,58 @@ def separation(honest, tampered):
     h, t = stats(honest), stats(tampered)
     return {name: (float(h[name].max()) if h[name].size else float("nan"),
                    float(t[name].min()) if t[name].size else float("nan")) for name in h}
+
+
+def main(argv=None):
+    """Prints the shape of the paper's statistics tables on seeded synthetic activations and a few kinds of
+    recomputation (the paper's own numbers need its models and dataset): python -m paper_2501_16007_amd.report"""
+    import argparse
+
+    from . import synth
+    ap = argparse.ArgumentParser(description=main.__doc__)
+    ap.add_argument("--seqs", type=int, default=8)
+    ap.add_argument("--tokens", type=int, default=512)
+    ap.add_argument("--hidden", type=int, default=4096)
+    ap.add_argument("--k", type=int, default=128)
+    ap.add_argument("--ks", type=int, nargs="*", default=[64, 128, 256, 512, 1024, 2048, 4096])
+    ap.add_argument("--device", default="cuda:0")
+    args = ap.parse_args(argv)
+    x = synth.activations(args.seqs, args.tokens, args.hidden, synth.BASE_SEED + 40, n_outlier=8, device=args.device)
+    chunks = synth.as_chunks(x)
+    pairs = [
+        ("relative noise 2^-9", synth.as_chunks(synth.perturb_relative(x, 2.0 ** -9, 41))),
+        ("relative noise 2^-7", synth.as_chunks(synth.perturb_relative(x, 2.0 ** -7, 42))),
+        ("relative noise 2^-5", synth.as_chunks(synth.perturb_relative(x, 2.0 ** -5, 43))),
+        ("fp8 e4m3 round trip", synth.as_chunks(synth.roundtrip_e4m3(x))),
+        ("another input", synth.as_chunks(synth.activations(args.seqs, args.tokens, args.hidden, synth.BASE_SEED + 44,
+                                                          n_outlier=8, device=args.device))),
+    ]
+    print("%d chunks of %d values, k = %d" % (chunks.shape[0], chunks.shape[1], args.k))
+    print("\nerror statistics per generation / validation pair (worst case; best case in brackets)")
+    print("%-22s %9s %14s %14s %14s %14s" % ("validation input", "accepted", "top-k mismatch", "exp mismatch", "mant mean",
+                                            "mant median"))
+    for name, val in pairs:
+        r = error_statistics_row(chunks, val, k=args.k)
+        fmt = lambda hi, lo: "-" if hi is None else "%.4g [%.4g]" % (hi, lo)
+        print("%-22s %4d/%-4d %14s %14s %14s %14s" % (
+            name, r["accepted"], r["chunks"], "%d (%.1f%%)" % (r["topk_mismatch_max"], r["topk_mismatch_max_pct"]),
+            "%d [%d]" % (r["exp_mismatch_max"], r["exp_mismatch_min"]), fmt(r["mant_mean_max"], r["mant_mean_min"]),
+            fmt(r["mant_median_max"], r["mant_median_min"])))
+    val = pairs[1][1]
+    ks = [k for k in args.ks if k <= chunks.shape[1]]
+    print("\nexponent deviation at the top-k positions, validation input '%s'" % pairs[1][0])
+    print("%6s " % "k" + " ".join("%11s" % c for c in EXPONENT_DEVIATION_COLUMNS))
+    for k in ks:
+        counts = exponent_deviation_counts(chunks, val, k)
+        print("%6d " % k + " ".join("%11d" % counts[c] for c in EXPONENT_DEVIATION_COLUMNS))
+    print("\ntop-k mismatch ratio by k (max / median over chunks), same pair")
+    for k, m in topk_mismatch_by_k(chunks, val, ks=ks).items():
+        print("%6d  %.4f / %.4f" % (k, m["max"], m["median"]))
+    proofs, _ = binding.toploc_build_proofs(chunks, k=args.k, chunk_tokens=1)
+    print("\ninjective modulus of the proofs (share of chunks)")
+    for m, share in list(modulus_distribution(proofs).items())[:6]:
+        print("%6d  %.4f" % (m, share))
+
+
+if __name__ == "__main__":
+    main()

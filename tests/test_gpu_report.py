@@ -151,3 +151,12 @@ def test_error_statistics_row_against_the_oracle():
             assert row["exp_mismatch_max"] <= 38 and row["mant_mean_max"] <= 10 and row["mant_median_max"] <= 8
         else:
             assert row["exp_mismatch_min"] > 38      # the best case of a wrong input is still far above T_exp
+
+
+def test_report_command_line_prints_every_table(capsys):
+    report.main(["--seqs", "2", "--tokens", "64", "--hidden", "1024", "--ks", "64", "128", "1024"])
+    out = capsys.readouterr().out
+    for title in ("error statistics per generation", "exponent deviation at the top-k positions",
+                  "top-k mismatch ratio by k", "injective modulus of the proofs"):
+        assert title in out
+    assert "relative noise 2^-7" in out and "   4/4" in out           # small noise: every chunk accepted
