@@ -97,3 +97,39 @@ def test_stream_state_size_and_argument_checks():
     assert L.toploc_stream_emit(fake, 1, 0, fake, fake, None, None) == binding.EINVAL
     assert L.toploc_stream_reset(fake, 0, 128, None) == binding.OK
     assert L.toploc_stream_reset(None, 3, 128, None) == binding.EINVAL
+
+
+def test_newer_entry_points_check_their_arguments_before_any_launch():
+    L = binding.lib()
+    fake = ctypes.c_void_p(1 << 40)  # never dereferenced: every call below is refused or empty
+    thr = binding.Thresholds(8, 256, 128)
+    # the selection alone reaches k = 4096, the proof calls stop at 512
+    wide = binding.Params(4096, 32, 4096, binding.PRIME)
+    too_wide = binding.Params(4097, 32, 4096, binding.PRIME)
+    assert L.toploc_topk(None, 1, ctypes.byref(wide), fake, fake, None) == binding.EINVAL        # only the null pointer is wrong
+    assert L.toploc_topk(fake, 0, ctypes.byref(wide), fake, fake, None) == binding.OK
+    assert L.toploc_topk(fake, 0, ctypes.byref(too_wide), fake, fake, None) == binding.EINVAL
+    assert L.toploc_build_proofs(fake, 0, ctypes.byref(wide), fake, fake, None, fake, 0, None) == binding.EINVAL
+    # continuous batching
+    assert L.toploc_stream_append_rows(fake, 8, fake, fake, fake, 0, 4096, 32, 128, None) == binding.OK
+    assert L.toploc_stream_append_rows(fake, 0, fake, fake, fake, 3, 4096, 32, 128, None) == binding.EINVAL   # no slots
+    assert L.toploc_stream_append_rows(fake, 8, fake, None, fake, 3, 4096, 32, 128, None) == binding.EINVAL
+    assert L.toploc_stream_append_rows(fake, 8, fake, ctypes.c_void_p((1 << 40) + 2), fake, 3, 4096, 32, 128,
+                                       None) == binding.EINVAL                                          # misaligned slots
+    assert L.toploc_stream_append_rows(fake, 8, fake, fake, fake, 3, 4100, 32, 128, None) == binding.EINVAL
+    assert L.toploc_stream_emit_rows(fake, 8, fake, 0, 128, fake, fake, None, None) == binding.OK
+    assert L.toploc_stream_emit_rows(fake, 8, None, 2, 128, fake, fake, None, None) == binding.EINVAL
+    assert L.toploc_stream_emit_rows(fake, 8, fake, 2, 513, fake, fake, None, None) == binding.EINVAL
+    # fp32 segments: k stops at 128, candidates are wider
+    off = (ctypes.c_uint64 * 3)(0, 5, 9)
+    b16 = L.toploc_segments_workspace_bytes_dtype(off, 2, 4096, 128, binding.DTYPE_BF16)
+    b32 = L.toploc_segments_workspace_bytes_dtype(off, 2, 4096, 128, binding.DTYPE_F32)
+    assert b16 == L.toploc_segments_workspace_bytes(off, 2, 4096, 128) and b32 > b16 > 0
+    assert L.toploc_segments_workspace_bytes_dtype(off, 2, 4096, 129, binding.DTYPE_F32) == 0
+    assert L.toploc_segments_workspace_bytes_dtype(off, 2, 4096, 128, 7) == 0                           # unknown dtype
+    assert L.toploc_build_proofs_segments_f32(fake, off, 2, 4096, 129, fake, fake, None, fake, 1 << 30, None) == binding.EINVAL
+    assert L.toploc_build_proofs_segments_f32(fake, off, 2, 4096, 128, fake, fake, None, fake, 16, None) == binding.EWORKSPACE
+    assert L.toploc_verify_proofs_segments_mixed(fake, binding.DTYPE_BF16, off, 2, 4096, 256, fake, binding.DTYPE_F32,
+                                                 ctypes.byref(thr), fake, fake, 1 << 30, None) == binding.EINVAL
+    assert L.toploc_verify_proofs_segments_mixed(fake, binding.DTYPE_F32, off, 0, 4096, 128, fake, binding.DTYPE_F32,
+                                                 ctypes.byref(thr), fake, fake, 0, None) == binding.OK
