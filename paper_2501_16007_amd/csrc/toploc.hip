@@ -34,7 +34,7 @@
 #define TOPLOC_QCAP 512
 #endif
 #ifndef TOPLOC_MIN_WAVES
-#define TOPLOC_MIN_WAVES 5  // waves per SIMD the streaming kernels must reach (bounds their VGPRs; 6 would spill)
+#define TOPLOC_MIN_WAVES 6  // waves per SIMD the streaming kernels must reach: 80 VGPRs, which 4 loads per lane just fit
 #endif
 
 namespace toploc {
@@ -50,6 +50,8 @@ constexpr int kCapLarge = 2048;           // candidate buffer for k <= TOPLOC_MA
 constexpr int kCapWide = 16384;           // candidate buffer of the selection alone up to TOPLOC_MAX_K_TOPK (140 KB of LDS:
                                           // one workgroup per compute unit; an aid for statistics, not a fast path)
 constexpr uint32_t kRoundVecs = kThreads * kLoads;
+// The larger candidate buffer (k > 128) costs registers in the prune and the ordering: one wave per SIMD less.
+constexpr int waves_for(int cap) { return cap > kCapSmall ? TOPLOC_MIN_WAVES - 1 : TOPLOC_MIN_WAVES; }
 static_assert(kCapLarge >= 4 * (int)TOPLOC_MAX_K && kCapSmall >= 4 * 128 && kCapWide >= 4 * (int)TOPLOC_MAX_K_TOPK,
               "soft limit CAP/2 must leave room above k");
 static_assert(kCapWide <= 65536, "prune keeps slot numbers in 16 bits");
@@ -90,7 +92,7 @@ __device__ __forceinline__ uint64_t chunk_of_block()
 // ---------------------------------------------------------------------------
 // topk(h, k) alone: writes the ordered (index, value) pairs of every chunk
 // ---------------------------------------------------------------------------
-template <int CAP, int WAVES = TOPLOC_MIN_WAVES>
+template <int CAP, int WAVES = waves_for(CAP)>
 __global__ __launch_bounds__(kThreads, WAVES) void select_kernel(const u32x4* __restrict__ hidden, uint32_t nvec,
                                                                  uint32_t k, uint32_t* __restrict__ out_idx,
                                                                  uint16_t* __restrict__ out_val)
@@ -110,7 +112,7 @@ __global__ __launch_bounds__(kThreads, WAVES) void select_kernel(const u32x4* __
 // then the same workgroup turns its k pairs into the proof out of LDS (the selection's
 // buffers are dead by then and are reused).
 // ---------------------------------------------------------------------------
-template <int KMAX, int CAP, typename F = Field16, typename Fmt = Bf16Fmt, int U = kLoads, int WAVES = TOPLOC_MIN_WAVES>
+template <int KMAX, int CAP, typename F = Field16, typename Fmt = Bf16Fmt, int U = kLoads, int WAVES = waves_for(CAP)>
 __global__ __launch_bounds__(kThreads, WAVES) void build_kernel(const u32x4* __restrict__ hidden, uint32_t nvec,
                                                                            uint32_t k, uint8_t* __restrict__ proofs,
                                                                            uint8_t* __restrict__ status,
@@ -163,7 +165,7 @@ struct DecodeFirst {
 
 // F is the proof's field, Fmt the format of the recomputed activations (Section 5.7
 // validates across the two precisions).
-template <int KMAX, int CAP, typename F = Field16, typename Fmt = Bf16Fmt, int U = kLoads, int WAVES = TOPLOC_MIN_WAVES>
+template <int KMAX, int CAP, typename F = Field16, typename Fmt = Bf16Fmt, int U = kLoads, int WAVES = waves_for(CAP)>
 __global__ __launch_bounds__(kThreads, WAVES) void verify_kernel(const u32x4* __restrict__ hidden, uint32_t nvec,
                                                                             uint32_t k, const uint8_t* __restrict__ proofs,
                                                                             toploc_thresholds thr,
@@ -186,26 +188,12 @@ __global__ __launch_bounds__(kThreads, WAVES) void verify_kernel(const u32x4* __
     TOPLOC_TICK_END(tail, 4);
 }
 
-// Two shapes of the fused kernels.  A launch of many generations of workgroups is served
-// best by 4 loads per lane and round at 5 waves per SIMD; a launch of only a few
-// generations (the 8B shape's 4096 chunks of 256 KB) spends a larger share of each
-// workgroup's life outside the streaming loop and gains more from a sixth resident
-// workgroup per compute unit, which 3 loads per lane leave registers for.
-#ifndef TOPLOC_LOADS_SHORT
-#define TOPLOC_LOADS_SHORT 3
-#endif
-#ifndef TOPLOC_WAVES_SHORT
-#define TOPLOC_WAVES_SHORT 6
-#endif
-constexpr int kLoadsShort = TOPLOC_LOADS_SHORT, kWavesShort = TOPLOC_WAVES_SHORT;
-constexpr uint64_t kShortLaunchGroups = 6 * 5 * 256;  // fewer than about six generations
-
 // ---------------------------------------------------------------------------
 // Split path, first launch: top-k of one part.  Writes k candidate slots per part,
 // the unused ones (part shorter than k values) padded with index 0xFFFFFFFF.
 // ---------------------------------------------------------------------------
 template <int CAP, typename Fmt = Bf16Fmt>
-__global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void part_kernel(const u32x4* __restrict__ hidden, Layout lay,
+__global__ __launch_bounds__(kThreads, waves_for(CAP)) void part_kernel(const u32x4* __restrict__ hidden, Layout lay,
                                                                           uint32_t k, uint32_t* __restrict__ c_idx,
                                                                           typename Fmt::bits_t* __restrict__ c_bits)
 {
@@ -370,7 +358,7 @@ struct StreamSeed {
 // sequences, each at its own position) row r goes to sequence slots[r] as token tokens[r];
 // a row whose slot or token is out of range is skipped.
 template <int CAP>
-__global__ __launch_bounds__(kThreads, TOPLOC_MIN_WAVES) void stream_append_kernel(char* __restrict__ state, size_t stride,
+__global__ __launch_bounds__(kThreads, waves_for(CAP)) void stream_append_kernel(char* __restrict__ state, size_t stride,
                                                                                    const u32x4* __restrict__ step_vec,
                                                                                    uint32_t hvec, uint32_t v0, uint32_t k,
                                                                                    const uint32_t* __restrict__ slots,
@@ -789,13 +777,8 @@ int toploc_build_proofs(const void* d_hidden_bf16, uint64_t n_chunks, const topl
     const bool have_ws = d_workspace && workspace_bytes >= cand_bytes(n_chunks * f.parts, k);
     if (k <= 128 && (f.parts == 1 || !have_ws)) {  // one launch; also the answer to a missing workspace
         ProfScope ps(TOPLOC_KERNEL_BUILD, st);
-        if (n_chunks < kShortLaunchGroups)
-            hipLaunchKernelGGL((build_kernel<128, kCapSmall, Field16, Bf16Fmt, kLoadsShort, kWavesShort>),
-                               dim3((uint32_t)n_chunks), dim3(kThreads), 0, st, (const u32x4*)d_hidden_bf16, nvec, k,
-                               d_proofs, d_status, d_topk_idx_opt);
-        else
-            hipLaunchKernelGGL((build_kernel<128, kCapSmall>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
-                               (const u32x4*)d_hidden_bf16, nvec, k, d_proofs, d_status, d_topk_idx_opt);
+        hipLaunchKernelGGL((build_kernel<128, kCapSmall>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
+                           (const u32x4*)d_hidden_bf16, nvec, k, d_proofs, d_status, d_topk_idx_opt);
         return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
     }
     if (!have_ws) return d_workspace ? TOPLOC_EWORKSPACE : TOPLOC_EINVAL;
@@ -829,11 +812,7 @@ int toploc_verify_proofs(const void* d_hidden_bf16, uint64_t n_chunks, const top
     const bool split = f.parts > 1 && d_workspace && workspace_bytes >= cand_bytes(slots, k) && slots < (1ull << 31);
     if (!split) {  // one launch; a missing workspace only costs speed on small batches
         ProfScope ps(TOPLOC_KERNEL_VERIFY, st);
-        if (k <= 128 && n_chunks < kShortLaunchGroups)
-            hipLaunchKernelGGL((verify_kernel<128, kCapSmall, Field16, Bf16Fmt, kLoadsShort, kWavesShort>),
-                               dim3((uint32_t)n_chunks), dim3(kThreads), 0, st, (const u32x4*)d_hidden_bf16, nvec, k,
-                               d_proofs, *thresholds, d_results);
-        else if (k <= 128)
+        if (k <= 128)
             hipLaunchKernelGGL((verify_kernel<128, kCapSmall>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
                                (const u32x4*)d_hidden_bf16, nvec, k, d_proofs, *thresholds, d_results);
         else
