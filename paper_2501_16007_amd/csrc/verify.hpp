@@ -136,12 +136,14 @@ __device__ __forceinline__ void verify_tail(VerifyShared<KMAX, WIDE>& vs, const 
             const uint32_t x2 = F::mulmod(x, x);
             const int terms = (int)((k - h + 1u) / 2u);   // coefficients h, h + 2, ...
             acc = 0;
+#pragma unroll 8   // eight coefficient reads in flight per round trip to LDS instead of one
             for (int i = terms - 1; i >= 0; --i) acc = F::muladdmod(acc, x2, vs.coef[2 * i + (int)h]);
             const uint32_t odd = __shfl_xor(acc, 1);      // the partner's chain
             acc = F::muladdmod(odd, x, acc);              // meaningful in the even lane
             if (h) continue;
         } else {
             acc = vs.coef[k - 1];
+#pragma unroll 8
             for (int i = (int)k - 2; i >= 0; --i) acc = F::muladdmod(acc, x, vs.coef[i]);
         }
         const uint32_t v = cand_bits[j];
