@@ -41,6 +41,12 @@
 
 namespace toploc {
 
+// prune: up to this many entries of the k-th magnitude are ranked against each other directly
+constexpr int kRankDirect = 256;
+// ... and always in the kernels whose candidate buffer is no larger than this: they run at their
+// register limit, the ranking then costs at most CAP^2 / THREADS steps, on tie-heavy data only
+constexpr int kRankDirectCap = 2048;
+
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -101,6 +107,8 @@ struct SelectShared {
     uint32_t qcount[2];       // queue slots handed out (may run past QCAP on overflow); one counter per
                               // drain epoch, so that the next epoch's is cleared without a barrier of its own
     uint32_t count;           // candidate slots in use
+    uint32_t count_base;      // `count` as the last prune (or the start) left it: what a sweep that ran past CAP
+                              // falls back to.  Written by lane 0 behind a barrier, never while a sweep appends
     uint32_t eq_count;
     uint32_t found_bin, found_above;  // prune: what wave 0 found in a histogram, for the other waves
     uint32_t hole_count;      // prune: slots below k whose entry does not survive
@@ -173,6 +181,39 @@ __device__ __forceinline__ bool before(int32_t mag, uint32_t idx, const Threshol
     return mag > t.tm || (mag == t.tm && idx < t.ti);
 }
 
+// Prune, tie-heavy data (all equal, a handful of distinct values): the need-th smallest index among
+// the E entries listed in eq_slot becomes the threshold index.  Ranking every entry against every other
+// one would cost E^2 / THREADS steps; this is a radix descent over the complemented index instead (the
+// need-th smallest index is the need-th largest complement), 8 bits per level.  Used by the selection
+// with the wide candidate buffer only (see kRankDirectCap).  All threads call.
+template <int THREADS, int CAP, int QCAP, typename Fmt>
+__device__ __forceinline__ void rank_by_radix(SelectShared<THREADS, CAP, QCAP, Fmt>& s, uint32_t E, uint32_t need,
+                                           uint32_t new_tm)
+{
+    const uint32_t tid = threadIdx.x;
+    uint32_t pre = 0, abv = 0;
+#pragma unroll 1
+    for (int sh = 24; sh >= 0; sh -= 8) {
+        for (uint32_t b = tid; b < 256u; b += THREADS) s.hist[0][b] = 0;
+        __syncthreads();
+#pragma unroll 1
+        for (uint32_t q = tid; q < E; q += THREADS) {
+            const uint32_t ci = ~s.cand_idx[s.eq_slot[q]];
+            if ((uint32_t)((uint64_t)ci >> (sh + 8)) == pre) atomicAdd(&s.hist[0][(ci >> sh) & 255u], 1u);
+        }
+        __syncthreads();
+        if (tid < 64) {
+            uint32_t d, a;
+            find_bin<4>(s.hist[0], abv, need, d, a);
+            if (tid == 0) { s.found_bin = d; s.found_above = a; }
+        }
+        __syncthreads();
+        pre = (pre << 8) | s.found_bin;
+        abv = s.found_above;
+    }
+    if (tid == 0) { s.ti = ~pre; s.tm = (int32_t)new_tm; }
+}
+
 // If the candidate buffer holds more than `limit` entries, reduce it to the exact
 // best k and make the k-th the threshold element.  Called by all threads, starts with a
 // barrier and, when it prunes, ends with one.  When it does not prune it ends with a
@@ -189,6 +230,7 @@ __device__ TOPLOC_PRUNE_ATTR uint32_t prune_if_above(SelectShared<THREADS, CAP, 
     __syncthreads();  // appends are visible
     const uint32_t M = s.count;
     if (M <= limit || M > (uint32_t)CAP) {  // uniform decision
+        if (tid == 0 && M <= (uint32_t)CAP) s.count_base = M;
         if (SYNC_AFTER) __syncthreads();  // everyone has read the count before anyone appends again
         return M;
     }
@@ -228,11 +270,16 @@ __device__ TOPLOC_PRUNE_ATTR uint32_t prune_if_above(SelectShared<THREADS, CAP, 
     __syncthreads();
     const uint32_t E = s.eq_count;
     // the need-th smallest index among the E equal-magnitude entries is the new threshold element
-    for (uint32_t q = tid; q < E; q += THREADS) {
-        const uint32_t mine = s.cand_idx[s.eq_slot[q]];
-        uint32_t rank = 0;
-        for (uint32_t u = 0; u < E; ++u) rank += (s.cand_idx[s.eq_slot[u]] < mine) ? 1u : 0u;
-        if (rank == need - 1) { s.ti = mine; s.tm = (int32_t)new_tm; }
+    // uniform; the usual case: a few dozen entries share the k-th magnitude
+    if (CAP <= kRankDirectCap || E <= (uint32_t)kRankDirect) {
+        for (uint32_t q = tid; q < E; q += THREADS) {
+            const uint32_t mine = s.cand_idx[s.eq_slot[q]];
+            uint32_t rank = 0;
+            for (uint32_t u = 0; u < E; ++u) rank += (s.cand_idx[s.eq_slot[u]] < mine) ? 1u : 0u;
+            if (rank == need - 1) { s.ti = mine; s.tm = (int32_t)new_tm; }
+        }
+    } else {
+        rank_by_radix(s, E, need, new_tm);
     }
     __syncthreads();
     t.tm = s.tm;
@@ -257,7 +304,7 @@ __device__ TOPLOC_PRUNE_ATTR uint32_t prune_if_above(SelectShared<THREADS, CAP, 
             s.cand_bits[dest] = (typename Fmt::bits_t)bits;
         }
     }
-    if (tid == 0) s.count = k;
+    if (tid == 0) { s.count = k; s.count_base = k; }
     __syncthreads();
     return M;
 }
@@ -311,14 +358,15 @@ __device__ TOPLOC_DRAIN_ATTR bool drain(SelectShared<THREADS, CAP, QCAP, Fmt>& s
     const uint32_t tid = threadIdx.x;
     const uint32_t raw = s.qcount[epoch & 1u];
     const uint32_t nq = raw < (uint32_t)QCAP ? raw : (uint32_t)QCAP;
-    const uint32_t count0 = s.count;  // <= CAP/2; only drains and prunes change it
     if (tid == 0) s.qcount[(epoch + 1u) & 1u] = 0;  // last read one drain ago; visible after the barrier below
     ++epoch;
     limit = limit < (uint32_t)(CAP / 2) ? limit : (uint32_t)(CAP / 2);
     drain_range(s, 0u, nq, t);
     if (prune_if_above<false>(s, k, limit, t) > (uint32_t)CAP) {  // uniform; rare
+        // Undo the sweep: back to the count the last prune left (count_base; <= CAP/2).  It is not read
+        // from s.count at the start of this function, where a wave that runs ahead may already be appending.
         __syncthreads();  // everyone has read the count
-        if (tid == 0) s.count = count0;
+        if (tid == 0) s.count = s.count_base;
         __syncthreads();
         for (uint32_t b0 = 0; b0 < nq; b0 += BATCH) {
             const uint32_t b1 = b0 + BATCH < nq ? b0 + BATCH : nq;
@@ -381,6 +429,14 @@ __device__ __forceinline__ void examine_round(const u32x4 (&buf)[U], uint32_t b,
     }
     while (true) {
         uint32_t* flag = &s.flag[round % 3u];
+        if (__ballot(pend != 0u)) {  // uniform within the wave
+            // A vector whose largest magnitude only equals the threshold's and whose first index is not
+            // below the threshold's holds nothing that comes before the threshold element: without this,
+            // data with many equal magnitudes would queue every vector of every round.
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (m[u] == t.tm && (b + u * THREADS + tid) * (uint32_t)Fmt::ELEMS >= t.ti) pend &= ~(1u << u);
+        }
         if (__ballot(pend != 0u)) {  // uniform within the wave
             uint64_t want[U];
             uint32_t total = 0;
@@ -458,7 +514,7 @@ __device__ __forceinline__ SelectStart select_topk_from(const u32x4* __restrict_
     const uint32_t k = start.k;
     const uint32_t n_seed = start.n;
     if (tid == 0) {
-        s.qcount[0] = 0; s.qcount[1] = 0; s.count = n_seed; s.eq_count = 0; s.tm = start.t.tm; s.ti = start.t.ti;
+        s.qcount[0] = 0; s.qcount[1] = 0; s.count = n_seed; s.count_base = n_seed; s.eq_count = 0; s.tm = start.t.tm; s.ti = start.t.ti;
         s.flag[0] = 0; s.flag[1] = 0; s.flag[2] = 0;
     }
     Threshold t = start.t;
@@ -523,7 +579,7 @@ __device__ __forceinline__ void merge_topk(const uint32_t* __restrict__ c_idx,
                                            SelectShared<THREADS, CAP, QCAP, Fmt>& s)
 {
     const uint32_t tid = threadIdx.x;
-    if (tid == 0) { s.count = 0; s.eq_count = 0; s.tm = 0; s.ti = 0xFFFFFFFFu; }
+    if (tid == 0) { s.count = 0; s.count_base = 0; s.eq_count = 0; s.tm = 0; s.ti = 0xFFFFFFFFu; }
     __syncthreads();
     Threshold t;
     t.tm = 0;
