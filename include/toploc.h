@@ -67,6 +67,8 @@ extern "C" {
                                 /* N not a multiple of 8, N >= 2^32, prime != 65497      */
 #define TOPLOC_EWORKSPACE (-2)  /* workspace smaller than toploc_workspace_bytes()       */
 #define TOPLOC_EHIP (-3)        /* a HIP runtime call failed; see toploc_last_hip_error  */
+#define TOPLOC_ESCRATCH (-4)    /* toploc_build_proofs_static: the batch needs more than */
+                                /* TOPLOC_STATIC_SCRATCH_BYTES of scratch                */
 
 /* per-chunk status codes */
 #define TOPLOC_CHUNK_OK 0
@@ -132,6 +134,25 @@ int toploc_set_split(uint32_t parts_per_chunk);
 int toploc_build_proofs(const void *d_hidden_bf16, uint64_t n_chunks, const toploc_params *params,
                         uint8_t *d_proofs, uint8_t *d_status, uint32_t *d_topk_idx_opt,
                         void *d_workspace, size_t workspace_bytes, void *hip_stream);
+
+/* toploc_build_proofs for callers that cannot allocate device memory or pass a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * same outputs, same bytes as toploc_build_proofs; the scratch that small batches and k > 128
+ * need (top-k candidates of the parts a chunk is cut into) is a fixed array of
+ * TOPLOC_STATIC_SCRATCH_BYTES in device memory that belongs to the library: every GPU the
+ * library runs on holds its own copy until the process ends.  The call allocates nothing, on
+ * the host or on the device.
+ *  - A batch whose cut needs more than TOPLOC_STATIC_SCRATCH_BYTES (6 bytes per candidate: k per
+ *    part; what toploc_workspace_bytes reports) is rejected with TOPLOC_ESCRATCH, nothing enqueued.
+ *    Large batches with k <= 128 run as one fused launch and use no scratch at all.
+ *  - All calls on one GPU share that GPU's array: calls whose work overlaps in time on one GPU
+ *    (different streams, or several host threads) race on it.  Order them on one stream.  Nothing
+ *    in the array needs to start at zero: every slot a merge reads was written by the same call.
+ *  - The first call on a device looks up the array's device address (hipGetSymbolAddress) and
+ *    keeps it; make that first call outside a graph capture. */
+#define TOPLOC_STATIC_SCRATCH_BYTES (8u << 20)
+int toploc_build_proofs_static(const void *d_hidden_bf16, uint64_t n_chunks, const toploc_params *params,
+                               uint8_t *d_proofs, uint8_t *d_status, uint32_t *d_topk_idx_opt, void *hip_stream);
 
 /* Algorithm 2 over n_chunks chunks: decode, top-k of the recomputed tensor,
  * index map, Horner evaluation (Algorithm 5) at the k mapped indices,
@@ -280,8 +301,10 @@ int toploc_stream_emit_rows(void *d_state, uint32_t n_slots, const uint32_t *d_s
 int toploc_bench_read(const void *d_hidden_bf16, uint64_t n_chunks, uint64_t chunk_values, uint32_t *d_out,
                       void *hip_stream);
 
-/* Kernel timing for benchmarks.  While enabled, every kernel launch of the
- * calling thread's device is bracketed by HIP events on the caller's stream.
+/* Kernel timing for benchmarks.  toploc_profile_enable(1) creates a pool of HIP events (the only
+ * place the library creates any; they live until the process ends); while enabled, every kernel
+ * launch is bracketed by two events of the pool on the caller's stream, and a launch that finds the
+ * pool empty (more than 8192 timed launches since the last read) goes untimed.
  * toploc_profile_read synchronises those events and returns, per kernel slot
  * (TOPLOC_KERNEL_*), the number of launches and their summed duration in
  * milliseconds since the last reset, then resets.  The list of events is shared by

@@ -15,7 +15,8 @@ LIB_PATH = os.path.join(_HERE, "libtoploc_hip.so")
 
 PRIME = 65497
 MAX_K = 512
-OK, EINVAL, EWORKSPACE, EHIP = 0, -1, -2, -3
+OK, EINVAL, EWORKSPACE, EHIP, ESCRATCH = 0, -1, -2, -3, -4
+STATIC_SCRATCH_BYTES = 8 << 20
 CHUNK_OK, CHUNK_NO_MODULUS, CHUNK_NO_INVERSE, CHUNK_MALFORMED, CHUNK_SHORT = 0, 1, 2, 3, 4
 (KERNEL_SELECT, KERNEL_PART, KERNEL_BUILD_MERGE, KERNEL_VERIFY_MERGE, KERNEL_BUILD, KERNEL_VERIFY, KERNEL_RING,
  KERNEL_READ, KERNEL_STREAM_APPEND, KERNEL_STREAM_EMIT, KERNEL_COUNT) = range(11)
@@ -47,6 +48,7 @@ EXPORTS = (
     "toploc_build_proofs_segments",
     "toploc_verify_proofs_segments",
     "toploc_build_proofs",
+    "toploc_build_proofs_static",
     "toploc_verify_proofs",
     "toploc_topk",
     "toploc_proof_bytes_dtype",
@@ -107,6 +109,7 @@ def lib():
         L.toploc_build_proofs.argtypes = [P, c.c_uint64, c.POINTER(Params), P, P, P, P, c.c_size_t, P]
         L.toploc_verify_proofs.argtypes = [P, c.c_uint64, c.POINTER(Params), P, c.POINTER(Thresholds), P, P,
                                            c.c_size_t, P]
+        L.toploc_build_proofs_static.argtypes = [P, c.c_uint64, c.POINTER(Params), P, P, P, P]
         L.toploc_topk.argtypes = [P, c.c_uint64, c.POINTER(Params), P, P, P]
         L.toploc_set_split.argtypes = [c.c_uint32]
         L.toploc_segments_workspace_bytes.argtypes = [P, c.c_uint64, c.c_uint32, c.c_uint32]
@@ -197,6 +200,19 @@ def toploc_build_proofs(hidden, k=128, chunk_tokens=32, want_topk=False, workspa
     if rc != OK:
         raise ToplocError(rc, "toploc_build_proofs")
     return (proofs, status, idx) if want_topk else (proofs, status)
+
+
+def toploc_build_proofs_static(hidden, out, k=128, chunk_tokens=32, topk_out=None):
+    """toploc_build_proofs with the library's own fixed scratch: allocates nothing, so the caller passes
+    every output. out = (proofs uint8 [n_chunks, 2+2k], status uint8 [n_chunks]); topk_out int32 [n_chunks, k]."""
+    n_chunks, h = _chunks(hidden, chunk_tokens)
+    p = Params(k, chunk_tokens, h, PRIME)
+    proofs, status = out
+    rc = lib().toploc_build_proofs_static(
+        hidden.data_ptr(), n_chunks, ctypes.byref(p), proofs.data_ptr(), status.data_ptr(),
+        topk_out.data_ptr() if topk_out is not None else None, _stream(hidden))
+    if rc != OK:
+        raise ToplocError(rc, "toploc_build_proofs_static")
 
 
 def toploc_verify_proofs(hidden, proofs, k=128, chunk_tokens=32, thresholds=BF16_THRESHOLDS, out=None, workspace=None):

@@ -487,7 +487,9 @@ static std::atomic<int> g_profile_on{0};
 static std::atomic<uint32_t> g_force_parts{0};  // toploc_set_split: 0 = choose, n = cut every chunk into n parts
 struct ProfRec { int slot; hipEvent_t a, b; };
 static std::mutex g_prof_mutex;
-static std::vector<ProfRec> g_prof;
+static std::vector<ProfRec> g_prof;            // recorded, not yet read
+static std::vector<hipEvent_t> g_event_pool;   // created by toploc_profile_enable, never by a launch
+constexpr size_t kProfPairs = 8192;            // launches that can be timed between two reads
 
 static bool hip_ok(hipError_t e)
 {
@@ -495,20 +497,37 @@ static bool hip_ok(hipError_t e)
     return true;
 }
 
+// Brackets one kernel launch with two events of the pool while timing is enabled.  With timing
+// off (the default) it does nothing; with the pool empty the launch simply goes untimed: a launch
+// never creates or destroys an event.
 struct ProfScope {
     int slot; hipStream_t st; hipEvent_t a = nullptr, b = nullptr; bool on;
     ProfScope(int slot_, hipStream_t st_) : slot(slot_), st(st_), on(g_profile_on != 0)
     {
-        if (on) {
-            on = hip_ok(hipEventCreate(&a)) && hip_ok(hipEventCreate(&b)) && hip_ok(hipEventRecord(a, st));
+        if (!on) return;
+        {
+            std::lock_guard<std::mutex> lock(g_prof_mutex);
+            on = g_event_pool.size() >= 2;
+            if (on) {
+                a = g_event_pool.back(); g_event_pool.pop_back();
+                b = g_event_pool.back(); g_event_pool.pop_back();
+            }
         }
+        if (on && !hip_ok(hipEventRecord(a, st))) give_back();
     }
     ~ProfScope()
     {
-        if (on && hip_ok(hipEventRecord(b, st))) {
-            std::lock_guard<std::mutex> lock(g_prof_mutex);
-            g_prof.push_back({slot, a, b});
-        }
+        if (!on) return;
+        if (!hip_ok(hipEventRecord(b, st))) { give_back(); return; }
+        std::lock_guard<std::mutex> lock(g_prof_mutex);
+        g_prof.push_back({slot, a, b});
+    }
+    void give_back()
+    {
+        std::lock_guard<std::mutex> lock(g_prof_mutex);
+        g_event_pool.push_back(a);
+        g_event_pool.push_back(b);
+        on = false;
     }
 };
 
@@ -760,20 +779,12 @@ int toploc_topk(const void* d_hidden_bf16, uint64_t n_chunks, const toploc_param
     return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
 }
 
-int toploc_build_proofs(const void* d_hidden_bf16, uint64_t n_chunks, const toploc_params* params, uint8_t* d_proofs,
-                        uint8_t* d_status, uint32_t* d_topk_idx_opt, void* d_workspace, size_t workspace_bytes,
-                        void* hip_stream)
+// Algorithm 1 over fixed chunks with the cut already chosen (`f`): one fused launch, or the split pair
+// of launches with the candidates in `d_workspace`.  Arguments are checked by the callers.
+static int build_fixed(const FixedPlan& f, const void* d_hidden_bf16, uint64_t n_chunks, uint32_t nvec, uint32_t k,
+                       uint8_t* d_proofs, uint8_t* d_status, uint32_t* d_topk_idx_opt, void* d_workspace,
+                       size_t workspace_bytes, hipStream_t st)
 {
-    const uint64_t n = chunk_len(params);
-    if (n == 0 || n_chunks >= (1ull << 31)) return TOPLOC_EINVAL;
-    if (n_chunks == 0) return TOPLOC_OK;
-    if (!d_hidden_bf16 || !d_proofs || !d_status || !aligned16(d_hidden_bf16)) return TOPLOC_EINVAL;
-    if ((reinterpret_cast<uintptr_t>(d_proofs) & 1u) != 0) return TOPLOC_EINVAL;
-    if (d_workspace && !aligned16(d_workspace)) return TOPLOC_EINVAL;
-    const uint32_t k = params->k;
-    const uint32_t nvec = (uint32_t)(n / 8);
-    hipStream_t st = (hipStream_t)hip_stream;
-    FixedPlan f = plan_fixed(n_chunks, nvec);
     const bool have_ws = d_workspace && workspace_bytes >= cand_bytes(n_chunks * f.parts, k);
     if (k <= 128 && (f.parts == 1 || !have_ws)) {  // one launch; also the answer to a missing workspace
         ProfScope ps(TOPLOC_KERNEL_BUILD, st);
@@ -791,6 +802,70 @@ int toploc_build_proofs(const void* d_hidden_bf16, uint64_t n_chunks, const topl
     if (!hip_ok(hipGetLastError())) return TOPLOC_EHIP;
     launch_build_merge(st, lay, n_chunks, k, c_idx, c_bits, d_proofs, d_status, d_topk_idx_opt);
     return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
+}
+
+int toploc_build_proofs(const void* d_hidden_bf16, uint64_t n_chunks, const toploc_params* params, uint8_t* d_proofs,
+                        uint8_t* d_status, uint32_t* d_topk_idx_opt, void* d_workspace, size_t workspace_bytes,
+                        void* hip_stream)
+{
+    const uint64_t n = chunk_len(params);
+    if (n == 0 || n_chunks >= (1ull << 31)) return TOPLOC_EINVAL;
+    if (n_chunks == 0) return TOPLOC_OK;
+    if (!d_hidden_bf16 || !d_proofs || !d_status || !aligned16(d_hidden_bf16)) return TOPLOC_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(d_proofs) & 1u) != 0) return TOPLOC_EINVAL;
+    if (d_workspace && !aligned16(d_workspace)) return TOPLOC_EINVAL;
+    const uint32_t nvec = (uint32_t)(n / 8);
+    return build_fixed(plan_fixed(n_chunks, nvec), d_hidden_bf16, n_chunks, nvec, params->k, d_proofs, d_status,
+                       d_topk_idx_opt, d_workspace, workspace_bytes, (hipStream_t)hip_stream);
+}
+
+// ---------------------------------------------------------------------------
+// toploc_build_proofs for callers that cannot allocate: the candidates of a split launch go to a
+// fixed array in device memory that belongs to the library (one copy per GPU, at its own address,
+// held until the process ends).  Host code never passes the array by name: the name is only the
+// host-side handle hipGetSymbolAddress turns into the device address, once per device.
+// ---------------------------------------------------------------------------
+constexpr size_t kScratchBytes = (size_t)TOPLOC_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices];   // device address of `scratch` on device i, once looked up
+
+// the current device's copy of the scratch array
+static int scratch_of_current_device(void** out)
+{
+    int dev = -1;
+    if (!hip_ok(hipGetDevice(&dev))) return TOPLOC_EHIP;
+    if (dev < 0 || dev >= kMaxDevices) return TOPLOC_EINVAL;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (!hip_ok(hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch))) || !ptr) return TOPLOC_EHIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return TOPLOC_OK;
+}
+
+int toploc_build_proofs_static(const void* d_hidden_bf16, uint64_t n_chunks, const toploc_params* params,
+                               uint8_t* d_proofs, uint8_t* d_status, uint32_t* d_topk_idx_opt, void* hip_stream)
+{
+    const uint64_t n = chunk_len(params);
+    if (n == 0 || n_chunks >= (1ull << 31)) return TOPLOC_EINVAL;
+    if (n_chunks == 0) return TOPLOC_OK;
+    if (!d_hidden_bf16 || !d_proofs || !d_status || !aligned16(d_hidden_bf16)) return TOPLOC_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(d_proofs) & 1u) != 0) return TOPLOC_EINVAL;
+    const uint32_t nvec = (uint32_t)(n / 8);
+    const FixedPlan f = plan_fixed(n_chunks, nvec);
+    const bool fused = f.parts == 1 && params->k <= 128;   // no scratch at all
+    if (!fused && cand_bytes(n_chunks * f.parts, params->k) > kScratchBytes) return TOPLOC_ESCRATCH;
+    void* ptr = nullptr;
+    if (!fused) {
+        const int rc = scratch_of_current_device(&ptr);
+        if (rc != TOPLOC_OK) return rc;
+    }
+    return build_fixed(f, d_hidden_bf16, n_chunks, nvec, params->k, d_proofs, d_status, d_topk_idx_opt, ptr,
+                       fused ? 0 : kScratchBytes, (hipStream_t)hip_stream);
 }
 
 int toploc_verify_proofs(const void* d_hidden_bf16, uint64_t n_chunks, const toploc_params* params,
@@ -1171,6 +1246,14 @@ int toploc_bench_read(const void* d_hidden_bf16, uint64_t n_chunks, uint64_t chu
 
 int toploc_profile_enable(int on)
 {
+    if (on) {  // the only place events are created: up to kProfPairs launches can be timed between two reads
+        std::lock_guard<std::mutex> lock(g_prof_mutex);
+        while (g_event_pool.size() + 2 * g_prof.size() < 2 * kProfPairs) {
+            hipEvent_t e;
+            if (!hip_ok(hipEventCreate(&e))) return TOPLOC_EHIP;
+            g_event_pool.push_back(e);
+        }
+    }
     g_profile_on = on ? 1 : 0;
     return TOPLOC_OK;
 }
@@ -1189,8 +1272,8 @@ int toploc_profile_read(uint32_t* launches, float* total_ms)
         } else {
             rc = TOPLOC_EHIP;
         }
-        (void)hipEventDestroy(r.a);
-        (void)hipEventDestroy(r.b);
+        g_event_pool.push_back(r.a);   // back to the pool: events live until the process ends
+        g_event_pool.push_back(r.b);
     }
     g_prof.clear();
     return rc;
@@ -1204,6 +1287,8 @@ const char* toploc_strerror(int code)
                                "chunk length not a multiple of 8 or >= 2^32, prime != 65497, workspace missing where needed)";
     case TOPLOC_EWORKSPACE: return "workspace smaller than the workspace_bytes function reports";
     case TOPLOC_EHIP: return "a HIP runtime call failed (see toploc_last_hip_error)";
+    case TOPLOC_ESCRATCH: return "the batch needs more scratch than the library's fixed array holds "
+                                 "(TOPLOC_STATIC_SCRATCH_BYTES): use toploc_build_proofs with a workspace";
     default: return "unknown toploc error code";
     }
 }

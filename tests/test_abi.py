@@ -133,3 +133,22 @@ def test_newer_entry_points_check_their_arguments_before_any_launch():
                                                  ctypes.byref(thr), fake, fake, 1 << 30, None) == binding.EINVAL
     assert L.toploc_verify_proofs_segments_mixed(fake, binding.DTYPE_F32, off, 0, 4096, 128, fake, binding.DTYPE_F32,
                                                  ctypes.byref(thr), fake, fake, 0, None) == binding.OK
+
+
+def test_static_scratch_entry_point_rejects_before_any_launch():
+    L = binding.lib()
+    fake = ctypes.c_void_p(1 << 40)  # never dereferenced: every call below is refused or empty
+    ok = binding.Params(128, 32, 4096, binding.PRIME)
+    bad = binding.Params(0, 32, 4096, binding.PRIME)
+    assert L.toploc_build_proofs_static(fake, 1, ctypes.byref(bad), fake, fake, None, None) == binding.EINVAL
+    assert L.toploc_build_proofs_static(None, 1, ctypes.byref(ok), fake, fake, None, None) == binding.EINVAL
+    assert L.toploc_build_proofs_static(ctypes.c_void_p((1 << 40) + 8), 1, ctypes.byref(ok), fake, fake, None,
+                                        None) == binding.EINVAL                 # misaligned input
+    assert L.toploc_build_proofs_static(fake, 0, ctypes.byref(ok), fake, fake, None, None) == binding.OK
+    # 16384 chunks at k = 512 hand 16384 x 512 candidates of 6 bytes on: far beyond the fixed array
+    big = binding.Params(512, 32, 8192, binding.PRIME)
+    assert binding.toploc_workspace_bytes(512, 32, 8192, 16384) > binding.STATIC_SCRATCH_BYTES
+    assert L.toploc_build_proofs_static(fake, 16384, ctypes.byref(big), fake, fake, None, None) == binding.ESCRATCH
+    assert b"TOPLOC_STATIC_SCRATCH_BYTES" in L.toploc_strerror(binding.ESCRATCH)
+    hdr = open(os.path.join(ROOT, "include", "toploc.h")).read()
+    assert re.search(r"#define TOPLOC_STATIC_SCRATCH_BYTES \(8u << 20\)", hdr) and binding.STATIC_SCRATCH_BYTES == 8 << 20
