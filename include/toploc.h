@@ -14,8 +14,9 @@
  *  - The caller owns every buffer.  The library allocates no device memory and
  *    keeps no reference after the work it enqueued has finished.
  *  - All work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL is
- *    the default stream).  No entry point synchronises; results are valid once
- *    the stream has reached the end of the enqueued work.
+ *    the default stream).  No entry point synchronises or copies: every call only
+ *    launches kernels (so it can be captured into a HIP graph); results are valid
+ *    once the stream has reached the end of the enqueued work.
  *  - bf16 values are read and written as their 16-bit patterns.  No floating
  *    point arithmetic happens anywhere on the path.
  *  - Return value: TOPLOC_OK (0) when the work was enqueued, a negative
@@ -73,10 +74,13 @@ extern "C" {
 /* per-chunk status codes */
 #define TOPLOC_CHUNK_OK 0
 #define TOPLOC_CHUNK_NO_MODULUS 1   /* Algorithm 6 exhausted [2^15+1, 65536]             */
-#define TOPLOC_CHUNK_NO_INVERSE 2   /* Algorithm 4's error exit; unreachable once the    */
-                                    /* modulus makes the points distinct in GF(p)        */
+/* 2 is not used: Algorithm 4's error exit (no inverse) cannot be reached once the modulus   */
+/* makes the points distinct in GF(p)                                                        */
 #define TOPLOC_CHUNK_MALFORMED 3    /* verify: decoded m < 2^15+1 or a coefficient >= p  */
-#define TOPLOC_CHUNK_SHORT 4        /* streaming emit: fewer than k values were appended */
+#define TOPLOC_CHUNK_SHORT 4        /* fewer than k values: a streaming emit before k    */
+                                    /* values were appended, a segment shorter than k    */
+#define TOPLOC_CHUNK_BAD_SEGMENT 5  /* segment calls: row offsets that decrease, leave   */
+                                    /* the matrix, or span 2^32 values or more           */
 
 typedef struct {
     uint32_t k;             /* top-k parameter of Algorithms 1 and 2 (128 in the paper) */
@@ -112,10 +116,16 @@ size_t toploc_proof_bytes(uint32_t k);
  * 0 means one fused launch needs no scratch (large batches, k <= 128), or invalid
  * parameters.  Host only. */
 size_t toploc_workspace_bytes(const toploc_params *params, uint64_t n_chunks);
+/* The same with the two meanings of 0 told apart: TOPLOC_EINVAL for unusable parameters (then
+ * *bytes = 0), TOPLOC_OK with *bytes = 0 when no scratch is needed.  The cut (and with it the size)
+ * depends on toploc_set_split: do not change that switch between the query and the call it sizes
+ * (a build with k > 128 would be refused with TOPLOC_EWORKSPACE, other calls fall back to the
+ * fused launch). */
+int toploc_workspace_query(const toploc_params *params, uint64_t n_chunks, size_t *bytes);
 
 /* Tuning / test knob: 0 (default) lets the library choose into how many parts a chunk
- * is cut, n >= 1 forces n parts per chunk (per longest segment for the *_segments
- * calls).  Affects later calls, including the workspace_bytes functions. */
+ * is cut, n >= 1 forces n parts per chunk (for the *_segments calls: n parts per segment
+ * of average length).  Affects later calls, including the workspace_bytes functions. */
 int toploc_set_split(uint32_t parts_per_chunk);
 
 /* Algorithm 1 over n_chunks chunks: top-k by magnitude, injective modulus
@@ -178,24 +188,32 @@ int toploc_topk(const void *d_hidden_bf16, uint64_t n_chunks, const toploc_param
 /* The same two algorithms over SEGMENTS of unequal length: the proof over a whole
  * prompt (Section 5.6: a set of top-k values is also kept for the activations of the
  * input prompt) and the ragged last chunk of a generation.  The activations are one
- * [total_rows][hidden] bf16 matrix; segment i is rows h_row_offsets[i] ..
- * h_row_offsets[i+1]-1 (n_segments + 1 non-decreasing HOST values), its flat index is
- * (row - first row) * hidden + channel.  Every segment must hold at least k and fewer
- * than 2^32 values; hidden must be a multiple of 8.  Proofs, status, results and the
- * optional indices are laid out per segment exactly as per chunk above; prime and
- * proof layout are the same.  Long segments are cut into parts like small batches.
- * d_workspace (required, 16-byte aligned) must hold toploc_segments_workspace_bytes()
- * bytes; the calls copy two small tables into it with hipMemcpyAsync from pageable
- * host memory, which may wait for earlier work of the stream (so these two calls, unlike
- * all others here, are not meant to be captured into a HIP graph). */
-size_t toploc_segments_workspace_bytes(const uint64_t *h_row_offsets, uint64_t n_segments, uint32_t hidden,
-                                       uint32_t k);
-int toploc_build_proofs_segments(const void *d_hidden_bf16, const uint64_t *h_row_offsets, uint64_t n_segments,
-                                 uint32_t hidden, uint32_t k, uint8_t *d_proofs, uint8_t *d_status,
+ * [total_rows][hidden] bf16 matrix; segment i is rows d_row_offsets[i] ..
+ * d_row_offsets[i+1]-1, its flat index is (row - first row) * hidden + channel.
+ *   total_rows      rows of the matrix: no segment may reach beyond it
+ *   d_row_offsets   in, DEVICE, n_segments + 1 non-decreasing uint64 row numbers (a serving
+ *                   engine's cumulative sequence lengths), 8-byte aligned.  The host never
+ *                   reads them: the cut into parts is planned from n_segments, total_rows and
+ *                   hidden alone and a small kernel derives every part from the offsets, so
+ *                   the calls only launch kernels and can be captured into a HIP graph; a
+ *                   replay uses whatever the array holds then
+ *   hidden          a multiple of 8
+ * Proofs, status, results and the optional indices are laid out per segment exactly as per
+ * chunk above; prime and proof layout are the same.  Per segment, not per call: a segment
+ * with fewer than k values gets TOPLOC_CHUNK_SHORT, one whose offsets decrease, leave the
+ * matrix or span 2^32 values or more gets TOPLOC_CHUNK_BAD_SEGMENT; both get a zero-filled
+ * proof (indices 0xFFFFFFFF) from a build and accept = 0 from a verify.  Offsets that are
+ * not monotonic as a whole leave the other segments' results undefined, but never lead to
+ * an access outside the matrix or the workspace.  Long segments are cut into parts like
+ * small batches.  d_workspace (required, 16-byte aligned) must hold
+ * toploc_segments_workspace_bytes() bytes. */
+size_t toploc_segments_workspace_bytes(uint64_t n_segments, uint64_t total_rows, uint32_t hidden, uint32_t k);
+int toploc_build_proofs_segments(const void *d_hidden_bf16, uint64_t total_rows, const uint64_t *d_row_offsets,
+                                 uint64_t n_segments, uint32_t hidden, uint32_t k, uint8_t *d_proofs, uint8_t *d_status,
                                  uint32_t *d_topk_idx_opt, void *d_workspace, size_t workspace_bytes,
                                  void *hip_stream);
-int toploc_verify_proofs_segments(const void *d_hidden_bf16, const uint64_t *h_row_offsets, uint64_t n_segments,
-                                  uint32_t hidden, uint32_t k, const uint8_t *d_proofs,
+int toploc_verify_proofs_segments(const void *d_hidden_bf16, uint64_t total_rows, const uint64_t *d_row_offsets,
+                                  uint64_t n_segments, uint32_t hidden, uint32_t k, const uint8_t *d_proofs,
                                   const toploc_thresholds *thresholds, toploc_verify_result *d_results,
                                   void *d_workspace, size_t workspace_bytes, void *hip_stream);
 
@@ -235,17 +253,17 @@ int toploc_build_proofs_f32(const void *d_hidden_f32, uint64_t n_chunks, const t
 int toploc_verify_proofs_mixed(const void *d_hidden, uint32_t hidden_dtype, uint64_t n_chunks, const toploc_params *params,
                                const uint8_t *d_proofs, uint32_t proof_dtype, const toploc_thresholds *thresholds,
                                toploc_verify_result *d_results, void *hip_stream);
-size_t toploc_segments_workspace_bytes_dtype(const uint64_t *h_row_offsets, uint64_t n_segments, uint32_t hidden,
-                                             uint32_t k, uint32_t hidden_dtype);
-int toploc_build_proofs_segments_f32(const void *d_hidden_f32, const uint64_t *h_row_offsets, uint64_t n_segments,
-                                     uint32_t hidden, uint32_t k, uint8_t *d_proofs, uint8_t *d_status,
-                                     uint32_t *d_topk_idx_opt, void *d_workspace, size_t workspace_bytes,
-                                     void *hip_stream);
-int toploc_verify_proofs_segments_mixed(const void *d_hidden, uint32_t hidden_dtype, const uint64_t *h_row_offsets,
-                                        uint64_t n_segments, uint32_t hidden, uint32_t k, const uint8_t *d_proofs,
-                                        uint32_t proof_dtype, const toploc_thresholds *thresholds,
-                                        toploc_verify_result *d_results, void *d_workspace, size_t workspace_bytes,
-                                        void *hip_stream);
+size_t toploc_segments_workspace_bytes_dtype(uint64_t n_segments, uint64_t total_rows, uint32_t hidden, uint32_t k,
+                                             uint32_t hidden_dtype);
+int toploc_build_proofs_segments_f32(const void *d_hidden_f32, uint64_t total_rows, const uint64_t *d_row_offsets,
+                                     uint64_t n_segments, uint32_t hidden, uint32_t k, uint8_t *d_proofs,
+                                     uint8_t *d_status, uint32_t *d_topk_idx_opt, void *d_workspace,
+                                     size_t workspace_bytes, void *hip_stream);
+int toploc_verify_proofs_segments_mixed(const void *d_hidden, uint32_t hidden_dtype, uint64_t total_rows,
+                                        const uint64_t *d_row_offsets, uint64_t n_segments, uint32_t hidden, uint32_t k,
+                                        const uint8_t *d_proofs, uint32_t proof_dtype,
+                                        const toploc_thresholds *thresholds, toploc_verify_result *d_results,
+                                        void *d_workspace, size_t workspace_bytes, void *hip_stream);
 
 /* Online path without the ring (a design of this build; the paper's provider keeps the
  * last hidden states, Table 6, only to take their top-k when the proof is cut).  Per
@@ -260,9 +278,7 @@ int toploc_verify_proofs_segments_mixed(const void *d_hidden, uint32_t hidden_dt
  *                               position at most once per chunk, any order) of every
  *                               sequence: d_step_bf16 [n_seq][hidden]; the flat index of
  *                               channel c is token*hidden + c.  hidden % 8 == 0,
- *                               chunk_tokens*hidden < 2^32, d_step_bf16 16-byte aligned (and,
- *                               because the kernel forms row - token*hidden, not within the
- *                               first 2*chunk_tokens*hidden bytes of the address space)
+ *                               chunk_tokens*hidden < 2^32, d_step_bf16 16-byte aligned
  *   toploc_stream_emit          Algorithm 1 steps 2-5 on every sequence's k pairs: proofs,
  *                               status (TOPLOC_CHUNK_SHORT when fewer than k values were
  *                               appended) and optionally the ordered indices, laid out as by

@@ -35,12 +35,22 @@ RESULT_DTYPE = np.dtype(
 assert RESULT_DTYPE.itemsize == 20
 
 
+# TOPLOC_ORACLE_SANITIZE=undefined selects a second build of the same two C files with gcc's
+# undefined-behaviour sanitizer (every finding aborts), so that the pins can be run against it.
+_SANITIZE = os.environ.get("TOPLOC_ORACLE_SANITIZE", "")
+if _SANITIZE:
+    _LIB = os.path.join(_HERE, "libtoploc_oracle_%s.so" % _SANITIZE.replace(",", "_"))
+
+
 def build_library(force=False):
     """Compile the oracle with gcc (plain C11, -O2, OpenMP over chunks)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < max(os.path.getmtime(_SRC),
                                                                           os.path.getmtime(_SRC32)):
+        flags = ["-O2"]
+        if _SANITIZE:
+            flags = ["-O1", "-g", "-fsanitize=" + _SANITIZE, "-fno-sanitize-recover=all"]
         subprocess.check_call(
-            ["gcc", "-O2", "-std=gnu11", "-Wall", "-Wextra", "-fopenmp", "-fPIC", "-shared", _SRC, _SRC32, "-o", _LIB]
+            ["gcc"] + flags + ["-std=gnu11", "-Wall", "-Wextra", "-fopenmp", "-fPIC", "-shared", _SRC, _SRC32, "-o", _LIB]
         )
     return _LIB
 

@@ -17,7 +17,7 @@ PRIME = 65497
 MAX_K = 512
 OK, EINVAL, EWORKSPACE, EHIP, ESCRATCH = 0, -1, -2, -3, -4
 STATIC_SCRATCH_BYTES = 8 << 20
-CHUNK_OK, CHUNK_NO_MODULUS, CHUNK_NO_INVERSE, CHUNK_MALFORMED, CHUNK_SHORT = 0, 1, 2, 3, 4
+CHUNK_OK, CHUNK_NO_MODULUS, CHUNK_MALFORMED, CHUNK_SHORT, CHUNK_BAD_SEGMENT = 0, 1, 3, 4, 5
 (KERNEL_SELECT, KERNEL_PART, KERNEL_BUILD_MERGE, KERNEL_VERIFY_MERGE, KERNEL_BUILD, KERNEL_VERIFY, KERNEL_RING,
  KERNEL_READ, KERNEL_STREAM_APPEND, KERNEL_STREAM_EMIT, KERNEL_COUNT) = range(11)
 KERNEL_NAMES = ("select_kernel", "part_kernel", "build_merge_kernel", "verify_merge_kernel", "build_kernel",
@@ -43,6 +43,7 @@ RESULT_DTYPE = np.dtype(
 EXPORTS = (
     "toploc_proof_bytes",
     "toploc_workspace_bytes",
+    "toploc_workspace_query",
     "toploc_set_split",
     "toploc_segments_workspace_bytes",
     "toploc_build_proofs_segments",
@@ -106,28 +107,31 @@ def lib():
         L.toploc_proof_bytes.restype = c.c_size_t
         L.toploc_workspace_bytes.argtypes = [c.POINTER(Params), c.c_uint64]
         L.toploc_workspace_bytes.restype = c.c_size_t
+        L.toploc_workspace_query.argtypes = [c.POINTER(Params), c.c_uint64, c.POINTER(c.c_size_t)]
         L.toploc_build_proofs.argtypes = [P, c.c_uint64, c.POINTER(Params), P, P, P, P, c.c_size_t, P]
         L.toploc_verify_proofs.argtypes = [P, c.c_uint64, c.POINTER(Params), P, c.POINTER(Thresholds), P, P,
                                            c.c_size_t, P]
         L.toploc_build_proofs_static.argtypes = [P, c.c_uint64, c.POINTER(Params), P, P, P, P]
         L.toploc_topk.argtypes = [P, c.c_uint64, c.POINTER(Params), P, P, P]
         L.toploc_set_split.argtypes = [c.c_uint32]
-        L.toploc_segments_workspace_bytes.argtypes = [P, c.c_uint64, c.c_uint32, c.c_uint32]
+        L.toploc_segments_workspace_bytes.argtypes = [c.c_uint64, c.c_uint64, c.c_uint32, c.c_uint32]
         L.toploc_segments_workspace_bytes.restype = c.c_size_t
-        L.toploc_build_proofs_segments.argtypes = [P, P, c.c_uint64, c.c_uint32, c.c_uint32, P, P, P, P, c.c_size_t, P]
-        L.toploc_verify_proofs_segments.argtypes = [P, P, c.c_uint64, c.c_uint32, c.c_uint32, P, c.POINTER(Thresholds), P,
-                                                    P, c.c_size_t, P]
+        L.toploc_build_proofs_segments.argtypes = [P, c.c_uint64, P, c.c_uint64, c.c_uint32, c.c_uint32, P, P, P, P,
+                                                   c.c_size_t, P]
+        L.toploc_verify_proofs_segments.argtypes = [P, c.c_uint64, P, c.c_uint64, c.c_uint32, c.c_uint32, P,
+                                                    c.POINTER(Thresholds), P, P, c.c_size_t, P]
         L.toploc_ring_append.argtypes = [P, P, c.c_uint32, c.c_uint32, c.c_uint32, c.c_uint32, P]
         L.toploc_proof_bytes_dtype.argtypes = [c.c_uint32, c.c_uint32]
         L.toploc_proof_bytes_dtype.restype = c.c_size_t
         L.toploc_build_proofs_f32.argtypes = [P, c.c_uint64, c.POINTER(Params), P, P, P, P]
         L.toploc_verify_proofs_mixed.argtypes = [P, c.c_uint32, c.c_uint64, c.POINTER(Params), P, c.c_uint32,
                                                  c.POINTER(Thresholds), P, P]
-        L.toploc_segments_workspace_bytes_dtype.argtypes = [P, c.c_uint64, c.c_uint32, c.c_uint32, c.c_uint32]
+        L.toploc_segments_workspace_bytes_dtype.argtypes = [c.c_uint64, c.c_uint64, c.c_uint32, c.c_uint32, c.c_uint32]
         L.toploc_segments_workspace_bytes_dtype.restype = c.c_size_t
-        L.toploc_build_proofs_segments_f32.argtypes = [P, P, c.c_uint64, c.c_uint32, c.c_uint32, P, P, P, P, c.c_size_t, P]
-        L.toploc_verify_proofs_segments_mixed.argtypes = [P, c.c_uint32, P, c.c_uint64, c.c_uint32, c.c_uint32, P, c.c_uint32,
-                                                          c.POINTER(Thresholds), P, P, c.c_size_t, P]
+        L.toploc_build_proofs_segments_f32.argtypes = [P, c.c_uint64, P, c.c_uint64, c.c_uint32, c.c_uint32, P, P, P, P,
+                                                       c.c_size_t, P]
+        L.toploc_verify_proofs_segments_mixed.argtypes = [P, c.c_uint32, c.c_uint64, P, c.c_uint64, c.c_uint32, c.c_uint32, P,
+                                                          c.c_uint32, c.POINTER(Thresholds), P, P, c.c_size_t, P]
         L.toploc_stream_state_bytes.argtypes = [c.c_uint32, c.c_uint32]
         L.toploc_stream_state_bytes.restype = c.c_size_t
         L.toploc_stream_reset.argtypes = [P, c.c_uint32, c.c_uint32, P]
@@ -173,6 +177,14 @@ def toploc_proof_bytes(k):
 def toploc_workspace_bytes(k, chunk_tokens, hidden, n_chunks):
     p = Params(k, chunk_tokens, hidden, PRIME)
     return int(lib().toploc_workspace_bytes(ctypes.byref(p), n_chunks))
+
+
+def toploc_workspace_query(k, chunk_tokens, hidden, n_chunks):
+    """(return code, bytes): tells unusable parameters (EINVAL) from 'no scratch needed' (OK, 0)."""
+    p = Params(k, chunk_tokens, hidden, PRIME)
+    nbytes = ctypes.c_size_t(0)
+    rc = lib().toploc_workspace_query(ctypes.byref(p), n_chunks, ctypes.byref(nbytes))
+    return rc, int(nbytes.value)
 
 
 def new_workspace(k, chunk_tokens, hidden, n_chunks, device):
@@ -259,51 +271,72 @@ def toploc_set_split(parts_per_chunk):
         raise ToplocError(rc, "toploc_set_split")
 
 
-def _segments(hidden, row_offsets):
-    if hidden.dtype != torch.bfloat16 or not hidden.is_cuda or not hidden.is_contiguous() or hidden.dim() != 2:
-        raise ValueError("hidden must be a contiguous [total_rows, H] bf16 tensor on the GPU")
-    off = np.ascontiguousarray(row_offsets, dtype=np.uint64)
-    if off.ndim != 1 or off.size < 1 or int(off[-1]) > hidden.shape[0]:
-        raise ValueError("row_offsets must be a 1-D array of n_segments + 1 row numbers inside the tensor")
-    return off, off.size - 1, hidden.shape[1]
+def _segments_any(hidden, row_offsets):
+    """[total_rows, H] bf16 or fp32 device tensor and n_segments + 1 row offsets -> (offsets as an int64 device
+    tensor, n_segments, H, dtype code).  Offsets given on the host (list, numpy) are checked and uploaded here;
+    an int64 device tensor is handed to the library as it is (the library never reads offsets on the host)."""
+    if hidden.dtype not in (torch.bfloat16, torch.float32) or not hidden.is_cuda or not hidden.is_contiguous() or \
+            hidden.dim() != 2:
+        raise ValueError("hidden must be a contiguous [total_rows, H] bf16 or fp32 tensor on the GPU")
+    if isinstance(row_offsets, torch.Tensor):
+        off = row_offsets
+        if off.dtype != torch.int64 or off.dim() != 1 or off.numel() < 1 or not off.is_contiguous() or \
+                off.device != hidden.device:
+            raise ValueError("row_offsets must be a contiguous 1-D int64 tensor on the device of hidden")
+    else:
+        host = np.ascontiguousarray(row_offsets, dtype=np.uint64)
+        if host.ndim != 1 or host.size < 1 or int(host[-1]) > hidden.shape[0]:
+            raise ValueError("row_offsets must be a 1-D array of n_segments + 1 row numbers inside the tensor")
+        off = torch.from_numpy(host.view(np.int64)).to(hidden.device)
+    return off, off.numel() - 1, hidden.shape[1], (DTYPE_F32 if hidden.dtype == torch.float32 else DTYPE_BF16)
 
 
-def toploc_segments_workspace_bytes(row_offsets, hidden_size, k):
-    off = np.ascontiguousarray(row_offsets, dtype=np.uint64)
-    return int(lib().toploc_segments_workspace_bytes(off.ctypes.data_as(ctypes.c_void_p), off.size - 1, hidden_size, k))
+def toploc_segments_workspace_bytes(n_segments, total_rows, hidden_size, k):
+    return int(lib().toploc_segments_workspace_bytes(n_segments, total_rows, hidden_size, k))
 
 
-def toploc_build_proofs_segments(hidden, row_offsets, k=128, want_topk=False):
-    """Algorithm 1 over segments of rows [row_offsets[i], row_offsets[i+1]) of hidden [total_rows, H]."""
-    off, n_seg, h = _segments(hidden, row_offsets)
+def toploc_segments_workspace_bytes_dtype(n_segments, total_rows, hidden_size, k, hidden_dtype):
+    return int(lib().toploc_segments_workspace_bytes_dtype(n_segments, total_rows, hidden_size, k, hidden_dtype))
+
+
+def new_segments_workspace(hidden, n_segments, k):
+    dt = DTYPE_F32 if hidden.dtype == torch.float32 else DTYPE_BF16
+    nbytes = toploc_segments_workspace_bytes_dtype(n_segments, hidden.shape[0], hidden.shape[1], k, dt)
+    return torch.empty(max(16, nbytes), dtype=torch.uint8, device=hidden.device)
+
+
+def _build_segments(hidden, row_offsets, k, want_topk, want_dtype, workspace, out):
+    off, n_seg, h, dt = _segments_any(hidden, row_offsets)
+    if dt != want_dtype:
+        raise ValueError("hidden must be %s" % ("fp32" if want_dtype == DTYPE_F32 else "bf16"))
     dev = hidden.device
-    proofs = torch.empty((n_seg, 2 + 2 * k), dtype=torch.uint8, device=dev)
-    status = torch.empty(n_seg, dtype=torch.uint8, device=dev)
-    idx = torch.empty((n_seg, k), dtype=torch.int32, device=dev) if want_topk else None
-    ws = torch.empty(max(16, toploc_segments_workspace_bytes(off, h, k)), dtype=torch.uint8, device=dev)
-    rc = lib().toploc_build_proofs_segments(
-        hidden.data_ptr(), off.ctypes.data_as(ctypes.c_void_p), n_seg, h, k, proofs.data_ptr(), status.data_ptr(),
-        idx.data_ptr() if want_topk else None, ws.data_ptr(), ws.numel(), _stream(hidden))
+    if out is None:
+        proofs = torch.empty((n_seg, 2 + (4 if dt == DTYPE_F32 else 2) * k), dtype=torch.uint8, device=dev)
+        status = torch.empty(n_seg, dtype=torch.uint8, device=dev)
+        idx = torch.empty((n_seg, k), dtype=torch.int32, device=dev) if want_topk else None
+    else:
+        proofs, status, idx = out
+    ws = workspace if workspace is not None else new_segments_workspace(hidden, n_seg, k)
+    fn = lib().toploc_build_proofs_segments_f32 if dt == DTYPE_F32 else lib().toploc_build_proofs_segments
+    rc = fn(hidden.data_ptr(), hidden.shape[0], off.data_ptr(), n_seg, h, k, proofs.data_ptr(), status.data_ptr(),
+            idx.data_ptr() if idx is not None else None, ws.data_ptr(), ws.numel(), _stream(hidden))
     if rc != OK:
-        raise ToplocError(rc, "toploc_build_proofs_segments")
+        raise ToplocError(rc, "toploc_build_proofs_segments" + ("_f32" if dt == DTYPE_F32 else ""))
     return (proofs, status, idx) if want_topk else (proofs, status)
 
 
-def toploc_verify_proofs_segments(hidden, row_offsets, proofs, k=128, thresholds=BF16_THRESHOLDS):
+def toploc_build_proofs_segments(hidden, row_offsets, k=128, want_topk=False, workspace=None, out=None):
+    """Algorithm 1 over segments of rows [row_offsets[i], row_offsets[i+1]) of hidden [total_rows, H] bf16.
+    row_offsets: host values or an int64 device tensor; out = (proofs, status, idx or None) to reuse buffers."""
+    return _build_segments(hidden, row_offsets, k, want_topk, DTYPE_BF16, workspace, out)
+
+
+def toploc_verify_proofs_segments(hidden, row_offsets, proofs, k=128, thresholds=BF16_THRESHOLDS, workspace=None, out=None):
     """Algorithm 2 over segments. Returns a uint8 device tensor [n_segments, 20]; see results_numpy."""
-    off, n_seg, h = _segments(hidden, row_offsets)
-    if proofs.dtype != torch.uint8 or not proofs.is_cuda or not proofs.is_contiguous() or \
-            proofs.numel() != n_seg * (2 + 2 * k):
-        raise ValueError("proofs must be a contiguous uint8 device tensor of n_segments * (2+2k) bytes")
-    t = Thresholds(*thresholds)
-    res = torch.empty((n_seg, RESULT_DTYPE.itemsize), dtype=torch.uint8, device=hidden.device)
-    ws = torch.empty(max(16, toploc_segments_workspace_bytes(off, h, k)), dtype=torch.uint8, device=hidden.device)
-    rc = lib().toploc_verify_proofs_segments(
-        hidden.data_ptr(), off.ctypes.data_as(ctypes.c_void_p), n_seg, h, k, proofs.data_ptr(), ctypes.byref(t),
-        res.data_ptr(), ws.data_ptr(), ws.numel(), _stream(hidden))
-    if rc != OK:
-        raise ToplocError(rc, "toploc_verify_proofs_segments")
-    return res
+    if hidden.dtype != torch.bfloat16:
+        raise ValueError("hidden must be bf16")
+    return toploc_verify_proofs_segments_mixed(hidden, row_offsets, proofs, DTYPE_BF16, k=k, thresholds=thresholds,
+                                               workspace=workspace, out=out)
 
 
 def generation_row_offsets(n_prompt, n_total, chunk_tokens=32):
@@ -396,42 +429,13 @@ def toploc_verify_proofs_mixed(hidden, proofs, proof_dtype, k=128, chunk_tokens=
     return res
 
 
-def _segments_any(hidden, row_offsets):
-    """[total_rows, H] bf16 or fp32 device tensor and row offsets -> (offsets uint64, n_segments, H, dtype code)."""
-    if hidden.dtype not in (torch.bfloat16, torch.float32) or not hidden.is_cuda or not hidden.is_contiguous() or \
-            hidden.dim() != 2:
-        raise ValueError("hidden must be a contiguous [total_rows, H] bf16 or fp32 tensor on the GPU")
-    off = np.ascontiguousarray(row_offsets, dtype=np.uint64)
-    if off.ndim != 1 or off.size < 1 or int(off[-1]) > hidden.shape[0]:
-        raise ValueError("row_offsets must be a 1-D array of n_segments + 1 row numbers inside the tensor")
-    return off, off.size - 1, hidden.shape[1], (DTYPE_F32 if hidden.dtype == torch.float32 else DTYPE_BF16)
-
-
-def toploc_segments_workspace_bytes_dtype(row_offsets, hidden_size, k, hidden_dtype):
-    off = np.ascontiguousarray(row_offsets, dtype=np.uint64)
-    return int(lib().toploc_segments_workspace_bytes_dtype(off.ctypes.data_as(ctypes.c_void_p), off.size - 1, hidden_size,
-                                                           k, hidden_dtype))
-
-
-def toploc_build_proofs_segments_f32(hidden, row_offsets, k=128, want_topk=False):
+def toploc_build_proofs_segments_f32(hidden, row_offsets, k=128, want_topk=False, workspace=None, out=None):
     """Algorithm 1 over segments of fp32 rows. Returns (proofs uint8 [n_segments, 2+4k], status[, idx])."""
-    off, n_seg, h, dt = _segments_any(hidden, row_offsets)
-    if dt != DTYPE_F32:
-        raise ValueError("hidden must be fp32")
-    dev = hidden.device
-    proofs = torch.empty((n_seg, 2 + 4 * k), dtype=torch.uint8, device=dev)
-    status = torch.empty(n_seg, dtype=torch.uint8, device=dev)
-    idx = torch.empty((n_seg, k), dtype=torch.int32, device=dev) if want_topk else None
-    ws = torch.empty(max(16, toploc_segments_workspace_bytes_dtype(off, h, k, dt)), dtype=torch.uint8, device=dev)
-    rc = lib().toploc_build_proofs_segments_f32(
-        hidden.data_ptr(), off.ctypes.data_as(ctypes.c_void_p), n_seg, h, k, proofs.data_ptr(), status.data_ptr(),
-        idx.data_ptr() if want_topk else None, ws.data_ptr(), ws.numel(), _stream(hidden))
-    if rc != OK:
-        raise ToplocError(rc, "toploc_build_proofs_segments_f32")
-    return (proofs, status, idx) if want_topk else (proofs, status)
+    return _build_segments(hidden, row_offsets, k, want_topk, DTYPE_F32, workspace, out)
 
 
-def toploc_verify_proofs_segments_mixed(hidden, row_offsets, proofs, proof_dtype, k=128, thresholds=None):
+def toploc_verify_proofs_segments_mixed(hidden, row_offsets, proofs, proof_dtype, k=128, thresholds=None, workspace=None,
+                                        out=None):
     """Algorithm 2 over segments with bf16 or fp32 activations and bf16 or fp32 proofs; thresholds default to
     the paper's for the validator's precision. Returns a uint8 device tensor [n_segments, 20]."""
     off, n_seg, h, dt = _segments_any(hidden, row_offsets)
@@ -441,11 +445,10 @@ def toploc_verify_proofs_segments_mixed(hidden, row_offsets, proofs, proof_dtype
     if thresholds is None:
         thresholds = F32_THRESHOLDS if dt == DTYPE_F32 else BF16_THRESHOLDS
     t = Thresholds(*thresholds)
-    res = torch.empty((n_seg, RESULT_DTYPE.itemsize), dtype=torch.uint8, device=hidden.device)
-    ws = torch.empty(max(16, toploc_segments_workspace_bytes_dtype(off, h, k, dt)), dtype=torch.uint8,
-                     device=hidden.device)
+    res = out if out is not None else torch.empty((n_seg, RESULT_DTYPE.itemsize), dtype=torch.uint8, device=hidden.device)
+    ws = workspace if workspace is not None else new_segments_workspace(hidden, n_seg, k)
     rc = lib().toploc_verify_proofs_segments_mixed(
-        hidden.data_ptr(), dt, off.ctypes.data_as(ctypes.c_void_p), n_seg, h, k, proofs.data_ptr(), proof_dtype,
+        hidden.data_ptr(), dt, hidden.shape[0], off.data_ptr(), n_seg, h, k, proofs.data_ptr(), proof_dtype,
         ctypes.byref(t), res.data_ptr(), ws.data_ptr(), ws.numel(), _stream(hidden))
     if rc != OK:
         raise ToplocError(rc, "toploc_verify_proofs_segments_mixed")

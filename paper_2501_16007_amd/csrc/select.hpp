@@ -384,22 +384,23 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t mask)
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
 
-// One round of loads: vectors b + u*THREADS + tid, u < U.  A round that lies wholly inside
-// [.., v1) is loaded without per-lane tests; vectors past v1 read as zero.
+// One round of loads: vectors b + u*THREADS + tid, u < U, of a range whose vector v0 sits at src
+// (vector v is read from src + (v - v0)).  A round that lies wholly inside [.., v1) is loaded
+// without per-lane tests; vectors past v1 read as zero.
 template <int THREADS, int U>
-__device__ __forceinline__ void load_round(u32x4 (&buf)[U], const u32x4* __restrict__ src, uint32_t b, uint32_t v1)
+__device__ __forceinline__ void load_round(u32x4 (&buf)[U], const u32x4* __restrict__ src, uint32_t v0, uint32_t b,
+                                           uint32_t v1)
 {
     const uint32_t tid = threadIdx.x;
+    const u32x4* p = src + (b - v0);   // uniform
     if (b + THREADS * U <= v1) {  // uniform
-        const u32x4* p = src + b;
 #pragma unroll
         for (int u = 0; u < U; ++u) buf[u] = __builtin_nontemporal_load(p + u * THREADS + tid);
     } else {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const uint32_t v = b + u * THREADS + tid;
             buf[u] = u32x4{0u, 0u, 0u, 0u};
-            if (v < v1) buf[u] = __builtin_nontemporal_load(src + v);
+            if (b + u * THREADS + tid < v1) buf[u] = __builtin_nontemporal_load(p + u * THREADS + tid);
         }
     }
 }
@@ -494,8 +495,8 @@ struct NoSeed {
     __device__ __forceinline__ SelectStart seed(Shared&) const { return SelectStart{0u, Threshold{0, 0xFFFFFFFFu}, k}; }
 };
 
-// Top-k of the vectors [v0, v1) of the chunk at src (8 values per vector, flat index of
-// value e of vector v is ELEMS*v + e) into s.cand_idx / s.cand_bits [0 .. k), in no
+// Top-k of the vectors [v0, v1) of a chunk, vector v0 being the one at src (8 values per vector,
+// flat index of value e of vector v is ELEMS*v + e) into s.cand_idx / s.cand_bits [0 .. k), in no
 // particular order (order_topk sorts them).
 // Requires k <= seeds + ELEMS*(v1 - v0), k <= CAP/4, ELEMS*v1 < 2^32.  All threads of the workgroup
 // call it; it ends with a barrier.  Returns k and the threshold the selection ended with:
@@ -508,8 +509,8 @@ __device__ __forceinline__ SelectStart select_topk_from(const u32x4* __restrict_
     const uint32_t tid = threadIdx.x;
     TOPLOC_TICK_BEGIN(boot);
     u32x4 even[U], odd[U];  // two rounds in registers: one is examined while the other one's loads fly
-    load_round<THREADS, U>(even, src, v0, v1);
-    load_round<THREADS, U>(odd, src, v0 + ROUND, v1);   // in flight while the first threshold is found
+    load_round<THREADS, U>(even, src, v0, v0, v1);
+    load_round<THREADS, U>(odd, src, v0, v0 + ROUND, v1);   // in flight while the first threshold is found
     const SelectStart start = seeder.seed(s);
     const uint32_t k = start.k;
     const uint32_t n_seed = start.n;
@@ -547,11 +548,11 @@ __device__ __forceinline__ SelectStart select_topk_from(const u32x4* __restrict_
         examine_round<THREADS, U>(even, base, v1, k, s, t, round, epoch);
         base += ROUND;
         if (base >= v1) break;
-        load_round<THREADS, U>(even, src, base + ROUND, v1);
+        load_round<THREADS, U>(even, src, v0, base + ROUND, v1);
         examine_round<THREADS, U>(odd, base, v1, k, s, t, round, epoch);
         base += ROUND;
         if (base >= v1) break;
-        load_round<THREADS, U>(odd, src, base + ROUND, v1);
+        load_round<THREADS, U>(odd, src, v0, base + ROUND, v1);
     }
     __syncthreads();
     TOPLOC_TICK_END(stream, 1);

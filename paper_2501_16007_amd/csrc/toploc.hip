@@ -24,12 +24,10 @@
 #include "../../include/toploc.h"
 #include "gf65497.hpp"
 #include "interp.hpp"
+#include "plan.hpp"
 #include "select.hpp"
 #include "verify.hpp"
 
-#ifndef TOPLOC_LOADS
-#define TOPLOC_LOADS 4
-#endif
 #ifndef TOPLOC_QCAP
 #define TOPLOC_QCAP 512
 #endif
@@ -39,8 +37,8 @@
 
 namespace toploc {
 
-constexpr int kThreads = 256;             // lanes per streaming workgroup
-constexpr int kLoads = TOPLOC_LOADS;      // 16-byte loads in flight per lane and round
+constexpr int kThreads = (int)plan::kThreads;   // lanes per streaming workgroup
+constexpr int kLoads = (int)plan::kLoads;       // 16-byte loads in flight per lane and round
 constexpr int kQcap = TOPLOC_QCAP;        // queue entries (16-byte vectors)
 #ifndef TOPLOC_CAP_SMALL
 #define TOPLOC_CAP_SMALL 1024
@@ -49,7 +47,6 @@ constexpr int kCapSmall = TOPLOC_CAP_SMALL;  // candidate buffer for k <= 128
 constexpr int kCapLarge = 2048;           // candidate buffer for k <= TOPLOC_MAX_K
 constexpr int kCapWide = 16384;           // candidate buffer of the selection alone up to TOPLOC_MAX_K_TOPK (140 KB of LDS:
                                           // one workgroup per compute unit; an aid for statistics, not a fast path)
-constexpr uint32_t kRoundVecs = kThreads * kLoads;
 // The larger candidate buffer (k > 128) costs registers in the prune and the ordering: one wave per SIMD less.
 constexpr int waves_for(int cap) { return cap > kCapSmall ? TOPLOC_MIN_WAVES - 1 : TOPLOC_MIN_WAVES; }
 static_assert(kCapLarge >= 4 * (int)TOPLOC_MAX_K && kCapSmall >= 4 * 128 && kCapWide >= 4 * (int)TOPLOC_MAX_K_TOPK,
@@ -57,22 +54,82 @@ static_assert(kCapLarge >= 4 * (int)TOPLOC_MAX_K && kCapSmall >= 4 * 128 && kCap
 static_assert(kCapWide <= 65536, "prune keeps slot numbers in 16 bits");
 
 // Where a workgroup of a split launch finds its piece.  Fixed chunks need no table:
-// chunk = block / parts, part = block % parts.  Segments come with two tables.
+// chunk = block / parts, part = block % parts.  Segments: the row offsets are a device
+// array; segment i starts at vector a_i = row_offsets[i] * row_vecs of the matrix, is cut into
+// parts of part_vecs vectors and owns the candidate slots from a_i / part_vecs + i on (see
+// plan.hpp).  A small planning kernel turns that into one PartDesc per slot.
 struct PartDesc {          // one per workgroup of part_kernel
-    uint64_t seg_vec;      // first vector of the segment, from the tensor base
+    uint64_t seg_vec;      // first vector of the segment, from the tensor base; kIdlePart: nothing to do
     uint32_t v0, v1;       // vectors [v0, v1) of the segment
 };
-struct SegDesc {           // one per workgroup of a merge kernel
-    uint32_t first_part;   // candidate slots first_part .. first_part + n_parts - 1
-    uint32_t n_parts;
-};
+static_assert(sizeof(PartDesc) == plan::kPartDescBytes, "workspace layout");
+constexpr uint64_t kIdlePart = ~0ull;
 struct Layout {
-    const PartDesc* part_table;  // NULL: fixed chunks
-    const SegDesc* seg_table;    // NULL: fixed chunks
-    uint32_t nvec;               // fixed chunks: vectors per chunk
-    uint32_t parts;              // fixed chunks: parts per chunk
-    uint32_t part_vecs;          // fixed chunks: vectors per part
+    const PartDesc* part_table;   // NULL: fixed chunks
+    const uint64_t* row_offsets;  // segments: device, n_segments + 1 row numbers
+    uint64_t total_rows;          // segments: rows of the matrix
+    uint32_t row_vecs;            // segments: 16-byte vectors per row
+    uint32_t row_values;          // segments: values per row (hidden)
+    uint32_t nvec;                // fixed chunks: vectors per chunk
+    uint32_t parts;               // fixed chunks: parts per chunk
+    uint32_t part_vecs;           // vectors per part
 };
+
+// One segment as the kernels see it.  status is TOPLOC_CHUNK_OK, TOPLOC_CHUNK_SHORT (fewer than k
+// values) or TOPLOC_CHUNK_BAD_SEGMENT (offsets that decrease, leave the matrix, or span 2^32 values
+// or more); only an OK segment has parts.
+struct SegInfo {
+    uint64_t a_vec;        // first vector, from the tensor base
+    uint32_t nvec;         // vectors
+    uint32_t n_parts;
+    uint64_t first_slot;
+    uint32_t status;
+};
+__device__ __forceinline__ SegInfo segment_info(const Layout& lay, uint64_t i, uint32_t k)
+{
+    SegInfo g = {0, 0, 0, 0, TOPLOC_CHUNK_BAD_SEGMENT};
+    const uint64_t r0 = lay.row_offsets[i], r1 = lay.row_offsets[i + 1];
+    if (r1 < r0 || r1 > lay.total_rows) return g;
+    const uint64_t values = (r1 - r0) * lay.row_values;   // < 2^62: total_rows * hidden is
+    if (values >= (1ull << 32)) return g;
+    if (values < k) { g.status = TOPLOC_CHUNK_SHORT; return g; }
+    g.a_vec = r0 * lay.row_vecs;
+    g.nvec = (uint32_t)((r1 - r0) * lay.row_vecs);
+    g.n_parts = (g.nvec + lay.part_vecs - 1) / lay.part_vecs;
+    g.first_slot = g.a_vec / lay.part_vecs + i;
+    g.status = TOPLOC_CHUNK_OK;
+    return g;
+}
+
+// Planning kernel of the segment calls, one thread per slot: which part of which segment the slot
+// holds.  The first slot of segment i, a_i / part_vecs + i, grows strictly with i (offsets do not
+// decrease), so the owner of slot p is the last segment whose first slot is <= p, found by bisection
+// over the offsets; p is idle when it lies behind that segment's parts.  Offsets are clamped to the
+// matrix before use, so whatever they hold no part ever points outside it.
+__global__ __launch_bounds__(256) void plan_segments_kernel(Layout lay, uint64_t n_segments, uint64_t slots, uint32_t k,
+                                                            PartDesc* __restrict__ table)
+{
+    const uint64_t p = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
+    if (p >= slots) return;
+    PartDesc d = {kIdlePart, 0u, 0u};
+    uint64_t lo = 0, hi = n_segments;   // invariant: first_slot(lo) <= p (checked below for lo = 0), first_slot(hi) > p
+    while (hi - lo > 1) {
+        const uint64_t mid = lo + (hi - lo) / 2;
+        uint64_t r = lay.row_offsets[mid];
+        r = r < lay.total_rows ? r : lay.total_rows;
+        if (r * lay.row_vecs / lay.part_vecs + mid <= p) lo = mid; else hi = mid;
+    }
+    if (n_segments) {
+        const SegInfo g = segment_info(lay, lo, k);
+        if (g.status == TOPLOC_CHUNK_OK && p >= g.first_slot && p - g.first_slot < g.n_parts) {
+            const uint32_t j = (uint32_t)(p - g.first_slot);
+            d.seg_vec = g.a_vec;
+            d.v0 = j * lay.part_vecs;
+            d.v1 = d.v0 + lay.part_vecs < g.nvec ? d.v0 + lay.part_vecs : g.nvec;
+        }
+    }
+    table[p] = d;
+}
 
 // Which chunk a workgroup takes.  Workgroups go to the 8 XCDs round-robin by block index,
 // so with chunk = block index consecutive chunks land on different XCDs and every XCD's
@@ -204,6 +261,7 @@ __global__ __launch_bounds__(kThreads, waves_for(CAP)) void part_kernel(const u3
     uint32_t v0, v1;
     if (lay.part_table) {
         const PartDesc d = lay.part_table[slot];
+        if (d.seg_vec == kIdlePart) return;  // uniform: a slot no segment owns
         src = hidden + d.seg_vec;
         v0 = d.v0;
         v1 = d.v1;
@@ -217,24 +275,26 @@ __global__ __launch_bounds__(kThreads, waves_for(CAP)) void part_kernel(const u3
     }
     const uint32_t have = (v1 - v0) * (uint32_t)Fmt::ELEMS;
     const uint32_t k_eff = have < k ? have : k;
-    if (k_eff) select_topk<kThreads, kLoads>(src, v0, v1, k_eff, s);
+    if (k_eff) select_topk<kThreads, kLoads>(src + v0, v0, v1, k_eff, s);
     for (uint32_t t = tid; t < k; t += kThreads) {
         c_idx[slot * k + t] = t < k_eff ? s.cand_idx[t] : 0xFFFFFFFFu;
         c_bits[slot * k + t] = t < k_eff ? s.cand_bits[t] : (typename Fmt::bits_t)0;
     }
 }
 
-// candidate slots of the chunk / segment a merge workgroup owns
-__device__ __forceinline__ void merge_range(const Layout& lay, uint64_t unit, uint64_t& first, uint32_t& n_parts)
+// candidate slots of the chunk / segment a merge workgroup owns; status as in SegInfo
+__device__ __forceinline__ uint32_t merge_range(const Layout& lay, uint64_t unit, uint32_t k, uint64_t& first,
+                                                uint32_t& n_parts)
 {
-    if (lay.seg_table) {
-        const SegDesc d = lay.seg_table[unit];
-        first = d.first_part;
-        n_parts = d.n_parts;
-    } else {
-        first = unit * lay.parts;
-        n_parts = lay.parts;
+    if (lay.row_offsets) {
+        const SegInfo g = segment_info(lay, unit, k);
+        first = g.first_slot;
+        n_parts = g.n_parts;
+        return g.status;
     }
+    first = unit * lay.parts;
+    n_parts = lay.parts;
+    return TOPLOC_CHUNK_OK;
 }
 
 // ---------------------------------------------------------------------------
@@ -257,7 +317,15 @@ __global__ __launch_bounds__(THREADS) void build_merge_kernel(Layout lay, uint32
     const uint64_t unit = blockIdx.x;
     uint64_t first;
     uint32_t n_parts;
-    merge_range(lay, unit, first, n_parts);
+    const uint32_t seg_status = merge_range(lay, unit, k, first, n_parts);
+    if (seg_status != TOPLOC_CHUNK_OK) {  // uniform: a segment without a proof
+        uint16_t* proof = reinterpret_cast<uint16_t*>(proofs + unit * (2 + 2 * (uint64_t)F::WORDS * k));
+        for (uint32_t j = tid; j <= k * F::WORDS; j += THREADS) proof[j] = 0;
+        if (out_idx)
+            for (uint32_t j = tid; j < k; j += THREADS) out_idx[unit * k + j] = 0xFFFFFFFFu;
+        if (tid == 0) status[unit] = (uint8_t)seg_status;
+        return;
+    }
     merge_topk(c_idx + first * k, c_bits + first * k, n_parts * k, k, sh.sel);
     if (out_idx) {
         order_topk(sh.sel, k);
@@ -288,10 +356,18 @@ __global__ __launch_bounds__(THREADS) void verify_merge_kernel(Layout lay, uint3
     __shared__ VerifyShared<KMAX, Fmt::ELEMS == 4> vs;
     const uint64_t unit = blockIdx.x;
     const uint16_t* proof = reinterpret_cast<const uint16_t*>(proofs + unit * (2 + 2 * (uint64_t)F::WORDS * k));
-    if (!verify_decode<THREADS, F>(vs, proof, k, results + unit)) return;
     uint64_t first;
     uint32_t n_parts;
-    merge_range(lay, unit, first, n_parts);
+    const uint32_t seg_status = merge_range(lay, unit, k, first, n_parts);
+    if (seg_status != TOPLOC_CHUNK_OK) {  // uniform: nothing to validate against
+        if (threadIdx.x == 0) {
+            toploc_verify_result r = {};
+            r.status = (uint8_t)seg_status;
+            results[unit] = r;
+        }
+        return;
+    }
+    if (!verify_decode<THREADS, F>(vs, proof, k, results + unit)) return;
     merge_topk(c_idx + first * k, c_bits + first * k, n_parts * k, k, s);
     verify_tail<THREADS, F, Fmt>(vs, s.cand_idx, s.cand_bits, k, thr, results + unit);
 }
@@ -308,11 +384,8 @@ struct StreamHeader {
 };
 static_assert(sizeof(StreamHeader) == 16, "state layout");
 
+static_assert(sizeof(StreamHeader) == plan::kStreamHeaderBytes, "state layout");
 __host__ __device__ __forceinline__ size_t stream_idx_bytes(uint32_t k) { return ((size_t)k * 4 + 15) & ~(size_t)15; }
-__host__ __device__ __forceinline__ size_t stream_stride(uint32_t k)
-{
-    return sizeof(StreamHeader) + stream_idx_bytes(k) + (((size_t)k * 2 + 15) & ~(size_t)15);
-}
 
 __global__ __launch_bounds__(256) void stream_reset_kernel(char* __restrict__ state, uint32_t n_seq, size_t stride)
 {
@@ -351,9 +424,8 @@ struct StreamSeed {
 };
 
 // One appended row per sequence: the selection of select.hpp over the row's vectors,
-// seeded with the pairs and the threshold the sequence holds.  `row_base` is the
-// sequence's row pointer moved back by v0 vectors, so that vector v0 + j of the
-// selection is vector j of the row and flat indices come out as token*hidden + channel.
+// seeded with the pairs and the threshold the sequence holds.  The row is the vector range
+// [v0, v0 + hvec) of the chunk, v0 = token*hvec, so flat indices come out as token*hidden + channel.
 // With `slots` (continuous batching: the rows of a step belong to any subset of the
 // sequences, each at its own position) row r goes to sequence slots[r] as token tokens[r];
 // a row whose slot or token is out of range is skipped.
@@ -378,11 +450,10 @@ __global__ __launch_bounds__(kThreads, waves_for(CAP)) void stream_append_kernel
     StreamHeader* hdr = reinterpret_cast<StreamHeader*>(st);
     uint32_t* g_idx = reinterpret_cast<uint32_t*>(st + sizeof(StreamHeader));
     uint16_t* g_bits = reinterpret_cast<uint16_t*>(st + sizeof(StreamHeader) + stream_idx_bytes(k));
-    const u32x4* row_base = reinterpret_cast<const u32x4*>(
-        reinterpret_cast<uintptr_t>(step_vec + (size_t)blockIdx.x * hvec) - (uintptr_t)v0 * sizeof(u32x4));
+    const u32x4* row = step_vec + (size_t)blockIdx.x * hvec;
     const uint32_t rows = hdr->rows;
     const SelectStart end = select_topk_from<kThreads, kLoads, CAP, kQcap>(
-        row_base, v0, v0 + hvec, s, StreamSeed<CAP>{hdr, g_idx, g_bits, k, hvec * 8u});
+        row, v0, v0 + hvec, s, StreamSeed<CAP>{hdr, g_idx, g_bits, k, hvec * 8u});
     for (uint32_t i = tid; i < end.k; i += kThreads) {
         g_idx[i] = s.cand_idx[i];
         g_bits[i] = s.cand_bits[i];
@@ -531,71 +602,16 @@ struct ProfScope {
     }
 };
 
-static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-static size_t up16(size_t b) { return (b + 15) & ~(size_t)15; }
+using plan::aligned16;
+using plan::bits_size_of;
+using plan::cand_bytes;
+using plan::chunk_len;
+using plan::chunk_len_mixed;
+using plan::FixedPlan;
+using plan::up16;
 
-// N (values per chunk) when the parameters are usable, else 0
-static uint64_t chunk_len(const toploc_params* p, uint32_t max_k = TOPLOC_MAX_K)
-{
-    if (!p || p->k == 0 || p->k > max_k || p->prime != TOPLOC_PRIME) return 0;
-    if (p->chunk_tokens == 0 || p->hidden == 0) return 0;
-    const uint64_t n = (uint64_t)p->chunk_tokens * p->hidden;
-    if (n % 8 != 0 || n >= (1ull << 32) || p->k > n) return 0;
-    return n;
-}
-
-// How a launch is cut.  One workgroup keeps about 16 KB of loads in flight, so roughly a
-// thousand streaming workgroups are needed to saturate HBM: a batch with fewer chunks is
-// cut into parts until there are that many, but a part still streams a few rounds (every
-// part pays for finding its own threshold), and no part is longer than kMaxPartVecs so
-// that one long segment cannot become the launch's straggler.
-constexpr uint64_t kTargetGroups = 1024;
-constexpr uint64_t kMinPartVecs = 4 * kRoundVecs;
-constexpr uint64_t kMaxPartVecs = 64 * kRoundVecs;
-
-static uint64_t clamp_part_vecs(uint64_t pv)
-{
-    pv = (pv + kRoundVecs - 1) / kRoundVecs * kRoundVecs;
-    return pv < kMinPartVecs ? kMinPartVecs : pv > kMaxPartVecs ? kMaxPartVecs : pv;
-}
-
-struct FixedPlan { uint32_t parts; uint32_t part_vecs; };
-static FixedPlan plan_fixed(uint64_t n_chunks, uint64_t nvec)
-{
-    uint64_t pv;
-    const uint64_t forced = g_force_parts.load();  // read once: another thread may change it
-    if (forced) {
-        pv = (nvec + forced - 1) / forced;
-        pv = pv ? pv : 1;
-    } else {
-        const uint64_t want = n_chunks < kTargetGroups ? kTargetGroups / n_chunks : 1;  // parts per chunk
-        pv = clamp_part_vecs((nvec + want - 1) / want);
-    }
-    FixedPlan f;
-    f.parts = (uint32_t)((nvec + pv - 1) / pv);
-    f.part_vecs = (uint32_t)(pv < nvec ? pv : nvec);
-    return f;
-}
-
-// vectors per part for segments: `total_vecs` vectors in `n_units` segments, the longest of `max_unit_vecs`
-static uint64_t pick_part_vecs(uint64_t total_vecs, uint64_t max_unit_vecs, uint64_t n_units)
-{
-    const uint64_t forced = g_force_parts.load();  // read once: another thread may change it
-    if (forced) {
-        const uint64_t pv = (max_unit_vecs + forced - 1) / forced;
-        return pv ? pv : 1;
-    }
-    const uint64_t groups = n_units > kTargetGroups ? n_units : kTargetGroups;
-    return clamp_part_vecs((total_vecs + groups - 1) / groups);
-}
-
-// candidate arrays for `slots` parts: [slots*k] uint32 indices, then [slots*k] patterns of
-// `bits_size` bytes (2: bf16, 4: fp32), each array 16-byte aligned
-static size_t cand_bytes(uint64_t slots, uint32_t k, size_t bits_size = sizeof(uint16_t))
-{
-    return up16((size_t)slots * k * sizeof(uint32_t)) + up16((size_t)slots * k * bits_size);
-}
-static size_t bits_size_of(uint32_t dtype) { return dtype == TOPLOC_DTYPE_F32 ? sizeof(uint32_t) : sizeof(uint16_t); }
+// the cut of a batch of fixed chunks; the split switch is read once per plan: another thread may change it
+static FixedPlan plan_fixed(uint64_t n_chunks, uint64_t nvec) { return plan::plan_fixed(n_chunks, nvec, g_force_parts.load()); }
 
 static void launch_part(hipStream_t st, const void* d_hidden, const Layout& lay, uint64_t slots, uint32_t k, uint32_t* c_idx,
                         void* c_bits_any, uint32_t hidden_dtype = TOPLOC_DTYPE_BF16)
@@ -665,71 +681,40 @@ static void launch_verify_merge(hipStream_t st, const Layout& lay, uint64_t unit
                            c_bits, d_proofs, thr, d_results);
 }
 
-// Segments: tables of parts and of segments, laid out behind the candidate arrays.
-struct SegPlan {
-    std::vector<PartDesc> parts;
-    std::vector<SegDesc> segs;
-    bool ok = false;
-};
-static SegPlan plan_segments(const uint64_t* h_row_offsets, uint64_t n_segments, uint32_t hidden, uint32_t k,
-                             uint32_t hidden_dtype = TOPLOC_DTYPE_BF16, uint32_t k_max = TOPLOC_MAX_K)
+// Segments: the host plans from sizes alone (plan.hpp); the part table is built on the device from the
+// row offsets, behind the candidate arrays of the workspace.
+static plan::SegmentPlan plan_segments(uint64_t n_segments, uint64_t total_rows, uint32_t hidden, uint32_t k,
+                                       uint32_t hidden_dtype, uint32_t proof_dtype)
 {
-    SegPlan pl;
-    if (!h_row_offsets || hidden == 0 || hidden % 8 != 0 || k == 0 || k > k_max || n_segments >= (1ull << 31)) return pl;
-    const uint64_t hv = hidden / (hidden_dtype == TOPLOC_DTYPE_F32 ? 4 : 8);  // 16-byte vectors per row
-    uint64_t max_vecs = 0;
-    for (uint64_t i = 0; i < n_segments; ++i) {
-        if (h_row_offsets[i + 1] < h_row_offsets[i]) return pl;
-        const uint64_t rows = h_row_offsets[i + 1] - h_row_offsets[i];
-        if (rows * hidden < k || rows * hidden >= (1ull << 32)) return pl;
-        if (rows * hv > max_vecs) max_vecs = rows * hv;
-    }
-    const uint64_t total_vecs = n_segments ? (h_row_offsets[n_segments] - h_row_offsets[0]) * hv : 0;
-    const uint64_t pv = pick_part_vecs(total_vecs, max_vecs, n_segments);
-    pl.segs.reserve(n_segments);
-    for (uint64_t i = 0; i < n_segments; ++i) {
-        const uint64_t nvec = (h_row_offsets[i + 1] - h_row_offsets[i]) * hv;
-        SegDesc sd;
-        sd.first_part = (uint32_t)pl.parts.size();
-        sd.n_parts = (uint32_t)((nvec + pv - 1) / pv);
-        for (uint64_t v0 = 0; v0 < nvec; v0 += pv) {
-            PartDesc pd;
-            pd.seg_vec = h_row_offsets[i] * hv;
-            pd.v0 = (uint32_t)v0;
-            pd.v1 = (uint32_t)(v0 + pv < nvec ? v0 + pv : nvec);
-            pl.parts.push_back(pd);
-        }
-        pl.segs.push_back(sd);
-        if (pl.parts.size() >= (1ull << 31)) return pl;
-    }
-    pl.ok = true;
-    return pl;
+    if (hidden_dtype > TOPLOC_DTYPE_F32 || proof_dtype > TOPLOC_DTYPE_F32) return plan::SegmentPlan{false, 0, 0, 0};
+    return plan::plan_segments(n_segments, total_rows, hidden, k, hidden_dtype, plan::max_k_of(hidden_dtype, proof_dtype),
+                               g_force_parts.load());
 }
 
-static size_t seg_workspace_bytes(const SegPlan& pl, uint32_t k, size_t bits_size = sizeof(uint16_t))
-{
-    return cand_bytes(pl.parts.size(), k, bits_size) + up16(pl.parts.size() * sizeof(PartDesc)) +
-           up16(pl.segs.size() * sizeof(SegDesc));
-}
-
-// copies the tables behind the candidate arrays and fills the layout
-template <typename Bits>
-static bool stage_segments(const SegPlan& pl, uint32_t k, void* d_workspace, hipStream_t st, Layout& lay, uint32_t*& c_idx,
-                           Bits*& c_bits)
+// Lays the workspace out, enqueues the planning kernel and the part launch of a segment call.
+static int launch_segment_parts(const plan::SegmentPlan& pl, const void* d_hidden, uint64_t total_rows,
+                                const uint64_t* d_row_offsets, uint64_t n_segments, uint32_t hidden, uint32_t k,
+                                uint32_t hidden_dtype, void* d_workspace, hipStream_t st, Layout& lay, uint32_t*& c_idx,
+                                void*& c_bits)
 {
     char* w = (char*)d_workspace;
+    const size_t bits_size = bits_size_of(hidden_dtype);
     c_idx = (uint32_t*)w;
-    c_bits = (Bits*)(w + up16(pl.parts.size() * (size_t)k * sizeof(uint32_t)));
-    char* t_parts = w + cand_bytes(pl.parts.size(), k, sizeof(Bits));
-    char* t_segs = t_parts + up16(pl.parts.size() * sizeof(PartDesc));
-    if (!hip_ok(hipMemcpyAsync(t_parts, pl.parts.data(), pl.parts.size() * sizeof(PartDesc), hipMemcpyHostToDevice, st)))
-        return false;
-    if (!hip_ok(hipMemcpyAsync(t_segs, pl.segs.data(), pl.segs.size() * sizeof(SegDesc), hipMemcpyHostToDevice, st)))
-        return false;
-    lay.part_table = (const PartDesc*)t_parts;
-    lay.seg_table = (const SegDesc*)t_segs;
-    lay.nvec = 0; lay.parts = 0; lay.part_vecs = 0;
-    return true;
+    c_bits = w + up16((size_t)pl.slots * k * sizeof(uint32_t));
+    PartDesc* table = (PartDesc*)(w + cand_bytes(pl.slots, k, bits_size));
+    lay.part_table = table;
+    lay.row_offsets = d_row_offsets;
+    lay.total_rows = total_rows;
+    lay.row_vecs = pl.row_vecs;
+    lay.row_values = hidden;
+    lay.nvec = 0;
+    lay.parts = 0;
+    lay.part_vecs = (uint32_t)pl.part_vecs;
+    hipLaunchKernelGGL(plan_segments_kernel, dim3((uint32_t)((pl.slots + 255) / 256)), dim3(256), 0, st, lay, n_segments,
+                       pl.slots, k, table);
+    if (!hip_ok(hipGetLastError())) return TOPLOC_EHIP;
+    launch_part(st, d_hidden, lay, pl.slots, k, c_idx, c_bits, hidden_dtype);
+    return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
 }
 
 }  // namespace toploc
@@ -740,13 +725,25 @@ extern "C" {
 
 size_t toploc_proof_bytes(uint32_t k) { return 2 + 2 * (size_t)k; }
 
+int toploc_workspace_query(const toploc_params* params, uint64_t n_chunks, size_t* bytes)
+{
+    if (!bytes) return TOPLOC_EINVAL;
+    *bytes = 0;
+    const uint64_t n = chunk_len(params);
+    if (n == 0 || n_chunks >= (1ull << 31)) return TOPLOC_EINVAL;
+    if (n_chunks == 0) return TOPLOC_OK;
+    const FixedPlan f = plan_fixed(n_chunks, n / 8);
+    if (f.parts == 1 && params->k <= 128) return TOPLOC_OK;  // one fused kernel, everything stays on chip
+    if (n_chunks * f.parts >= (1ull << 31)) return TOPLOC_EINVAL;
+    *bytes = cand_bytes(n_chunks * f.parts, params->k);
+    return TOPLOC_OK;
+}
+
 size_t toploc_workspace_bytes(const toploc_params* params, uint64_t n_chunks)
 {
-    const uint64_t n = chunk_len(params);
-    if (n == 0 || n_chunks == 0) return 0;
-    const FixedPlan f = plan_fixed(n_chunks, n / 8);
-    if (f.parts == 1 && params->k <= 128) return 0;  // one fused kernel, everything stays on chip
-    return cand_bytes(n_chunks * f.parts, params->k);
+    size_t bytes = 0;
+    (void)toploc_workspace_query(params, n_chunks, &bytes);
+    return bytes;
 }
 
 int toploc_set_split(uint32_t parts_per_chunk)
@@ -760,9 +757,8 @@ int toploc_topk(const void* d_hidden_bf16, uint64_t n_chunks, const toploc_param
                 uint16_t* d_topk_val, void* hip_stream)
 {
     const uint64_t n = chunk_len(params, TOPLOC_MAX_K_TOPK);
-    if (n == 0 || n_chunks >= (1ull << 31)) return TOPLOC_EINVAL;
-    if (n_chunks == 0) return TOPLOC_OK;
-    if (!d_hidden_bf16 || !d_topk_idx || !d_topk_val || !aligned16(d_hidden_bf16)) return TOPLOC_EINVAL;
+    const int chk = plan::check_fixed(n, n_chunks, d_hidden_bf16, d_topk_idx, 4, d_topk_val, 2, nullptr);
+    if (chk != plan::kGo) return chk;
     hipStream_t st = (hipStream_t)hip_stream;
     {
         ProfScope ps(TOPLOC_KERNEL_SELECT, st);
@@ -795,7 +791,7 @@ static int build_fixed(const FixedPlan& f, const void* d_hidden_bf16, uint64_t n
     if (!have_ws) return d_workspace ? TOPLOC_EWORKSPACE : TOPLOC_EINVAL;
     const uint64_t slots = n_chunks * f.parts;
     if (slots >= (1ull << 31)) return TOPLOC_EINVAL;
-    Layout lay = {nullptr, nullptr, nvec, f.parts, f.part_vecs};
+    Layout lay = {nullptr, nullptr, 0, 0, 0, nvec, f.parts, f.part_vecs};
     uint32_t* c_idx = (uint32_t*)d_workspace;
     uint16_t* c_bits = (uint16_t*)((char*)d_workspace + up16((size_t)slots * k * sizeof(uint32_t)));
     launch_part(st, d_hidden_bf16, lay, slots, k, c_idx, c_bits);
@@ -809,11 +805,8 @@ int toploc_build_proofs(const void* d_hidden_bf16, uint64_t n_chunks, const topl
                         void* hip_stream)
 {
     const uint64_t n = chunk_len(params);
-    if (n == 0 || n_chunks >= (1ull << 31)) return TOPLOC_EINVAL;
-    if (n_chunks == 0) return TOPLOC_OK;
-    if (!d_hidden_bf16 || !d_proofs || !d_status || !aligned16(d_hidden_bf16)) return TOPLOC_EINVAL;
-    if ((reinterpret_cast<uintptr_t>(d_proofs) & 1u) != 0) return TOPLOC_EINVAL;
-    if (d_workspace && !aligned16(d_workspace)) return TOPLOC_EINVAL;
+    const int chk = plan::check_fixed(n, n_chunks, d_hidden_bf16, d_proofs, 2, d_status, 1, d_workspace);
+    if (chk != plan::kGo) return chk;
     const uint32_t nvec = (uint32_t)(n / 8);
     return build_fixed(plan_fixed(n_chunks, nvec), d_hidden_bf16, n_chunks, nvec, params->k, d_proofs, d_status,
                        d_topk_idx_opt, d_workspace, workspace_bytes, (hipStream_t)hip_stream);
@@ -851,14 +844,13 @@ int toploc_build_proofs_static(const void* d_hidden_bf16, uint64_t n_chunks, con
                                uint8_t* d_proofs, uint8_t* d_status, uint32_t* d_topk_idx_opt, void* hip_stream)
 {
     const uint64_t n = chunk_len(params);
-    if (n == 0 || n_chunks >= (1ull << 31)) return TOPLOC_EINVAL;
-    if (n_chunks == 0) return TOPLOC_OK;
-    if (!d_hidden_bf16 || !d_proofs || !d_status || !aligned16(d_hidden_bf16)) return TOPLOC_EINVAL;
-    if ((reinterpret_cast<uintptr_t>(d_proofs) & 1u) != 0) return TOPLOC_EINVAL;
+    const int chk = plan::check_fixed(n, n_chunks, d_hidden_bf16, d_proofs, 2, d_status, 1, nullptr);
+    if (chk != plan::kGo) return chk;
     const uint32_t nvec = (uint32_t)(n / 8);
     const FixedPlan f = plan_fixed(n_chunks, nvec);
-    const bool fused = f.parts == 1 && params->k <= 128;   // no scratch at all
-    if (!fused && cand_bytes(n_chunks * f.parts, params->k) > kScratchBytes) return TOPLOC_ESCRATCH;
+    const bool fused = plan::fixed_plan_is_fused(f, params->k);   // no scratch at all
+    const int fits = plan::check_static_scratch(f, n_chunks, params->k, kScratchBytes);
+    if (fits != plan::kGo) return fits;
     void* ptr = nullptr;
     if (!fused) {
         const int rc = scratch_of_current_device(&ptr);
@@ -873,12 +865,9 @@ int toploc_verify_proofs(const void* d_hidden_bf16, uint64_t n_chunks, const top
                          void* d_workspace, size_t workspace_bytes, void* hip_stream)
 {
     const uint64_t n = chunk_len(params);
-    if (n == 0 || n_chunks >= (1ull << 31) || !thresholds) return TOPLOC_EINVAL;
-    if (n_chunks == 0) return TOPLOC_OK;
-    if (!d_hidden_bf16 || !d_proofs || !d_results || !aligned16(d_hidden_bf16)) return TOPLOC_EINVAL;
-    if ((reinterpret_cast<uintptr_t>(d_proofs) & 1u) != 0 || (reinterpret_cast<uintptr_t>(d_results) & 3u) != 0)
-        return TOPLOC_EINVAL;
-    if (d_workspace && !aligned16(d_workspace)) return TOPLOC_EINVAL;
+    if (!thresholds) return TOPLOC_EINVAL;
+    const int chk = plan::check_fixed(n, n_chunks, d_hidden_bf16, d_proofs, 2, d_results, 4, d_workspace);
+    if (chk != plan::kGo) return chk;
     const uint32_t k = params->k;
     const uint32_t nvec = (uint32_t)(n / 8);
     hipStream_t st = (hipStream_t)hip_stream;
@@ -895,7 +884,7 @@ int toploc_verify_proofs(const void* d_hidden_bf16, uint64_t n_chunks, const top
                                (const u32x4*)d_hidden_bf16, nvec, k, d_proofs, *thresholds, d_results);
         return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
     }
-    Layout lay = {nullptr, nullptr, nvec, f.parts, f.part_vecs};
+    Layout lay = {nullptr, nullptr, 0, 0, 0, nvec, f.parts, f.part_vecs};
     uint32_t* c_idx = (uint32_t*)d_workspace;
     uint16_t* c_bits = (uint16_t*)((char*)d_workspace + up16((size_t)slots * k * sizeof(uint32_t)));
     launch_part(st, d_hidden_bf16, lay, slots, k, c_idx, c_bits);
@@ -904,70 +893,86 @@ int toploc_verify_proofs(const void* d_hidden_bf16, uint64_t n_chunks, const top
     return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
 }
 
-size_t toploc_segments_workspace_bytes(const uint64_t* h_row_offsets, uint64_t n_segments, uint32_t hidden, uint32_t k)
+size_t toploc_segments_workspace_bytes_dtype(uint64_t n_segments, uint64_t total_rows, uint32_t hidden, uint32_t k,
+                                             uint32_t hidden_dtype)
 {
-    const SegPlan pl = plan_segments(h_row_offsets, n_segments, hidden, k);
+    const plan::SegmentPlan pl = plan_segments(n_segments, total_rows, hidden, k, hidden_dtype, hidden_dtype);
     if (!pl.ok || n_segments == 0) return 0;
-    return seg_workspace_bytes(pl, k);
+    return plan::segments_workspace_bytes(pl, k, bits_size_of(hidden_dtype));
 }
 
-int toploc_build_proofs_segments(const void* d_hidden_bf16, const uint64_t* h_row_offsets, uint64_t n_segments,
-                                 uint32_t hidden, uint32_t k, uint8_t* d_proofs, uint8_t* d_status,
-                                 uint32_t* d_topk_idx_opt, void* d_workspace, size_t workspace_bytes, void* hip_stream)
+size_t toploc_segments_workspace_bytes(uint64_t n_segments, uint64_t total_rows, uint32_t hidden, uint32_t k)
 {
-    const SegPlan pl = plan_segments(h_row_offsets, n_segments, hidden, k);
-    if (!pl.ok) return TOPLOC_EINVAL;
-    if (n_segments == 0) return TOPLOC_OK;
-    if (!d_hidden_bf16 || !d_proofs || !d_status || !d_workspace || !aligned16(d_hidden_bf16) || !aligned16(d_workspace))
-        return TOPLOC_EINVAL;
-    if ((reinterpret_cast<uintptr_t>(d_proofs) & 1u) != 0) return TOPLOC_EINVAL;
-    if (workspace_bytes < seg_workspace_bytes(pl, k)) return TOPLOC_EWORKSPACE;
+    return toploc_segments_workspace_bytes_dtype(n_segments, total_rows, hidden, k, TOPLOC_DTYPE_BF16);
+}
+
+// Algorithm 1 over segments, activations of `hidden_dtype` (the proof has the same precision)
+static int build_segments(const void* d_hidden, uint32_t hidden_dtype, uint64_t total_rows, const uint64_t* d_row_offsets,
+                          uint64_t n_segments, uint32_t hidden, uint32_t k, uint8_t* d_proofs, uint8_t* d_status,
+                          uint32_t* d_topk_idx_opt, void* d_workspace, size_t workspace_bytes, void* hip_stream)
+{
+    const plan::SegmentPlan pl = plan_segments(n_segments, total_rows, hidden, k, hidden_dtype, hidden_dtype);
+    const int chk = plan::check_segments(pl, n_segments, k, hidden_dtype, d_hidden, d_row_offsets, d_proofs, d_status, 1, d_workspace,
+                                   workspace_bytes);
+    if (chk != plan::kGo) return chk;
     hipStream_t st = (hipStream_t)hip_stream;
     Layout lay;
     uint32_t* c_idx;
-    uint16_t* c_bits;
-    if (!stage_segments(pl, k, d_workspace, st, lay, c_idx, c_bits)) return TOPLOC_EHIP;
-    launch_part(st, d_hidden_bf16, lay, pl.parts.size(), k, c_idx, c_bits);
-    if (!hip_ok(hipGetLastError())) return TOPLOC_EHIP;
-    launch_build_merge(st, lay, n_segments, k, c_idx, c_bits, d_proofs, d_status, d_topk_idx_opt);
+    void* c_bits;
+    const int rc = launch_segment_parts(pl, d_hidden, total_rows, d_row_offsets, n_segments, hidden, k, hidden_dtype,
+                                        d_workspace, st, lay, c_idx, c_bits);
+    if (rc != TOPLOC_OK) return rc;
+    launch_build_merge(st, lay, n_segments, k, c_idx, c_bits, d_proofs, d_status, d_topk_idx_opt, hidden_dtype);
     return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
 }
 
-int toploc_verify_proofs_segments(const void* d_hidden_bf16, const uint64_t* h_row_offsets, uint64_t n_segments,
-                                  uint32_t hidden, uint32_t k, const uint8_t* d_proofs,
+int toploc_build_proofs_segments(const void* d_hidden_bf16, uint64_t total_rows, const uint64_t* d_row_offsets,
+                                 uint64_t n_segments, uint32_t hidden, uint32_t k, uint8_t* d_proofs, uint8_t* d_status,
+                                 uint32_t* d_topk_idx_opt, void* d_workspace, size_t workspace_bytes, void* hip_stream)
+{
+    return build_segments(d_hidden_bf16, TOPLOC_DTYPE_BF16, total_rows, d_row_offsets, n_segments, hidden, k, d_proofs,
+                          d_status, d_topk_idx_opt, d_workspace, workspace_bytes, hip_stream);
+}
+
+int toploc_build_proofs_segments_f32(const void* d_hidden_f32, uint64_t total_rows, const uint64_t* d_row_offsets,
+                                     uint64_t n_segments, uint32_t hidden, uint32_t k, uint8_t* d_proofs, uint8_t* d_status,
+                                     uint32_t* d_topk_idx_opt, void* d_workspace, size_t workspace_bytes,
+                                     void* hip_stream)
+{
+    return build_segments(d_hidden_f32, TOPLOC_DTYPE_F32, total_rows, d_row_offsets, n_segments, hidden, k, d_proofs,
+                          d_status, d_topk_idx_opt, d_workspace, workspace_bytes, hip_stream);
+}
+
+int toploc_verify_proofs_segments_mixed(const void* d_hidden, uint32_t hidden_dtype, uint64_t total_rows,
+                                        const uint64_t* d_row_offsets, uint64_t n_segments, uint32_t hidden, uint32_t k,
+                                        const uint8_t* d_proofs, uint32_t proof_dtype, const toploc_thresholds* thresholds,
+                                        toploc_verify_result* d_results, void* d_workspace, size_t workspace_bytes,
+                                        void* hip_stream)
+{
+    const plan::SegmentPlan pl = plan_segments(n_segments, total_rows, hidden, k, hidden_dtype, proof_dtype);
+    if (!thresholds) return TOPLOC_EINVAL;
+    const int chk = plan::check_segments(pl, n_segments, k, hidden_dtype, d_hidden, d_row_offsets, d_proofs, d_results, 4,
+                                   d_workspace, workspace_bytes);
+    if (chk != plan::kGo) return chk;
+    hipStream_t st = (hipStream_t)hip_stream;
+    Layout lay;
+    uint32_t* c_idx;
+    void* c_bits;
+    const int rc = launch_segment_parts(pl, d_hidden, total_rows, d_row_offsets, n_segments, hidden, k, hidden_dtype,
+                                        d_workspace, st, lay, c_idx, c_bits);
+    if (rc != TOPLOC_OK) return rc;
+    launch_verify_merge(st, lay, n_segments, k, c_idx, c_bits, d_proofs, *thresholds, d_results, hidden_dtype, proof_dtype);
+    return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
+}
+
+int toploc_verify_proofs_segments(const void* d_hidden_bf16, uint64_t total_rows, const uint64_t* d_row_offsets,
+                                  uint64_t n_segments, uint32_t hidden, uint32_t k, const uint8_t* d_proofs,
                                   const toploc_thresholds* thresholds, toploc_verify_result* d_results, void* d_workspace,
                                   size_t workspace_bytes, void* hip_stream)
 {
-    const SegPlan pl = plan_segments(h_row_offsets, n_segments, hidden, k);
-    if (!pl.ok || !thresholds) return TOPLOC_EINVAL;
-    if (n_segments == 0) return TOPLOC_OK;
-    if (!d_hidden_bf16 || !d_proofs || !d_results || !d_workspace || !aligned16(d_hidden_bf16) || !aligned16(d_workspace))
-        return TOPLOC_EINVAL;
-    if ((reinterpret_cast<uintptr_t>(d_proofs) & 1u) != 0 || (reinterpret_cast<uintptr_t>(d_results) & 3u) != 0)
-        return TOPLOC_EINVAL;
-    if (workspace_bytes < seg_workspace_bytes(pl, k)) return TOPLOC_EWORKSPACE;
-    hipStream_t st = (hipStream_t)hip_stream;
-    Layout lay;
-    uint32_t* c_idx;
-    uint16_t* c_bits;
-    if (!stage_segments(pl, k, d_workspace, st, lay, c_idx, c_bits)) return TOPLOC_EHIP;
-    launch_part(st, d_hidden_bf16, lay, pl.parts.size(), k, c_idx, c_bits);
-    if (!hip_ok(hipGetLastError())) return TOPLOC_EHIP;
-    launch_verify_merge(st, lay, n_segments, k, c_idx, c_bits, d_proofs, *thresholds, d_results);
-    return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
-}
-
-// N (values per chunk) for the calls that involve fp32: k <= TOPLOC_MAX_K_F32, the chunk a
-// whole number of 16-byte vectors in both formats
-static uint64_t chunk_len_mixed(const toploc_params* p, uint32_t hidden_dtype, uint32_t proof_dtype)
-{
-    if (!p || hidden_dtype > TOPLOC_DTYPE_F32 || proof_dtype > TOPLOC_DTYPE_F32) return 0;
-    if (p->prime != (proof_dtype == TOPLOC_DTYPE_F32 ? TOPLOC_PRIME32 : TOPLOC_PRIME)) return 0;
-    const uint32_t kmax = (hidden_dtype == TOPLOC_DTYPE_F32 || proof_dtype == TOPLOC_DTYPE_F32) ? TOPLOC_MAX_K_F32 : TOPLOC_MAX_K;
-    if (p->k == 0 || p->k > kmax || p->chunk_tokens == 0 || p->hidden == 0) return 0;
-    const uint64_t n = (uint64_t)p->chunk_tokens * p->hidden;
-    if (n % 8 != 0 || n >= (1ull << 32) || p->k > n) return 0;
-    return n;
+    return toploc_verify_proofs_segments_mixed(d_hidden_bf16, TOPLOC_DTYPE_BF16, total_rows, d_row_offsets, n_segments,
+                                               hidden, k, d_proofs, TOPLOC_DTYPE_BF16, thresholds, d_results, d_workspace,
+                                               workspace_bytes, hip_stream);
 }
 
 size_t toploc_proof_bytes_dtype(uint32_t k, uint32_t dtype)
@@ -979,10 +984,8 @@ int toploc_build_proofs_f32(const void* d_hidden_f32, uint64_t n_chunks, const t
                             uint8_t* d_status, uint32_t* d_topk_idx_opt, void* hip_stream)
 {
     const uint64_t n = chunk_len_mixed(params, TOPLOC_DTYPE_F32, TOPLOC_DTYPE_F32);
-    if (n == 0 || n_chunks >= (1ull << 31)) return TOPLOC_EINVAL;
-    if (n_chunks == 0) return TOPLOC_OK;
-    if (!d_hidden_f32 || !d_proofs || !d_status || !aligned16(d_hidden_f32)) return TOPLOC_EINVAL;
-    if ((reinterpret_cast<uintptr_t>(d_proofs) & 1u) != 0) return TOPLOC_EINVAL;
+    const int chk = plan::check_fixed(n, n_chunks, d_hidden_f32, d_proofs, 2, d_status, 1, nullptr);
+    if (chk != plan::kGo) return chk;
     hipStream_t st = (hipStream_t)hip_stream;
     {
         ProfScope ps(TOPLOC_KERNEL_BUILD, st);
@@ -997,11 +1000,9 @@ int toploc_verify_proofs_mixed(const void* d_hidden, uint32_t hidden_dtype, uint
                                toploc_verify_result* d_results, void* hip_stream)
 {
     const uint64_t n = chunk_len_mixed(params, hidden_dtype, proof_dtype);
-    if (n == 0 || n_chunks >= (1ull << 31) || !thresholds) return TOPLOC_EINVAL;
-    if (n_chunks == 0) return TOPLOC_OK;
-    if (!d_hidden || !d_proofs || !d_results || !aligned16(d_hidden)) return TOPLOC_EINVAL;
-    if ((reinterpret_cast<uintptr_t>(d_proofs) & 1u) != 0 || (reinterpret_cast<uintptr_t>(d_results) & 3u) != 0)
-        return TOPLOC_EINVAL;
+    if (!thresholds) return TOPLOC_EINVAL;
+    const int chk = plan::check_fixed(n, n_chunks, d_hidden, d_proofs, 2, d_results, 4, nullptr);
+    if (chk != plan::kGo) return chk;
     if (hidden_dtype == TOPLOC_DTYPE_BF16 && proof_dtype == TOPLOC_DTYPE_BF16)
         return toploc_verify_proofs(d_hidden, n_chunks, params, d_proofs, thresholds, d_results, nullptr, 0, hip_stream);
     hipStream_t st = (hipStream_t)hip_stream;
@@ -1023,117 +1024,39 @@ int toploc_verify_proofs_mixed(const void* d_hidden, uint32_t hidden_dtype, uint
     return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
 }
 
-// k limit and table plan of the segment calls that involve fp32
-static SegPlan plan_segments_mixed(const uint64_t* h_row_offsets, uint64_t n_segments, uint32_t hidden, uint32_t k,
-                                   uint32_t hidden_dtype, uint32_t proof_dtype)
-{
-    if (hidden_dtype > TOPLOC_DTYPE_F32 || proof_dtype > TOPLOC_DTYPE_F32) return SegPlan();
-    const bool any32 = hidden_dtype == TOPLOC_DTYPE_F32 || proof_dtype == TOPLOC_DTYPE_F32;
-    return plan_segments(h_row_offsets, n_segments, hidden, k, hidden_dtype, any32 ? TOPLOC_MAX_K_F32 : TOPLOC_MAX_K);
-}
-
-size_t toploc_segments_workspace_bytes_dtype(const uint64_t* h_row_offsets, uint64_t n_segments, uint32_t hidden,
-                                             uint32_t k, uint32_t hidden_dtype)
-{
-    const SegPlan pl = plan_segments_mixed(h_row_offsets, n_segments, hidden, k, hidden_dtype, hidden_dtype);
-    if (!pl.ok || n_segments == 0) return 0;
-    return seg_workspace_bytes(pl, k, bits_size_of(hidden_dtype));
-}
-
-int toploc_build_proofs_segments_f32(const void* d_hidden_f32, const uint64_t* h_row_offsets, uint64_t n_segments,
-                                     uint32_t hidden, uint32_t k, uint8_t* d_proofs, uint8_t* d_status,
-                                     uint32_t* d_topk_idx_opt, void* d_workspace, size_t workspace_bytes,
-                                     void* hip_stream)
-{
-    const SegPlan pl = plan_segments_mixed(h_row_offsets, n_segments, hidden, k, TOPLOC_DTYPE_F32, TOPLOC_DTYPE_F32);
-    if (!pl.ok) return TOPLOC_EINVAL;
-    if (n_segments == 0) return TOPLOC_OK;
-    if (!d_hidden_f32 || !d_proofs || !d_status || !d_workspace || !aligned16(d_hidden_f32) || !aligned16(d_workspace))
-        return TOPLOC_EINVAL;
-    if ((reinterpret_cast<uintptr_t>(d_proofs) & 1u) != 0) return TOPLOC_EINVAL;
-    if (workspace_bytes < seg_workspace_bytes(pl, k, sizeof(uint32_t))) return TOPLOC_EWORKSPACE;
-    hipStream_t st = (hipStream_t)hip_stream;
-    Layout lay;
-    uint32_t* c_idx;
-    uint32_t* c_bits;
-    if (!stage_segments(pl, k, d_workspace, st, lay, c_idx, c_bits)) return TOPLOC_EHIP;
-    launch_part(st, d_hidden_f32, lay, pl.parts.size(), k, c_idx, c_bits, TOPLOC_DTYPE_F32);
-    if (!hip_ok(hipGetLastError())) return TOPLOC_EHIP;
-    launch_build_merge(st, lay, n_segments, k, c_idx, c_bits, d_proofs, d_status, d_topk_idx_opt, TOPLOC_DTYPE_F32);
-    return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
-}
-
-int toploc_verify_proofs_segments_mixed(const void* d_hidden, uint32_t hidden_dtype, const uint64_t* h_row_offsets,
-                                        uint64_t n_segments, uint32_t hidden, uint32_t k, const uint8_t* d_proofs,
-                                        uint32_t proof_dtype, const toploc_thresholds* thresholds,
-                                        toploc_verify_result* d_results, void* d_workspace, size_t workspace_bytes,
-                                        void* hip_stream)
-{
-    const SegPlan pl = plan_segments_mixed(h_row_offsets, n_segments, hidden, k, hidden_dtype, proof_dtype);
-    if (!pl.ok || !thresholds) return TOPLOC_EINVAL;
-    if (n_segments == 0) return TOPLOC_OK;
-    if (!d_hidden || !d_proofs || !d_results || !d_workspace || !aligned16(d_hidden) || !aligned16(d_workspace))
-        return TOPLOC_EINVAL;
-    if ((reinterpret_cast<uintptr_t>(d_proofs) & 1u) != 0 || (reinterpret_cast<uintptr_t>(d_results) & 3u) != 0)
-        return TOPLOC_EINVAL;
-    if (workspace_bytes < seg_workspace_bytes(pl, k, bits_size_of(hidden_dtype))) return TOPLOC_EWORKSPACE;
-    hipStream_t st = (hipStream_t)hip_stream;
-    Layout lay;
-    uint32_t* c_idx;
-    void* c_bits;
-    if (hidden_dtype == TOPLOC_DTYPE_F32) {
-        uint32_t* b32;
-        if (!stage_segments(pl, k, d_workspace, st, lay, c_idx, b32)) return TOPLOC_EHIP;
-        c_bits = b32;
-    } else {
-        uint16_t* b16;
-        if (!stage_segments(pl, k, d_workspace, st, lay, c_idx, b16)) return TOPLOC_EHIP;
-        c_bits = b16;
-    }
-    launch_part(st, d_hidden, lay, pl.parts.size(), k, c_idx, c_bits, hidden_dtype);
-    if (!hip_ok(hipGetLastError())) return TOPLOC_EHIP;
-    launch_verify_merge(st, lay, n_segments, k, c_idx, c_bits, d_proofs, *thresholds, d_results, hidden_dtype, proof_dtype);
-    return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
-}
-
 size_t toploc_stream_state_bytes(uint32_t n_seq, uint32_t k)
 {
-    if (k == 0 || k > TOPLOC_MAX_K) return 0;
-    return (size_t)n_seq * stream_stride(k);
+    if (!plan::stream_k_ok(k)) return 0;
+    return (size_t)n_seq * plan::stream_stride(k);
 }
 
 int toploc_stream_reset(void* d_state, uint32_t n_seq, uint32_t k, void* hip_stream)
 {
-    if (k == 0 || k > TOPLOC_MAX_K) return TOPLOC_EINVAL;
+    if (!plan::stream_k_ok(k)) return TOPLOC_EINVAL;
     if (n_seq == 0) return TOPLOC_OK;
     if (!d_state || !aligned16(d_state)) return TOPLOC_EINVAL;
     hipStream_t st = (hipStream_t)hip_stream;
     hipLaunchKernelGGL(stream_reset_kernel, dim3((n_seq + 255) / 256), dim3(256), 0, st, (char*)d_state, n_seq,
-                       stream_stride(k));
+                       plan::stream_stride(k));
     return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
 }
 
 int toploc_stream_append(void* d_state, const void* d_step_bf16, uint32_t n_seq, uint32_t hidden, uint32_t chunk_tokens,
                          uint32_t token, uint32_t k, void* hip_stream)
 {
-    if (k == 0 || k > TOPLOC_MAX_K || hidden == 0 || hidden % 8 != 0 || chunk_tokens == 0 || token >= chunk_tokens)
-        return TOPLOC_EINVAL;
-    const uint64_t chunk_values = (uint64_t)chunk_tokens * hidden;
-    if (chunk_values >= (1ull << 32)) return TOPLOC_EINVAL;
-    if (n_seq == 0) return TOPLOC_OK;
-    if (!d_state || !d_step_bf16 || !aligned16(d_state) || !aligned16(d_step_bf16)) return TOPLOC_EINVAL;
-    if (reinterpret_cast<uintptr_t>(d_step_bf16) < chunk_values * 2) return TOPLOC_EINVAL;  // the kernel forms row - v0
+    const int chk = plan::check_stream_append(d_state, d_step_bf16, n_seq, hidden, chunk_tokens, token, k);
+    if (chk != plan::kGo) return chk;
     hipStream_t st = (hipStream_t)hip_stream;
     const uint32_t hvec = hidden / 8;
     {
         ProfScope ps(TOPLOC_KERNEL_STREAM_APPEND, st);
         if (k <= 128)
             hipLaunchKernelGGL((stream_append_kernel<kCapSmall>), dim3(n_seq), dim3(kThreads), 0, st, (char*)d_state,
-                               stream_stride(k), (const u32x4*)d_step_bf16, hvec, token * hvec, k, nullptr, nullptr, n_seq,
+                               plan::stream_stride(k), (const u32x4*)d_step_bf16, hvec, token * hvec, k, nullptr, nullptr, n_seq,
                                chunk_tokens);
         else
             hipLaunchKernelGGL((stream_append_kernel<kCapLarge>), dim3(n_seq), dim3(kThreads), 0, st, (char*)d_state,
-                               stream_stride(k), (const u32x4*)d_step_bf16, hvec, token * hvec, k, nullptr, nullptr, n_seq,
+                               plan::stream_stride(k), (const u32x4*)d_step_bf16, hvec, token * hvec, k, nullptr, nullptr, n_seq,
                                chunk_tokens);
     }
     return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
@@ -1143,26 +1066,20 @@ int toploc_stream_append_rows(void* d_state, uint32_t n_slots, const void* d_ste
                               const uint32_t* d_tokens, uint32_t n_rows, uint32_t hidden, uint32_t chunk_tokens,
                               uint32_t k, void* hip_stream)
 {
-    if (k == 0 || k > TOPLOC_MAX_K || hidden == 0 || hidden % 8 != 0 || chunk_tokens == 0) return TOPLOC_EINVAL;
-    const uint64_t chunk_values = (uint64_t)chunk_tokens * hidden;
-    if (chunk_values >= (1ull << 32)) return TOPLOC_EINVAL;
-    if (n_rows == 0) return TOPLOC_OK;
-    if (!d_state || !d_step_bf16 || !d_slots || !d_tokens || n_slots == 0) return TOPLOC_EINVAL;
-    if (!aligned16(d_state) || !aligned16(d_step_bf16)) return TOPLOC_EINVAL;
-    if ((reinterpret_cast<uintptr_t>(d_slots) & 3u) != 0 || (reinterpret_cast<uintptr_t>(d_tokens) & 3u) != 0)
-        return TOPLOC_EINVAL;
-    if (reinterpret_cast<uintptr_t>(d_step_bf16) < chunk_values * 2) return TOPLOC_EINVAL;  // the kernel forms row - v0
+    const int chk = plan::check_stream_append_rows(d_state, n_slots, d_step_bf16, d_slots, d_tokens, n_rows, hidden,
+                                                   chunk_tokens, k);
+    if (chk != plan::kGo) return chk;
     hipStream_t st = (hipStream_t)hip_stream;
     const uint32_t hvec = hidden / 8;
     {
         ProfScope ps(TOPLOC_KERNEL_STREAM_APPEND, st);
         if (k <= 128)
             hipLaunchKernelGGL((stream_append_kernel<kCapSmall>), dim3(n_rows), dim3(kThreads), 0, st, (char*)d_state,
-                               stream_stride(k), (const u32x4*)d_step_bf16, hvec, 0u, k, d_slots, d_tokens, n_slots,
+                               plan::stream_stride(k), (const u32x4*)d_step_bf16, hvec, 0u, k, d_slots, d_tokens, n_slots,
                                chunk_tokens);
         else
             hipLaunchKernelGGL((stream_append_kernel<kCapLarge>), dim3(n_rows), dim3(kThreads), 0, st, (char*)d_state,
-                               stream_stride(k), (const u32x4*)d_step_bf16, hvec, 0u, k, d_slots, d_tokens, n_slots,
+                               plan::stream_stride(k), (const u32x4*)d_step_bf16, hvec, 0u, k, d_slots, d_tokens, n_slots,
                                chunk_tokens);
     }
     return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
@@ -1171,19 +1088,17 @@ int toploc_stream_append_rows(void* d_state, uint32_t n_slots, const void* d_ste
 int toploc_stream_emit(void* d_state, uint32_t n_seq, uint32_t k, uint8_t* d_proofs, uint8_t* d_status,
                        uint32_t* d_topk_idx_opt, void* hip_stream)
 {
-    if (k == 0 || k > TOPLOC_MAX_K) return TOPLOC_EINVAL;
-    if (n_seq == 0) return TOPLOC_OK;
-    if (!d_state || !d_proofs || !d_status || !aligned16(d_state)) return TOPLOC_EINVAL;
-    if ((reinterpret_cast<uintptr_t>(d_proofs) & 1u) != 0) return TOPLOC_EINVAL;
+    const int chk = plan::check_stream_emit(d_state, n_seq, k, d_proofs, d_status, false, nullptr, 0);
+    if (chk != plan::kGo) return chk;
     hipStream_t st = (hipStream_t)hip_stream;
     {
         ProfScope ps(TOPLOC_KERNEL_STREAM_EMIT, st);
         if (k <= 128)
             hipLaunchKernelGGL((stream_emit_kernel<256, 128, kCapSmall>), dim3(n_seq), dim3(256), 0, st, (char*)d_state,
-                               stream_stride(k), k, d_proofs, d_status, d_topk_idx_opt, nullptr, n_seq);
+                               plan::stream_stride(k), k, d_proofs, d_status, d_topk_idx_opt, nullptr, n_seq);
         else
             hipLaunchKernelGGL((stream_emit_kernel<1024, 512, kCapLarge>), dim3(n_seq), dim3(1024), 0, st, (char*)d_state,
-                               stream_stride(k), k, d_proofs, d_status, d_topk_idx_opt, nullptr, n_seq);
+                               plan::stream_stride(k), k, d_proofs, d_status, d_topk_idx_opt, nullptr, n_seq);
     }
     return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
 }
@@ -1191,20 +1106,17 @@ int toploc_stream_emit(void* d_state, uint32_t n_seq, uint32_t k, uint8_t* d_pro
 int toploc_stream_emit_rows(void* d_state, uint32_t n_slots, const uint32_t* d_slots, uint32_t n_rows, uint32_t k,
                             uint8_t* d_proofs, uint8_t* d_status, uint32_t* d_topk_idx_opt, void* hip_stream)
 {
-    if (k == 0 || k > TOPLOC_MAX_K) return TOPLOC_EINVAL;
-    if (n_rows == 0) return TOPLOC_OK;
-    if (!d_state || !d_slots || !d_proofs || !d_status || n_slots == 0 || !aligned16(d_state)) return TOPLOC_EINVAL;
-    if ((reinterpret_cast<uintptr_t>(d_proofs) & 1u) != 0 || (reinterpret_cast<uintptr_t>(d_slots) & 3u) != 0)
-        return TOPLOC_EINVAL;
+    const int chk = plan::check_stream_emit(d_state, n_rows, k, d_proofs, d_status, true, d_slots, n_slots);
+    if (chk != plan::kGo) return chk;
     hipStream_t st = (hipStream_t)hip_stream;
     {
         ProfScope ps(TOPLOC_KERNEL_STREAM_EMIT, st);
         if (k <= 128)
             hipLaunchKernelGGL((stream_emit_kernel<256, 128, kCapSmall>), dim3(n_rows), dim3(256), 0, st, (char*)d_state,
-                               stream_stride(k), k, d_proofs, d_status, d_topk_idx_opt, d_slots, n_slots);
+                               plan::stream_stride(k), k, d_proofs, d_status, d_topk_idx_opt, d_slots, n_slots);
         else
             hipLaunchKernelGGL((stream_emit_kernel<1024, 512, kCapLarge>), dim3(n_rows), dim3(1024), 0, st, (char*)d_state,
-                               stream_stride(k), k, d_proofs, d_status, d_topk_idx_opt, d_slots, n_slots);
+                               plan::stream_stride(k), k, d_proofs, d_status, d_topk_idx_opt, d_slots, n_slots);
     }
     return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
 }
@@ -1212,9 +1124,8 @@ int toploc_stream_emit_rows(void* d_state, uint32_t n_slots, const uint32_t* d_s
 int toploc_ring_append(void* d_ring_bf16, const void* d_step_bf16, uint32_t n_seq, uint32_t hidden,
                        uint32_t chunk_tokens, uint32_t step, void* hip_stream)
 {
-    if (hidden == 0 || hidden % 8 != 0 || chunk_tokens == 0) return TOPLOC_EINVAL;
-    if (n_seq == 0) return TOPLOC_OK;
-    if (!d_ring_bf16 || !d_step_bf16 || !aligned16(d_ring_bf16) || !aligned16(d_step_bf16)) return TOPLOC_EINVAL;
+    const int chk = plan::check_ring_append(d_ring_bf16, d_step_bf16, n_seq, hidden, chunk_tokens);
+    if (chk != plan::kGo) return chk;
     hipStream_t st = (hipStream_t)hip_stream;
     const uint32_t hvec = hidden / 8;
     const uint64_t total = (uint64_t)n_seq * hvec;

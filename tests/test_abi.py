@@ -45,6 +45,12 @@ def test_workspace_bytes_and_parameter_validation():
     L = binding.lib()
     bad = binding.Params(128, 32, 4096, 65521)                         # wrong prime
     assert L.toploc_workspace_bytes(ctypes.byref(bad), 1) == 0
+    # the query tells the two meanings of 0 apart
+    assert binding.toploc_workspace_query(128, 32, 8192, 16384) == (binding.OK, 0)
+    assert binding.toploc_workspace_query(0, 32, 4096, 10) == (binding.EINVAL, 0)
+    assert binding.toploc_workspace_query(128, 32, 4096, 10) == (binding.OK, binding.toploc_workspace_bytes(128, 32, 4096, 10))
+    assert binding.toploc_workspace_query(128, 32, 4096, 0) == (binding.OK, 0)
+    assert L.toploc_workspace_query(ctypes.byref(bad), 1, None) == binding.EINVAL
 
 
 def test_calls_are_rejected_before_any_launch():
@@ -60,16 +66,20 @@ def test_calls_are_rejected_before_any_launch():
     big = binding.Params(512, 32, 4096, binding.PRIME)
     assert L.toploc_build_proofs(fake, 1, ctypes.byref(big), fake, fake, None, fake, 16, None) == binding.EWORKSPACE
     assert L.toploc_build_proofs(fake, 1, ctypes.byref(big), fake, fake, None, None, 1 << 20, None) == binding.EINVAL
-    off = (ctypes.c_uint64 * 3)(0, 5, 4)                                     # decreasing offsets
-    assert L.toploc_segments_workspace_bytes(off, 2, 4096, 128) == 0
-    assert L.toploc_build_proofs_segments(fake, off, 2, 4096, 128, fake, fake, None, fake, 1 << 30, None) == binding.EINVAL
-    off = (ctypes.c_uint64 * 3)(0, 5, 9)
-    assert L.toploc_segments_workspace_bytes(off, 2, 4096, 128) > 0
-    assert L.toploc_segments_workspace_bytes(off, 2, 4100, 128) == 0         # hidden % 8 != 0
-    assert L.toploc_build_proofs_segments(fake, off, 2, 4096, 128, fake, fake, None, fake, 16, None) == binding.EWORKSPACE
-    assert L.toploc_verify_proofs_segments(fake, off, 0, 4096, 128, fake, ctypes.byref(thr), fake, fake, 0, None) == binding.OK
-    off = (ctypes.c_uint64 * 2)(0, 0)                                        # a segment shorter than k
-    assert L.toploc_build_proofs_segments(fake, off, 1, 4096, 128, fake, fake, None, fake, 1 << 30, None) == binding.EINVAL
+    # segment calls: the row offsets are device memory the host never reads, the plan comes from sizes alone
+    assert L.toploc_segments_workspace_bytes(2, 9, 4096, 128) > 0
+    assert L.toploc_segments_workspace_bytes(2, 9, 4100, 128) == 0           # hidden % 8 != 0
+    assert L.toploc_segments_workspace_bytes(2, 9, 4096, 513) == 0           # k > TOPLOC_MAX_K
+    assert L.toploc_segments_workspace_bytes(0, 9, 4096, 128) == 0           # nothing to do
+    assert L.toploc_segments_workspace_bytes(1 << 31, 9, 4096, 128) == 0     # too many segments
+    assert L.toploc_segments_workspace_bytes(2, 1 << 60, 4096, 128) == 0     # value count leaves 64 bits
+    assert L.toploc_build_proofs_segments(fake, 9, fake, 2, 4096, 128, fake, fake, None, fake, 16, None) == binding.EWORKSPACE
+    assert L.toploc_build_proofs_segments(fake, 9, None, 2, 4096, 128, fake, fake, None, fake, 1 << 30, None) == binding.EINVAL
+    assert L.toploc_build_proofs_segments(fake, 9, ctypes.c_void_p(0x1004), 2, 4096, 128, fake, fake, None, fake, 1 << 30,
+                                          None) == binding.EINVAL            # misaligned offsets
+    assert L.toploc_build_proofs_segments(fake, 9, fake, 2, 4096, 0, fake, fake, None, fake, 1 << 30, None) == binding.EINVAL
+    assert L.toploc_verify_proofs_segments(fake, 9, fake, 0, 4096, 128, fake, ctypes.byref(thr), fake, fake, 0, None) == binding.OK
+    assert L.toploc_verify_proofs_segments(fake, 9, fake, 2, 4096, 128, fake, None, fake, fake, 1 << 30, None) == binding.EINVAL
     assert L.toploc_set_split(5000) == binding.EINVAL and L.toploc_set_split(0) == binding.OK
     assert L.toploc_build_proofs(fake, 0, ctypes.byref(ok), fake, fake, None, fake, 0, None) == binding.OK
     assert L.toploc_verify_proofs(fake, 1, ctypes.byref(ok), fake, None, fake, None, 0, None) == binding.EINVAL
@@ -121,19 +131,17 @@ def test_newer_entry_points_check_their_arguments_before_any_launch():
     assert L.toploc_stream_emit_rows(fake, 8, None, 2, 128, fake, fake, None, None) == binding.EINVAL
     assert L.toploc_stream_emit_rows(fake, 8, fake, 2, 513, fake, fake, None, None) == binding.EINVAL
     # fp32 segments: k stops at 128, candidates are wider
-    off = (ctypes.c_uint64 * 3)(0, 5, 9)
-    b16 = L.toploc_segments_workspace_bytes_dtype(off, 2, 4096, 128, binding.DTYPE_BF16)
-    b32 = L.toploc_segments_workspace_bytes_dtype(off, 2, 4096, 128, binding.DTYPE_F32)
-    assert b16 == L.toploc_segments_workspace_bytes(off, 2, 4096, 128) and b32 > b16 > 0
-    assert L.toploc_segments_workspace_bytes_dtype(off, 2, 4096, 129, binding.DTYPE_F32) == 0
-    assert L.toploc_segments_workspace_bytes_dtype(off, 2, 4096, 128, 7) == 0                           # unknown dtype
-    assert L.toploc_build_proofs_segments_f32(fake, off, 2, 4096, 129, fake, fake, None, fake, 1 << 30, None) == binding.EINVAL
-    assert L.toploc_build_proofs_segments_f32(fake, off, 2, 4096, 128, fake, fake, None, fake, 16, None) == binding.EWORKSPACE
-    assert L.toploc_verify_proofs_segments_mixed(fake, binding.DTYPE_BF16, off, 2, 4096, 256, fake, binding.DTYPE_F32,
+    b16 = L.toploc_segments_workspace_bytes_dtype(2, 9, 4096, 128, binding.DTYPE_BF16)
+    b32 = L.toploc_segments_workspace_bytes_dtype(2, 9, 4096, 128, binding.DTYPE_F32)
+    assert b16 == L.toploc_segments_workspace_bytes(2, 9, 4096, 128) and b32 > b16 > 0
+    assert L.toploc_segments_workspace_bytes_dtype(2, 9, 4096, 129, binding.DTYPE_F32) == 0
+    assert L.toploc_segments_workspace_bytes_dtype(2, 9, 4096, 128, 7) == 0                           # unknown dtype
+    assert L.toploc_build_proofs_segments_f32(fake, 9, fake, 2, 4096, 129, fake, fake, None, fake, 1 << 30, None) == binding.EINVAL
+    assert L.toploc_build_proofs_segments_f32(fake, 9, fake, 2, 4096, 128, fake, fake, None, fake, 16, None) == binding.EWORKSPACE
+    assert L.toploc_verify_proofs_segments_mixed(fake, binding.DTYPE_BF16, 9, fake, 2, 4096, 256, fake, binding.DTYPE_F32,
                                                  ctypes.byref(thr), fake, fake, 1 << 30, None) == binding.EINVAL
-    assert L.toploc_verify_proofs_segments_mixed(fake, binding.DTYPE_F32, off, 0, 4096, 128, fake, binding.DTYPE_F32,
+    assert L.toploc_verify_proofs_segments_mixed(fake, binding.DTYPE_F32, 9, fake, 0, 4096, 128, fake, binding.DTYPE_F32,
                                                  ctypes.byref(thr), fake, fake, 0, None) == binding.OK
-
 
 def test_static_scratch_entry_point_rejects_before_any_launch():
     L = binding.lib()

@@ -231,5 +231,5 @@ def test_f32_segments_equal_fixed_chunks_and_reject_bad_arguments():
     with pytest.raises(tl.ToplocError):
         tl.toploc_verify_proofs_segments_mixed(x.to(torch.bfloat16), off,
                                                torch.zeros((4, 2 + 4 * 256), dtype=torch.uint8, device=DEV), orc.F32, k=256)
-    assert tl.toploc_segments_workspace_bytes_dtype(off, 1024, 128, tl.DTYPE_F32) > \
-        tl.toploc_segments_workspace_bytes_dtype(off, 1024, 128, tl.DTYPE_BF16) > 0
+    assert tl.toploc_segments_workspace_bytes_dtype(4, 128, 1024, 128, tl.DTYPE_F32) > \
+        tl.toploc_segments_workspace_bytes_dtype(4, 128, 1024, 128, tl.DTYPE_BF16) > 0

@@ -144,10 +144,91 @@ def test_segments_empty_and_invalid():
     x = torch.zeros((4, 64), dtype=torch.bfloat16, device=DEV)
     proofs, status = tl.toploc_build_proofs_segments(x, np.zeros(1, dtype=np.uint64), k=8)
     assert proofs.shape == (0, 18) and status.shape == (0,)
-    with pytest.raises(tl.ToplocError):
-        tl.toploc_build_proofs_segments(x, np.array([0, 1, 4], dtype=np.uint64), k=128)   # segment 0 holds 64 < k values
     with pytest.raises(ValueError):
         tl.toploc_build_proofs_segments(x, np.array([0, 9], dtype=np.uint64), k=8)        # past the tensor
+    with pytest.raises(tl.ToplocError):
+        tl.toploc_build_proofs_segments(x, np.array([0, 4], dtype=np.uint64), k=513)      # k above the limit
+
+
+def test_segments_that_cannot_carry_a_proof_are_reported_per_segment():
+    """The offsets live on the device, so what is wrong with one segment is that segment's status: too short
+    for k, offsets that decrease or leave the matrix.  The other segments get their oracle bytes."""
+    hidden, k = 256, 128
+    x = synth.activations(1, 40, hidden, 5050, n_outlier=4, device=DEV).reshape(40, hidden)
+    bits = synth.bits_numpy(x)
+    #        0: fine        1: empty   2: fine     3: decreasing  4: beyond the matrix (41 > 40 rows)
+    off = torch.tensor([0, 12, 12, 30, 25, 41], dtype=torch.int64, device=DEV)
+    say("segments with bad offsets: %s of %d rows" % (off.tolist(), x.shape[0]))
+    proofs, status, idx = tl.toploc_build_proofs_segments(x, off, k=k, want_topk=True)
+    res = tl.toploc_verify_proofs_segments(x, off, proofs, k=k)
+    torch.cuda.synchronize()
+    g = tl.results_numpy(res)
+    assert status.tolist() == [tl.CHUNK_OK, tl.CHUNK_SHORT, tl.CHUNK_OK, tl.CHUNK_BAD_SEGMENT, tl.CHUNK_BAD_SEGMENT]
+    assert g["status"].tolist() == status.tolist() and g["accept"].tolist() == [1, 0, 1, 0, 0]
+    for i, (a, b) in ((0, (0, 12)), (2, (12, 30))):
+        o_proofs, o_status, o_idx = orc.build(bits[a:b].reshape(1, -1), k, want_topk=True)
+        assert np.array_equal(proofs[i].cpu().numpy(), o_proofs[0]) and np.array_equal(idx[i].cpu().numpy().view(np.uint32), o_idx[0])
+    for i in (1, 3, 4):
+        assert not proofs[i].any() and (idx[i] == -1).all()
+    # one row of 256 values is exactly k = 256: the shortest segment that works; k = 257 does not fit
+    one = torch.tensor([7, 8], dtype=torch.int64, device=DEV)
+    p256, s256 = tl.toploc_build_proofs_segments(x, one, k=256)
+    p257, s257 = tl.toploc_build_proofs_segments(x, one, k=257)
+    torch.cuda.synchronize()
+    assert s256.tolist() == [tl.CHUNK_OK] and s257.tolist() == [tl.CHUNK_SHORT]
+    assert np.array_equal(p256[0].cpu().numpy(), orc.build(bits[7:8].reshape(1, -1), 256)[0][0])
+
+
+def test_segment_calls_captured_in_a_graph_follow_the_offsets_on_the_device():
+    """The segment calls only launch kernels: a captured build + verify pair is replayed with different row
+    offsets written into the same device array between replays, program work and synchronisations in between,
+    and every replay must give the bytes of an eager call and of the oracle on those offsets."""
+    hidden, k, total, n_seg = 2048, 128, 300, 5
+    x = synth.activations(1, total, hidden, 5400, n_outlier=4, device=DEV).reshape(total, hidden)
+    rec = synth.perturb_relative(x, 2.0 ** -7, 5401)
+    bits, rbits = synth.bits_numpy(x), synth.bits_numpy(rec)
+    layouts = [[0, 100, 132, 164, 196, 203], [0, 1, 2, 130, 131, 300], [10, 50, 50, 90, 290, 300],
+               [0, 100, 132, 164, 196, 203]]
+    off = torch.zeros(n_seg + 1, dtype=torch.int64, device=DEV)
+    out = (torch.empty((n_seg, 2 + 2 * k), dtype=torch.uint8, device=DEV), torch.empty(n_seg, dtype=torch.uint8, device=DEV),
+           torch.empty((n_seg, k), dtype=torch.int32, device=DEV))
+    res = torch.empty((n_seg, 20), dtype=torch.uint8, device=DEV)
+    ws_b, ws_v = tl.new_segments_workspace(x, n_seg, k), tl.new_segments_workspace(x, n_seg, k)
+    off.copy_(torch.tensor(layouts[0], dtype=torch.int64))
+    side = torch.cuda.Stream(device=DEV)
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):       # warm-up on the capture stream, then capture
+        tl.toploc_build_proofs_segments(x, off, k=k, want_topk=True, workspace=ws_b, out=out)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            tl.toploc_build_proofs_segments(x, off, k=k, want_topk=True, workspace=ws_b, out=out)
+            tl.toploc_verify_proofs_segments(rec, off, out[0], k=k, workspace=ws_v, out=res)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep, lay in enumerate(layouts):
+        say("graph replay %d with offsets %s" % (rep, lay))
+        off.copy_(torch.tensor(lay, dtype=torch.int64))
+        for t in out + (res,):
+            t.fill_(0x5A if t.dtype == torch.uint8 else 7)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        e_proofs, e_status, e_idx = tl.toploc_build_proofs_segments(x, lay, k=k, want_topk=True)      # eager, fresh buffers
+        e_res = tl.toploc_verify_proofs_segments(rec, lay, e_proofs, k=k)
+        torch.cuda.synchronize()
+        assert torch.equal(out[0], e_proofs) and torch.equal(out[1], e_status) and torch.equal(out[2], e_idx), "replay %d" % rep
+        assert torch.equal(res, e_res), "replay %d: verify records" % rep
+        g = tl.results_numpy(res)
+        for i in range(n_seg):
+            a, b = lay[i], lay[i + 1]
+            if (b - a) * hidden < k:
+                assert int(out[1][i]) == tl.CHUNK_SHORT and g["status"][i] == tl.CHUNK_SHORT
+                continue
+            o_proofs, o_status = orc.build(bits[a:b].reshape(1, -1), k)
+            assert np.array_equal(out[0][i].cpu().numpy(), o_proofs[0]) and int(out[1][i]) == int(o_status[0])
+            o = orc.verify(rbits[a:b].reshape(1, -1), o_proofs, k)
+            for f in FIELDS:
+                assert g[f][i] == o[f][0], "replay %d segment %d field %s" % (rep, i, f)
 
 
 def test_generation_layout_prefill_plus_decode_segments():
