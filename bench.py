@@ -30,12 +30,15 @@ def main():
                     help="config3 is the benchmark line; config2 is the 8B shape; config4 (verification stress) and "
                          "config5 (online decode-step path) print their own report line; config3_f32 is the 70B "
                          "shape with fp32 activations (64 sequences, the same 8 GiB) through the fp32 calls")
+    ap.add_argument("--law", default="outliers", choices=["outliers", "gaussian", "heavy_tail", "ascending"],
+                    help="value law of the synthetic activations (config3 / config2 only): outliers is the workload's "
+                         "recipe and the benchmark line; the others show how the selection's cost depends on the input")
     ap.add_argument("--k", type=int, default=128)
     ap.add_argument("--cpu-sample-chunks", type=int, default=6144)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
-                    help="also run one plain 1 GiB device copy and one pure read of the tensor, so that a "
-                         "rocprofv3 --pmc run of this command holds kernels of known traffic to scale by")
+                    help="also run one plain 1 GiB device copy, so that a rocprofv3 --pmc run of this command holds "
+                         "a kernel of known traffic to scale by (the pure read of the tensor is always run)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (chunks are independent; a multi-GPU run would "
@@ -57,11 +60,15 @@ def main():
         x = synth.activations(64, 4096, 8192, synth.BASE_SEED + 3, n_outlier=16, device=dev, dtype=torch.float32)
         name = "llama-3.1-70b-shaped, fp32: 64 seq x 4096 tok x hidden 8192 fp32, 32-token chunks, k=%d" % k
     elif args.workload == "config3":
-        x = synth.config3(dev)
+        x = synth.law_activations(args.law, 128, 4096, 8192, synth.BASE_SEED + 3, 16, device=dev)
         name = "llama-3.1-70b-shaped: 128 seq x 4096 tok x hidden 8192 bf16, 32-token chunks, k=%d" % k
     else:
-        x = synth.config2(dev)
+        x = synth.law_activations(args.law, 64, 2048, 4096, synth.BASE_SEED + 2, 8, device=dev)
         name = "llama-3.1-8b-shaped: 64 seq x 2048 tok x hidden 4096 bf16, 32-token chunks, k=%d" % k
+    if args.law != "outliers":
+        if f32:
+            sys.exit("bench.py: --law applies to config3 and config2")
+        name += ", value law: " + args.law
     chunks = synth.as_chunks(x)
     n_chunks, n = chunks.shape
     act_bytes = n_chunks * n * (4 if f32 else 2)
@@ -118,17 +125,40 @@ def main():
                            "GBps": alg_bytes[kn] * n_chunks / (avg_ms * 1e-3) / 1e9}
     dom = max(kernels, key=lambda kn: kernels[kn]["avg_ms"])
     # HBM traffic per launch from the committed rocprofv3 --pmc summary (FETCH_SIZE and WRITE_SIZE, each
-    # scaled by a plain copy of known size); it holds for the workload it was taken on and is null otherwise
+    # scaled by a plain copy of known size).  It is reported only for the workload it was taken on and only
+    # when the summary's stamp names the very build of the library loaded here; otherwise null.
     traffic = None
-    if args.workload == "config3" and k == 128:
+    build_id = tl.toploc_build_id()
+    if args.workload == "config3" and k == 128 and args.law == "outliers":
         import os
         pmc = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
                            "build_verify_kernels_70b_shape_hbm_traffic.txt")
         if os.path.exists(pmc):
+            stamp, found = None, None
             for line in open(pmc):
                 cols = line.split()
+                if len(cols) == 2 and cols[0] == "library_build_id":
+                    stamp = cols[1]
                 if len(cols) == 3 and cols[0] == "traffic_bytes_per_launch" and cols[1] == dom:
-                    traffic = float(cols[2])
+                    found = float(cols[2])
+            if stamp == build_id:
+                traffic = found
+    # what a pure read of the same tensor with the same access pattern reaches on this machine: the practical ceiling
+    ceiling = None
+    if not f32:
+        tl.toploc_profile_enable(True)
+        for _ in range(12):
+            tl.toploc_bench_read(chunks)
+        torch.cuda.synchronize()
+        rd = tl.toploc_profile_read()["read_kernel"]
+        tl.toploc_profile_enable(False)
+        ceiling = act_bytes / (rd[1] / rd[0] * 1e-3) / 1e9
+    # what the selection did per chunk on this input (a separate, instrumented launch outside the timed region)
+    selection = None
+    if not f32:
+        st4 = tl.toploc_selection_stats(chunks, k=k, chunk_tokens=1).to(torch.float64).mean(dim=0).tolist()
+        selection = {"drains_per_chunk": st4[0], "prunes_per_chunk": st4[1], "queued_vectors_per_chunk": st4[2],
+                     "candidates_per_chunk": st4[3]}
     roofline = {
         "bound": "hbm",
         "kernel": dom,
@@ -137,6 +167,7 @@ def main():
         "unit": "GB/s",
         "frac": kernels[dom]["GBps"] / HBM_PEAK_GBPS,
         "traffic": traffic,
+        "read_ceiling": ceiling,
         "avg_launch_ms": kernels[dom]["avg_ms"],
         "algorithmic_bytes_per_launch": alg_bytes[dom] * n_chunks,
     }
@@ -146,7 +177,6 @@ def main():
         src = chunks.reshape(-1)[: gib // 2]
         dst = torch.empty_like(src)
         dst.copy_(src)                       # reads 2^30 bytes, writes 2^30 bytes
-        tl.toploc_bench_read(chunks)         # reads the whole tensor, writes nothing
         torch.cuda.synchronize()
 
     cpu = None
@@ -202,7 +232,9 @@ def main():
         "dtype": "u32" if f32 else "u16",
         "data": "synthetic",
         "config": {"workload": name, "n_chunks": n_chunks, "chunk_values": n, "k": k,
-                   "activation_bytes": act_bytes},
+                   "activation_bytes": act_bytes, "law": args.law},
+        "library_build_id": build_id,
+        "selection": selection,
         "chunks_per_s": n_chunks / (ms_per_step * 1e-3),
         "frac_hbm_peak": 2 * act_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "kernels": kernels,

@@ -317,6 +317,13 @@ int toploc_stream_emit_rows(void *d_state, uint32_t n_slots, const uint32_t *d_s
 int toploc_bench_read(const void *d_hidden_bf16, uint64_t n_chunks, uint64_t chunk_values, uint32_t *d_out,
                       void *hip_stream);
 
+/* Measurement aid, not part of the method: what the selection (the top-k step of Algorithm 1 / 2)
+ * did on every chunk.  d_stats: out, device, n_chunks * 4 uint32: drains of the queue, prunes of
+ * the candidate buffer, vectors queued, candidates appended (the final drain and prune of a chunk
+ * included).  Parameters as toploc_build_proofs.  Input laws differ in exactly these numbers. */
+int toploc_selection_stats(const void *d_hidden_bf16, uint64_t n_chunks, const toploc_params *params,
+                           uint32_t *d_stats, void *hip_stream);
+
 /* Kernel timing for benchmarks.  toploc_profile_enable(1) creates a pool of HIP events (the only
  * place the library creates any; they live until the process ends); while enabled, every kernel
  * launch is bracketed by two events of the pool on the caller's stream, and a launch that finds the
@@ -344,6 +351,11 @@ const char *toploc_strerror(int code);
 
 /* hipError_t (as int) of the last failed HIP call in this process, 0 if none. */
 int toploc_last_hip_error(void);
+
+/* Identifies the sources and compiler flags this library was built from (a hash the in-tree build
+ * stamps in; "unstamped" otherwise).  Profile summaries record it, so that a reader of a number can
+ * tell whether it was measured on this code.  Never NULL. */
+const char *toploc_build_id(void);
 
 #ifdef __cplusplus
 }

@@ -66,6 +66,8 @@ EXPORTS = (
     "toploc_stream_emit_rows",
     "toploc_ring_append",
     "toploc_bench_read",
+    "toploc_selection_stats",
+    "toploc_build_id",
     "toploc_profile_enable",
     "toploc_profile_read",
     "toploc_strerror",
@@ -140,6 +142,8 @@ def lib():
         L.toploc_stream_append_rows.argtypes = [P, c.c_uint32, P, P, P, c.c_uint32, c.c_uint32, c.c_uint32, c.c_uint32, P]
         L.toploc_stream_emit_rows.argtypes = [P, c.c_uint32, P, c.c_uint32, c.c_uint32, P, P, P, P]
         L.toploc_bench_read.argtypes = [P, c.c_uint64, c.c_uint64, P, P]
+        L.toploc_selection_stats.argtypes = [P, c.c_uint64, c.POINTER(Params), P, P]
+        L.toploc_build_id.restype = c.c_char_p
         L.toploc_profile_enable.argtypes = [c.c_int]
         L.toploc_profile_read.argtypes = [c.POINTER(c.c_uint32), c.POINTER(c.c_float)]
         L.toploc_strerror.argtypes = [c.c_int]
@@ -558,6 +562,22 @@ def toploc_bench_read(hidden, out=None):
     if rc != OK:
         raise ToplocError(rc, "toploc_bench_read")
     return out
+
+
+def toploc_selection_stats(hidden, k=128, chunk_tokens=32):
+    """Per chunk: drains, prunes, queued vectors, appended candidates of the selection (int32 [n_chunks, 4])."""
+    n_chunks, h = _chunks(hidden, chunk_tokens)
+    p = Params(k, chunk_tokens, h, PRIME)
+    stats = torch.zeros((n_chunks, 4), dtype=torch.int32, device=hidden.device)
+    rc = lib().toploc_selection_stats(hidden.data_ptr(), n_chunks, ctypes.byref(p), stats.data_ptr(), _stream(hidden))
+    if rc != OK:
+        raise ToplocError(rc, "toploc_selection_stats")
+    return stats
+
+
+def toploc_build_id():
+    """Hash of the sources and flags the loaded library was built from."""
+    return lib().toploc_build_id().decode()
 
 
 def toploc_profile_enable(on):

@@ -2,6 +2,8 @@
 
     python -m paper_2501_16007_amd.build [--verbose]
 """
+import glob
+import hashlib
 import os
 import subprocess
 import sys
@@ -16,8 +18,19 @@ FLAGS = [
 ]
 
 
+def build_id():
+    """sha256 (first 16 hex digits) over the kernel sources, the public header and the compiler flags."""
+    h = hashlib.sha256()
+    files = sorted(glob.glob(os.path.join(HERE, "csrc", "*"))) + [os.path.join(os.path.dirname(HERE), "include", "toploc.h")]
+    for path in files:
+        h.update(os.path.basename(path).encode())
+        h.update(open(path, "rb").read())
+    h.update(" ".join(FLAGS).encode())
+    return h.hexdigest()[:16]
+
+
 def build(verbose=False):
-    cmd = ["hipcc"] + FLAGS + ([
+    cmd = ["hipcc"] + FLAGS + ['-DTOPLOC_BUILD_ID="%s"' % build_id()] + ([
         "-Rpass-analysis=kernel-resource-usage"] if verbose else []) + [SRC, "-o", LIB]
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     out = "\n".join(l for l in res.stdout.splitlines() if "not a recognized feature" not in l)

@@ -68,6 +68,7 @@ __device__ __forceinline__ int32_t vec_max_mag(const u32x4& r)
 // (exponent, then mantissa pieces); half a vector (8 bytes) holds ELEMS/2 patterns.
 struct Bf16Fmt {
     typedef uint16_t bits_t;
+    static constexpr bool STATS = false;   // see Bf16FmtStats
     static constexpr int ELEMS = 8;
     static constexpr uint32_t MAG_MASK = 0x7FFFu;
     static constexpr int LEVELS = 2;
@@ -79,8 +80,14 @@ struct Bf16Fmt {
         return (((e >> 1) ? w.y : w.x) >> (16 * (e & 1))) & 0xFFFFu;
     }
 };
+// The same format with the selection's event counters switched on (a measurement aid: how many
+// drains and prunes a chunk costs, how many vectors were queued, how many candidates appended).
+struct Bf16FmtStats : Bf16Fmt {
+    static constexpr bool STATS = true;
+};
 struct F32Fmt {
     typedef uint32_t bits_t;
+    static constexpr bool STATS = false;
     static constexpr int ELEMS = 4;
     static constexpr uint32_t MAG_MASK = 0x7FFFFFFFu;
     static constexpr int LEVELS = 4;
@@ -116,7 +123,9 @@ struct SelectShared {
     int32_t tm;               // threshold magnitude
     uint32_t ti;              // threshold index
     uint32_t flag[3];         // "queue passed its soft limit" for barrier round r mod 3
+    uint32_t stats[Fmt::STATS ? 4 : 1];   // STATS only: drains, prunes, queued vectors, appended candidates
 };
+enum { kStatDrains = 0, kStatPrunes = 1, kStatQueued = 2, kStatAppended = 3 };
 
 __device__ __forceinline__ uint32_t lane_id() { return __lane_id(); }
 
@@ -230,12 +239,14 @@ __device__ TOPLOC_PRUNE_ATTR uint32_t prune_if_above(SelectShared<THREADS, CAP, 
     __syncthreads();  // appends are visible
     const uint32_t M = s.count;
     if (M <= limit || M > (uint32_t)CAP) {  // uniform decision
+        if (Fmt::STATS && tid == 0 && M <= (uint32_t)CAP) s.stats[kStatAppended] += M - s.count_base;
         if (tid == 0 && M <= (uint32_t)CAP) s.count_base = M;
         if (SYNC_AFTER) __syncthreads();  // everyone has read the count before anyone appends again
         return M;
     }
     for (uint32_t b = tid; b < 256u * Fmt::LEVELS; b += THREADS) (&s.hist[0][0])[b] = 0;
     if (tid == 0) { s.eq_count = 0; s.hole_count = 0; s.move_count = 0; }
+    if (Fmt::STATS && tid == 0) { s.stats[kStatPrunes] += 1; s.stats[kStatAppended] += M - s.count_base; }
     __syncthreads();
     // radix descent: digit l of the k-th largest magnitude, among the entries that share its higher digits
     uint32_t prefix = 0, above = 0;
@@ -359,6 +370,7 @@ __device__ TOPLOC_DRAIN_ATTR bool drain(SelectShared<THREADS, CAP, QCAP, Fmt>& s
     const uint32_t raw = s.qcount[epoch & 1u];
     const uint32_t nq = raw < (uint32_t)QCAP ? raw : (uint32_t)QCAP;
     if (tid == 0) s.qcount[(epoch + 1u) & 1u] = 0;  // last read one drain ago; visible after the barrier below
+    if (Fmt::STATS && tid == 0) { s.stats[kStatDrains] += 1; s.stats[kStatQueued] += nq; }
     ++epoch;
     limit = limit < (uint32_t)(CAP / 2) ? limit : (uint32_t)(CAP / 2);
     drain_range(s, 0u, nq, t);
@@ -517,6 +529,7 @@ __device__ __forceinline__ SelectStart select_topk_from(const u32x4* __restrict_
     if (tid == 0) {
         s.qcount[0] = 0; s.qcount[1] = 0; s.count = n_seed; s.count_base = n_seed; s.eq_count = 0; s.tm = start.t.tm; s.ti = start.t.ti;
         s.flag[0] = 0; s.flag[1] = 0; s.flag[2] = 0;
+        if (Fmt::STATS) { s.stats[0] = 0; s.stats[1] = 0; s.stats[2] = 0; s.stats[3] = 0; }
     }
     Threshold t = start.t;
     uint32_t round = 0;    // barrier rounds; flag[round % 3] belongs to the current one

@@ -164,6 +164,18 @@ __global__ __launch_bounds__(kThreads, WAVES) void select_kernel(const u32x4* __
     }
 }
 
+// Measurement aid: the same selection with its event counters on; writes, per chunk, the number of
+// drains and prunes, of queued vectors and of candidates appended (the final drain and prune included).
+template <int CAP>
+__global__ __launch_bounds__(kThreads) void select_stats_kernel(const u32x4* __restrict__ hidden, uint32_t nvec, uint32_t k,
+                                                                uint32_t* __restrict__ out_stats)
+{
+    __shared__ SelectShared<kThreads, CAP, kQcap, Bf16FmtStats> s;
+    const uint64_t chunk = blockIdx.x;
+    select_topk<kThreads, kLoads, CAP, kQcap>(hidden + chunk * nvec, 0u, nvec, k, s);
+    if (threadIdx.x < 4) out_stats[chunk * 4 + threadIdx.x] = s.stats[threadIdx.x];
+}
+
 // ---------------------------------------------------------------------------
 // Algorithm 1 in one launch, k <= KMAX <= kThreads: the selection streams the chunk,
 // then the same workgroup turns its k pairs into the proof out of LDS (the selection's
@@ -1155,6 +1167,22 @@ int toploc_bench_read(const void* d_hidden_bf16, uint64_t n_chunks, uint64_t chu
     return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
 }
 
+int toploc_selection_stats(const void* d_hidden_bf16, uint64_t n_chunks, const toploc_params* params, uint32_t* d_stats,
+                           void* hip_stream)
+{
+    const uint64_t n = chunk_len(params);
+    const int chk = plan::check_fixed(n, n_chunks, d_hidden_bf16, d_stats, 4, d_stats, 4, nullptr);
+    if (chk != plan::kGo) return chk;
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (params->k <= 128)
+        hipLaunchKernelGGL((select_stats_kernel<kCapSmall>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
+                           (const u32x4*)d_hidden_bf16, (uint32_t)(n / 8), params->k, d_stats);
+    else
+        hipLaunchKernelGGL((select_stats_kernel<kCapLarge>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
+                           (const u32x4*)d_hidden_bf16, (uint32_t)(n / 8), params->k, d_stats);
+    return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
+}
+
 int toploc_profile_enable(int on)
 {
     if (on) {  // the only place events are created: up to kProfPairs launches can be timed between two reads
@@ -1205,6 +1233,11 @@ const char* toploc_strerror(int code)
 }
 
 int toploc_last_hip_error(void) { return g_last_hip_error; }
+
+#ifndef TOPLOC_BUILD_ID
+#define TOPLOC_BUILD_ID "unstamped"
+#endif
+const char* toploc_build_id(void) { return TOPLOC_BUILD_ID; }
 
 #ifdef TOPLOC_TIMING
 // debug builds only: read (out != NULL) or clear the per-phase tick sums

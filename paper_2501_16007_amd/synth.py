@@ -141,6 +141,41 @@ def config3(device="cpu", n_seq=128, n_tok=4096):
     return activations(n_seq, n_tok, 8192, BASE_SEED + 3, n_outlier=16, device=device)
 
 
+LAWS = ("outliers", "gaussian", "heavy_tail", "ascending")
+
+
+def law_activations(law, n_seq, n_tok, hidden, seed, n_outlier, device="cpu"):
+    """The same shape under four value laws, to show how much the selection's cost depends on the input:
+    outliers    the recipe of `activations` (what the workloads use)
+    gaussian    N(0,1) everywhere, no outlier channels: the top-k are spread over all channels
+    heavy_tail  N(0,1) * exp(N(0,1)) per element: large values everywhere, the threshold keeps rising
+    ascending   inside every 32-token chunk the magnitudes never decrease with the flat index (random signs):
+                every value read is larger than all before it, the worst case of a streaming selection"""
+    if law == "outliers":
+        return activations(n_seq, n_tok, hidden, seed, n_outlier=n_outlier, device=device)
+    if law == "gaussian":
+        return activations(n_seq, n_tok, hidden, seed, n_outlier=0, device=device)
+    device = torch.device(device)
+    g = _gen(seed + 1, device)
+    out = torch.empty((n_seq, n_tok, hidden), dtype=torch.bfloat16, device=device)
+    if law == "heavy_tail":
+        for s in range(n_seq):
+            x = torch.randn((n_tok, hidden), generator=g, device=device, dtype=torch.float32)
+            x *= torch.exp(torch.randn((n_tok, hidden), generator=g, device=device, dtype=torch.float32))
+            out[s] = x.to(torch.bfloat16)
+        return out
+    if law == "ascending":
+        assert n_tok % CHUNK_TOKENS == 0
+        n = CHUNK_TOKENS * hidden
+        ramp = (torch.arange(n, device=device, dtype=torch.int64) * 0x7F00 // (n + 64)).to(torch.int32)   # finite patterns
+        for s in range(n_seq):
+            sign = torch.randint(0, 2, (n_tok // CHUNK_TOKENS, n), generator=g, device=device, dtype=torch.int32) << 15
+            bits = (ramp[None, :] | sign).to(torch.uint16).view(torch.bfloat16)
+            out[s] = bits.reshape(n_tok, hidden)
+        return out
+    raise ValueError("unknown law %r" % (law,))
+
+
 def config4_variants(x, device=None):
     """Recomputed tensors for the verification stress test, from the original x:
     (a) relative perturbation <= 2^-7, (b) independent activations (different

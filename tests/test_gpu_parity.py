@@ -497,3 +497,24 @@ def test_decode_edges_and_the_zero_modulus_field():
     g = gpu_verify(x, o_proofs, k)
     assert_results_equal(g, orc.verify(h, o_proofs, k), "zero field")
     assert (g["accept"] == 1).all() and (g["mant_sum"] == 0).all() and (g["n_match"] == k).all()
+
+
+def test_selection_statistics_tell_input_laws_apart():
+    """toploc_selection_stats (a measurement aid): counters of the instrumented selection on inputs whose
+    behaviour is known.  Descending magnitudes: the first round holds the whole top-k, nothing is queued
+    afterwards.  Ascending: every round brings values above everything seen so far, so the queue overflows
+    in every round and the candidate buffer is pruned again and again."""
+    n, k = 32 * 1024, 128
+    mags = (np.arange(n, dtype=np.uint32) * 0x7F00 // n).astype(np.uint16)
+    asc = mags.copy()
+    asc[1::2] |= 0x8000
+    bits = np.stack([asc, asc[::-1].copy()])
+    st = tl.toploc_selection_stats(_from_bits(bits), k=k, chunk_tokens=1)
+    torch.cuda.synchronize()
+    drains, prunes, queued, appended = st.cpu().numpy().T.tolist()
+    say("selection stats asc/desc: drains %s prunes %s queued %s appended %s" % (drains, prunes, queued, appended))
+    nvec = n // 8
+    assert drains[1] == 1 and prunes[1] == 1 and queued[1] <= 256 and k <= appended[1] <= 2048      # the final ones only
+    assert drains[0] >= 4 and prunes[0] >= 8 and nvec // 4 <= queued[0] <= nvec and 4096 <= appended[0] <= n
+    with pytest.raises(tl.ToplocError):
+        tl.toploc_selection_stats(_from_bits(bits), k=0, chunk_tokens=1)
