@@ -60,7 +60,7 @@ extern "C" {
 #define TOPLOC_DTYPE_BF16 0u
 #define TOPLOC_DTYPE_F32 1u
 #define TOPLOC_PRIME32 4294967291u  /* 2^32 - 5: the field modulus when fp32 patterns are encoded */
-#define TOPLOC_MAX_K_F32 128u       /* largest k of the calls that involve fp32                    */
+#define TOPLOC_MAX_K_F32 512u       /* largest k of the calls that involve fp32                    */
 
 /* call-level return codes */
 #define TOPLOC_OK 0
@@ -232,7 +232,9 @@ int toploc_ring_append(void *d_ring_bf16, const void *d_step_bf16, uint32_t n_se
  *   toploc_proof_bytes_dtype   2 + 2k (TOPLOC_DTYPE_BF16) or 2 + 4k (TOPLOC_DTYPE_F32)
  *   toploc_build_proofs_f32    Algorithm 1 over [n_chunks][chunk_tokens*hidden] fp32 values;
  *                              params->prime must be TOPLOC_PRIME32, k <= TOPLOC_MAX_K_F32;
- *                              proofs are 2 + 4k bytes each; other arguments as toploc_build_proofs
+ *                              proofs are 2 + 4k bytes each; other arguments as toploc_build_proofs,
+ *                              the workspace (toploc_workspace_bytes_f32; candidates carry 4-byte
+ *                              patterns) being required for k > 128 and optional otherwise
  *   toploc_verify_proofs_mixed Algorithm 2 with activations of `hidden_dtype` and proofs of
  *                              `proof_dtype` (params->prime: the proof's field).  Exponent and
  *                              mantissa are compared in the validator's (the activations')
@@ -240,7 +242,7 @@ int toploc_ring_append(void *d_ring_bf16, const void *d_step_bf16, uint32_t n_se
  *                              (>> 16) for a bf16 validator, a bf16 proof's value gets 16 zero
  *                              bits appended for an fp32 validator.  Thresholds are the caller's
  *                              (the paper uses the validator's precision's).
- * Both run as one fused launch per call and need no workspace.
+ * The validation runs as one fused launch per call and needs no workspace.
  *   toploc_build_proofs_segments_f32, toploc_verify_proofs_segments_mixed
  *                              the same two over segments of unequal length (the whole prompt,
  *                              a ragged last chunk), arguments as toploc_build_proofs_segments /
@@ -248,8 +250,10 @@ int toploc_ring_append(void *d_ring_bf16, const void *d_step_bf16, uint32_t n_se
  *                              toploc_segments_workspace_bytes_dtype(..., hidden_dtype) bytes
  *                              (candidates carry 4-byte patterns when the activations are fp32) */
 size_t toploc_proof_bytes_dtype(uint32_t k, uint32_t dtype);
+size_t toploc_workspace_bytes_f32(const toploc_params *params, uint64_t n_chunks);
 int toploc_build_proofs_f32(const void *d_hidden_f32, uint64_t n_chunks, const toploc_params *params, uint8_t *d_proofs,
-                            uint8_t *d_status, uint32_t *d_topk_idx_opt, void *hip_stream);
+                            uint8_t *d_status, uint32_t *d_topk_idx_opt, void *d_workspace, size_t workspace_bytes,
+                            void *hip_stream);
 int toploc_verify_proofs_mixed(const void *d_hidden, uint32_t hidden_dtype, uint64_t n_chunks, const toploc_params *params,
                                const uint8_t *d_proofs, uint32_t proof_dtype, const toploc_thresholds *thresholds,
                                toploc_verify_result *d_results, void *hip_stream);
@@ -307,6 +311,24 @@ int toploc_stream_append_rows(void *d_state, uint32_t n_slots, const void *d_ste
                               uint32_t k, void *hip_stream);
 int toploc_stream_emit_rows(void *d_state, uint32_t n_slots, const uint32_t *d_slots, uint32_t n_rows, uint32_t k,
                             uint8_t *d_proofs, uint8_t *d_status, uint32_t *d_topk_idx_opt, void *hip_stream);
+
+/* The running top-k for either precision (Section 5.7: fp32 inference): the same four operations
+ * with the element type as an argument; the calls above are these with TOPLOC_DTYPE_BF16.  With
+ * TOPLOC_DTYPE_F32 a state holds 4-byte patterns (16 + 8k bytes per sequence, parts rounded up to
+ * 16), rows are fp32, proofs are 2 + 4k bytes over GF(TOPLOC_PRIME32), k <= TOPLOC_MAX_K_F32.
+ *   toploc_stream_append_dtype  d_slots and d_tokens both NULL: row r of d_step [n_rows][hidden] is
+ *                               token `token` of sequence r (n_slots is ignored); both given: row r
+ *                               is token d_tokens[r] of sequence d_slots[r] < n_slots (`token` is
+ *                               ignored)
+ *   toploc_stream_emit_dtype    d_slots NULL: output row r is sequence r; else sequence d_slots[r] */
+size_t toploc_stream_state_bytes_dtype(uint32_t n_seq, uint32_t k, uint32_t dtype);
+int toploc_stream_reset_dtype(void *d_state, uint32_t n_seq, uint32_t k, uint32_t dtype, void *hip_stream);
+int toploc_stream_append_dtype(void *d_state, uint32_t n_slots, const void *d_step, uint32_t dtype,
+                               const uint32_t *d_slots, const uint32_t *d_tokens, uint32_t n_rows, uint32_t hidden,
+                               uint32_t chunk_tokens, uint32_t token, uint32_t k, void *hip_stream);
+int toploc_stream_emit_dtype(void *d_state, uint32_t n_slots, uint32_t dtype, const uint32_t *d_slots, uint32_t n_rows,
+                             uint32_t k, uint8_t *d_proofs, uint8_t *d_status, uint32_t *d_topk_idx_opt,
+                             void *hip_stream);
 
 /* Measurement aid, not part of the method: reads n_chunks * chunk_values bf16
  * values with the access pattern of the selection kernel (one workgroup per

@@ -26,7 +26,7 @@ BF16_THRESHOLDS = (38, 10, 8)  # T_exp, T_mean, T_median (Section 5.2 of the pap
 F32_THRESHOLDS = (8, 256, 128)  # the same for fp32 inference
 DTYPE_BF16, DTYPE_F32 = 0, 1
 PRIME32 = 4294967291
-MAX_K_F32 = 128
+MAX_K_F32 = 512
 
 RESULT_DTYPE = np.dtype(
     [
@@ -53,6 +53,7 @@ EXPORTS = (
     "toploc_verify_proofs",
     "toploc_topk",
     "toploc_proof_bytes_dtype",
+    "toploc_workspace_bytes_f32",
     "toploc_build_proofs_f32",
     "toploc_verify_proofs_mixed",
     "toploc_segments_workspace_bytes_dtype",
@@ -64,6 +65,10 @@ EXPORTS = (
     "toploc_stream_emit",
     "toploc_stream_append_rows",
     "toploc_stream_emit_rows",
+    "toploc_stream_state_bytes_dtype",
+    "toploc_stream_reset_dtype",
+    "toploc_stream_append_dtype",
+    "toploc_stream_emit_dtype",
     "toploc_ring_append",
     "toploc_bench_read",
     "toploc_selection_stats",
@@ -125,7 +130,9 @@ def lib():
         L.toploc_ring_append.argtypes = [P, P, c.c_uint32, c.c_uint32, c.c_uint32, c.c_uint32, P]
         L.toploc_proof_bytes_dtype.argtypes = [c.c_uint32, c.c_uint32]
         L.toploc_proof_bytes_dtype.restype = c.c_size_t
-        L.toploc_build_proofs_f32.argtypes = [P, c.c_uint64, c.POINTER(Params), P, P, P, P]
+        L.toploc_workspace_bytes_f32.argtypes = [c.POINTER(Params), c.c_uint64]
+        L.toploc_workspace_bytes_f32.restype = c.c_size_t
+        L.toploc_build_proofs_f32.argtypes = [P, c.c_uint64, c.POINTER(Params), P, P, P, P, c.c_size_t, P]
         L.toploc_verify_proofs_mixed.argtypes = [P, c.c_uint32, c.c_uint64, c.POINTER(Params), P, c.c_uint32,
                                                  c.POINTER(Thresholds), P, P]
         L.toploc_segments_workspace_bytes_dtype.argtypes = [c.c_uint64, c.c_uint64, c.c_uint32, c.c_uint32, c.c_uint32]
@@ -141,6 +148,12 @@ def lib():
         L.toploc_stream_emit.argtypes = [P, c.c_uint32, c.c_uint32, P, P, P, P]
         L.toploc_stream_append_rows.argtypes = [P, c.c_uint32, P, P, P, c.c_uint32, c.c_uint32, c.c_uint32, c.c_uint32, P]
         L.toploc_stream_emit_rows.argtypes = [P, c.c_uint32, P, c.c_uint32, c.c_uint32, P, P, P, P]
+        L.toploc_stream_state_bytes_dtype.argtypes = [c.c_uint32, c.c_uint32, c.c_uint32]
+        L.toploc_stream_state_bytes_dtype.restype = c.c_size_t
+        L.toploc_stream_reset_dtype.argtypes = [P, c.c_uint32, c.c_uint32, c.c_uint32, P]
+        L.toploc_stream_append_dtype.argtypes = [P, c.c_uint32, P, c.c_uint32, P, P, c.c_uint32, c.c_uint32, c.c_uint32,
+                                                 c.c_uint32, c.c_uint32, P]
+        L.toploc_stream_emit_dtype.argtypes = [P, c.c_uint32, c.c_uint32, P, c.c_uint32, c.c_uint32, P, P, P, P]
         L.toploc_bench_read.argtypes = [P, c.c_uint64, c.c_uint64, P, P]
         L.toploc_selection_stats.argtypes = [P, c.c_uint64, c.POINTER(Params), P, P]
         L.toploc_build_id.restype = c.c_char_p
@@ -397,7 +410,12 @@ def _chunks_any(hidden, chunk_tokens):
     raise ValueError("hidden must be [n_seq, n_tok, H] or [n_chunks, chunk_tokens*H]")
 
 
-def toploc_build_proofs_f32(hidden, k=128, chunk_tokens=32, want_topk=False):
+def toploc_workspace_bytes_f32(k, chunk_tokens, hidden, n_chunks):
+    p = Params(k, chunk_tokens, hidden, PRIME32)
+    return int(lib().toploc_workspace_bytes_f32(ctypes.byref(p), n_chunks))
+
+
+def toploc_build_proofs_f32(hidden, k=128, chunk_tokens=32, want_topk=False, workspace=None):
     """Algorithm 1 over fp32 activations. Returns (proofs uint8 [n_chunks, 2+4k], status[, idx])."""
     n_chunks, h, dt = _chunks_any(hidden, chunk_tokens)
     if dt != DTYPE_F32:
@@ -407,8 +425,11 @@ def toploc_build_proofs_f32(hidden, k=128, chunk_tokens=32, want_topk=False):
     proofs = torch.empty((n_chunks, 2 + 4 * k), dtype=torch.uint8, device=dev)
     status = torch.empty(n_chunks, dtype=torch.uint8, device=dev)
     idx = torch.empty((n_chunks, k), dtype=torch.int32, device=dev) if want_topk else None
+    if workspace is None:
+        workspace = torch.empty(max(16, toploc_workspace_bytes_f32(k, chunk_tokens, h, n_chunks)), dtype=torch.uint8, device=dev)
     rc = lib().toploc_build_proofs_f32(hidden.data_ptr(), n_chunks, ctypes.byref(p), proofs.data_ptr(), status.data_ptr(),
-                                       idx.data_ptr() if want_topk else None, _stream(hidden))
+                                       idx.data_ptr() if want_topk else None, workspace.data_ptr(), workspace.numel(),
+                                       _stream(hidden))
     if rc != OK:
         raise ToplocError(rc, "toploc_build_proofs_f32")
     return (proofs, status, idx) if want_topk else (proofs, status)
@@ -459,50 +480,56 @@ def toploc_verify_proofs_segments_mixed(hidden, row_offsets, proofs, proof_dtype
     return res
 
 
-def toploc_stream_state_bytes(n_seq, k):
-    return int(lib().toploc_stream_state_bytes(n_seq, k))
+def toploc_stream_state_bytes(n_seq, k, dtype=DTYPE_BF16):
+    return int(lib().toploc_stream_state_bytes_dtype(n_seq, k, dtype))
 
 
-def toploc_stream_new_state(n_seq, k, device):
-    """Device memory for the running top-k of n_seq sequences, emptied."""
-    nbytes = toploc_stream_state_bytes(n_seq, k)
+def toploc_stream_new_state(n_seq, k, device, dtype=DTYPE_BF16):
+    """Device memory for the running top-k of n_seq sequences (bf16 or fp32 rows), emptied."""
+    nbytes = toploc_stream_state_bytes(n_seq, k, dtype)
     if nbytes == 0 and n_seq:
         raise ToplocError(EINVAL, "toploc_stream_state_bytes")
     state = torch.empty(max(16, nbytes), dtype=torch.uint8, device=device)
-    toploc_stream_reset(state, n_seq, k)
+    toploc_stream_reset(state, n_seq, k, dtype)
     return state
 
 
-def toploc_stream_reset(state, n_seq, k):
-    rc = lib().toploc_stream_reset(state.data_ptr(), n_seq, k, _stream(state))
+def toploc_stream_reset(state, n_seq, k, dtype=DTYPE_BF16):
+    rc = lib().toploc_stream_reset_dtype(state.data_ptr(), n_seq, k, dtype, _stream(state))
     if rc != OK:
         raise ToplocError(rc, "toploc_stream_reset")
 
 
+def _step_dtype(step_vec):
+    if step_vec.dtype not in (torch.bfloat16, torch.float32) or not step_vec.is_cuda or not step_vec.is_contiguous() or \
+            step_vec.dim() != 2:
+        raise ValueError("step_vec must be a contiguous [rows, H] bf16 or fp32 tensor on the GPU")
+    return DTYPE_F32 if step_vec.dtype == torch.float32 else DTYPE_BF16
+
+
 def toploc_stream_append(state, step_vec, token, k=128, chunk_tokens=32):
-    """Row `token` of the current chunk for every sequence: step_vec [n_seq, H] bf16."""
-    if step_vec.dtype != torch.bfloat16 or not step_vec.is_cuda or not step_vec.is_contiguous() or step_vec.dim() != 2:
-        raise ValueError("step_vec must be a contiguous [n_seq, H] bf16 tensor on the GPU")
+    """Row `token` of the current chunk for every sequence: step_vec [n_seq, H] bf16 or fp32 (the state's precision)."""
+    dt = _step_dtype(step_vec)
     n_seq, h = step_vec.shape
-    if state.numel() < toploc_stream_state_bytes(n_seq, k):
+    if state.numel() < toploc_stream_state_bytes(n_seq, k, dt):
         raise ValueError("state too small for n_seq sequences")
-    rc = lib().toploc_stream_append(state.data_ptr(), step_vec.data_ptr(), n_seq, h, chunk_tokens, token, k,
-                                    _stream(step_vec))
+    rc = lib().toploc_stream_append_dtype(state.data_ptr(), n_seq, step_vec.data_ptr(), dt, None, None, n_seq, h, chunk_tokens,
+                                          token, k, _stream(step_vec))
     if rc != OK:
         raise ToplocError(rc, "toploc_stream_append")
 
 
-def toploc_stream_emit(state, n_seq, k=128, want_topk=False, out=None):
+def toploc_stream_emit(state, n_seq, k=128, want_topk=False, out=None, dtype=DTYPE_BF16):
     """Proofs of the chunks appended since the last emission; empties the states."""
     dev = state.device
     if out is None:
-        proofs = torch.empty((n_seq, 2 + 2 * k), dtype=torch.uint8, device=dev)
+        proofs = torch.empty((n_seq, 2 + (4 if dtype == DTYPE_F32 else 2) * k), dtype=torch.uint8, device=dev)
         status = torch.empty(n_seq, dtype=torch.uint8, device=dev)
     else:
         proofs, status = out
     idx = torch.empty((n_seq, k), dtype=torch.int32, device=dev) if want_topk else None
-    rc = lib().toploc_stream_emit(state.data_ptr(), n_seq, k, proofs.data_ptr(), status.data_ptr(),
-                                  idx.data_ptr() if want_topk else None, _stream(state))
+    rc = lib().toploc_stream_emit_dtype(state.data_ptr(), n_seq, dtype, None, n_seq, k, proofs.data_ptr(), status.data_ptr(),
+                                        idx.data_ptr() if want_topk else None, _stream(state))
     if rc != OK:
         raise ToplocError(rc, "toploc_stream_emit")
     return (proofs, status, idx) if want_topk else (proofs, status)
@@ -520,34 +547,35 @@ def _u32_device(values, device, what):
 
 
 def toploc_stream_append_rows(state, n_slots, step_vec, slots, tokens, k=128, chunk_tokens=32):
-    """Continuous batching: row r of step_vec [n_rows, H] bf16 is token tokens[r] of sequence slots[r]."""
-    if step_vec.dtype != torch.bfloat16 or not step_vec.is_cuda or not step_vec.is_contiguous() or step_vec.dim() != 2:
-        raise ValueError("step_vec must be a contiguous [n_rows, H] bf16 tensor on the GPU")
+    """Continuous batching: row r of step_vec [n_rows, H] (bf16 or fp32) is token tokens[r] of sequence slots[r]."""
+    dt = _step_dtype(step_vec)
     n_rows, h = step_vec.shape
     slots = _u32_device(slots, step_vec.device, "slots")
     tokens = _u32_device(tokens, step_vec.device, "tokens")
     if slots.numel() != n_rows or tokens.numel() != n_rows:
         raise ValueError("one slot and one token per row")
-    if state.numel() < toploc_stream_state_bytes(n_slots, k):
+    if state.numel() < toploc_stream_state_bytes(n_slots, k, dt):
         raise ValueError("state too small for n_slots sequences")
-    rc = lib().toploc_stream_append_rows(state.data_ptr(), n_slots, step_vec.data_ptr(), slots.data_ptr(),
-                                         tokens.data_ptr(), n_rows, h, chunk_tokens, k, _stream(step_vec))
+    rc = lib().toploc_stream_append_dtype(state.data_ptr(), n_slots, step_vec.data_ptr(), dt, slots.data_ptr(),
+                                          tokens.data_ptr(), n_rows, h, chunk_tokens, 0, k, _stream(step_vec))
     if rc != OK:
         raise ToplocError(rc, "toploc_stream_append_rows")
 
 
-def toploc_stream_emit_rows(state, n_slots, slots, k=128, want_topk=False):
+def toploc_stream_emit_rows(state, n_slots, slots, k=128, want_topk=False, dtype=DTYPE_BF16):
     """Proofs of the sequences `slots` (output row r belongs to slots[r]); empties their states."""
     dev = state.device
     slots = _u32_device(slots, dev, "slots")
     n_rows = slots.numel()
-    proofs = torch.empty((n_rows, 2 + 2 * k), dtype=torch.uint8, device=dev)
+    proofs = torch.empty((n_rows, 2 + (4 if dtype == DTYPE_F32 else 2) * k), dtype=torch.uint8, device=dev)
     status = torch.empty(n_rows, dtype=torch.uint8, device=dev)
     idx = torch.empty((n_rows, k), dtype=torch.int32, device=dev) if want_topk else None
-    if state.numel() < toploc_stream_state_bytes(n_slots, k):
+    if state.numel() < toploc_stream_state_bytes(n_slots, k, dtype):
         raise ValueError("state too small for n_slots sequences")
-    rc = lib().toploc_stream_emit_rows(state.data_ptr(), n_slots, slots.data_ptr(), n_rows, k, proofs.data_ptr(),
-                                       status.data_ptr(), idx.data_ptr() if want_topk else None, _stream(state))
+    if n_rows == 0:
+        return (proofs, status, idx) if want_topk else (proofs, status)
+    rc = lib().toploc_stream_emit_dtype(state.data_ptr(), n_slots, dtype, slots.data_ptr(), n_rows, k, proofs.data_ptr(),
+                                        status.data_ptr(), idx.data_ptr() if want_topk else None, _stream(state))
     if rc != OK:
         raise ToplocError(rc, "toploc_stream_emit_rows")
     return (proofs, status, idx) if want_topk else (proofs, status)

@@ -182,40 +182,43 @@ inline int check_segments(const SegmentPlan& pl, uint64_t n_segments, uint32_t k
     return kGo;
 }
 
-// The running top-k calls.  State of one sequence: a 16-byte header, k indices, k patterns, each
-// part rounded up to 16 bytes.
+// The running top-k calls.  State of one sequence: a 16-byte header, k indices, k patterns (2 bytes
+// each for bf16, 4 for fp32), each part rounded up to 16 bytes.
 constexpr size_t kStreamHeaderBytes = 16;
 inline size_t stream_idx_bytes(uint32_t k) { return ((size_t)k * 4 + 15) & ~(size_t)15; }
-inline size_t stream_stride(uint32_t k) { return kStreamHeaderBytes + stream_idx_bytes(k) + (((size_t)k * 2 + 15) & ~(size_t)15); }
-inline bool stream_k_ok(uint32_t k) { return k != 0 && k <= TOPLOC_MAX_K; }
-
-inline int check_stream_rows(uint32_t k, uint32_t hidden, uint32_t chunk_tokens)
+inline size_t stream_stride(uint32_t k, uint32_t dtype = TOPLOC_DTYPE_BF16)
 {
-    if (!stream_k_ok(k) || hidden == 0 || hidden % 8 != 0 || chunk_tokens == 0) return TOPLOC_EINVAL;
+    return kStreamHeaderBytes + stream_idx_bytes(k) + (((size_t)k * bits_size_of(dtype) + 15) & ~(size_t)15);
+}
+inline bool stream_k_ok(uint32_t k, uint32_t dtype = TOPLOC_DTYPE_BF16)
+{
+    return dtype <= TOPLOC_DTYPE_F32 && k != 0 && k <= max_k_of(dtype, dtype);
+}
+
+inline int check_stream_rows(uint32_t k, uint32_t hidden, uint32_t chunk_tokens, uint32_t dtype = TOPLOC_DTYPE_BF16)
+{
+    if (!stream_k_ok(k, dtype) || hidden == 0 || hidden % 8 != 0 || chunk_tokens == 0) return TOPLOC_EINVAL;
     if ((uint64_t)chunk_tokens * hidden >= (1ull << 32)) return TOPLOC_EINVAL;
     return kGo;
 }
-inline int check_stream_append(const void* d_state, const void* d_step, uint32_t n_seq, uint32_t hidden, uint32_t chunk_tokens,
-                               uint32_t token, uint32_t k)
+// one row per sequence (d_slots and d_tokens NULL: row r is token `token` of sequence r, n_rows sequences)
+// or rows of any subset of the sequences (both given: row r is token d_tokens[r] of sequence d_slots[r])
+inline int check_stream_append(const void* d_state, uint32_t n_slots, const void* d_step, const void* d_slots,
+                               const void* d_tokens, uint32_t n_rows, uint32_t hidden, uint32_t chunk_tokens, uint32_t token,
+                               uint32_t k, uint32_t dtype = TOPLOC_DTYPE_BF16)
 {
-    if (check_stream_rows(k, hidden, chunk_tokens) != kGo || token >= chunk_tokens) return TOPLOC_EINVAL;
-    if (n_seq == 0) return TOPLOC_OK;
-    if (!d_state || !d_step || !aligned16(d_state) || !aligned16(d_step)) return TOPLOC_EINVAL;
-    return kGo;
-}
-inline int check_stream_append_rows(const void* d_state, uint32_t n_slots, const void* d_step, const void* d_slots,
-                                    const void* d_tokens, uint32_t n_rows, uint32_t hidden, uint32_t chunk_tokens, uint32_t k)
-{
-    if (check_stream_rows(k, hidden, chunk_tokens) != kGo) return TOPLOC_EINVAL;
+    if (check_stream_rows(k, hidden, chunk_tokens, dtype) != kGo) return TOPLOC_EINVAL;
+    const bool indexed = d_slots || d_tokens;
+    if (!indexed && token >= chunk_tokens) return TOPLOC_EINVAL;
     if (n_rows == 0) return TOPLOC_OK;
-    if (!d_state || !d_step || !d_slots || !d_tokens || n_slots == 0) return TOPLOC_EINVAL;
-    if (!aligned16(d_state) || !aligned16(d_step) || !aligned(d_slots, 4) || !aligned(d_tokens, 4)) return TOPLOC_EINVAL;
+    if (!d_state || !d_step || !aligned16(d_state) || !aligned16(d_step)) return TOPLOC_EINVAL;
+    if (indexed && (!d_slots || !d_tokens || n_slots == 0 || !aligned(d_slots, 4) || !aligned(d_tokens, 4))) return TOPLOC_EINVAL;
     return kGo;
 }
 inline int check_stream_emit(const void* d_state, uint32_t n_rows, uint32_t k, const void* d_proofs, const void* d_status,
-                             bool indexed, const void* d_slots, uint32_t n_slots)
+                             bool indexed, const void* d_slots, uint32_t n_slots, uint32_t dtype = TOPLOC_DTYPE_BF16)
 {
-    if (!stream_k_ok(k)) return TOPLOC_EINVAL;
+    if (!stream_k_ok(k, dtype)) return TOPLOC_EINVAL;
     if (n_rows == 0) return TOPLOC_OK;
     if (!d_state || !d_proofs || !d_status || !aligned16(d_state) || !aligned(d_proofs, 2)) return TOPLOC_EINVAL;
     if (indexed && (!d_slots || n_slots == 0 || !aligned(d_slots, 4))) return TOPLOC_EINVAL;

@@ -408,13 +408,13 @@ __global__ __launch_bounds__(256) void stream_reset_kernel(char* __restrict__ st
 // What a sequence holds enters the selection of its next row: all k slots are read
 // before the header says how many of them count, so that header, pairs and the row's
 // first vectors are in flight together.
-template <int CAP>
+template <int CAP, typename Fmt = Bf16Fmt>
 struct StreamSeed {
     const StreamHeader* hdr;
     const uint32_t* g_idx;
-    const uint16_t* g_bits;
+    const typename Fmt::bits_t* g_bits;
     uint32_t k, row_values;
-    __device__ __forceinline__ SelectStart seed(SelectShared<kThreads, CAP, kQcap>& s) const
+    __device__ __forceinline__ SelectStart seed(SelectShared<kThreads, CAP, kQcap, Fmt>& s) const
     {
         constexpr int SPT = (CAP / 4 + kThreads - 1) / kThreads;  // k <= CAP/4 slots over the lanes
         uint32_t si[SPT], sb[SPT];
@@ -428,7 +428,7 @@ struct StreamSeed {
 #pragma unroll
         for (int j = 0; j < SPT; ++j) {
             const uint32_t i = threadIdx.x + j * kThreads;
-            if (i < h.count) { s.cand_idx[i] = si[j]; s.cand_bits[i] = (uint16_t)sb[j]; }
+            if (i < h.count) { s.cand_idx[i] = si[j]; s.cand_bits[i] = (typename Fmt::bits_t)sb[j]; }
         }
         const uint64_t have = (uint64_t)h.count + row_values;
         return SelectStart{h.count, Threshold{h.tm, h.ti}, have < k ? (uint32_t)have : k};
@@ -441,7 +441,7 @@ struct StreamSeed {
 // With `slots` (continuous batching: the rows of a step belong to any subset of the
 // sequences, each at its own position) row r goes to sequence slots[r] as token tokens[r];
 // a row whose slot or token is out of range is skipped.
-template <int CAP>
+template <int CAP, typename Fmt = Bf16Fmt>
 __global__ __launch_bounds__(kThreads, waves_for(CAP)) void stream_append_kernel(char* __restrict__ state, size_t stride,
                                                                                    const u32x4* __restrict__ step_vec,
                                                                                    uint32_t hvec, uint32_t v0, uint32_t k,
@@ -449,7 +449,8 @@ __global__ __launch_bounds__(kThreads, waves_for(CAP)) void stream_append_kernel
                                                                                    const uint32_t* __restrict__ tokens,
                                                                                    uint32_t n_slots, uint32_t chunk_tokens)
 {
-    __shared__ SelectShared<kThreads, CAP, kQcap> s;
+    __shared__ SelectShared<kThreads, CAP, kQcap, Fmt> s;
+    typedef typename Fmt::bits_t bits_t;
     const uint32_t tid = threadIdx.x;
     uint32_t seq = blockIdx.x;
     if (slots) {  // uniform
@@ -461,11 +462,11 @@ __global__ __launch_bounds__(kThreads, waves_for(CAP)) void stream_append_kernel
     char* st = state + (size_t)seq * stride;
     StreamHeader* hdr = reinterpret_cast<StreamHeader*>(st);
     uint32_t* g_idx = reinterpret_cast<uint32_t*>(st + sizeof(StreamHeader));
-    uint16_t* g_bits = reinterpret_cast<uint16_t*>(st + sizeof(StreamHeader) + stream_idx_bytes(k));
+    bits_t* g_bits = reinterpret_cast<bits_t*>(st + sizeof(StreamHeader) + stream_idx_bytes(k));
     const u32x4* row = step_vec + (size_t)blockIdx.x * hvec;
     const uint32_t rows = hdr->rows;
     const SelectStart end = select_topk_from<kThreads, kLoads, CAP, kQcap>(
-        row, v0, v0 + hvec, s, StreamSeed<CAP>{hdr, g_idx, g_bits, k, hvec * 8u});
+        row, v0, v0 + hvec, s, StreamSeed<CAP, Fmt>{hdr, g_idx, g_bits, k, hvec * (uint32_t)Fmt::ELEMS});
     for (uint32_t i = tid; i < end.k; i += kThreads) {
         g_idx[i] = s.cand_idx[i];
         g_bits[i] = s.cand_bits[i];
@@ -474,7 +475,7 @@ __global__ __launch_bounds__(kThreads, waves_for(CAP)) void stream_append_kernel
 }
 
 // Emission: steps 2-5 of Algorithm 1 on the k pairs a sequence holds, then the state is emptied.
-template <int THREADS, int KMAX, int CAP>
+template <int THREADS, int KMAX, int CAP, typename F = Field16, typename Fmt = Bf16Fmt>
 __global__ __launch_bounds__(THREADS) void stream_emit_kernel(char* __restrict__ state, size_t stride, uint32_t k,
                                                               uint8_t* __restrict__ proofs, uint8_t* __restrict__ status,
                                                               uint32_t* __restrict__ out_idx,
@@ -482,10 +483,11 @@ __global__ __launch_bounds__(THREADS) void stream_emit_kernel(char* __restrict__
 {
     static_assert(KMAX <= THREADS, "one pair per lane is carried across the phase change");
     __shared__ union EmitShared {
-        SelectShared<THREADS, CAP, 1> sel;
-        InterpShared<KMAX> itp;
+        SelectShared<THREADS, CAP, 1, Fmt> sel;
+        InterpShared<KMAX, F> itp;
     } sh;
     __shared__ uint32_t coef[KMAX];
+    typedef typename Fmt::bits_t bits_t;
     const uint32_t tid = threadIdx.x;
     const uint64_t seq = blockIdx.x;  // output row; with `slots` the state of sequence slots[seq]
     const uint64_t owner = slots ? slots[seq] : seq;
@@ -493,13 +495,13 @@ __global__ __launch_bounds__(THREADS) void stream_emit_kernel(char* __restrict__
     char* st = state + (known ? owner : 0) * stride;
     StreamHeader* hdr = reinterpret_cast<StreamHeader*>(st);
     const uint32_t* g_idx = reinterpret_cast<const uint32_t*>(st + sizeof(StreamHeader));
-    const uint16_t* g_bits = reinterpret_cast<const uint16_t*>(st + sizeof(StreamHeader) + stream_idx_bytes(k));
+    const bits_t* g_bits = reinterpret_cast<const bits_t*>(st + sizeof(StreamHeader) + stream_idx_bytes(k));
     const uint32_t count = known ? hdr->count : 0u;
-    uint16_t* proof = reinterpret_cast<uint16_t*>(proofs + seq * (2 + 2 * (uint64_t)k));
+    uint16_t* proof = reinterpret_cast<uint16_t*>(proofs + seq * (2 + 2 * (uint64_t)F::WORDS * k));
     __syncthreads();  // every lane has read the header
     if (tid == 0 && known) *hdr = StreamHeader{0u, 0, 0xFFFFFFFFu, 0u};
     if (count < k) {  // uniform
-        for (uint32_t j = tid; j <= k; j += THREADS) proof[j] = 0;
+        for (uint32_t j = tid; j <= k * F::WORDS; j += THREADS) proof[j] = 0;
         if (out_idx)
             for (uint32_t j = tid; j < k; j += THREADS) out_idx[seq * k + j] = 0xFFFFFFFFu;
         if (tid == 0) status[seq] = TOPLOC_CHUNK_SHORT;
@@ -518,7 +520,7 @@ __global__ __launch_bounds__(THREADS) void stream_emit_kernel(char* __restrict__
     }
     if (tid < k) {
         sh.itp.idx[tid] = my_idx;
-        sh.itp.ys[tid] = (uint16_t)(my_y >= kPrime ? my_y - kPrime : my_y);
+        sh.itp.ys[tid] = (typename F::elem_t)F::from_pattern(my_y);
     }
     finish_proof<THREADS>(sh.itp, coef, k, proof, status + seq);
 }
@@ -629,9 +631,13 @@ static void launch_part(hipStream_t st, const void* d_hidden, const Layout& lay,
                         void* c_bits_any, uint32_t hidden_dtype = TOPLOC_DTYPE_BF16)
 {
     ProfScope ps(TOPLOC_KERNEL_PART, st);
-    if (hidden_dtype == TOPLOC_DTYPE_F32) {  // k <= TOPLOC_MAX_K_F32
-        hipLaunchKernelGGL((part_kernel<kCapSmall, F32Fmt>), dim3((uint32_t)slots), dim3(kThreads), 0, st,
-                           (const u32x4*)d_hidden, lay, k, c_idx, (uint32_t*)c_bits_any);
+    if (hidden_dtype == TOPLOC_DTYPE_F32) {
+        if (k <= 128)
+            hipLaunchKernelGGL((part_kernel<kCapSmall, F32Fmt>), dim3((uint32_t)slots), dim3(kThreads), 0, st,
+                               (const u32x4*)d_hidden, lay, k, c_idx, (uint32_t*)c_bits_any);
+        else
+            hipLaunchKernelGGL((part_kernel<kCapLarge, F32Fmt>), dim3((uint32_t)slots), dim3(kThreads), 0, st,
+                               (const u32x4*)d_hidden, lay, k, c_idx, (uint32_t*)c_bits_any);
         return;
     }
     uint16_t* c_bits = (uint16_t*)c_bits_any;
@@ -648,9 +654,13 @@ static void launch_build_merge(hipStream_t st, const Layout& lay, uint64_t units
                                uint32_t dtype = TOPLOC_DTYPE_BF16)
 {
     ProfScope ps(TOPLOC_KERNEL_BUILD_MERGE, st);
-    if (dtype == TOPLOC_DTYPE_F32) {  // k <= TOPLOC_MAX_K_F32
-        hipLaunchKernelGGL((build_merge_kernel<256, 128, kCapSmall, Field32, F32Fmt>), dim3((uint32_t)units), dim3(256), 0, st,
-                           lay, k, c_idx, (const uint32_t*)c_bits_any, d_proofs, d_status, d_topk_idx_opt);
+    if (dtype == TOPLOC_DTYPE_F32) {
+        if (k <= 128)
+            hipLaunchKernelGGL((build_merge_kernel<256, 128, kCapSmall, Field32, F32Fmt>), dim3((uint32_t)units), dim3(256), 0,
+                               st, lay, k, c_idx, (const uint32_t*)c_bits_any, d_proofs, d_status, d_topk_idx_opt);
+        else
+            hipLaunchKernelGGL((build_merge_kernel<1024, 512, kCapLarge, Field32, F32Fmt>), dim3((uint32_t)units), dim3(1024),
+                               0, st, lay, k, c_idx, (const uint32_t*)c_bits_any, d_proofs, d_status, d_topk_idx_opt);
         return;
     }
     const uint16_t* c_bits = (const uint16_t*)c_bits_any;
@@ -668,29 +678,42 @@ static void launch_verify_merge(hipStream_t st, const Layout& lay, uint64_t unit
                                 uint32_t proof_dtype = TOPLOC_DTYPE_BF16)
 {
     ProfScope ps(TOPLOC_KERNEL_VERIFY_MERGE, st);
-    const dim3 grid((uint32_t)units), block(256);
+    const dim3 grid((uint32_t)units), block(256), block_wide(512);
+    const bool wide = k > 128;   // the larger candidate buffer and 512 lanes
     if (hidden_dtype == TOPLOC_DTYPE_F32 && proof_dtype == TOPLOC_DTYPE_F32) {
-        hipLaunchKernelGGL((verify_merge_kernel<256, 128, kCapSmall, Field32, F32Fmt>), grid, block, 0, st, lay, k, c_idx,
-                           (const uint32_t*)c_bits_any, d_proofs, thr, d_results);
+        if (!wide)
+            hipLaunchKernelGGL((verify_merge_kernel<256, 128, kCapSmall, Field32, F32Fmt>), grid, block, 0, st, lay, k, c_idx,
+                               (const uint32_t*)c_bits_any, d_proofs, thr, d_results);
+        else
+            hipLaunchKernelGGL((verify_merge_kernel<512, 512, kCapLarge, Field32, F32Fmt>), grid, block_wide, 0, st, lay, k,
+                               c_idx, (const uint32_t*)c_bits_any, d_proofs, thr, d_results);
         return;
     }
     if (hidden_dtype == TOPLOC_DTYPE_F32) {  // bf16 proof, fp32 validator
-        hipLaunchKernelGGL((verify_merge_kernel<256, 128, kCapSmall, Field16, F32Fmt>), grid, block, 0, st, lay, k, c_idx,
-                           (const uint32_t*)c_bits_any, d_proofs, thr, d_results);
+        if (!wide)
+            hipLaunchKernelGGL((verify_merge_kernel<256, 128, kCapSmall, Field16, F32Fmt>), grid, block, 0, st, lay, k, c_idx,
+                               (const uint32_t*)c_bits_any, d_proofs, thr, d_results);
+        else
+            hipLaunchKernelGGL((verify_merge_kernel<512, 512, kCapLarge, Field16, F32Fmt>), grid, block_wide, 0, st, lay, k,
+                               c_idx, (const uint32_t*)c_bits_any, d_proofs, thr, d_results);
         return;
     }
     const uint16_t* c_bits = (const uint16_t*)c_bits_any;
     if (proof_dtype == TOPLOC_DTYPE_F32) {   // fp32 proof, bf16 validator
-        hipLaunchKernelGGL((verify_merge_kernel<256, 128, kCapSmall, Field32, Bf16Fmt>), grid, block, 0, st, lay, k, c_idx,
-                           c_bits, d_proofs, thr, d_results);
+        if (!wide)
+            hipLaunchKernelGGL((verify_merge_kernel<256, 128, kCapSmall, Field32, Bf16Fmt>), grid, block, 0, st, lay, k, c_idx,
+                               c_bits, d_proofs, thr, d_results);
+        else
+            hipLaunchKernelGGL((verify_merge_kernel<512, 512, kCapLarge, Field32, Bf16Fmt>), grid, block_wide, 0, st, lay, k,
+                               c_idx, c_bits, d_proofs, thr, d_results);
         return;
     }
-    if (k <= 128)
-        hipLaunchKernelGGL((verify_merge_kernel<256, 128, kCapSmall>), dim3((uint32_t)units), dim3(256), 0, st, lay, k, c_idx,
-                           c_bits, d_proofs, thr, d_results);
+    if (!wide)
+        hipLaunchKernelGGL((verify_merge_kernel<256, 128, kCapSmall>), grid, block, 0, st, lay, k, c_idx, c_bits, d_proofs, thr,
+                           d_results);
     else
-        hipLaunchKernelGGL((verify_merge_kernel<512, 512, kCapLarge>), dim3((uint32_t)units), dim3(512), 0, st, lay, k, c_idx,
-                           c_bits, d_proofs, thr, d_results);
+        hipLaunchKernelGGL((verify_merge_kernel<512, 512, kCapLarge>), grid, block_wide, 0, st, lay, k, c_idx, c_bits, d_proofs,
+                           thr, d_results);
 }
 
 // Segments: the host plans from sizes alone (plan.hpp); the part table is built on the device from the
@@ -789,15 +812,21 @@ int toploc_topk(const void* d_hidden_bf16, uint64_t n_chunks, const toploc_param
 
 // Algorithm 1 over fixed chunks with the cut already chosen (`f`): one fused launch, or the split pair
 // of launches with the candidates in `d_workspace`.  Arguments are checked by the callers.
-static int build_fixed(const FixedPlan& f, const void* d_hidden_bf16, uint64_t n_chunks, uint32_t nvec, uint32_t k,
+static int build_fixed(const FixedPlan& f, const void* d_hidden, uint64_t n_chunks, uint32_t nvec, uint32_t k,
                        uint8_t* d_proofs, uint8_t* d_status, uint32_t* d_topk_idx_opt, void* d_workspace,
-                       size_t workspace_bytes, hipStream_t st)
+                       size_t workspace_bytes, hipStream_t st, uint32_t dtype = TOPLOC_DTYPE_BF16)
 {
-    const bool have_ws = d_workspace && workspace_bytes >= cand_bytes(n_chunks * f.parts, k);
+    const void* d_hidden_bf16 = d_hidden;
+    const size_t bits_size = bits_size_of(dtype);
+    const bool have_ws = d_workspace && workspace_bytes >= cand_bytes(n_chunks * f.parts, k, bits_size);
     if (k <= 128 && (f.parts == 1 || !have_ws)) {  // one launch; also the answer to a missing workspace
         ProfScope ps(TOPLOC_KERNEL_BUILD, st);
-        hipLaunchKernelGGL((build_kernel<128, kCapSmall>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
-                           (const u32x4*)d_hidden_bf16, nvec, k, d_proofs, d_status, d_topk_idx_opt);
+        if (dtype == TOPLOC_DTYPE_F32)
+            hipLaunchKernelGGL((build_kernel<128, kCapSmall, Field32, F32Fmt>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
+                               (const u32x4*)d_hidden, nvec, k, d_proofs, d_status, d_topk_idx_opt);
+        else
+            hipLaunchKernelGGL((build_kernel<128, kCapSmall>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
+                               (const u32x4*)d_hidden_bf16, nvec, k, d_proofs, d_status, d_topk_idx_opt);
         return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
     }
     if (!have_ws) return d_workspace ? TOPLOC_EWORKSPACE : TOPLOC_EINVAL;
@@ -805,10 +834,10 @@ static int build_fixed(const FixedPlan& f, const void* d_hidden_bf16, uint64_t n
     if (slots >= (1ull << 31)) return TOPLOC_EINVAL;
     Layout lay = {nullptr, nullptr, 0, 0, 0, nvec, f.parts, f.part_vecs};
     uint32_t* c_idx = (uint32_t*)d_workspace;
-    uint16_t* c_bits = (uint16_t*)((char*)d_workspace + up16((size_t)slots * k * sizeof(uint32_t)));
-    launch_part(st, d_hidden_bf16, lay, slots, k, c_idx, c_bits);
+    void* c_bits = (char*)d_workspace + up16((size_t)slots * k * sizeof(uint32_t));
+    launch_part(st, d_hidden, lay, slots, k, c_idx, c_bits, dtype);
     if (!hip_ok(hipGetLastError())) return TOPLOC_EHIP;
-    launch_build_merge(st, lay, n_chunks, k, c_idx, c_bits, d_proofs, d_status, d_topk_idx_opt);
+    launch_build_merge(st, lay, n_chunks, k, c_idx, c_bits, d_proofs, d_status, d_topk_idx_opt, dtype);
     return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
 }
 
@@ -992,19 +1021,25 @@ size_t toploc_proof_bytes_dtype(uint32_t k, uint32_t dtype)
     return 2 + (size_t)k * (dtype == TOPLOC_DTYPE_F32 ? 4 : 2);
 }
 
-int toploc_build_proofs_f32(const void* d_hidden_f32, uint64_t n_chunks, const toploc_params* params, uint8_t* d_proofs,
-                            uint8_t* d_status, uint32_t* d_topk_idx_opt, void* hip_stream)
+size_t toploc_workspace_bytes_f32(const toploc_params* params, uint64_t n_chunks)
 {
     const uint64_t n = chunk_len_mixed(params, TOPLOC_DTYPE_F32, TOPLOC_DTYPE_F32);
-    const int chk = plan::check_fixed(n, n_chunks, d_hidden_f32, d_proofs, 2, d_status, 1, nullptr);
+    if (n == 0 || n_chunks == 0 || n_chunks >= (1ull << 31)) return 0;
+    const FixedPlan f = plan_fixed(n_chunks, n / 4);
+    if (plan::fixed_plan_is_fused(f, params->k) || n_chunks * f.parts >= (1ull << 31)) return 0;
+    return cand_bytes(n_chunks * f.parts, params->k, sizeof(uint32_t));
+}
+
+int toploc_build_proofs_f32(const void* d_hidden_f32, uint64_t n_chunks, const toploc_params* params, uint8_t* d_proofs,
+                            uint8_t* d_status, uint32_t* d_topk_idx_opt, void* d_workspace, size_t workspace_bytes,
+                            void* hip_stream)
+{
+    const uint64_t n = chunk_len_mixed(params, TOPLOC_DTYPE_F32, TOPLOC_DTYPE_F32);
+    const int chk = plan::check_fixed(n, n_chunks, d_hidden_f32, d_proofs, 2, d_status, 1, d_workspace);
     if (chk != plan::kGo) return chk;
-    hipStream_t st = (hipStream_t)hip_stream;
-    {
-        ProfScope ps(TOPLOC_KERNEL_BUILD, st);
-        hipLaunchKernelGGL((build_kernel<128, kCapSmall, Field32, F32Fmt>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
-                           (const u32x4*)d_hidden_f32, (uint32_t)(n / 4), params->k, d_proofs, d_status, d_topk_idx_opt);
-    }
-    return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
+    const uint32_t nvec = (uint32_t)(n / 4);
+    return build_fixed(plan_fixed(n_chunks, nvec), d_hidden_f32, n_chunks, nvec, params->k, d_proofs, d_status, d_topk_idx_opt,
+                       d_workspace, workspace_bytes, (hipStream_t)hip_stream, TOPLOC_DTYPE_F32);
 }
 
 int toploc_verify_proofs_mixed(const void* d_hidden, uint32_t hidden_dtype, uint64_t n_chunks, const toploc_params* params,
@@ -1023,114 +1058,148 @@ int toploc_verify_proofs_mixed(const void* d_hidden, uint32_t hidden_dtype, uint
     const u32x4* h = (const u32x4*)d_hidden;
     {
         ProfScope ps(TOPLOC_KERNEL_VERIFY, st);
-        if (hidden_dtype == TOPLOC_DTYPE_F32 && proof_dtype == TOPLOC_DTYPE_F32)
-            hipLaunchKernelGGL((verify_kernel<128, kCapSmall, Field32, F32Fmt>), grid, block, 0, st, h, (uint32_t)(n / 4), k,
-                               d_proofs, *thresholds, d_results);
-        else if (hidden_dtype == TOPLOC_DTYPE_F32)   // bf16 proof, fp32 validator
-            hipLaunchKernelGGL((verify_kernel<128, kCapSmall, Field16, F32Fmt>), grid, block, 0, st, h, (uint32_t)(n / 4), k,
-                               d_proofs, *thresholds, d_results);
-        else                                          // fp32 proof, bf16 validator
-            hipLaunchKernelGGL((verify_kernel<128, kCapSmall, Field32, Bf16Fmt>), grid, block, 0, st, h, (uint32_t)(n / 8), k,
-                               d_proofs, *thresholds, d_results);
+        const bool wide = k > 128;   // the larger candidate buffer
+        if (hidden_dtype == TOPLOC_DTYPE_F32 && proof_dtype == TOPLOC_DTYPE_F32) {
+            if (!wide)
+                hipLaunchKernelGGL((verify_kernel<128, kCapSmall, Field32, F32Fmt>), grid, block, 0, st, h, (uint32_t)(n / 4), k,
+                                   d_proofs, *thresholds, d_results);
+            else
+                hipLaunchKernelGGL((verify_kernel<512, kCapLarge, Field32, F32Fmt>), grid, block, 0, st, h, (uint32_t)(n / 4), k,
+                                   d_proofs, *thresholds, d_results);
+        } else if (hidden_dtype == TOPLOC_DTYPE_F32) {   // bf16 proof, fp32 validator
+            if (!wide)
+                hipLaunchKernelGGL((verify_kernel<128, kCapSmall, Field16, F32Fmt>), grid, block, 0, st, h, (uint32_t)(n / 4), k,
+                                   d_proofs, *thresholds, d_results);
+            else
+                hipLaunchKernelGGL((verify_kernel<512, kCapLarge, Field16, F32Fmt>), grid, block, 0, st, h, (uint32_t)(n / 4), k,
+                                   d_proofs, *thresholds, d_results);
+        } else {                                          // fp32 proof, bf16 validator
+            if (!wide)
+                hipLaunchKernelGGL((verify_kernel<128, kCapSmall, Field32, Bf16Fmt>), grid, block, 0, st, h, (uint32_t)(n / 8), k,
+                                   d_proofs, *thresholds, d_results);
+            else
+                hipLaunchKernelGGL((verify_kernel<512, kCapLarge, Field32, Bf16Fmt>), grid, block, 0, st, h, (uint32_t)(n / 8), k,
+                                   d_proofs, *thresholds, d_results);
+        }
     }
     return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
 }
 
-size_t toploc_stream_state_bytes(uint32_t n_seq, uint32_t k)
+size_t toploc_stream_state_bytes_dtype(uint32_t n_seq, uint32_t k, uint32_t dtype)
 {
-    if (!plan::stream_k_ok(k)) return 0;
-    return (size_t)n_seq * plan::stream_stride(k);
+    if (!plan::stream_k_ok(k, dtype)) return 0;
+    return (size_t)n_seq * plan::stream_stride(k, dtype);
 }
 
-int toploc_stream_reset(void* d_state, uint32_t n_seq, uint32_t k, void* hip_stream)
+int toploc_stream_reset_dtype(void* d_state, uint32_t n_seq, uint32_t k, uint32_t dtype, void* hip_stream)
 {
-    if (!plan::stream_k_ok(k)) return TOPLOC_EINVAL;
+    if (!plan::stream_k_ok(k, dtype)) return TOPLOC_EINVAL;
     if (n_seq == 0) return TOPLOC_OK;
     if (!d_state || !aligned16(d_state)) return TOPLOC_EINVAL;
     hipStream_t st = (hipStream_t)hip_stream;
     hipLaunchKernelGGL(stream_reset_kernel, dim3((n_seq + 255) / 256), dim3(256), 0, st, (char*)d_state, n_seq,
-                       plan::stream_stride(k));
+                       plan::stream_stride(k, dtype));
     return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
+}
+
+int toploc_stream_append_dtype(void* d_state, uint32_t n_slots, const void* d_step, uint32_t dtype, const uint32_t* d_slots,
+                               const uint32_t* d_tokens, uint32_t n_rows, uint32_t hidden, uint32_t chunk_tokens,
+                               uint32_t token, uint32_t k, void* hip_stream)
+{
+    const int chk = plan::check_stream_append(d_state, n_slots, d_step, d_slots, d_tokens, n_rows, hidden, chunk_tokens, token,
+                                              k, dtype);
+    if (chk != plan::kGo) return chk;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const bool f32 = dtype == TOPLOC_DTYPE_F32;
+    const uint32_t hvec = hidden / plan::elems_per_vec(dtype);
+    const uint32_t v0 = d_slots ? 0u : token * hvec;
+    const uint32_t n_known = d_slots ? n_slots : n_rows;
+    const size_t stride = plan::stream_stride(k, dtype);
+    const u32x4* step = (const u32x4*)d_step;
+    {
+        ProfScope ps(TOPLOC_KERNEL_STREAM_APPEND, st);
+        const dim3 grid(n_rows), block(kThreads);
+        if (!f32 && k <= 128)
+            hipLaunchKernelGGL((stream_append_kernel<kCapSmall>), grid, block, 0, st, (char*)d_state, stride, step, hvec, v0, k,
+                               d_slots, d_tokens, n_known, chunk_tokens);
+        else if (!f32)
+            hipLaunchKernelGGL((stream_append_kernel<kCapLarge>), grid, block, 0, st, (char*)d_state, stride, step, hvec, v0, k,
+                               d_slots, d_tokens, n_known, chunk_tokens);
+        else if (k <= 128)
+            hipLaunchKernelGGL((stream_append_kernel<kCapSmall, F32Fmt>), grid, block, 0, st, (char*)d_state, stride, step, hvec,
+                               v0, k, d_slots, d_tokens, n_known, chunk_tokens);
+        else
+            hipLaunchKernelGGL((stream_append_kernel<kCapLarge, F32Fmt>), grid, block, 0, st, (char*)d_state, stride, step, hvec,
+                               v0, k, d_slots, d_tokens, n_known, chunk_tokens);
+    }
+    return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
+}
+
+int toploc_stream_emit_dtype(void* d_state, uint32_t n_slots, uint32_t dtype, const uint32_t* d_slots, uint32_t n_rows,
+                             uint32_t k, uint8_t* d_proofs, uint8_t* d_status, uint32_t* d_topk_idx_opt, void* hip_stream)
+{
+    const int chk = plan::check_stream_emit(d_state, n_rows, k, d_proofs, d_status, d_slots != nullptr, d_slots, n_slots, dtype);
+    if (chk != plan::kGo) return chk;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const bool f32 = dtype == TOPLOC_DTYPE_F32;
+    const uint32_t n_known = d_slots ? n_slots : n_rows;
+    const size_t stride = plan::stream_stride(k, dtype);
+    {
+        ProfScope ps(TOPLOC_KERNEL_STREAM_EMIT, st);
+        const dim3 grid(n_rows);
+        if (!f32 && k <= 128)
+            hipLaunchKernelGGL((stream_emit_kernel<256, 128, kCapSmall>), grid, dim3(256), 0, st, (char*)d_state, stride, k,
+                               d_proofs, d_status, d_topk_idx_opt, d_slots, n_known);
+        else if (!f32)
+            hipLaunchKernelGGL((stream_emit_kernel<1024, 512, kCapLarge>), grid, dim3(1024), 0, st, (char*)d_state, stride, k,
+                               d_proofs, d_status, d_topk_idx_opt, d_slots, n_known);
+        else if (k <= 128)
+            hipLaunchKernelGGL((stream_emit_kernel<256, 128, kCapSmall, Field32, F32Fmt>), grid, dim3(256), 0, st,
+                               (char*)d_state, stride, k, d_proofs, d_status, d_topk_idx_opt, d_slots, n_known);
+        else
+            hipLaunchKernelGGL((stream_emit_kernel<1024, 512, kCapLarge, Field32, F32Fmt>), grid, dim3(1024), 0, st,
+                               (char*)d_state, stride, k, d_proofs, d_status, d_topk_idx_opt, d_slots, n_known);
+    }
+    return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
+}
+
+// the bf16 calls of the running top-k
+size_t toploc_stream_state_bytes(uint32_t n_seq, uint32_t k) { return toploc_stream_state_bytes_dtype(n_seq, k, TOPLOC_DTYPE_BF16); }
+
+int toploc_stream_reset(void* d_state, uint32_t n_seq, uint32_t k, void* hip_stream)
+{
+    return toploc_stream_reset_dtype(d_state, n_seq, k, TOPLOC_DTYPE_BF16, hip_stream);
 }
 
 int toploc_stream_append(void* d_state, const void* d_step_bf16, uint32_t n_seq, uint32_t hidden, uint32_t chunk_tokens,
                          uint32_t token, uint32_t k, void* hip_stream)
 {
-    const int chk = plan::check_stream_append(d_state, d_step_bf16, n_seq, hidden, chunk_tokens, token, k);
-    if (chk != plan::kGo) return chk;
-    hipStream_t st = (hipStream_t)hip_stream;
-    const uint32_t hvec = hidden / 8;
-    {
-        ProfScope ps(TOPLOC_KERNEL_STREAM_APPEND, st);
-        if (k <= 128)
-            hipLaunchKernelGGL((stream_append_kernel<kCapSmall>), dim3(n_seq), dim3(kThreads), 0, st, (char*)d_state,
-                               plan::stream_stride(k), (const u32x4*)d_step_bf16, hvec, token * hvec, k, nullptr, nullptr, n_seq,
-                               chunk_tokens);
-        else
-            hipLaunchKernelGGL((stream_append_kernel<kCapLarge>), dim3(n_seq), dim3(kThreads), 0, st, (char*)d_state,
-                               plan::stream_stride(k), (const u32x4*)d_step_bf16, hvec, token * hvec, k, nullptr, nullptr, n_seq,
-                               chunk_tokens);
-    }
-    return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
+    return toploc_stream_append_dtype(d_state, n_seq, d_step_bf16, TOPLOC_DTYPE_BF16, nullptr, nullptr, n_seq, hidden,
+                                      chunk_tokens, token, k, hip_stream);
 }
 
 int toploc_stream_append_rows(void* d_state, uint32_t n_slots, const void* d_step_bf16, const uint32_t* d_slots,
                               const uint32_t* d_tokens, uint32_t n_rows, uint32_t hidden, uint32_t chunk_tokens,
                               uint32_t k, void* hip_stream)
 {
-    const int chk = plan::check_stream_append_rows(d_state, n_slots, d_step_bf16, d_slots, d_tokens, n_rows, hidden,
-                                                   chunk_tokens, k);
-    if (chk != plan::kGo) return chk;
-    hipStream_t st = (hipStream_t)hip_stream;
-    const uint32_t hvec = hidden / 8;
-    {
-        ProfScope ps(TOPLOC_KERNEL_STREAM_APPEND, st);
-        if (k <= 128)
-            hipLaunchKernelGGL((stream_append_kernel<kCapSmall>), dim3(n_rows), dim3(kThreads), 0, st, (char*)d_state,
-                               plan::stream_stride(k), (const u32x4*)d_step_bf16, hvec, 0u, k, d_slots, d_tokens, n_slots,
-                               chunk_tokens);
-        else
-            hipLaunchKernelGGL((stream_append_kernel<kCapLarge>), dim3(n_rows), dim3(kThreads), 0, st, (char*)d_state,
-                               plan::stream_stride(k), (const u32x4*)d_step_bf16, hvec, 0u, k, d_slots, d_tokens, n_slots,
-                               chunk_tokens);
-    }
-    return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
+    if (n_rows != 0 && (!d_slots || !d_tokens)) return TOPLOC_EINVAL;
+    return toploc_stream_append_dtype(d_state, n_slots, d_step_bf16, TOPLOC_DTYPE_BF16, d_slots, d_tokens, n_rows, hidden,
+                                      chunk_tokens, 0, k, hip_stream);
 }
 
 int toploc_stream_emit(void* d_state, uint32_t n_seq, uint32_t k, uint8_t* d_proofs, uint8_t* d_status,
                        uint32_t* d_topk_idx_opt, void* hip_stream)
 {
-    const int chk = plan::check_stream_emit(d_state, n_seq, k, d_proofs, d_status, false, nullptr, 0);
-    if (chk != plan::kGo) return chk;
-    hipStream_t st = (hipStream_t)hip_stream;
-    {
-        ProfScope ps(TOPLOC_KERNEL_STREAM_EMIT, st);
-        if (k <= 128)
-            hipLaunchKernelGGL((stream_emit_kernel<256, 128, kCapSmall>), dim3(n_seq), dim3(256), 0, st, (char*)d_state,
-                               plan::stream_stride(k), k, d_proofs, d_status, d_topk_idx_opt, nullptr, n_seq);
-        else
-            hipLaunchKernelGGL((stream_emit_kernel<1024, 512, kCapLarge>), dim3(n_seq), dim3(1024), 0, st, (char*)d_state,
-                               plan::stream_stride(k), k, d_proofs, d_status, d_topk_idx_opt, nullptr, n_seq);
-    }
-    return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
+    return toploc_stream_emit_dtype(d_state, n_seq, TOPLOC_DTYPE_BF16, nullptr, n_seq, k, d_proofs, d_status, d_topk_idx_opt,
+                                    hip_stream);
 }
 
 int toploc_stream_emit_rows(void* d_state, uint32_t n_slots, const uint32_t* d_slots, uint32_t n_rows, uint32_t k,
                             uint8_t* d_proofs, uint8_t* d_status, uint32_t* d_topk_idx_opt, void* hip_stream)
 {
-    const int chk = plan::check_stream_emit(d_state, n_rows, k, d_proofs, d_status, true, d_slots, n_slots);
-    if (chk != plan::kGo) return chk;
-    hipStream_t st = (hipStream_t)hip_stream;
-    {
-        ProfScope ps(TOPLOC_KERNEL_STREAM_EMIT, st);
-        if (k <= 128)
-            hipLaunchKernelGGL((stream_emit_kernel<256, 128, kCapSmall>), dim3(n_rows), dim3(256), 0, st, (char*)d_state,
-                               plan::stream_stride(k), k, d_proofs, d_status, d_topk_idx_opt, d_slots, n_slots);
-        else
-            hipLaunchKernelGGL((stream_emit_kernel<1024, 512, kCapLarge>), dim3(n_rows), dim3(1024), 0, st, (char*)d_state,
-                               plan::stream_stride(k), k, d_proofs, d_status, d_topk_idx_opt, d_slots, n_slots);
-    }
-    return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
+    if (n_rows != 0 && !d_slots) return TOPLOC_EINVAL;
+    return toploc_stream_emit_dtype(d_state, n_slots, TOPLOC_DTYPE_BF16, d_slots, n_rows, k, d_proofs, d_status,
+                                    d_topk_idx_opt, hip_stream);
 }
 
 int toploc_ring_append(void* d_ring_bf16, const void* d_step_bf16, uint32_t n_seq, uint32_t hidden,

@@ -94,17 +94,24 @@ static void check_rejections()
     CHECK(!plan_segments(2, 9, 4096, 128, 5, TOPLOC_MAX_K, 0).ok);
     // running top-k, ring
     CHECK(stream_stride(128) == 16 + 512 + 256 && stream_stride(5) == 16 + 32 + 16);
-    CHECK(check_stream_append(fake, fake, 4, 4096, 32, 0, 128) == kGo);
-    CHECK(check_stream_append(fake, fake, 4, 4096, 32, 32, 128) == TOPLOC_EINVAL);
-    CHECK(check_stream_append(fake, fake, 4, 4100, 32, 0, 128) == TOPLOC_EINVAL);
-    CHECK(check_stream_append(fake, fake, 4, 1u << 20, 1u << 12, 0, 128) == TOPLOC_EINVAL);
-    CHECK(check_stream_append(nullptr, fake, 4, 4096, 32, 0, 128) == TOPLOC_EINVAL);
-    CHECK(check_stream_append(nullptr, nullptr, 0, 4096, 32, 0, 128) == TOPLOC_OK);
-    CHECK(check_stream_append(fake, fake, 4, 4096, 32, 0, 513) == TOPLOC_EINVAL);
-    CHECK(check_stream_append_rows(fake, 8, fake, fake, fake, 3, 4096, 32, 128) == kGo);
-    CHECK(check_stream_append_rows(fake, 0, fake, fake, fake, 3, 4096, 32, 128) == TOPLOC_EINVAL);
-    CHECK(check_stream_append_rows(fake, 8, fake, (const void*)(uintptr_t)0x10002, fake, 3, 4096, 32, 128) == TOPLOC_EINVAL);
-    CHECK(check_stream_append_rows(fake, 8, fake, fake, fake, 0, 4096, 32, 128) == TOPLOC_OK);
+    CHECK(stream_stride(128, TOPLOC_DTYPE_F32) == 16 + 512 + 512 && stream_stride(5, TOPLOC_DTYPE_F32) == 16 + 32 + 32);
+    CHECK(stream_k_ok(512, TOPLOC_DTYPE_F32) && !stream_k_ok(513, TOPLOC_DTYPE_F32) && !stream_k_ok(128, 2) && !stream_k_ok(0));
+    // one row per sequence
+    CHECK(check_stream_append(fake, 4, fake, nullptr, nullptr, 4, 4096, 32, 0, 128) == kGo);
+    CHECK(check_stream_append(fake, 4, fake, nullptr, nullptr, 4, 4096, 32, 32, 128) == TOPLOC_EINVAL);      // token >= chunk_tokens
+    CHECK(check_stream_append(fake, 4, fake, nullptr, nullptr, 4, 4100, 32, 0, 128) == TOPLOC_EINVAL);
+    CHECK(check_stream_append(fake, 4, fake, nullptr, nullptr, 4, 1u << 20, 1u << 12, 0, 128) == TOPLOC_EINVAL);
+    CHECK(check_stream_append(nullptr, 4, fake, nullptr, nullptr, 4, 4096, 32, 0, 128) == TOPLOC_EINVAL);
+    CHECK(check_stream_append(nullptr, 0, nullptr, nullptr, nullptr, 0, 4096, 32, 0, 128) == TOPLOC_OK);
+    CHECK(check_stream_append(fake, 4, fake, nullptr, nullptr, 4, 4096, 32, 0, 513) == TOPLOC_EINVAL);
+    CHECK(check_stream_append(fake, 4, fake, nullptr, nullptr, 4, 4096, 32, 0, 512, TOPLOC_DTYPE_F32) == kGo);
+    CHECK(check_stream_append(fake, 4, fake, nullptr, nullptr, 4, 4096, 32, 0, 128, 7) == TOPLOC_EINVAL);
+    // rows of any subset of the sequences
+    CHECK(check_stream_append(fake, 8, fake, fake, fake, 3, 4096, 32, 99, 128) == kGo);                       // `token` is ignored
+    CHECK(check_stream_append(fake, 0, fake, fake, fake, 3, 4096, 32, 0, 128) == TOPLOC_EINVAL);
+    CHECK(check_stream_append(fake, 8, fake, fake, nullptr, 3, 4096, 32, 0, 128) == TOPLOC_EINVAL);
+    CHECK(check_stream_append(fake, 8, fake, (const void*)(uintptr_t)0x10002, fake, 3, 4096, 32, 0, 128) == TOPLOC_EINVAL);
+    CHECK(check_stream_append(fake, 8, fake, fake, fake, 0, 4096, 32, 0, 128) == TOPLOC_OK);
     CHECK(check_stream_emit(fake, 2, 128, fake, fake, false, nullptr, 0) == kGo);
     CHECK(check_stream_emit(fake, 2, 0, fake, fake, false, nullptr, 0) == TOPLOC_EINVAL);
     CHECK(check_stream_emit(fake, 2, 128, odd, fake, false, nullptr, 0) == TOPLOC_EINVAL);

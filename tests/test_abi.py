@@ -134,12 +134,30 @@ def test_newer_entry_points_check_their_arguments_before_any_launch():
     b16 = L.toploc_segments_workspace_bytes_dtype(2, 9, 4096, 128, binding.DTYPE_BF16)
     b32 = L.toploc_segments_workspace_bytes_dtype(2, 9, 4096, 128, binding.DTYPE_F32)
     assert b16 == L.toploc_segments_workspace_bytes(2, 9, 4096, 128) and b32 > b16 > 0
-    assert L.toploc_segments_workspace_bytes_dtype(2, 9, 4096, 129, binding.DTYPE_F32) == 0
+    assert L.toploc_segments_workspace_bytes_dtype(2, 9, 4096, 513, binding.DTYPE_F32) == 0
     assert L.toploc_segments_workspace_bytes_dtype(2, 9, 4096, 128, 7) == 0                           # unknown dtype
-    assert L.toploc_build_proofs_segments_f32(fake, 9, fake, 2, 4096, 129, fake, fake, None, fake, 1 << 30, None) == binding.EINVAL
+    assert L.toploc_build_proofs_segments_f32(fake, 9, fake, 2, 4096, 513, fake, fake, None, fake, 1 << 30, None) == binding.EINVAL
     assert L.toploc_build_proofs_segments_f32(fake, 9, fake, 2, 4096, 128, fake, fake, None, fake, 16, None) == binding.EWORKSPACE
-    assert L.toploc_verify_proofs_segments_mixed(fake, binding.DTYPE_BF16, 9, fake, 2, 4096, 256, fake, binding.DTYPE_F32,
+    assert L.toploc_verify_proofs_segments_mixed(fake, binding.DTYPE_BF16, 9, fake, 2, 4096, 513, fake, binding.DTYPE_F32,
                                                  ctypes.byref(thr), fake, fake, 1 << 30, None) == binding.EINVAL
+    # fp32 fixed chunks: k up to 512 with a workspace, refused without one
+    p32 = binding.Params(512, 32, 4096, binding.PRIME32)
+    assert binding.toploc_workspace_bytes_f32(512, 32, 4096, 16) >= 16 * 512 * 8
+    assert binding.toploc_workspace_bytes_f32(513, 32, 4096, 16) == 0
+    assert L.toploc_build_proofs_f32(fake, 16, ctypes.byref(p32), fake, fake, None, None, 0, None) == binding.EINVAL
+    assert L.toploc_build_proofs_f32(fake, 16, ctypes.byref(p32), fake, fake, None, fake, 16, None) == binding.EWORKSPACE
+    # the running top-k with the element type as an argument
+    assert L.toploc_stream_state_bytes_dtype(1, 128, binding.DTYPE_F32) == 16 + 512 + 512
+    assert L.toploc_stream_state_bytes_dtype(1, 128, binding.DTYPE_BF16) == binding.toploc_stream_state_bytes(1, 128)
+    assert L.toploc_stream_state_bytes_dtype(1, 128, 2) == 0 and L.toploc_stream_state_bytes_dtype(1, 513, binding.DTYPE_F32) == 0
+    assert L.toploc_stream_reset_dtype(fake, 0, 128, binding.DTYPE_F32, None) == binding.OK
+    assert L.toploc_stream_reset_dtype(fake, 1, 128, 3, None) == binding.EINVAL
+    assert L.toploc_stream_append_dtype(fake, 4, fake, binding.DTYPE_F32, None, None, 0, 4096, 32, 0, 128, None) == binding.OK
+    assert L.toploc_stream_append_dtype(fake, 4, fake, binding.DTYPE_F32, None, None, 4, 4096, 32, 32, 128, None) == binding.EINVAL
+    assert L.toploc_stream_append_dtype(fake, 4, fake, binding.DTYPE_F32, fake, None, 4, 4096, 32, 0, 128, None) == binding.EINVAL
+    assert L.toploc_stream_append_dtype(fake, 4, fake, 9, None, None, 4, 4096, 32, 0, 128, None) == binding.EINVAL
+    assert L.toploc_stream_emit_dtype(fake, 4, binding.DTYPE_F32, None, 0, 128, fake, fake, None, None) == binding.OK
+    assert L.toploc_stream_emit_dtype(fake, 4, binding.DTYPE_F32, None, 4, 513, fake, fake, None, None) == binding.EINVAL
     assert L.toploc_verify_proofs_segments_mixed(fake, binding.DTYPE_F32, 9, fake, 0, 4096, 128, fake, binding.DTYPE_F32,
                                                  ctypes.byref(thr), fake, fake, 0, None) == binding.OK
 

@@ -139,7 +139,7 @@ def test_decode_edges_in_the_32_bit_field():
 def test_f32_arguments_are_checked():
     x = torch.zeros((1, 32 * 64), dtype=torch.float32, device=DEV)
     with pytest.raises(tl.ToplocError):
-        tl.toploc_build_proofs_f32(x, k=256, chunk_tokens=32)        # k > TOPLOC_MAX_K_F32
+        tl.toploc_build_proofs_f32(x, k=513, chunk_tokens=32)        # k > TOPLOC_MAX_K_F32
     with pytest.raises(tl.ToplocError):
         tl.toploc_build_proofs_f32(x, k=0, chunk_tokens=32)
     e = torch.empty((0, 2048), dtype=torch.float32, device=DEV)
@@ -175,6 +175,8 @@ def _to_bf16_model(x32):
     (8, [1, 2, 5], 8, 0),                  # the smallest rows: two vectors each
     (4096, [300, 5], 128, 5),              # forced cuts: parts of unequal length, ties across borders by chance
     (5120, [40, 32], 32, 1),
+    (4096, [70, 32, 9], 512, 0),           # k above 128: the larger candidate buffer, 512 points in the 32-bit field
+    (1024, [33, 64], 256, 3),
 ])
 def test_f32_segments_build_and_the_four_precision_pairs(hidden, rows, k, parts):
     """Segments of unequal length with fp32 activations: proofs, status, indices and the verify records of all
@@ -227,9 +229,88 @@ def test_f32_segments_equal_fixed_chunks_and_reject_bad_arguments():
     torch.cuda.synchronize()
     assert torch.equal(p_seg, p_fix) and torch.equal(s_seg, s_fix) and torch.equal(i_seg, i_fix)
     with pytest.raises(tl.ToplocError):
-        tl.toploc_build_proofs_segments_f32(x, off, k=129)                       # k above the fp32 limit
+        tl.toploc_build_proofs_segments_f32(x, off, k=513)                       # k above the fp32 limit
     with pytest.raises(tl.ToplocError):
         tl.toploc_verify_proofs_segments_mixed(x.to(torch.bfloat16), off,
-                                               torch.zeros((4, 2 + 4 * 256), dtype=torch.uint8, device=DEV), orc.F32, k=256)
+                                               torch.zeros((4, 2 + 4 * 513), dtype=torch.uint8, device=DEV), orc.F32, k=513)
     assert tl.toploc_segments_workspace_bytes_dtype(4, 128, 1024, 128, tl.DTYPE_F32) > \
         tl.toploc_segments_workspace_bytes_dtype(4, 128, 1024, 128, tl.DTYPE_BF16) > 0
+
+
+# ---------------------------------------------------------------------------
+# k above 128 in the 32-bit field (Section 5.7's precision study does not bound k) and the running top-k
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("hidden,tokens,k,n_chunks,parts", [
+    (4096, 32, 512, 3, 0),       # the 8B shape, largest k: split launches with the library's cut
+    (5120, 32, 256, 2, 0),
+    (1024, 32, 129, 4, 1),       # just above the fused limit, one part per chunk
+    (4096, 32, 512, 2, 5),       # forced cut into 5 parts
+    (64, 32, 512, 2, 0),         # N = 2048, k = N/4
+])
+def test_f32_large_k_build_and_the_four_precision_pairs(hidden, tokens, k, n_chunks, parts):
+    x32 = f32_chunks(n_chunks, hidden, tokens, 9500 + hidden + k)
+    x16 = _to_bf16_model(x32)
+    try:
+        tl.toploc_set_split(parts)
+        assert tl.toploc_workspace_bytes_f32(k, 1, x32.shape[1], n_chunks) >= n_chunks * k * 8
+        p32 = check_build(x32, k, "large k H=%d parts=%d" % (hidden, parts))
+    finally:
+        tl.toploc_set_split(0)
+    p16, _ = orc.build(synth.bits_numpy(x16), k)
+    r32 = (x32 * (1.0 + 2.0 ** -12 * torch.sin(torch.arange(x32.shape[1], device=DEV, dtype=torch.float32)))).contiguous()
+    r16 = _to_bf16_model(r32)
+    res = check_verify(x32, p32, orc.F32, k, "self")
+    assert (res["accept"] == 1).all() and (res["mant_sum"] == 0).all() and (res["n_match"] == k).all()
+    for rec in (r32, r16):
+        for p, p_dt in ((p32, orc.F32), (p16, orc.BF16)):
+            check_verify(rec, p, p_dt, k, "large k")
+    with pytest.raises(tl.ToplocError):     # k > 128 needs the workspace
+        tl.toploc_build_proofs_f32(x32, k=k, chunk_tokens=1, workspace=torch.empty(16, dtype=torch.uint8, device=DEV))
+
+
+@pytest.mark.parametrize("hidden,T,k,n_seq", [
+    (5120, 32, 128, 5),
+    (4096, 32, 512, 3),
+    (1000, 7, 32, 3),
+    (8, 16, 16, 2),
+])
+def test_f32_running_topk_matches_the_oracle_on_the_assembled_chunk(hidden, T, k, n_seq):
+    """The running top-k over fp32 rows: proofs, status and indices of the emission equal the 32-bit oracle's on
+    the chunk assembled from the appended rows; rows arrive in a scrambled order, the state is reused."""
+    say("f32 stream H=%d T=%d k=%d n_seq=%d" % (hidden, T, k, n_seq))
+    steps = synth.activations(n_seq, 2 * T, hidden, 9600 + hidden + k, n_outlier=min(8, hidden), device=DEV,
+                              dtype=torch.float32).transpose(0, 1).contiguous()          # [2T, n_seq, hidden]
+    state = tl.toploc_stream_new_state(n_seq, k, DEV, dtype=tl.DTYPE_F32)
+    assert state.numel() >= n_seq * (16 + 8 * k)
+    order = np.random.default_rng(96).permutation(T)
+    for window in range(2):
+        for t in order:
+            tl.toploc_stream_append(state, steps[window * T + int(t)], int(t), k=k, chunk_tokens=T)
+        proofs, status, idx = tl.toploc_stream_emit(state, n_seq, k=k, want_topk=True, dtype=tl.DTYPE_F32)
+        torch.cuda.synchronize()
+        chunk = steps[window * T:(window + 1) * T].transpose(0, 1).contiguous().reshape(n_seq, T * hidden)
+        o_proofs, o_status, o_idx = orc.build32(synth.bits_numpy(chunk), k, want_topk=True)
+        assert np.array_equal(idx.cpu().numpy().view(np.uint32), o_idx), "window %d: indices" % window
+        assert np.array_equal(status.cpu().numpy(), o_status) and np.array_equal(proofs.cpu().numpy(), o_proofs), window
+        g_proofs, _ = tl.toploc_build_proofs_f32(chunk, k=k, chunk_tokens=1)
+        torch.cuda.synchronize()
+        assert torch.equal(g_proofs, proofs)
+    # continuous batching in fp32: rows of a subset of the sequences, each at its own position; a short state
+    tl.toploc_stream_append_rows(state, n_seq, steps[0, :2].contiguous(), [1, 0], [3, 0], k=k, chunk_tokens=T)
+    proofs, status = tl.toploc_stream_emit_rows(state, n_seq, [0, 1], k=k, dtype=tl.DTYPE_F32)
+    torch.cuda.synchronize()
+    if hidden >= k:
+        # one row as token `tok`: the proof of a chunk that is zero except for that row would rank the zeros by
+        # index too, so compare with the oracle on exactly what was appended: a one-row chunk whose flat
+        # indices start at tok * hidden (the oracle ranks a flat array; shift its indices accordingly)
+        assert status.tolist() == [tl.CHUNK_OK, tl.CHUNK_OK]
+        state2 = tl.toploc_stream_new_state(n_seq, k, DEV, dtype=tl.DTYPE_F32)
+        tl.toploc_stream_append_rows(state2, n_seq, steps[0, :2].contiguous(), [1, 0], [3, 0], k=k, chunk_tokens=T)
+        _, _, idx = tl.toploc_stream_emit_rows(state2, n_seq, [0, 1], k=k, want_topk=True, dtype=tl.DTYPE_F32)
+        torch.cuda.synchronize()
+        for out_row, (src_row, tok) in enumerate(((1, 0), (0, 3))):
+            oi, _ = orc.topk32(synth.bits_numpy(steps[0, src_row]), k)
+            assert np.array_equal(idx[out_row].cpu().numpy().view(np.uint32), oi + np.uint32(tok * hidden))
+    else:
+        assert status.tolist() == [tl.CHUNK_SHORT, tl.CHUNK_SHORT] and not proofs.any()
