@@ -24,6 +24,12 @@
 #include "../../include/toploc.h"
 #include "gf65497.hpp"
 #include "interp.hpp"
+#ifndef TOPLOC_INTERP_PLANES
+#define TOPLOC_INTERP_PLANES 1   // 1: GF(65497) interpolation on byte planes and packed dot products (interp16.hpp)
+#endif
+#if TOPLOC_INTERP_PLANES
+#include "interp16.hpp"
+#endif
 #include "plan.hpp"
 #include "select.hpp"
 #include "verify.hpp"
