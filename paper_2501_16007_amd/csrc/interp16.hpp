@@ -153,11 +153,11 @@ __device__ __forceinline__ void interpolate(InterpShared<KMAX, Field16>& s, uint
 
     // ---- levels: blocks of d coefficients are multiplied in pairs ----
     uint32_t b = 0;   // buffer the level reads
-    for (uint32_t d = 16u; d < k; d <<= 1, b ^= 1u) {
-        const uint32_t span = 2u * d;
-        const uint32_t kceil = (k + span - 1u) / span * span;   // outputs: whole blocks of 2d (<= KMAX)
+    for (uint32_t ld = 4u; (1u << ld) < k; ++ld, b ^= 1u) {   // d = 2^ld
+        const uint32_t d = 1u << ld, span = 2u * d;
+        const uint32_t kceil = ((k + span - 1u) >> (ld + 1u)) << (ld + 1u);   // outputs: whole blocks of 2d (<= KMAX)
         if (o < kceil) {
-            const uint32_t q = o / span, t = o - q * span, start = q * span;
+            const uint32_t q = o >> (ld + 1u), t = o & (span - 1u), start = o & ~(span - 1u);
             const uint32_t df = (k - start) < d ? (k - start) : d;
             const uint32_t rem = k - start - df;
             const uint32_t dg = rem < d ? rem : d;
