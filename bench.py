@@ -26,10 +26,12 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="config3", choices=["config3", "config2", "config4", "config5", "config3_f32"],
+    ap.add_argument("--workload", default="config3",
+                    choices=["config3", "config2", "config4", "config5", "config3_f32", "segments"],
                     help="config3 is the benchmark line; config2 is the 8B shape; config4 (verification stress) and "
                          "config5 (online decode-step path) print their own report line; config3_f32 is the 70B "
-                         "shape with fp32 activations (64 sequences, the same 8 GiB) through the fp32 calls")
+                         "shape with fp32 activations (64 sequences, the same 8 GiB) through the fp32 calls; segments is "
+                         "a serving-style batch of whole-prompt proofs and ragged decode chunks through the segment calls")
     ap.add_argument("--law", default="outliers", choices=["outliers", "gaussian", "heavy_tail", "ascending"],
                     help="value law of the synthetic activations (config3 / config2 only): outliers is the workload's "
                          "recipe and the benchmark line; the others show how the selection's cost depends on the input")
@@ -55,6 +57,8 @@ def main():
         return report_config4(args, tl, synth, torch, dev)
     if args.workload == "config5":
         return report_config5(args, tl, synth, torch, dev)
+    if args.workload == "segments":
+        return report_segments(args, tl, synth, torch, dev)
     f32 = args.workload == "config3_f32"
     if f32:
         x = synth.activations(64, 4096, 8192, synth.BASE_SEED + 3, n_outlier=16, device=dev, dtype=torch.float32)
@@ -299,6 +303,45 @@ def report_config4(args, tl, synth, torch, dev):
         "config": {"workload": "8B shape 64 x 2048 x 4096 bf16, k=%d, three recomputed tensors" % k,
                    "n_chunks": n_chunks, "chunk_values": n, "k": k},
         "variants": variants}))
+
+
+def report_segments(args, tl, synth, torch, dev):
+    """Variable-length segments at the 8B shape: 48 sequences, each a whole-prompt proof (128 to 6000 tokens, seeded)
+    followed by decode chunks of 32 tokens and a ragged last one; one matrix of rows, row offsets on the device."""
+    import numpy as np
+    k, hidden = args.k, 4096
+    rng = np.random.default_rng(synth.BASE_SEED + 6)
+    cuts = [0]
+    for _ in range(48):
+        n_prompt = int(rng.integers(128, 6000))
+        n_decode = int(rng.integers(1, 400))
+        cuts.append(cuts[-1] + n_prompt)
+        t = 0
+        while t < n_decode:
+            step = min(32, n_decode - t)
+            cuts.append(cuts[-1] + step)
+            t += step
+    total = cuts[-1]
+    x = synth.activations(1, total, hidden, synth.BASE_SEED + 6, n_outlier=8, device=dev).reshape(total, hidden)
+    off = torch.tensor(cuts, dtype=torch.int64, device=dev)
+    n_seg = len(cuts) - 1
+    out = (torch.empty((n_seg, 2 + 2 * k), dtype=torch.uint8, device=dev), torch.empty(n_seg, dtype=torch.uint8, device=dev), None)
+    res = torch.empty((n_seg, 20), dtype=torch.uint8, device=dev)
+    ws = tl.new_segments_workspace(x, n_seg, k)
+    bms = _kernel_ms(tl, torch, lambda: tl.toploc_build_proofs_segments(x, off, k=k, workspace=ws, out=out), args.steps)
+    vms = _kernel_ms(tl, torch, lambda: tl.toploc_verify_proofs_segments(x, off, out[0], k=k, workspace=ws, out=res), args.steps)
+    g = tl.results_numpy(res)
+    assert int(out[1].max()) == 0 and bool((g["accept"] == 1).all())
+    act = total * hidden * 2
+    b_tot, v_tot = sum(bms.values()), sum(vms.values())
+    print(json.dumps({
+        "metric": "segment calls: proof build + verify throughput (activation GB/s)", "unit": "GB/s",
+        "value": 2 * act / ((b_tot + v_tot) * 1e-3) / 1e9, "n_gpus": 1, "steps": args.steps, "dtype": "u16", "data": "synthetic",
+        "config": {"workload": "48 sequences at hidden 4096: whole-prompt segments of 128-6000 tokens, 32-token decode "
+                               "segments, ragged last ones; k=%d" % k, "n_segments": n_seg, "total_rows": total,
+                   "activation_bytes": act},
+        "build": {"kernels_ms": bms, "GBps": act / (b_tot * 1e-3) / 1e9},
+        "verify": {"kernels_ms": vms, "GBps": act / (v_tot * 1e-3) / 1e9}}))
 
 
 def report_config5(args, tl, synth, torch, dev):

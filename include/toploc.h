@@ -364,7 +364,8 @@ int toploc_selection_stats(const void *d_hidden_bf16, uint64_t n_chunks, const t
 #define TOPLOC_KERNEL_READ 7          /* toploc_bench_read                               */
 #define TOPLOC_KERNEL_STREAM_APPEND 8 /* toploc_stream_append, toploc_stream_append_rows  */
 #define TOPLOC_KERNEL_STREAM_EMIT 9   /* toploc_stream_emit, toploc_stream_emit_rows      */
-#define TOPLOC_KERNEL_COUNT 10
+#define TOPLOC_KERNEL_PLAN 10         /* segment calls: the part table from the row offsets */
+#define TOPLOC_KERNEL_COUNT 11
 int toploc_profile_enable(int on);
 int toploc_profile_read(uint32_t *launches /*[TOPLOC_KERNEL_COUNT]*/, float *total_ms /*[TOPLOC_KERNEL_COUNT]*/);
 

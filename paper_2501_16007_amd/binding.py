@@ -19,9 +19,10 @@ OK, EINVAL, EWORKSPACE, EHIP, ESCRATCH = 0, -1, -2, -3, -4
 STATIC_SCRATCH_BYTES = 8 << 20
 CHUNK_OK, CHUNK_NO_MODULUS, CHUNK_MALFORMED, CHUNK_SHORT, CHUNK_BAD_SEGMENT = 0, 1, 3, 4, 5
 (KERNEL_SELECT, KERNEL_PART, KERNEL_BUILD_MERGE, KERNEL_VERIFY_MERGE, KERNEL_BUILD, KERNEL_VERIFY, KERNEL_RING,
- KERNEL_READ, KERNEL_STREAM_APPEND, KERNEL_STREAM_EMIT, KERNEL_COUNT) = range(11)
+ KERNEL_READ, KERNEL_STREAM_APPEND, KERNEL_STREAM_EMIT, KERNEL_PLAN, KERNEL_COUNT) = range(12)
 KERNEL_NAMES = ("select_kernel", "part_kernel", "build_merge_kernel", "verify_merge_kernel", "build_kernel",
-                "verify_kernel", "ring_kernel", "read_kernel", "stream_append_kernel", "stream_emit_kernel")
+                "verify_kernel", "ring_kernel", "read_kernel", "stream_append_kernel", "stream_emit_kernel",
+                "plan_segments_kernel")
 BF16_THRESHOLDS = (38, 10, 8)  # T_exp, T_mean, T_median (Section 5.2 of the paper)
 F32_THRESHOLDS = (8, 256, 128)  # the same for fp32 inference
 DTYPE_BF16, DTYPE_F32 = 0, 1

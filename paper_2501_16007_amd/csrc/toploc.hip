@@ -751,8 +751,11 @@ static int launch_segment_parts(const plan::SegmentPlan& pl, const void* d_hidde
     lay.nvec = 0;
     lay.parts = 0;
     lay.part_vecs = (uint32_t)pl.part_vecs;
-    hipLaunchKernelGGL(plan_segments_kernel, dim3((uint32_t)((pl.slots + 255) / 256)), dim3(256), 0, st, lay, n_segments,
-                       pl.slots, k, table);
+    {
+        ProfScope ps(TOPLOC_KERNEL_PLAN, st);
+        hipLaunchKernelGGL(plan_segments_kernel, dim3((uint32_t)((pl.slots + 255) / 256)), dim3(256), 0, st, lay, n_segments,
+                           pl.slots, k, table);
+    }
     if (!hip_ok(hipGetLastError())) return TOPLOC_EHIP;
     launch_part(st, d_hidden, lay, pl.slots, k, c_idx, c_bits, hidden_dtype);
     return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
