@@ -417,11 +417,14 @@ __device__ __forceinline__ void load_round(u32x4 (&buf)[U], const u32x4* __restr
     }
 }
 
-// Examine the round held in buf (vectors b + u*THREADS + tid): every vector with a
-// magnitude >= t.tm goes to the queue.  A wave with nothing to queue goes straight to the
-// barrier; otherwise the wave takes all its queue slots with one LDS atomic.  One barrier
-// per pass; the workgroup drains the queue when it passed its soft limit, and lanes that
-// found the queue full retry after the drain (against the new threshold).
+// Examine the round held in buf (vectors b + u*THREADS + tid): every vector that may hold a value
+// coming before the threshold element goes to the queue.  A vector's largest magnitude decides:
+// above the threshold's it goes, below it does not, and a vector that only equals it goes when its
+// first index is below the threshold's index.  The threshold element usually lies before the round
+// (it was read in an earlier one); then "equal" never goes and one compare against tm + 1 settles it.
+// A wave with nothing to queue goes straight to the barrier; otherwise the wave takes all its queue
+// slots with one LDS atomic.  One barrier per pass; the workgroup drains the queue when it passed its soft limit, and
+// lanes that found the queue full retry after the drain (against the new threshold).
 template <int THREADS, int U, int CAP, int QCAP, typename Fmt>
 __device__ __forceinline__ void examine_round(const u32x4 (&buf)[U], uint32_t b, uint32_t v1, uint32_t k,
                                               SelectShared<THREADS, CAP, QCAP, Fmt>& s, Threshold& t, uint32_t& round,
@@ -432,25 +435,26 @@ __device__ __forceinline__ void examine_round(const u32x4 (&buf)[U], uint32_t b,
     int32_t m[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) m[u] = Fmt::vec_max(buf[u]);
+    // uniform: does the threshold element lie inside or behind this round (or is there none yet)?
+    bool by_index = t.ti > b * (uint32_t)Fmt::ELEMS;
+    const uint32_t thr = (uint32_t)t.tm + (by_index ? 0u : 1u);  // magnitudes are below 2^31: no wrap
     uint32_t pend = 0;  // bit u: vector u still has to be queued
     if (b + THREADS * U <= v1) {  // uniform
 #pragma unroll
-        for (int u = 0; u < U; ++u) pend |= (m[u] >= t.tm) ? (1u << u) : 0u;
+        for (int u = 0; u < U; ++u) pend |= ((uint32_t)m[u] >= thr) ? (1u << u) : 0u;
     } else {
 #pragma unroll
-        for (int u = 0; u < U; ++u) pend |= (m[u] >= t.tm && b + u * THREADS + tid < v1) ? (1u << u) : 0u;
+        for (int u = 0; u < U; ++u) pend |= ((uint32_t)m[u] >= thr && b + u * THREADS + tid < v1) ? (1u << u) : 0u;
     }
     while (true) {
         uint32_t* flag = &s.flag[round % 3u];
-        if (__ballot(pend != 0u)) {  // uniform within the wave
-            // A vector whose largest magnitude only equals the threshold's and whose first index is not
-            // below the threshold's holds nothing that comes before the threshold element: without this,
-            // data with many equal magnitudes would queue every vector of every round.
+        if (by_index && __ballot(pend != 0u)) {  // uniform within the wave
+            // without this, data with many equal magnitudes would queue every vector of every round
 #pragma unroll
             for (int u = 0; u < U; ++u)
                 if (m[u] == t.tm && (b + u * THREADS + tid) * (uint32_t)Fmt::ELEMS >= t.ti) pend &= ~(1u << u);
         }
-        if (__ballot(pend != 0u)) {  // uniform within the wave
+        if (__ballot(pend != 0u)) {  // uniform within the wave: it takes all its queue slots with one LDS atomic
             uint64_t want[U];
             uint32_t total = 0;
 #pragma unroll
@@ -484,6 +488,7 @@ __device__ __forceinline__ void examine_round(const u32x4 (&buf)[U], uint32_t b,
         const bool again = drain(s, k, TOPLOC_PRUNE_LIMIT(CAP, k), t, epoch);
         TOPLOC_TICK_END(drain, 2);
         if (!again) break;
+        by_index = true;  // the new threshold element may be one of this round's
 #pragma unroll
         for (int u = 0; u < U; ++u)
             if (m[u] < t.tm) pend &= ~(1u << u);
@@ -535,22 +540,32 @@ __device__ __forceinline__ SelectStart select_topk_from(const u32x4* __restrict_
     uint32_t round = 0;    // barrier rounds; flag[round % 3] belongs to the current one
     uint32_t epoch = 0;    // drains so far; qcount[epoch % 2] counts the current pushes
 
-    // First threshold: the largest magnitude of every vector of the first round belongs
-    // to a distinct real element.  If at least k of those maxima have exponent >= e, then
-    // k elements have magnitude >= e << (mantissa bits), and nothing below that can be in the top-k.
-    // One exponent histogram finds the largest such e; exact thresholds follow from the
-    // first prune.
+    // First threshold: the largest magnitude of every vector of the first round belongs to a distinct
+    // real element, so the k-th largest of those maxima is a magnitude that at least k elements reach:
+    // nothing below it can be in the top-k.  Two radix digits of the maxima (exponent, then the next
+    // digit among the maxima that share the k-th's exponent) find it: exactly for bf16, to 16 of the
+    // 31 magnitude bits for fp32.  Exact thresholds follow from the first prune.
     const uint32_t first = (v1 - v0) < ROUND ? (v1 - v0) : ROUND;
     if (n_seed == 0 && first >= k) {  // uniform
-        for (uint32_t b = tid; b < 256; b += THREADS) s.hist[0][b] = 0;
+        constexpr int S0 = Fmt::shift(0), S1 = Fmt::shift(1), W1 = Fmt::width(1);
+        for (uint32_t b = tid; b < 512u; b += THREADS) (&s.hist[0][0])[b] = 0;
         __syncthreads();
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            if (v0 + u * THREADS + tid < v1) atomicAdd(&s.hist[0][(uint32_t)Fmt::vec_max(even[u]) >> Fmt::shift(0)], 1u);
+            if (v0 + u * THREADS + tid < v1) atomicAdd(&s.hist[0][(uint32_t)Fmt::vec_max(even[u]) >> S0], 1u);
         __syncthreads();
-        uint32_t e_star, above;
+        uint32_t e_star, above;   // every wave searches for itself: no broadcast, no barrier
         find_bin<4>(s.hist[0], 0u, k, e_star, above);
-        t.tm = (int32_t)(e_star << Fmt::shift(0));
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t mx = (uint32_t)Fmt::vec_max(even[u]);
+            if (v0 + u * THREADS + tid < v1 && (mx >> S0) == e_star) atomicAdd(&s.hist[1][(mx >> S1) & ((1u << W1) - 1u)], 1u);
+        }
+        __syncthreads();
+        uint32_t digit, above1;
+        if (W1 == 8) find_bin<4>(s.hist[1], above, k, digit, above1);
+        else find_bin<2>(s.hist[1], above, k, digit, above1);
+        t.tm = (int32_t)((e_star << S0) | (digit << S1));
     }
     __syncthreads();
 
