@@ -540,26 +540,31 @@ __device__ __forceinline__ SelectStart select_topk_from(const u32x4* __restrict_
     uint32_t round = 0;    // barrier rounds; flag[round % 3] belongs to the current one
     uint32_t epoch = 0;    // drains so far; qcount[epoch % 2] counts the current pushes
 
-    // First threshold: the largest magnitude of every vector of the first round belongs to a distinct
-    // real element, so the k-th largest of those maxima is a magnitude that at least k elements reach:
-    // nothing below it can be in the top-k.  Two radix digits of the maxima (exponent, then the next
-    // digit among the maxima that share the k-th's exponent) find it: exactly for bf16, to 16 of the
-    // 31 magnitude bits for fp32.  Exact thresholds follow from the first prune.
-    const uint32_t first = (v1 - v0) < ROUND ? (v1 - v0) : ROUND;
+    // First threshold: the largest magnitude of every vector of the first two rounds (both are on
+    // their way by now) belongs to a distinct real element, so the k-th largest of those maxima is a
+    // magnitude that at least k elements reach: nothing below it can be in the top-k.  Two radix
+    // digits of the maxima (exponent, then the next digit among the maxima that share the k-th's
+    // exponent) find it: exactly for bf16, to 16 of the 31 magnitude bits for fp32.  Exact
+    // thresholds follow from the first prune.
+    const uint32_t first = (v1 - v0) < 2u * ROUND ? (v1 - v0) : 2u * ROUND;
     if (n_seed == 0 && first >= k) {  // uniform
         constexpr int S0 = Fmt::shift(0), S1 = Fmt::shift(1), W1 = Fmt::width(1);
         for (uint32_t b = tid; b < 512u; b += THREADS) (&s.hist[0][0])[b] = 0;
         __syncthreads();
 #pragma unroll
-        for (int u = 0; u < U; ++u)
+        for (int u = 0; u < U; ++u) {
             if (v0 + u * THREADS + tid < v1) atomicAdd(&s.hist[0][(uint32_t)Fmt::vec_max(even[u]) >> S0], 1u);
+            if (v0 + ROUND + u * THREADS + tid < v1) atomicAdd(&s.hist[0][(uint32_t)Fmt::vec_max(odd[u]) >> S0], 1u);
+        }
         __syncthreads();
         uint32_t e_star, above;   // every wave searches for itself: no broadcast, no barrier
         find_bin<4>(s.hist[0], 0u, k, e_star, above);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const uint32_t mx = (uint32_t)Fmt::vec_max(even[u]);
-            if (v0 + u * THREADS + tid < v1 && (mx >> S0) == e_star) atomicAdd(&s.hist[1][(mx >> S1) & ((1u << W1) - 1u)], 1u);
+            const uint32_t me = (uint32_t)Fmt::vec_max(even[u]), mo = (uint32_t)Fmt::vec_max(odd[u]);
+            if (v0 + u * THREADS + tid < v1 && (me >> S0) == e_star) atomicAdd(&s.hist[1][(me >> S1) & ((1u << W1) - 1u)], 1u);
+            if (v0 + ROUND + u * THREADS + tid < v1 && (mo >> S0) == e_star)
+                atomicAdd(&s.hist[1][(mo >> S1) & ((1u << W1) - 1u)], 1u);
         }
         __syncthreads();
         uint32_t digit, above1;
