@@ -22,12 +22,25 @@ __device__ __forceinline__ uint32_t mul24(uint32_t a, uint32_t b)
     return (uint32_t)__umul24(a, b);
 }
 
+// (v >> 16) * 39 + (v & 0xFFFF): one folding step, congruent to v
+__device__ __forceinline__ uint32_t fold16(uint32_t v)
+{
+    return mul24(v >> 16, kFold16) + (v & 0xFFFFu);
+}
+
+// v < 2p -> v mod p: v - p wraps to a huge value exactly when v < p
+__device__ __forceinline__ uint32_t below_2p(uint32_t v)
+{
+    const uint32_t w = v - kPrime;
+    return w < v ? w : v;
+}
+
 // any 32-bit v -> v mod p
 __device__ __forceinline__ uint32_t reduce32(uint32_t v)
 {
-    v = mul24(v >> 16, kFold16) + (v & 0xFFFFu);  // < 40 * 2^16
-    v = mul24(v >> 16, kFold16) + (v & 0xFFFFu);  // <= 39*39 + 65535 < 2p
-    return v >= kPrime ? v - kPrime : v;
+    v = fold16(v);  // < 40 * 2^16
+    v = fold16(v);  // <= 39*39 + 65535 < 2p
+    return below_2p(v);
 }
 
 // a, b < 2^16
@@ -58,16 +71,21 @@ __device__ __forceinline__ uint32_t reduce64(uint64_t acc)
 
 // a^(p-2): the inverse of a != 0 by Fermat's little theorem (replaces the
 // extended Euclid of Algorithm 4; the inverse is unique, so the result is the same).
+// p - 2 = 65495 = 0b1111111111010111, taken three bits at a time where they are 111:
+// 16 squarings and 6 multiplications.
 __device__ __forceinline__ uint32_t invmod(uint32_t a)
 {
-    // p - 2 = 65495 = 0b1111111111010111
-    uint32_t r = a;
-#pragma unroll
-    for (int bit = 14; bit >= 0; --bit) {
-        r = mulmod(r, r);
-        if ((65495u >> bit) & 1u) r = mulmod(r, a);
-    }
-    return r;
+    const uint32_t a3 = mulmod(mulmod(a, a), a);
+    const uint32_t a7 = mulmod(mulmod(a3, a3), a);
+    auto sq3 = [](uint32_t r) { r = mulmod(r, r); r = mulmod(r, r); return mulmod(r, r); };
+    uint32_t r = a7;                       // 111
+    r = mulmod(sq3(r), a7);                // 111111
+    r = mulmod(sq3(r), a7);                // 111111111
+    r = mulmod(mulmod(r, r), a);           // 1111111111
+    r = mulmod(r, r);                      // 11111111110
+    r = mulmod(mulmod(r, r), a);           // 111111111101
+    r = mulmod(r, r);                      // 1111111111010
+    return mulmod(sq3(r), a7);             // 1111111111010111
 }
 
 // The field as the interpolation and evaluation code sees it.
@@ -86,8 +104,7 @@ struct Field16 {
     }
     static __device__ __forceinline__ uint32_t addmod(uint32_t a, uint32_t b)   // a, b < p
     {
-        const uint32_t s = a + b;
-        return s >= P ? s - P : s;
+        return below_2p(a + b);
     }
     static __device__ __forceinline__ uint32_t submod(uint32_t a, uint32_t b) { return toploc::submod(a, b); }
     static __device__ __forceinline__ uint32_t neg(uint32_t a) { return a ? P - a : 0u; }
