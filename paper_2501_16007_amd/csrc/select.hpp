@@ -421,10 +421,50 @@ __device__ __forceinline__ void load_round(u32x4 (&buf)[U], const u32x4* __restr
 // coming before the threshold element goes to the queue.  A vector's largest magnitude decides:
 // above the threshold's it goes, below it does not, and a vector that only equals it goes when its
 // first index is below the threshold's index.  The threshold element usually lies before the round
-// (it was read in an earlier one); then "equal" never goes and one compare against tm + 1 settles it.
-// A wave with nothing to queue goes straight to the barrier; otherwise the wave takes all its queue
-// slots with one LDS atomic.  One barrier per pass; the workgroup drains the queue when it passed its soft limit, and
-// lanes that found the queue full retry after the drain (against the new threshold).
+// (it was read in an earlier one); then "equal" never goes and one compare against tm + 1 settles it:
+// the four compares leave their lane masks in scalar registers, and a wave whose masks are all
+// empty goes straight to the barrier.  Otherwise the wave takes all its queue slots with one LDS
+// atomic (slot of a lane = the wave's first slot + set bits of the masks below it), and lane 0 raises
+// the round's flag when the queue passed its soft limit.  One barrier per pass; the workgroup drains
+// the queue when the flag is up.  Lanes that found the queue full (rare: the wave's slots ran past the
+// end) remember their vectors in `pend` and try again after the drain, against the new threshold.
+template <int THREADS, int U, int CAP, int QCAP, typename Fmt, bool PLAIN>
+__device__ __forceinline__ uint32_t queue_first_pass(const u32x4 (&buf)[U], const int32_t (&m)[U], const uint64_t (&want)[U],
+                                                     uint32_t thr, uint32_t b, SelectShared<THREADS, CAP, QCAP, Fmt>& s,
+                                                     uint32_t* flag, uint32_t epoch)
+{
+    constexpr uint32_t QSOFT = QCAP / 2;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t lane = lane_id();
+    uint32_t total = 0;
+#pragma unroll
+    for (int u = 0; u < U; ++u) total += (uint32_t)__popcll(want[u]);
+    uint32_t first = 0;
+    if (lane == 0) first = atomicAdd(&s.qcount[epoch & 1u], total);
+    first = __builtin_amdgcn_readfirstlane(first);
+    if (first + total > QSOFT && lane == 0) *flag = 1u;       // some slot at or past the soft limit was handed out
+    const bool spill = first + total > (uint32_t)QCAP;         // uniform: some lane finds no room
+    uint32_t pend = 0;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if (want[u] != 0) {  // uniform
+            // the lane's bit of want[u]: in a plain round the compare that made the mask, evaluated again
+            const bool mine = PLAIN ? ((uint32_t)m[u] >= thr) : (((want[u] >> lane) & 1ull) != 0);
+            if (mine) {
+                const uint32_t slot = first + lanes_below(want[u]);
+                if (!spill || slot < (uint32_t)QCAP) {
+                    s.qvec[slot] = buf[u];
+                    s.qidx[slot] = b + u * THREADS + tid;
+                } else {
+                    pend |= 1u << u;
+                }
+            }
+            first += (uint32_t)__popcll(want[u]);
+        }
+    }
+    return pend;
+}
+
 template <int THREADS, int U, int CAP, int QCAP, typename Fmt>
 __device__ __forceinline__ void examine_round(const u32x4 (&buf)[U], uint32_t b, uint32_t v1, uint32_t k,
                                               SelectShared<THREADS, CAP, QCAP, Fmt>& s, Threshold& t, uint32_t& round,
@@ -435,52 +475,36 @@ __device__ __forceinline__ void examine_round(const u32x4 (&buf)[U], uint32_t b,
     int32_t m[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) m[u] = Fmt::vec_max(buf[u]);
-    // uniform: does the threshold element lie inside or behind this round (or is there none yet)?
-    bool by_index = t.ti > b * (uint32_t)Fmt::ELEMS;
-    const uint32_t thr = (uint32_t)t.tm + (by_index ? 0u : 1u);  // magnitudes are below 2^31: no wrap
-    uint32_t pend = 0;  // bit u: vector u still has to be queued
-    if (b + THREADS * U <= v1) {  // uniform
+    // uniform: is there a threshold element yet (before the first prune tm is only a bound that at least k
+    // values reach: equal magnitudes count), and if so, does it lie inside or behind this round?
+    const bool element = t.ti != 0xFFFFFFFFu;
+    const bool by_index = element && t.ti > b * (uint32_t)Fmt::ELEMS;
+    const uint32_t thr = (uint32_t)t.tm + (element && !by_index ? 1u : 0u);  // magnitudes are below 2^31: no wrap
+    const bool plain = !by_index && b + THREADS * U <= v1;        // uniform: one compare per vector decides
+    uint64_t want[U];   // lanes whose vector u goes to the queue
+    uint64_t any = 0;
+    if (plain) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) pend |= ((uint32_t)m[u] >= thr) ? (1u << u) : 0u;
+        for (int u = 0; u < U; ++u) { want[u] = __ballot((uint32_t)m[u] >= thr); any |= want[u]; }
     } else {
+        // the ragged last round, and rounds that may hold the threshold element itself: without the index rule
+        // data with many equal magnitudes would queue every vector of every round
 #pragma unroll
-        for (int u = 0; u < U; ++u) pend |= ((uint32_t)m[u] >= thr && b + u * THREADS + tid < v1) ? (1u << u) : 0u;
+        for (int u = 0; u < U; ++u) {
+            const uint32_t v = b + u * THREADS + tid;
+            want[u] = __ballot((uint32_t)m[u] >= thr && v < v1 && !(m[u] == t.tm && v * (uint32_t)Fmt::ELEMS >= t.ti));
+            any |= want[u];
+        }
+    }
+    uint32_t pend = 0;  // bit u: vector u found the queue full and still has to be queued
+    if (any != 0) {     // uniform within the wave
+        uint32_t* flag = &s.flag[round % 3u];
+        pend = plain ? queue_first_pass<THREADS, U, CAP, QCAP, Fmt, true>(buf, m, want, thr, b, s, flag, epoch)
+                     : queue_first_pass<THREADS, U, CAP, QCAP, Fmt, false>(buf, m, want, thr, b, s, flag, epoch);
     }
     while (true) {
-        uint32_t* flag = &s.flag[round % 3u];
-        if (by_index && __ballot(pend != 0u)) {  // uniform within the wave
-            // without this, data with many equal magnitudes would queue every vector of every round
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (m[u] == t.tm && (b + u * THREADS + tid) * (uint32_t)Fmt::ELEMS >= t.ti) pend &= ~(1u << u);
-        }
-        if (__ballot(pend != 0u)) {  // uniform within the wave: it takes all its queue slots with one LDS atomic
-            uint64_t want[U];
-            uint32_t total = 0;
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                want[u] = __ballot((pend >> u) & 1u);
-                total += (uint32_t)__popcll(want[u]);
-            }
-            uint32_t first = 0;
-            if (lane_id() == 0) first = atomicAdd(&s.qcount[epoch & 1u], total);
-            first = __builtin_amdgcn_readfirstlane(first);
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if ((pend >> u) & 1u) {
-                    const uint32_t slot = first + lanes_below(want[u]);
-                    if (slot >= QSOFT) *flag = 1u;
-                    if (slot < (uint32_t)QCAP) {
-                        s.qvec[slot] = buf[u];
-                        s.qidx[slot] = b + u * THREADS + tid;
-                        pend &= ~(1u << u);
-                    }
-                }
-                first += (uint32_t)__popcll(want[u]);
-            }
-        }
         __syncthreads();
-        const uint32_t f = *flag;
+        const uint32_t f = s.flag[round % 3u];
         if (tid == 0) s.flag[(round + 2u) % 3u] = 0;  // the previous round's flag: read by all before this barrier
         ++round;
         if (!f) break;  // no slot at or past the soft limit was handed out: nothing is pending either
@@ -488,10 +512,37 @@ __device__ __forceinline__ void examine_round(const u32x4 (&buf)[U], uint32_t b,
         const bool again = drain(s, k, TOPLOC_PRUNE_LIMIT(CAP, k), t, epoch);
         TOPLOC_TICK_END(drain, 2);
         if (!again) break;
-        by_index = true;  // the new threshold element may be one of this round's
+        // The queue was full for some lanes: they queue what still comes before the new threshold element,
+        // which may be one of this round's.
+        uint32_t* flag = &s.flag[round % 3u];
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            if (m[u] < t.tm) pend &= ~(1u << u);
+            if (m[u] < t.tm || (m[u] == t.tm && (b + u * THREADS + tid) * (uint32_t)Fmt::ELEMS >= t.ti)) pend &= ~(1u << u);
+        if (__ballot(pend != 0u)) {  // uniform within the wave
+            uint64_t left[U];
+            uint32_t total = 0;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                left[u] = __ballot((pend >> u) & 1u);
+                total += (uint32_t)__popcll(left[u]);
+            }
+            uint32_t first = 0;
+            if (lane_id() == 0) first = atomicAdd(&s.qcount[epoch & 1u], total);
+            first = __builtin_amdgcn_readfirstlane(first);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if ((pend >> u) & 1u) {
+                    const uint32_t slot = first + lanes_below(left[u]);
+                    if (slot >= QSOFT) *flag = 1u;
+                    if (slot < (uint32_t)QCAP) {
+                        s.qvec[slot] = buf[u];
+                        s.qidx[slot] = b + u * THREADS + tid;
+                        pend &= ~(1u << u);
+                    }
+                }
+                first += (uint32_t)__popcll(left[u]);
+            }
+        }
     }
 }
 
