@@ -42,11 +42,12 @@ struct InterpShared<KMAX, Field16> {
     alignas(16) uint8_t r_hi[2][RLEN], r_lo[2][RLEN];   //                              blocks that are the g, reversed and padded
     alignas(16) uint8_t wd_hi[KMAX], wd_lo[KMAX];       // coefficients of W'
     alignas(16) uint8_t s_hi[KMAX + 16], s_lo[KMAX + 16];   // S_r
+    E dj[KMAX];               // W'(x_j), then a_j = y_j / W'(x_j): handed between the lanes that sum and the lanes that invert
     alignas(16) union {
         uint32_t bitmap[2048];                    // modulus search: one bit per residue below 65536
         struct {
-            uint8_t bt_hi[16 * BT_STRIDE], bt_lo[16 * BT_STRIDE];       // BT[r0][j] = x_j^r0
-            uint8_t g_hi[(KMAX / 16) * KMAX], g_lo[(KMAX / 16) * KMAX]; // G[r1][j] = x_j^(16 r1), later a_j x_j^(16 r1)
+            uint8_t bt_hi[16 * BT_STRIDE], bt_lo[16 * BT_STRIDE];       // BT[r0][j] = x_j^r0, later a_j x_j^r0
+            uint8_t g_hi[(KMAX / 16) * KMAX], g_lo[(KMAX / 16) * KMAX]; // G[r1][j] = x_j^(16 r1)
         } pw;
     } u;
     uint32_t collide[2];
@@ -72,7 +73,18 @@ struct PlaneAcc {
         const uint32_t h39 = (hh << 5) + (hh << 3) - hh;          // 39 hh < 2^31
         return reduce32(h39 + (reduce32(m) << 8) + ll);           // < 2^31 + 2^24 + 2^25
     }
+    // the same for at most 28 steps: hh, ll < 28 * 2^18 < 2^23, m < 2^24, so 39 hh + 2^8 m + ll < 2^32 as it is
+    __device__ __forceinline__ uint32_t value_short() const
+    {
+        return reduce32(mul24(hh, kFold16) + (m << 8) + ll);
+    }
 };
+
+// the value the other lane of the pair (lane ^ 1) holds: a DPP move inside the quad, no LDS round trip
+__device__ __forceinline__ uint32_t pair_swap(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0xB1, 0xF, 0xF, true);   // quad_perm:[1,0,3,2]
+}
 
 // bytes sh .. sh+3 of the eight bytes {hi, lo}
 __device__ __forceinline__ uint32_t byte_window(uint32_t hi, uint32_t lo, uint32_t sh)
@@ -184,7 +196,7 @@ __device__ __forceinline__ void interpolate(InterpShared<KMAX, Field16>& s, uint
                                      reinterpret_cast<const uint32_t*>(F0) + (first >> 2), reinterpret_cast<const uint32_t*>(R1),
                                      reinterpret_cast<const uint32_t*>(R0), 4u + (d - 1u - t) + first, mine);
                 val = acc.value();
-                val = F::addmod(val, __shfl_xor(val, 1));
+                val = F::addmod(val, pair_swap(val));
                 if (t < len) {   // the two terms that meet a leading 1
                     if (t >= d) val = F::addmod(val, plane_get(R1, R0, 4u + d - 1u - (t - d)));
                     if (t >= dg) val = F::addmod(val, plane_get(F1, F0, t - dg));
@@ -255,7 +267,7 @@ __device__ __forceinline__ void interpolate(InterpShared<KMAX, Field16>& s, uint
     __syncthreads();
     TOPLOC_TICK_END(tables, 8);
     TOPLOC_TICK_BEGIN(denom);
-    // ---- d_j = sum_r1 x_j^(16 r1) * (sum_r0 W'_(16 r1 + r0) x_j^r0); a_j = y_j / d_j; G <- a_j G ----
+    // ---- d_j = sum_r1 x_j^(16 r1) * (sum_r0 W'_(16 r1 + r0) x_j^r0); a_j = y_j / d_j; BT[r0][j] <- a_j x_j^r0 ----
     {
         const uint32_t j = o;
         if (j < k) {
@@ -268,23 +280,57 @@ __device__ __forceinline__ void interpolate(InterpShared<KMAX, Field16>& s, uint
                 acc.step(w1.y, w0.y, pw1[1], pw0[1]);
                 acc.step(w1.z, w0.z, pw1[2], pw0[2]);
                 acc.step(w1.w, w0.w, pw1[3], pw0[3]);
-                dacc += (uint64_t)mul24(acc.value(), plane_get(s.u.pw.g_hi, s.u.pw.g_lo, r1 * KMAX + j));
+                dacc += (uint64_t)mul24(acc.value_short(), plane_get(s.u.pw.g_hi, s.u.pw.g_lo, r1 * KMAX + j));
             }
             uint32_t dsum = reduce64(dacc);
-            dsum = F::addmod(dsum, __shfl_xor(dsum, 1));
-            uint32_t a = 0;
-            if (h == 0) a = F::mulmod(s.ys[j], F::inv(dsum));
-            a = __shfl(a, (int)(__lane_id() & ~1u));
-            for (uint32_t r1 = h; r1 < n_giant; r1 += 2u) {
-                const uint32_t at = r1 * KMAX + j;
-                plane_put(s.u.pw.g_hi, s.u.pw.g_lo, at, F::mulmod(a, plane_get(s.u.pw.g_hi, s.u.pw.g_lo, at)));
+            dsum = F::addmod(dsum, pair_swap(dsum));
+            if (h == 0) s.dj[j] = (typename Sh::E)dsum;
+        }
+    }
+    __syncthreads();
+    // The inverses: a quarter of the waves take two points per lane and invert the product of their two
+    // denominators (1/d0 = d1/(d0 d1), 1/d1 = d0/(d0 d1)), so the exponentiation runs once per two points
+    // and on a quarter of the waves only; which quarter rotates with the workgroup so that, with several
+    // workgroups on a CU, the chains spread over the SIMDs.  The denominators of distinct points are
+    // non-zero (products of differences), so the product has an inverse.
+    {
+        constexpr uint32_t LANES = KMAX / 2;                  // lanes that invert
+        static_assert(LANES % 64 == 0, "whole waves invert");
+        const uint32_t w0 = (blockIdx.x & 3u) * LANES;        // THREADS = 4 LANES
+        if (tid - w0 < LANES) {                               // whole waves (LANES is a multiple of 64)
+            const uint32_t j0 = 2u * (tid - w0), j1 = j0 + 1u;
+            if (j0 < k) {
+                const uint32_t d0 = s.dj[j0];
+                const uint32_t d1 = j1 < k ? (uint32_t)s.dj[j1] : 1u;
+                const uint32_t inv01 = F::inv(F::mulmod(d0, d1));
+                s.dj[j0] = (typename Sh::E)F::mulmod(s.ys[j0], F::mulmod(inv01, d1));
+                if (j1 < k) s.dj[j1] = (typename Sh::E)F::mulmod(s.ys[j1], F::mulmod(inv01, d0));
+            }
+        }
+    }
+    __syncthreads();
+    // BT[r0][j] <- a_j x_j^r0 (the power sums then need no scaled copy of the giant steps): the two lanes of a
+    // point take eight powers each, the second one starting from a_j x_j^8
+    {
+        const uint32_t j = o;
+        if (j < k) {
+            const uint32_t a = s.dj[j];
+            const uint32_t x = s.xs[j];
+            const uint32_t x8 = ((pw1[2] & 0xFFu) << 8) | (pw0[2] & 0xFFu);
+            uint32_t p = h ? F::mulmod(a, x8) : a;
+#pragma unroll
+            for (uint32_t i = 0; i < kBaby / 2u; ++i) {
+                const uint32_t at = (h * (kBaby / 2u) + i) * Sh::BT_STRIDE + j;
+                s.u.pw.bt_hi[at] = (uint8_t)(p >> 8);
+                s.u.pw.bt_lo[at] = (uint8_t)p;
+                p = F::mulmod(p, x);
             }
         }
     }
     __syncthreads();
     TOPLOC_TICK_END(denom, 9);
     TOPLOC_TICK_BEGIN(sums);
-    // ---- S_r = sum_j (a_j x_j^(16 r1)) x_j^r0, r = 16 r1 + r0: a dot product of two contiguous planes ----
+    // ---- S_r = sum_j x_j^(16 r1) (a_j x_j^r0), r = 16 r1 + r0: a dot product of two contiguous planes ----
     {
         const uint32_t r = o;
         if (r < k) {
@@ -305,7 +351,7 @@ __device__ __forceinline__ void interpolate(InterpShared<KMAX, Field16>& s, uint
                 acc.step(x1.w, x0.w, y1.w, y0.w);
             }
             uint32_t v = acc.value();
-            v = F::addmod(v, __shfl_xor(v, 1));
+            v = F::addmod(v, pair_swap(v));
             if (h == 0) plane_put(s.s_hi, s.s_lo, r, v);
         }
     }
@@ -325,7 +371,7 @@ __device__ __forceinline__ void interpolate(InterpShared<KMAX, Field16>& s, uint
                 plane_dot_window(acc, reinterpret_cast<const uint32_t*>(s.s_hi) + first, reinterpret_cast<const uint32_t*>(s.s_lo) + first,
                                  reinterpret_cast<const uint32_t*>(W1), reinterpret_cast<const uint32_t*>(W0), i + 1u + 4u * first, mine);
             uint32_t c = acc.value();
-            c = F::addmod(c, __shfl_xor(c, 1));
+            c = F::addmod(c, pair_swap(c));
             if (h == 0) coef_out[i] = F::addmod(c, plane_get(s.s_hi, s.s_lo, last));
         }
     }
