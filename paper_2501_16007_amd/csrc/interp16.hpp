@@ -15,7 +15,7 @@
 //     REVERSED order with four zero bytes on either side, so that the four bytes g_{t-i} .. g_{t-i-3}
 //     are consecutive in memory for every t and out-of-range terms read zeros; the window is not
 //     4-byte aligned in general: two aligned words and v_alignbyte_b32;
-//   * the baby-step table is kept transposed (BT[r0][j] = x_j^r0, rows padded against bank
+//   * the baby-step table, scaled by a_j = y_j / W'(x_j), is kept transposed (BT[r0][j] = a_j x_j^r0, rows padded against bank
 //     conflicts) so that S_r is a plain dot product over j of two contiguous planes;
 //   * c_i reads W forward at byte offset i + 1 + r (unaligned window again) against S.
 // The polynomial is unique, so the bytes are those of any exact method.
@@ -84,6 +84,13 @@ struct PlaneAcc {
 __device__ __forceinline__ uint32_t pair_swap(uint32_t v)
 {
     return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0xB1, 0xF, 0xF, true);   // quad_perm:[1,0,3,2]
+}
+
+// a DPP move inside the quad: QP = 0xA0 gives both lanes of a pair the even lane's value, 0xF5 the odd lane's
+template <int QP>
+__device__ __forceinline__ uint32_t quad_from(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, QP, 0xF, 0xF, true);
 }
 
 // bytes sh .. sh+3 of the eight bytes {hi, lo}
@@ -234,26 +241,26 @@ __device__ __forceinline__ void interpolate(InterpShared<KMAX, Field16>& s, uint
     {
         const uint32_t j = o;
         if (j < k16) {
+            // the two lanes of a point take eight powers each: lane h computes x^(8h) .. x^(8h+7)
             const uint32_t x = j < k ? (uint32_t)s.xs[j] : 0u;
-            uint32_t pw[kBaby];
-            uint32_t p = j < k ? 1u : 0u;
+            const uint32_t x2 = F::mulmod(x, x), x4 = F::mulmod(x2, x2), x8 = F::mulmod(x4, x4);
+            uint32_t q[8];
+            uint32_t p = j < k ? (h ? x8 : 1u) : 0u;
 #pragma unroll
-            for (uint32_t r0 = 0; r0 < kBaby; ++r0) {
-                pw[r0] = p;
+            for (uint32_t i = 0; i < 8u; ++i) {
+                q[i] = p;
                 p = F::mulmod(p, x);
             }
-            const uint32_t x16 = p;   // x^16 (0 for a padding lane)
-#pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                const uint32_t t0 = __builtin_amdgcn_perm(pw[4 * w + 1], pw[4 * w], 0x05010400u);   // a0 b0 a1 b1
-                const uint32_t t1 = __builtin_amdgcn_perm(pw[4 * w + 3], pw[4 * w + 2], 0x05010400u);
-                pw0[w] = __builtin_amdgcn_perm(t1, t0, 0x05040100u);
-                pw1[w] = __builtin_amdgcn_perm(t1, t0, 0x07060302u);
-            }
-            // transposed baby steps: this lane writes one plane
-            uint8_t* bt = h ? s.u.pw.bt_lo : s.u.pw.bt_hi;
-#pragma unroll
-            for (uint32_t r0 = 0; r0 < kBaby; ++r0) bt[r0 * Sh::BT_STRIDE + j] = (uint8_t)(h ? pw[r0] : pw[r0] >> 8);
+            const uint32_t x16 = quad_from<0xF5>(p);   // the odd lane ends on x^16 (0 for a padding lane)
+            const uint32_t ta = __builtin_amdgcn_perm(q[1], q[0], 0x05010400u);   // a0 b0 a1 b1
+            const uint32_t tb = __builtin_amdgcn_perm(q[3], q[2], 0x05010400u);
+            const uint32_t tc = __builtin_amdgcn_perm(q[5], q[4], 0x05010400u);
+            const uint32_t td = __builtin_amdgcn_perm(q[7], q[6], 0x05010400u);
+            const uint32_t lo_a = __builtin_amdgcn_perm(tb, ta, 0x05040100u), hi_a = __builtin_amdgcn_perm(tb, ta, 0x07060302u);
+            const uint32_t lo_b = __builtin_amdgcn_perm(td, tc, 0x05040100u), hi_b = __builtin_amdgcn_perm(td, tc, 0x07060302u);
+            // words 0, 1 come from the even lane of the pair, words 2, 3 from the odd one
+            pw0[0] = quad_from<0xA0>(lo_a); pw0[1] = quad_from<0xA0>(lo_b); pw0[2] = quad_from<0xF5>(lo_a); pw0[3] = quad_from<0xF5>(lo_b);
+            pw1[0] = quad_from<0xA0>(hi_a); pw1[1] = quad_from<0xA0>(hi_b); pw1[2] = quad_from<0xF5>(hi_a); pw1[3] = quad_from<0xF5>(hi_b);
             // giant steps 1, x^16, x^32, ..: the two lanes take alternate ones
             const uint32_t x32 = F::mulmod(x16, x16);
             uint32_t g = h ? x16 : (j < k ? 1u : 0u);
@@ -313,9 +320,9 @@ __device__ __forceinline__ void interpolate(InterpShared<KMAX, Field16>& s, uint
     // point take eight powers each, the second one starting from a_j x_j^8
     {
         const uint32_t j = o;
-        if (j < k) {
-            const uint32_t a = s.dj[j];
-            const uint32_t x = s.xs[j];
+        if (j < k16) {   // the lanes of the padding points write the zeros the sums read there
+            const uint32_t a = j < k ? (uint32_t)s.dj[j] : 0u;
+            const uint32_t x = j < k ? (uint32_t)s.xs[j] : 0u;
             const uint32_t x8 = ((pw1[2] & 0xFFu) << 8) | (pw0[2] & 0xFFu);
             uint32_t p = h ? F::mulmod(a, x8) : a;
 #pragma unroll
