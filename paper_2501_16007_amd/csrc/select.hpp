@@ -569,16 +569,21 @@ struct NoSeed {
 // Requires k <= seeds + ELEMS*(v1 - v0), k <= CAP/4, ELEMS*v1 < 2^32.  All threads of the workgroup
 // call it; it ends with a barrier.  Returns k and the threshold the selection ended with:
 // (0, 0xFFFFFFFF) as long as nothing had to be pruned, else the k-th element.
-template <int THREADS, int U, int CAP, int QCAP, typename Fmt, typename Seed>
+template <int THREADS, int U, int DEPTH = 2, int CAP, int QCAP, typename Fmt, typename Seed>
 __device__ __forceinline__ SelectStart select_topk_from(const u32x4* __restrict__ src, uint32_t v0, uint32_t v1,
                                                         SelectShared<THREADS, CAP, QCAP, Fmt>& s, const Seed& seeder)
 {
+    static_assert(DEPTH == 2 || DEPTH == 3, "two or three rounds of loads in registers");
     constexpr uint32_t ROUND = THREADS * U;
     const uint32_t tid = threadIdx.x;
     TOPLOC_TICK_BEGIN(boot);
-    u32x4 even[U], odd[U];  // two rounds in registers: one is examined while the other one's loads fly
+    // DEPTH rounds in registers: one is examined while the loads of the others fly.  Three cost 16 more
+    // registers than two (one workgroup per CU less): worth it only for a launch that fits the chip in one
+    // generation, where nobody else's streaming covers a workgroup's pauses.
+    u32x4 even[U], odd[U], third[DEPTH == 3 ? U : 1];
     load_round<THREADS, U>(even, src, v0, v0, v1);
     load_round<THREADS, U>(odd, src, v0, v0 + ROUND, v1);   // in flight while the first threshold is found
+    if (DEPTH == 3) load_round<THREADS, U>(reinterpret_cast<u32x4(&)[U]>(third), src, v0, v0 + 2u * ROUND, v1);
     const SelectStart start = seeder.seed(s);
     const uint32_t k = start.k;
     const uint32_t n_seed = start.n;
@@ -628,15 +633,22 @@ __device__ __forceinline__ SelectStart select_topk_from(const u32x4* __restrict_
     TOPLOC_TICK_END(boot, 0);
     TOPLOC_TICK_BEGIN(stream);
     uint32_t base = v0;  // v1 - v0 >= 1
+    constexpr uint32_t AHEAD = (DEPTH - 1) * ROUND;   // the buffer just examined takes the round this far ahead
     while (true) {
         examine_round<THREADS, U>(even, base, v1, k, s, t, round, epoch);
         base += ROUND;
         if (base >= v1) break;
-        load_round<THREADS, U>(even, src, v0, base + ROUND, v1);
+        load_round<THREADS, U>(even, src, v0, base + AHEAD, v1);
         examine_round<THREADS, U>(odd, base, v1, k, s, t, round, epoch);
         base += ROUND;
         if (base >= v1) break;
-        load_round<THREADS, U>(odd, src, v0, base + ROUND, v1);
+        load_round<THREADS, U>(odd, src, v0, base + AHEAD, v1);
+        if (DEPTH == 3) {
+            examine_round<THREADS, U>(reinterpret_cast<const u32x4(&)[U]>(third), base, v1, k, s, t, round, epoch);
+            base += ROUND;
+            if (base >= v1) break;
+            load_round<THREADS, U>(reinterpret_cast<u32x4(&)[U]>(third), src, v0, base + AHEAD, v1);
+        }
     }
     __syncthreads();
     TOPLOC_TICK_END(stream, 1);
@@ -647,11 +659,11 @@ __device__ __forceinline__ SelectStart select_topk_from(const u32x4* __restrict_
     return SelectStart{k, t, k};
 }
 
-template <int THREADS, int U, int CAP, int QCAP, typename Fmt>
+template <int THREADS, int U, int DEPTH = 2, int CAP, int QCAP, typename Fmt>
 __device__ __forceinline__ void select_topk(const u32x4* __restrict__ src, uint32_t v0, uint32_t v1, uint32_t k,
                                             SelectShared<THREADS, CAP, QCAP, Fmt>& s)
 {
-    (void)select_topk_from<THREADS, U>(src, v0, v1, s, NoSeed{k});
+    (void)select_topk_from<THREADS, U, DEPTH>(src, v0, v1, s, NoSeed{k});
 }
 
 // Top-k of candidate lists: `n` (index, pattern) pairs in global memory, entries whose

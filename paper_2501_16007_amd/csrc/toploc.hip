@@ -55,6 +55,12 @@ constexpr int kCapWide = 16384;           // candidate buffer of the selection a
                                           // one workgroup per compute unit; an aid for statistics, not a fast path)
 // The larger candidate buffer (k > 128) costs registers in the prune and the ordering: one wave per SIMD less.
 constexpr int waves_for(int cap) { return cap > kCapSmall ? TOPLOC_MIN_WAVES - 1 : TOPLOC_MIN_WAVES; }
+// A fused launch of at most this many chunks fits the chip in one generation even at 5 workgroups per CU (256 CUs):
+// it runs the kernels that keep three rounds of loads in flight (95 VGPRs, 5 waves per SIMD).
+#ifndef TOPLOC_ONE_GENERATION
+#define TOPLOC_ONE_GENERATION 1280
+#endif
+constexpr uint64_t kOneGeneration = TOPLOC_ONE_GENERATION;
 static_assert(kCapLarge >= 4 * (int)TOPLOC_MAX_K && kCapSmall >= 4 * 128 && kCapWide >= 4 * (int)TOPLOC_MAX_K_TOPK,
               "soft limit CAP/2 must leave room above k");
 static_assert(kCapWide <= 65536, "prune keeps slot numbers in 16 bits");
@@ -162,7 +168,7 @@ __global__ __launch_bounds__(kThreads, WAVES) void select_kernel(const u32x4* __
 {
     __shared__ SelectShared<kThreads, CAP, kQcap> s;
     const uint64_t chunk = chunk_of_block();
-    select_topk<kThreads, kLoads, CAP, kQcap>(hidden + chunk * nvec, 0u, nvec, k, s);
+    select_topk<kThreads, kLoads, 2, CAP, kQcap>(hidden + chunk * nvec, 0u, nvec, k, s);
     order_topk(s, k);
     for (uint32_t t = threadIdx.x; t < k; t += kThreads) {
         out_idx[chunk * k + t] = s.cand_idx[t];
@@ -178,7 +184,7 @@ __global__ __launch_bounds__(kThreads) void select_stats_kernel(const u32x4* __r
 {
     __shared__ SelectShared<kThreads, CAP, kQcap, Bf16FmtStats> s;
     const uint64_t chunk = blockIdx.x;
-    select_topk<kThreads, kLoads, CAP, kQcap>(hidden + chunk * nvec, 0u, nvec, k, s);
+    select_topk<kThreads, kLoads, 2, CAP, kQcap>(hidden + chunk * nvec, 0u, nvec, k, s);
     if (threadIdx.x < 4) out_stats[chunk * 4 + threadIdx.x] = s.stats[threadIdx.x];
 }
 
@@ -187,7 +193,7 @@ __global__ __launch_bounds__(kThreads) void select_stats_kernel(const u32x4* __r
 // then the same workgroup turns its k pairs into the proof out of LDS (the selection's
 // buffers are dead by then and are reused).
 // ---------------------------------------------------------------------------
-template <int KMAX, int CAP, typename F = Field16, typename Fmt = Bf16Fmt, int U = kLoads, int WAVES = waves_for(CAP)>
+template <int KMAX, int CAP, typename F = Field16, typename Fmt = Bf16Fmt, int U = kLoads, int WAVES = waves_for(CAP), int DEPTH = 2>
 __global__ __launch_bounds__(kThreads, WAVES) void build_kernel(const u32x4* __restrict__ hidden, uint32_t nvec,
                                                                            uint32_t k, uint8_t* __restrict__ proofs,
                                                                            uint8_t* __restrict__ status,
@@ -201,7 +207,7 @@ __global__ __launch_bounds__(kThreads, WAVES) void build_kernel(const u32x4* __r
     __shared__ uint32_t coef[KMAX];
     const uint32_t tid = threadIdx.x;
     const uint64_t chunk = chunk_of_block();
-    select_topk<kThreads, U>(hidden + chunk * nvec, 0u, nvec, k, sh.sel);
+    select_topk<kThreads, U, DEPTH>(hidden + chunk * nvec, 0u, nvec, k, sh.sel);
     if (out_idx) {  // uniform: the caller wants the ordered indices
         order_topk(sh.sel, k);
         if (tid < k) out_idx[chunk * k + tid] = sh.sel.cand_idx[tid];
@@ -240,7 +246,7 @@ struct DecodeFirst {
 
 // F is the proof's field, Fmt the format of the recomputed activations (Section 5.7
 // validates across the two precisions).
-template <int KMAX, int CAP, typename F = Field16, typename Fmt = Bf16Fmt, int U = kLoads, int WAVES = waves_for(CAP)>
+template <int KMAX, int CAP, typename F = Field16, typename Fmt = Bf16Fmt, int U = kLoads, int WAVES = waves_for(CAP), int DEPTH = 2>
 __global__ __launch_bounds__(kThreads, WAVES) void verify_kernel(const u32x4* __restrict__ hidden, uint32_t nvec,
                                                                             uint32_t k, const uint8_t* __restrict__ proofs,
                                                                             toploc_thresholds thr,
@@ -256,7 +262,7 @@ __global__ __launch_bounds__(kThreads, WAVES) void verify_kernel(const u32x4* __
     bool ok = true;
     const ProofWords<kThreads, KMAX> words = verify_load_proof<kThreads, F, KMAX>(proof, k);
     const DecodeFirst<F, KMAX, Fmt::ELEMS == 4> first{vs, words, k, results + chunk, &ok};
-    (void)select_topk_from<kThreads, U>(hidden + chunk * nvec, 0u, nvec, s, first);  // order is irrelevant here
+    (void)select_topk_from<kThreads, U, DEPTH>(hidden + chunk * nvec, 0u, nvec, s, first);  // order is irrelevant here
     if (!ok) return;  // uniform
     TOPLOC_TICK_BEGIN(tail);
     verify_tail<kThreads, F, Fmt>(vs, s.cand_idx, s.cand_bits, k, thr, results + chunk);
@@ -267,8 +273,8 @@ __global__ __launch_bounds__(kThreads, WAVES) void verify_kernel(const u32x4* __
 // Split path, first launch: top-k of one part.  Writes k candidate slots per part,
 // the unused ones (part shorter than k values) padded with index 0xFFFFFFFF.
 // ---------------------------------------------------------------------------
-template <int CAP, typename Fmt = Bf16Fmt>
-__global__ __launch_bounds__(kThreads, waves_for(CAP)) void part_kernel(const u32x4* __restrict__ hidden, Layout lay,
+template <int CAP, typename Fmt = Bf16Fmt, int DEPTH = 2>
+__global__ __launch_bounds__(kThreads, DEPTH == 3 ? TOPLOC_MIN_WAVES - 1 : waves_for(CAP)) void part_kernel(const u32x4* __restrict__ hidden, Layout lay,
                                                                           uint32_t k, uint32_t* __restrict__ c_idx,
                                                                           typename Fmt::bits_t* __restrict__ c_bits)
 {
@@ -293,7 +299,7 @@ __global__ __launch_bounds__(kThreads, waves_for(CAP)) void part_kernel(const u3
     }
     const uint32_t have = (v1 - v0) * (uint32_t)Fmt::ELEMS;
     const uint32_t k_eff = have < k ? have : k;
-    if (k_eff) select_topk<kThreads, kLoads>(src + v0, v0, v1, k_eff, s);
+    if (k_eff) select_topk<kThreads, kLoads, DEPTH>(src + v0, v0, v1, k_eff, s);
     for (uint32_t t = tid; t < k; t += kThreads) {
         c_idx[slot * k + t] = t < k_eff ? s.cand_idx[t] : 0xFFFFFFFFu;
         c_bits[slot * k + t] = t < k_eff ? s.cand_bits[t] : (typename Fmt::bits_t)0;
@@ -471,7 +477,7 @@ __global__ __launch_bounds__(kThreads, waves_for(CAP)) void stream_append_kernel
     bits_t* g_bits = reinterpret_cast<bits_t*>(st + sizeof(StreamHeader) + stream_idx_bytes(k));
     const u32x4* row = step_vec + (size_t)blockIdx.x * hvec;
     const uint32_t rows = hdr->rows;
-    const SelectStart end = select_topk_from<kThreads, kLoads, CAP, kQcap>(
+    const SelectStart end = select_topk_from<kThreads, kLoads, 2, CAP, kQcap>(
         row, v0, v0 + hvec, s, StreamSeed<CAP, Fmt>{hdr, g_idx, g_bits, k, hvec * (uint32_t)Fmt::ELEMS});
     for (uint32_t i = tid; i < end.k; i += kThreads) {
         g_idx[i] = s.cand_idx[i];
@@ -647,12 +653,16 @@ static void launch_part(hipStream_t st, const void* d_hidden, const Layout& lay,
         return;
     }
     uint16_t* c_bits = (uint16_t*)c_bits_any;
-    if (k <= 128)
+    const bool one_generation = slots <= kOneGeneration;   // every part resident at once: three rounds of loads in flight each
+    if (k <= 128 && one_generation)
+        hipLaunchKernelGGL((part_kernel<kCapSmall, Bf16Fmt, 3>), dim3((uint32_t)slots), dim3(kThreads), 0, st, (const u32x4*)d_hidden,
+                           lay, k, c_idx, c_bits);
+    else if (k <= 128)
         hipLaunchKernelGGL((part_kernel<kCapSmall>), dim3((uint32_t)slots), dim3(kThreads), 0, st, (const u32x4*)d_hidden, lay,
                            k, c_idx, c_bits);
-    else
-        hipLaunchKernelGGL((part_kernel<kCapLarge>), dim3((uint32_t)slots), dim3(kThreads), 0, st, (const u32x4*)d_hidden, lay,
-                           k, c_idx, c_bits);
+    else   // the wide candidate buffer allows 5 workgroups per CU anyway: the third round of loads is free
+        hipLaunchKernelGGL((part_kernel<kCapLarge, Bf16Fmt, 3>), dim3((uint32_t)slots), dim3(kThreads), 0, st, (const u32x4*)d_hidden,
+                           lay, k, c_idx, c_bits);
 }
 
 static void launch_build_merge(hipStream_t st, const Layout& lay, uint64_t units, uint32_t k, const uint32_t* c_idx,
@@ -833,6 +843,9 @@ static int build_fixed(const FixedPlan& f, const void* d_hidden, uint64_t n_chun
         if (dtype == TOPLOC_DTYPE_F32)
             hipLaunchKernelGGL((build_kernel<128, kCapSmall, Field32, F32Fmt>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
                                (const u32x4*)d_hidden, nvec, k, d_proofs, d_status, d_topk_idx_opt);
+        else if (n_chunks <= kOneGeneration)   // every workgroup resident at once: three rounds of loads in flight each
+            hipLaunchKernelGGL((build_kernel<128, kCapSmall, Field16, Bf16Fmt, kLoads, TOPLOC_MIN_WAVES - 1, 3>), dim3((uint32_t)n_chunks),
+                               dim3(kThreads), 0, st, (const u32x4*)d_hidden_bf16, nvec, k, d_proofs, d_status, d_topk_idx_opt);
         else
             hipLaunchKernelGGL((build_kernel<128, kCapSmall>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
                                (const u32x4*)d_hidden_bf16, nvec, k, d_proofs, d_status, d_topk_idx_opt);
@@ -926,12 +939,15 @@ int toploc_verify_proofs(const void* d_hidden_bf16, uint64_t n_chunks, const top
     const bool split = f.parts > 1 && d_workspace && workspace_bytes >= cand_bytes(slots, k) && slots < (1ull << 31);
     if (!split) {  // one launch; a missing workspace only costs speed on small batches
         ProfScope ps(TOPLOC_KERNEL_VERIFY, st);
-        if (k <= 128)
+        if (k <= 128 && n_chunks <= kOneGeneration)
+            hipLaunchKernelGGL((verify_kernel<128, kCapSmall, Field16, Bf16Fmt, kLoads, TOPLOC_MIN_WAVES - 1, 3>), dim3((uint32_t)n_chunks),
+                               dim3(kThreads), 0, st, (const u32x4*)d_hidden_bf16, nvec, k, d_proofs, *thresholds, d_results);
+        else if (k <= 128)
             hipLaunchKernelGGL((verify_kernel<128, kCapSmall>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
                                (const u32x4*)d_hidden_bf16, nvec, k, d_proofs, *thresholds, d_results);
-        else
-            hipLaunchKernelGGL((verify_kernel<512, kCapLarge>), dim3((uint32_t)n_chunks), dim3(kThreads), 0, st,
-                               (const u32x4*)d_hidden_bf16, nvec, k, d_proofs, *thresholds, d_results);
+        else   // 5 workgroups per CU either way (LDS): the third round of loads is free
+            hipLaunchKernelGGL((verify_kernel<512, kCapLarge, Field16, Bf16Fmt, kLoads, TOPLOC_MIN_WAVES - 1, 3>), dim3((uint32_t)n_chunks),
+                               dim3(kThreads), 0, st, (const u32x4*)d_hidden_bf16, nvec, k, d_proofs, *thresholds, d_results);
         return hip_ok(hipGetLastError()) ? TOPLOC_OK : TOPLOC_EHIP;
     }
     Layout lay = {nullptr, nullptr, 0, 0, 0, nvec, f.parts, f.part_vecs};
