@@ -42,10 +42,9 @@
 namespace toploc {
 
 // prune: up to this many entries of the k-th magnitude are ranked against each other directly
+// (E^2 / THREADS steps); more of them (tie-heavy data: all equal, a handful of distinct values)
+// go through a radix descent over their indices
 constexpr int kRankDirect = 256;
-// ... and always in the kernels whose candidate buffer is no larger than this: they run at their
-// register limit, the ranking then costs at most CAP^2 / THREADS steps, on tie-heavy data only
-constexpr int kRankDirectCap = 2048;
 
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -129,6 +128,9 @@ enum { kStatDrains = 0, kStatPrunes = 1, kStatQueued = 2, kStatAppended = 3 };
 
 __device__ __forceinline__ uint32_t lane_id() { return __lane_id(); }
 
+// A value every lane of the wave read from the same LDS word: keep it in a scalar register.
+__device__ __forceinline__ uint32_t uniform(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
+
 // Inclusive prefix sum over the 64 lanes of a wave with DPP adds: four shifts inside the
 // rows of 16 lanes, then lane 15 of rows 0 and 2 into rows 1 and 3, then lane 31 into rows 2
 // and 3.  Lanes without a source add 0.  No LDS round trip, unlike the shuffle form.
@@ -193,8 +195,7 @@ __device__ __forceinline__ bool before(int32_t mag, uint32_t idx, const Threshol
 // Prune, tie-heavy data (all equal, a handful of distinct values): the need-th smallest index among
 // the E entries listed in eq_slot becomes the threshold index.  Ranking every entry against every other
 // one would cost E^2 / THREADS steps; this is a radix descent over the complemented index instead (the
-// need-th smallest index is the need-th largest complement), 8 bits per level.  Used by the selection
-// with the wide candidate buffer only (see kRankDirectCap).  All threads call.
+// need-th smallest index is the need-th largest complement), 8 bits per level.  All threads call.
 template <int THREADS, int CAP, int QCAP, typename Fmt>
 __device__ __forceinline__ void rank_by_radix(SelectShared<THREADS, CAP, QCAP, Fmt>& s, uint32_t E, uint32_t need,
                                            uint32_t new_tm)
@@ -217,8 +218,8 @@ __device__ __forceinline__ void rank_by_radix(SelectShared<THREADS, CAP, QCAP, F
             if (tid == 0) { s.found_bin = d; s.found_above = a; }
         }
         __syncthreads();
-        pre = (pre << 8) | s.found_bin;
-        abv = s.found_above;
+        pre = (pre << 8) | uniform(s.found_bin);
+        abv = uniform(s.found_above);
     }
     if (tid == 0) { s.ti = ~pre; s.tm = (int32_t)new_tm; }
 }
@@ -237,7 +238,7 @@ __device__ TOPLOC_PRUNE_ATTR uint32_t prune_if_above(SelectShared<THREADS, CAP, 
 {
     const uint32_t tid = threadIdx.x;
     __syncthreads();  // appends are visible
-    const uint32_t M = s.count;
+    const uint32_t M = uniform(s.count);
     if (M <= limit || M > (uint32_t)CAP) {  // uniform decision
         if (Fmt::STATS && tid == 0 && M <= (uint32_t)CAP) s.stats[kStatAppended] += M - s.count_base;
         if (tid == 0 && M <= (uint32_t)CAP) s.count_base = M;
@@ -266,8 +267,8 @@ __device__ TOPLOC_PRUNE_ATTR uint32_t prune_if_above(SelectShared<THREADS, CAP, 
             if (tid == 0) { s.found_bin = d; s.found_above = a; }
         }
         __syncthreads();
-        const uint32_t digit = s.found_bin;
-        above = s.found_above;
+        const uint32_t digit = uniform(s.found_bin);
+        above = uniform(s.found_above);
         prefix = (prefix << w) | digit;
     }
     const uint32_t new_tm = prefix;
@@ -279,10 +280,10 @@ __device__ TOPLOC_PRUNE_ATTR uint32_t prune_if_above(SelectShared<THREADS, CAP, 
             s.eq_slot[q] = (uint16_t)slot;
         }
     __syncthreads();
-    const uint32_t E = s.eq_count;
+    const uint32_t E = uniform(s.eq_count);
     // the need-th smallest index among the E equal-magnitude entries is the new threshold element
     // uniform; the usual case: a few dozen entries share the k-th magnitude
-    if (CAP <= kRankDirectCap || E <= (uint32_t)kRankDirect) {
+    if (E <= (uint32_t)kRankDirect) {
         for (uint32_t q = tid; q < E; q += THREADS) {
             const uint32_t mine = s.cand_idx[s.eq_slot[q]];
             uint32_t rank = 0;
@@ -293,8 +294,8 @@ __device__ TOPLOC_PRUNE_ATTR uint32_t prune_if_above(SelectShared<THREADS, CAP, 
         rank_by_radix(s, E, need, new_tm);
     }
     __syncthreads();
-    t.tm = s.tm;
-    t.ti = s.ti;
+    t.tm = (int32_t)uniform((uint32_t)s.tm);
+    t.ti = uniform(s.ti);
     // Compact in place: exactly k entries survive.  Survivors already below slot k stay;
     // every survivor at or above slot k moves into a slot below k that lost its entry.
 #pragma unroll 1
@@ -367,7 +368,7 @@ __device__ TOPLOC_DRAIN_ATTR bool drain(SelectShared<THREADS, CAP, QCAP, Fmt>& s
 {
     constexpr uint32_t BATCH = (CAP / 16 < THREADS / 2) ? CAP / 16 : THREADS / 2;  // vectors: ELEMS * BATCH <= CAP / 2
     const uint32_t tid = threadIdx.x;
-    const uint32_t raw = s.qcount[epoch & 1u];
+    const uint32_t raw = uniform(s.qcount[epoch & 1u]);
     const uint32_t nq = raw < (uint32_t)QCAP ? raw : (uint32_t)QCAP;
     if (tid == 0) s.qcount[(epoch + 1u) & 1u] = 0;  // last read one drain ago; visible after the barrier below
     if (Fmt::STATS && tid == 0) { s.stats[kStatDrains] += 1; s.stats[kStatQueued] += nq; }
@@ -504,7 +505,7 @@ __device__ __forceinline__ void examine_round(const u32x4 (&buf)[U], uint32_t b,
     }
     while (true) {
         __syncthreads();
-        const uint32_t f = s.flag[round % 3u];
+        const uint32_t f = uniform(s.flag[round % 3u]);
         if (tid == 0) s.flag[(round + 2u) % 3u] = 0;  // the previous round's flag: read by all before this barrier
         ++round;
         if (!f) break;  // no slot at or past the soft limit was handed out: nothing is pending either
