@@ -32,7 +32,7 @@ def main():
                          "config5 (online decode-step path) print their own report line; config3_f32 is the 70B "
                          "shape with fp32 activations (64 sequences, the same 8 GiB) through the fp32 calls; segments is "
                          "a serving-style batch of whole-prompt proofs and ragged decode chunks through the segment calls")
-    ap.add_argument("--law", default="outliers", choices=["outliers", "gaussian", "heavy_tail", "ascending"],
+    ap.add_argument("--law", default="outliers", choices=["outliers", "gaussian", "heavy_tail", "ascending", "all_equal", "few_values"],
                     help="value law of the synthetic activations (config3 / config2 only): outliers is the workload's "
                          "recipe and the benchmark line; the others show how the selection's cost depends on the input")
     ap.add_argument("--k", type=int, default=128)

@@ -141,16 +141,18 @@ def config3(device="cpu", n_seq=128, n_tok=4096):
     return activations(n_seq, n_tok, 8192, BASE_SEED + 3, n_outlier=16, device=device)
 
 
-LAWS = ("outliers", "gaussian", "heavy_tail", "ascending")
+LAWS = ("outliers", "gaussian", "heavy_tail", "ascending", "all_equal", "few_values")
 
 
 def law_activations(law, n_seq, n_tok, hidden, seed, n_outlier, device="cpu"):
-    """The same shape under four value laws, to show how much the selection's cost depends on the input:
+    """The same shape under six value laws, to show how much the selection's cost depends on the input:
     outliers    the recipe of `activations` (what the workloads use)
     gaussian    N(0,1) everywhere, no outlier channels: the top-k are spread over all channels
     heavy_tail  N(0,1) * exp(N(0,1)) per element: large values everywhere, the threshold keeps rising
     ascending   inside every 32-token chunk the magnitudes never decrease with the flat index (random signs):
-                every value read is larger than all before it, the worst case of a streaming selection"""
+                every value read is larger than all before it, the worst case of a streaming selection
+    all_equal   one magnitude per sequence (zero padding is the everyday case), random signs: ranking is by index alone
+    few_values  seven patterns drawn uniformly (five magnitudes, zero among them): thousands share the k-th magnitude"""
     if law == "outliers":
         return activations(n_seq, n_tok, hidden, seed, n_outlier=n_outlier, device=device)
     if law == "gaussian":
@@ -172,6 +174,17 @@ def law_activations(law, n_seq, n_tok, hidden, seed, n_outlier, device="cpu"):
             sign = torch.randint(0, 2, (n_tok // CHUNK_TOKENS, n), generator=g, device=device, dtype=torch.int32) << 15
             bits = (ramp[None, :] | sign).to(torch.uint16).view(torch.bfloat16)
             out[s] = bits.reshape(n_tok, hidden)
+        return out
+    if law == "all_equal":
+        for s in range(n_seq):
+            sign = torch.randint(0, 2, (n_tok, hidden), generator=g, device=device, dtype=torch.int32) << 15
+            out[s] = ((0x3F00 + s % 97) | sign).to(torch.uint16).view(torch.bfloat16)
+        return out
+    if law == "few_values":
+        table = torch.tensor([0x3F80, 0xBF80, 0x4000, 0xC040, 0x0000, 0x8000, 0x3E00], device=device, dtype=torch.int32)
+        for s in range(n_seq):
+            pick = torch.randint(0, table.numel(), (n_tok, hidden), generator=g, device=device)
+            out[s] = table[pick].to(torch.uint16).view(torch.bfloat16)
         return out
     raise ValueError("unknown law %r" % (law,))
 

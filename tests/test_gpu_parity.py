@@ -89,6 +89,16 @@ def test_parity_shapes(hidden, tokens, k, n_chunks):
     assert (res["accept"] == 1).all()
 
 
+@pytest.mark.parametrize("law", synth.LAWS)
+def test_parity_every_input_law(law):
+    """the value laws of `bench.py --law` (Gaussian, heavy tail, ascending, one magnitude, seven patterns) at a size
+    the oracle does at once: the selection takes different paths on them, the bytes must not"""
+    x = synth.law_activations(law, 3, 64, 1024, 4242, 8, device=DEV)
+    chunks = synth.as_chunks(x)
+    for k in (128, 512):
+        check_chunks(chunks, k, what="law %s" % law)
+
+
 # ---------------------------------------------------------------------------
 # degenerate inputs
 # ---------------------------------------------------------------------------
