@@ -25,6 +25,7 @@
 
 #include "gf65497.hpp"
 #include "interp.hpp"
+#include "planes.hpp"
 
 namespace toploc {
 
@@ -52,62 +53,6 @@ struct InterpShared<KMAX, Field16> {
     } u;
     uint32_t collide[2];
 };
-
-typedef uint32_t u32v4 __attribute__((ext_vector_type(4)));
-
-// three accumulators of a sum of products of byte-plane vectors
-struct PlaneAcc {
-    uint32_t hh, m, ll;
-    __device__ __forceinline__ PlaneAcc() : hh(0), m(0), ll(0) {}
-    // four terms: a and b each as a word of high bytes and a word of low bytes
-    __device__ __forceinline__ void step(uint32_t a1, uint32_t a0, uint32_t b1, uint32_t b0)
-    {
-        hh = __builtin_amdgcn_udot4(a1, b1, hh, false);
-        m = __builtin_amdgcn_udot4(a1, b0, m, false);
-        m = __builtin_amdgcn_udot4(a0, b1, m, false);
-        ll = __builtin_amdgcn_udot4(a0, b0, ll, false);
-    }
-    // (hh 2^16 + m 2^8 + ll) mod p for at most 128 steps: hh, ll < 2^25, m < 2^26
-    __device__ __forceinline__ uint32_t value() const
-    {
-        const uint32_t h39 = (hh << 5) + (hh << 3) - hh;          // 39 hh < 2^31
-        return reduce32(h39 + (reduce32(m) << 8) + ll);           // < 2^31 + 2^24 + 2^25
-    }
-    // the same for at most 28 steps: hh, ll < 28 * 2^18 < 2^23, m < 2^24, so 39 hh + 2^8 m + ll < 2^32 as it is
-    __device__ __forceinline__ uint32_t value_short() const
-    {
-        return reduce32(mul24(hh, kFold16) + (m << 8) + ll);
-    }
-};
-
-// the value the other lane of the pair (lane ^ 1) holds: a DPP move inside the quad, no LDS round trip
-__device__ __forceinline__ uint32_t pair_swap(uint32_t v)
-{
-    return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0xB1, 0xF, 0xF, true);   // quad_perm:[1,0,3,2]
-}
-
-// a DPP move inside the quad: QP = 0xA0 gives both lanes of a pair the even lane's value, 0xF5 the odd lane's
-template <int QP>
-__device__ __forceinline__ uint32_t quad_from(uint32_t v)
-{
-    return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, QP, 0xF, 0xF, true);
-}
-
-// bytes sh .. sh+3 of the eight bytes {hi, lo}
-__device__ __forceinline__ uint32_t byte_window(uint32_t hi, uint32_t lo, uint32_t sh)
-{
-    return __builtin_amdgcn_alignbyte(hi, lo, sh);
-}
-
-__device__ __forceinline__ uint32_t plane_get(const uint8_t* hi, const uint8_t* lo, uint32_t j)
-{
-    return ((uint32_t)hi[j] << 8) | (uint32_t)lo[j];
-}
-__device__ __forceinline__ void plane_put(uint8_t* hi, uint8_t* lo, uint32_t j, uint32_t v)
-{
-    hi[j] = (uint8_t)(v >> 8);
-    lo[j] = (uint8_t)v;
-}
 
 // Sum over `n` steps of four terms of a forward plane pair (aligned, from word a_w on) times a window
 // that starts at byte position `p` of another plane pair and moves forward.

@@ -19,6 +19,7 @@
 #include "gf32.hpp"
 #include "gf65497.hpp"
 #include "interp.hpp"
+#include "planes.hpp"
 #include "select.hpp"
 
 #ifndef TOPLOC_HORNER_LANES
@@ -29,7 +30,8 @@ namespace toploc {
 
 template <int KMAX, bool WIDE = false>
 struct VerifyShared {
-    uint32_t coef[KMAX];                 // c_0..c_{k-1}
+    uint32_t coef[KMAX];                 // c_0..c_{k-1}  (proofs over GF(2^32 - 5); unused with GF(65497))
+    alignas(16) uint8_t c_hi[KMAX], c_lo[KMAX];   // proofs over GF(65497): the coefficients as byte planes, zeros from k to the next multiple of 16
     uint32_t hist_d[128];                // bf16 validator: err_m as a histogram of |m_p - m_v| in [0, 127]
     uint32_t diffs[WIDE ? KMAX : 1];     // fp32 validator: err_m as a list
     uint32_t err_e, mant_sum, bad, m, n_match, median;
@@ -73,12 +75,17 @@ __device__ __forceinline__ bool verify_decode(VerifyShared<KMAX, WIDE>& vs, cons
     for (uint32_t b = tid; b < 128; b += THREADS) vs.hist_d[b] = 0;
     __syncthreads();
     const uint32_t m = w.mf ? w.mf : kModHigh;   // the 2-byte field stores m mod 65536
+    static_assert(KMAX % 16 == 0, "the coefficient planes are read 16 bytes at a time");
 #pragma unroll
     for (int i = 0; i < ProofWords<THREADS, KMAX>::PER_LANE; ++i) {
         const uint32_t j = tid + i * THREADS;
         if (j < k) {
-            vs.coef[j] = w.c[i];
+            if (F::WORDS == 1) { vs.c_hi[j] = (uint8_t)(w.c[i] >> 8); vs.c_lo[j] = (uint8_t)w.c[i]; }
+            else vs.coef[j] = w.c[i];
             if (w.c[i] >= F::P) vs.bad = 1u;
+        } else if (F::WORDS == 1 && j < ((k + 15u) & ~15u)) {
+            vs.c_hi[j] = 0;
+            vs.c_lo[j] = 0;
         }
     }
     if (tid == 0) {
@@ -125,14 +132,41 @@ __device__ __forceinline__ void verify_tail(VerifyShared<KMAX, WIDE>& vs, const 
     static_assert(WIDE == (Fmt::ELEMS == 4), "an fp32 validator keeps err_m as a list");
     const uint32_t tid = threadIdx.x;
     const uint32_t m = vs.m;
-    // With lanes to spare two lanes share a point: P(x) = E(x^2) + x O(x^2), the even and the odd
-    // coefficients as two Horner chains of half the length (the chain is the tail's critical path).
+    // With lanes to spare two lanes share a point: P(x) = E(y) + x' O(y) with the terms split by parity, two
+    // chains of half the length (the chain is the tail's critical path).
     constexpr int L = (2 * KMAX <= THREADS && TOPLOC_HORNER_LANES == 2) ? 2 : 1;
     const uint32_t h = (L == 2) ? (tid & 1u) : 0u;
     for (uint32_t j = tid / L; j < k; j += THREADS / L) {
         const uint32_t x = F::from_residue(cand_idx[j] % m);
         uint32_t acc;
-        if (L == 2) {
+        if (F::WORDS == 1) {
+            // GF(65497): P(x) = sum_r1 X^r1 I_r1(x), X = x^16, I_r1(x) = sum_r0 c_(16 r1 + r0) x^r0 a 16-term sum of
+            // products on the packed dot-product instruction (coefficients and powers as byte planes), Horner over r1
+            // in X (two lanes: even and odd r1 in X^2): k/16 dependent steps instead of k
+            uint32_t pw1[4], pw0[4];
+            const uint32_t X = plane_powers16(x, pw1, pw0);
+            const uint32_t step = (L == 2) ? mulmod(X, X) : X;
+            const uint32_t n_giant = (k + 15u) >> 4;
+            const int terms = (int)((n_giant - h + (uint32_t)L - 1u) / (uint32_t)L);   // r1 = h, h + L, ..
+            acc = 0;
+#pragma unroll 2
+            for (int i = terms - 1; i >= 0; --i) {
+                const uint32_t r1 = (uint32_t)i * (uint32_t)L + h;
+                const u32v4 w1 = *reinterpret_cast<const u32v4*>(&vs.c_hi[r1 * 16u]);   // the same 16 coefficients for every lane
+                const u32v4 w0 = *reinterpret_cast<const u32v4*>(&vs.c_lo[r1 * 16u]);
+                PlaneAcc inner;
+                inner.step(w1.x, w0.x, pw1[0], pw0[0]);
+                inner.step(w1.y, w0.y, pw1[1], pw0[1]);
+                inner.step(w1.z, w0.z, pw1[2], pw0[2]);
+                inner.step(w1.w, w0.w, pw1[3], pw0[3]);
+                acc = muladdmod(acc, step, inner.value_short());
+            }
+            if (L == 2) {
+                const uint32_t odd = pair_swap(acc);          // the partner's chain
+                acc = muladdmod(odd, X, acc);                 // meaningful in the even lane
+                if (h) continue;
+            }
+        } else if (L == 2) {
             const uint32_t x2 = F::mulmod(x, x);
             const int terms = (int)((k - h + 1u) / 2u);   // coefficients h, h + 2, ...
             acc = 0;
