@@ -51,6 +51,8 @@ constexpr int kQcap = TOPLOC_QCAP;        // queue entries (16-byte vectors)
 #endif
 constexpr int kCapSmall = TOPLOC_CAP_SMALL;  // candidate buffer for k <= 128
 constexpr int kCapLarge = 2048;           // candidate buffer for k <= TOPLOC_MAX_K
+constexpr int kCapMerge = 4096;           // candidate buffer of the merge kernels: few workgroups, LDS to spare, and a long segment
+                                          // brings dozens of parts: 2048 candidates per batch and prune instead of 512
 constexpr int kCapWide = 16384;           // candidate buffer of the selection alone up to TOPLOC_MAX_K_TOPK (140 KB of LDS:
                                           // one workgroup per compute unit; an aid for statistics, not a fast path)
 // The larger candidate buffer (k > 128) costs registers in the prune and the ordering: one wave per SIMD less.
@@ -672,19 +674,19 @@ static void launch_build_merge(hipStream_t st, const Layout& lay, uint64_t units
     ProfScope ps(TOPLOC_KERNEL_BUILD_MERGE, st);
     if (dtype == TOPLOC_DTYPE_F32) {
         if (k <= 128)
-            hipLaunchKernelGGL((build_merge_kernel<256, 128, kCapSmall, Field32, F32Fmt>), dim3((uint32_t)units), dim3(256), 0,
+            hipLaunchKernelGGL((build_merge_kernel<256, 128, kCapMerge, Field32, F32Fmt>), dim3((uint32_t)units), dim3(256), 0,
                                st, lay, k, c_idx, (const uint32_t*)c_bits_any, d_proofs, d_status, d_topk_idx_opt);
         else
-            hipLaunchKernelGGL((build_merge_kernel<1024, 512, kCapLarge, Field32, F32Fmt>), dim3((uint32_t)units), dim3(1024),
+            hipLaunchKernelGGL((build_merge_kernel<1024, 512, kCapMerge, Field32, F32Fmt>), dim3((uint32_t)units), dim3(1024),
                                0, st, lay, k, c_idx, (const uint32_t*)c_bits_any, d_proofs, d_status, d_topk_idx_opt);
         return;
     }
     const uint16_t* c_bits = (const uint16_t*)c_bits_any;
     if (k <= 128)
-        hipLaunchKernelGGL((build_merge_kernel<256, 128, kCapSmall>), dim3((uint32_t)units), dim3(256), 0, st, lay, k, c_idx,
+        hipLaunchKernelGGL((build_merge_kernel<256, 128, kCapMerge>), dim3((uint32_t)units), dim3(256), 0, st, lay, k, c_idx,
                            c_bits, d_proofs, d_status, d_topk_idx_opt);
     else
-        hipLaunchKernelGGL((build_merge_kernel<1024, 512, kCapLarge>), dim3((uint32_t)units), dim3(1024), 0, st, lay, k, c_idx,
+        hipLaunchKernelGGL((build_merge_kernel<1024, 512, kCapMerge>), dim3((uint32_t)units), dim3(1024), 0, st, lay, k, c_idx,
                            c_bits, d_proofs, d_status, d_topk_idx_opt);
 }
 
@@ -698,37 +700,37 @@ static void launch_verify_merge(hipStream_t st, const Layout& lay, uint64_t unit
     const bool wide = k > 128;   // the larger candidate buffer and 512 lanes
     if (hidden_dtype == TOPLOC_DTYPE_F32 && proof_dtype == TOPLOC_DTYPE_F32) {
         if (!wide)
-            hipLaunchKernelGGL((verify_merge_kernel<256, 128, kCapSmall, Field32, F32Fmt>), grid, block, 0, st, lay, k, c_idx,
+            hipLaunchKernelGGL((verify_merge_kernel<256, 128, kCapMerge, Field32, F32Fmt>), grid, block, 0, st, lay, k, c_idx,
                                (const uint32_t*)c_bits_any, d_proofs, thr, d_results);
         else
-            hipLaunchKernelGGL((verify_merge_kernel<512, 512, kCapLarge, Field32, F32Fmt>), grid, block_wide, 0, st, lay, k,
+            hipLaunchKernelGGL((verify_merge_kernel<512, 512, kCapMerge, Field32, F32Fmt>), grid, block_wide, 0, st, lay, k,
                                c_idx, (const uint32_t*)c_bits_any, d_proofs, thr, d_results);
         return;
     }
     if (hidden_dtype == TOPLOC_DTYPE_F32) {  // bf16 proof, fp32 validator
         if (!wide)
-            hipLaunchKernelGGL((verify_merge_kernel<256, 128, kCapSmall, Field16, F32Fmt>), grid, block, 0, st, lay, k, c_idx,
+            hipLaunchKernelGGL((verify_merge_kernel<256, 128, kCapMerge, Field16, F32Fmt>), grid, block, 0, st, lay, k, c_idx,
                                (const uint32_t*)c_bits_any, d_proofs, thr, d_results);
         else
-            hipLaunchKernelGGL((verify_merge_kernel<512, 512, kCapLarge, Field16, F32Fmt>), grid, block_wide, 0, st, lay, k,
+            hipLaunchKernelGGL((verify_merge_kernel<512, 512, kCapMerge, Field16, F32Fmt>), grid, block_wide, 0, st, lay, k,
                                c_idx, (const uint32_t*)c_bits_any, d_proofs, thr, d_results);
         return;
     }
     const uint16_t* c_bits = (const uint16_t*)c_bits_any;
     if (proof_dtype == TOPLOC_DTYPE_F32) {   // fp32 proof, bf16 validator
         if (!wide)
-            hipLaunchKernelGGL((verify_merge_kernel<256, 128, kCapSmall, Field32, Bf16Fmt>), grid, block, 0, st, lay, k, c_idx,
+            hipLaunchKernelGGL((verify_merge_kernel<256, 128, kCapMerge, Field32, Bf16Fmt>), grid, block, 0, st, lay, k, c_idx,
                                c_bits, d_proofs, thr, d_results);
         else
-            hipLaunchKernelGGL((verify_merge_kernel<512, 512, kCapLarge, Field32, Bf16Fmt>), grid, block_wide, 0, st, lay, k,
+            hipLaunchKernelGGL((verify_merge_kernel<512, 512, kCapMerge, Field32, Bf16Fmt>), grid, block_wide, 0, st, lay, k,
                                c_idx, c_bits, d_proofs, thr, d_results);
         return;
     }
     if (!wide)
-        hipLaunchKernelGGL((verify_merge_kernel<256, 128, kCapSmall>), grid, block, 0, st, lay, k, c_idx, c_bits, d_proofs, thr,
+        hipLaunchKernelGGL((verify_merge_kernel<256, 128, kCapMerge>), grid, block, 0, st, lay, k, c_idx, c_bits, d_proofs, thr,
                            d_results);
     else
-        hipLaunchKernelGGL((verify_merge_kernel<512, 512, kCapLarge>), grid, block_wide, 0, st, lay, k, c_idx, c_bits, d_proofs,
+        hipLaunchKernelGGL((verify_merge_kernel<512, 512, kCapMerge>), grid, block_wide, 0, st, lay, k, c_idx, c_bits, d_proofs,
                            thr, d_results);
 }
 
