@@ -185,6 +185,8 @@ __device__ __forceinline__ void find_bin(const uint32_t* hist, uint32_t above0, 
 struct Threshold {
     int32_t tm;
     uint32_t ti;
+    bool ties = false;   // uniform: the chunk has shown hundreds of values of one magnitude (set by the first threshold
+                         // or by a prune; it only steers which way the overflow path goes first)
 };
 
 __device__ __forceinline__ bool before(int32_t mag, uint32_t idx, const Threshold& t)
@@ -281,6 +283,7 @@ __device__ TOPLOC_PRUNE_ATTR uint32_t prune_if_above(SelectShared<THREADS, CAP, 
         }
     __syncthreads();
     const uint32_t E = uniform(s.eq_count);
+    if (E > (uint32_t)kRankDirect) t.ties = true;
     // the need-th smallest index among the E equal-magnitude entries is the new threshold element
     // uniform; the usual case: a few dozen entries share the k-th magnitude
     if (E <= (uint32_t)kRankDirect) {
@@ -349,13 +352,71 @@ __device__ __forceinline__ void drain_range(SelectShared<THREADS, CAP, QCAP, Fmt
     }
 }
 
+// The overflow path's first resort: when one sweep over the queue would hand out more candidate slots
+// than there are (sorted or otherwise adversarial data: nearly every queued value passes), find the k-th
+// largest magnitude among the candidates kept so far and ALL queued values by a radix descent over both
+// (the same histograms as the prune, fed from the queue two lanes per vector).  At least k real elements
+// reach that magnitude, so it is a valid bound; it becomes the threshold (without an index: equal magnitudes
+// still pass) and the queue is then swept once.  Returns false, and leaves the threshold alone, when
+// even that sweep might not fit: many values share the k-th magnitude (tie-heavy data), which the batches
+// handle.  All threads call, after a barrier behind which s.count is the count before the sweep.
+template <int THREADS, int CAP, int QCAP, typename Fmt>
+__device__ __forceinline__ bool bound_from_queue(SelectShared<THREADS, CAP, QCAP, Fmt>& s, uint32_t k, uint32_t nq, Threshold& t)
+{
+    constexpr int HALF = Fmt::ELEMS / 2;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t M0 = uniform(s.count);
+    for (uint32_t b = tid; b < 256u * Fmt::LEVELS; b += THREADS) (&s.hist[0][0])[b] = 0;
+    if (Fmt::STATS && tid == 0) s.stats[kStatPrunes] += 1;   // counted with the prunes: it is the same radix descent
+    __syncthreads();
+    uint32_t prefix = 0, above = 0, in_bin = 0;
+#pragma unroll
+    for (int l = 0; l < Fmt::LEVELS; ++l) {
+        const int sh = Fmt::shift(l), w = Fmt::width(l);
+#pragma unroll 1
+        for (uint32_t slot = tid; slot < M0; slot += THREADS) {
+            const uint32_t mag = (uint32_t)s.cand_bits[slot] & Fmt::MAG_MASK;
+            if (l == 0 || (mag >> (sh + w)) == prefix) atomicAdd(&s.hist[l][(mag >> sh) & ((1u << w) - 1u)], 1u);
+        }
+#pragma unroll 1
+        for (uint32_t q = tid >> 1; q < nq; q += THREADS / 2) {
+            const u32x2 wv = reinterpret_cast<const u32x2*>(&s.qvec[q])[tid & 1u];
+#pragma unroll
+            for (int e = 0; e < HALF; ++e) {
+                const uint32_t mag = Fmt::half_elem(wv, e) & Fmt::MAG_MASK;
+                if (l == 0 || (mag >> (sh + w)) == prefix) atomicAdd(&s.hist[l][(mag >> sh) & ((1u << w) - 1u)], 1u);
+            }
+        }
+        __syncthreads();
+        if (tid < 64) {
+            uint32_t d, a;
+            if (w == 8) find_bin<4>(s.hist[l], above, k, d, a);
+            else find_bin<2>(s.hist[l], above, k, d, a);
+            if (tid == 0) { s.found_bin = d; s.found_above = a; }
+        }
+        __syncthreads();
+        const uint32_t digit = uniform(s.found_bin);
+        above = uniform(s.found_above);
+        in_bin = uniform(s.hist[l][digit]);   // values that share every digit so far
+        prefix = (prefix << w) | digit;
+    }
+    // the sweep appends at most the queued values that reach the bound: above + in_bin of them
+    if (M0 + above + in_bin > (uint32_t)CAP) return false;
+    if ((int32_t)prefix > t.tm) {
+        t.tm = (int32_t)prefix;
+        t.ti = 0xFFFFFFFFu;
+    }
+    return true;
+}
+
 // Move every queued value that comes before the threshold element into the candidate
 // buffer, prune that buffer when it holds more than `limit` (CAP/2 while streaming, k
 // at the end), then empty the queue.  Two lanes share
 // a vector.  The whole queue is taken in one sweep; should that ever hand out more than
-// CAP slots (the excess is dropped, not written), the sweep is undone and repeated in
-// batches of at most CAP/16 vectors with a prune check after each: a batch adds at most
-// CAP/2 values to a buffer holding at most CAP/2.
+// CAP slots (the excess is dropped, not written), the sweep is undone; then either the threshold is
+// raised from the queue's own values so that one sweep fits (bound_from_queue), or, on tie-heavy
+// data, the sweep is repeated in batches of at most CAP/16 vectors with a prune check after each: a
+// batch adds at most CAP/2 values to a buffer holding at most CAP/2.
 // Called by all threads after a barrier that made the queue writes visible.  `epoch`
 // (uniform) says which queue counter the pushes used; the drain clears the other one and
 // switches to it, so the usual drain costs one barrier: the caller must pass one more
@@ -381,10 +442,14 @@ __device__ TOPLOC_DRAIN_ATTR bool drain(SelectShared<THREADS, CAP, QCAP, Fmt>& s
         __syncthreads();  // everyone has read the count
         if (tid == 0) s.count = s.count_base;
         __syncthreads();
-        for (uint32_t b0 = 0; b0 < nq; b0 += BATCH) {
-            const uint32_t b1 = b0 + BATCH < nq ? b0 + BATCH : nq;
-            drain_range(s, b0, b1, t);
-            (void)prune_if_above(s, k, CAP / 2, t);
+        if (!t.ties && bound_from_queue(s, k, nq, t)) {  // uniform
+            drain_range(s, 0u, nq, t);
+        } else {
+            for (uint32_t b0 = 0; b0 < nq; b0 += BATCH) {
+                const uint32_t b1 = b0 + BATCH < nq ? b0 + BATCH : nq;
+                drain_range(s, b0, b1, t);
+                (void)prune_if_above(s, k, CAP / 2, t);
+            }
         }
         (void)prune_if_above(s, k, limit, t);
     }
@@ -628,6 +693,7 @@ __device__ __forceinline__ SelectStart select_topk_from(const u32x4* __restrict_
         if (W1 == 8) find_bin<4>(s.hist[1], above, k, digit, above1);
         else find_bin<2>(s.hist[1], above, k, digit, above1);
         t.tm = (int32_t)((e_star << S0) | (digit << S1));
+        t.ties = uniform(s.hist[1][digit]) > (uint32_t)kRankDirect;   // that many maxima share the k-th's digits
     }
     __syncthreads();
 

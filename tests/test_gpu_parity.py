@@ -513,7 +513,8 @@ def test_selection_statistics_tell_input_laws_apart():
     """toploc_selection_stats (a measurement aid): counters of the instrumented selection on inputs whose
     behaviour is known.  Descending magnitudes: the first round holds the whole top-k, nothing is queued
     afterwards.  Ascending: every round behind the two that set the first threshold brings values above
-    everything seen so far, so the queue overflows there and the candidate buffer is pruned again and again."""
+    everything seen so far, so the queue fills up there, is drained more than once and the threshold has to be
+    found again from the queue's own values (counted with the prunes)."""
     n, k = 32 * 1024, 128
     mags = (np.arange(n, dtype=np.uint32) * 0x7F00 // n).astype(np.uint16)
     asc = mags.copy()
@@ -525,6 +526,6 @@ def test_selection_statistics_tell_input_laws_apart():
     say("selection stats asc/desc: drains %s prunes %s queued %s appended %s" % (drains, prunes, queued, appended))
     nvec = n // 8
     assert drains[1] == 1 and prunes[1] == 1 and queued[1] <= 256 and k <= appended[1] <= 2048      # the final ones only
-    assert drains[0] >= 2 and prunes[0] >= 8 and nvec // 4 <= queued[0] <= nvec and 4096 <= appended[0] <= n
+    assert drains[0] >= 2 and prunes[0] > prunes[1] and nvec // 4 <= queued[0] <= nvec and 2 * k <= appended[0] <= n
     with pytest.raises(tl.ToplocError):
         tl.toploc_selection_stats(_from_bits(bits), k=0, chunk_tokens=1)
