@@ -16,25 +16,20 @@
 //     limit it is pruned to the exact best k (radix select on the 8-bit exponent,
 //     then the mantissa, then the index among equal magnitudes); the k-th
 //     survivor becomes the new threshold element;
-//   * the first threshold comes from the per-vector maxima of the first round, so
+//   * the first threshold is the k-th largest of the per-vector maxima of the first two rounds, so
 //     nothing is ever flooded; a queue overflow loses nothing either: the vectors of
 //     the round are still in registers and the lanes that found no room retry after
-//     the drain.
-// The threshold is always an element that k-1 seen elements precede, so a value
-// that fails the test can never belong to the top-k: the result is exact and does
-// not depend on the order in which waves run.
+//     the drain; a candidate-buffer overflow (sorted data) is undone and redone against a bound
+//     found from the queue's own values.
+// The threshold is always either an element that k-1 seen elements precede or a magnitude
+// that at least k seen elements reach, so a value that fails the test can never belong to
+// the top-k: the result is exact and does not depend on the order in which waves run.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 #ifndef TOPLOC_PRUNE_LIMIT
 #define TOPLOC_PRUNE_LIMIT(cap, k) ((cap) / 2)
-#endif
-#ifndef TOPLOC_PRUNE_ATTR
-#define TOPLOC_PRUNE_ATTR __forceinline__
-#endif
-#ifndef TOPLOC_DRAIN_ATTR
-#define TOPLOC_DRAIN_ATTR __forceinline__
 #endif
 
 #include "ticks.hpp"
@@ -235,7 +230,7 @@ __device__ __forceinline__ void rank_by_radix(SelectShared<THREADS, CAP, QCAP, F
 // and nothing is pruned then (the caller redoes them); a value in (limit, CAP] means it
 // pruned and `t` is the new threshold.
 template <bool SYNC_AFTER = true, int THREADS, int CAP, int QCAP, typename Fmt>
-__device__ TOPLOC_PRUNE_ATTR uint32_t prune_if_above(SelectShared<THREADS, CAP, QCAP, Fmt>& s, uint32_t k, uint32_t limit,
+__device__ __forceinline__ uint32_t prune_if_above(SelectShared<THREADS, CAP, QCAP, Fmt>& s, uint32_t k, uint32_t limit,
                                                      Threshold& t)
 {
     const uint32_t tid = threadIdx.x;
@@ -424,7 +419,7 @@ __device__ __forceinline__ bool bound_from_queue(SelectShared<THREADS, CAP, QCAP
 // round; select_topk_from ends with one).  Returns true when lanes are still waiting for
 // room in the queue.
 template <int THREADS, int CAP, int QCAP, typename Fmt>
-__device__ TOPLOC_DRAIN_ATTR bool drain(SelectShared<THREADS, CAP, QCAP, Fmt>& s, uint32_t k, uint32_t limit, Threshold& t,
+__device__ __forceinline__ bool drain(SelectShared<THREADS, CAP, QCAP, Fmt>& s, uint32_t k, uint32_t limit, Threshold& t,
                                         uint32_t& epoch)
 {
     constexpr uint32_t BATCH = (CAP / 16 < THREADS / 2) ? CAP / 16 : THREADS / 2;  // vectors: ELEMS * BATCH <= CAP / 2

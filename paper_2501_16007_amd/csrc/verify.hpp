@@ -1,7 +1,9 @@
 // The paper's Algorithm 2 after topk(h, k) for one chunk, one workgroup: decode,
 // index map, Horner evaluation of the proof polynomial at the k mapped indices
 // (Algorithm 5), extractBits, the err_e / err_m statistics and the three thresholds
-// (Section 5.2).  All integer arithmetic.
+// (Section 5.2).  All integer arithmetic.  Over GF(65497) the evaluation groups the coefficients in
+// blocks of sixteen (sums of products on the packed dot-product instruction, planes.hpp) and runs
+// Horner over the blocks; the value is that of Algorithm 5.
 //
 // Two precisions meet here (Section 5.7): the proof's (its field F: GF(65497) carries
 // bf16 patterns, GF(2^32 - 5) fp32 patterns) and the validator's (the format of the
