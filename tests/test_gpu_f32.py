@@ -83,6 +83,23 @@ def test_f32_ties_signs_and_special_patterns():
     check_build(synth.from_bits(eq, DEV), 64, "all equal")
 
 
+def test_f32_sorted_magnitudes_overflow_the_candidate_buffer():
+    """fp32 magnitudes that never decrease along the chunk (random signs), and the same descending: in the ascending
+    chunk every value read is a candidate, sweeps over the queue overflow the candidate buffer and the bound is found from
+    the queue's own values through all four radix digits of the 31-bit magnitude.  k = 128 and 512."""
+    rng = np.random.default_rng(92)
+    n = 32 * 2048
+    mag = (np.arange(n, dtype=np.uint64) * 0x7F000000 // (n + 64)).astype(np.uint32)      # finite patterns
+    asc = mag | (rng.integers(0, 2, size=n, dtype=np.uint32) << 31)
+    few = (np.arange(n, dtype=np.uint32) // 512 * 0x00800000 + 0x20000000).astype(np.uint32)   # 128 steps of 512 equal values
+    bits = np.stack([asc, asc[::-1].copy(), few])
+    chunks = synth.from_bits(bits, DEV)
+    for k in (128, 512):
+        proofs = check_build(chunks, k, "sorted fp32 k=%d" % k)
+        res = check_verify(chunks, proofs, orc.F32, k, "sorted fp32 k=%d" % k)
+        assert (res["accept"] == 1).all()
+
+
 def test_all_four_precision_pairs_match_the_oracle_and_table5_outcomes():
     """Generation in fp32 or bf16, validation in fp32 or bf16, on the 8B shape: the recomputed tensors are
     the original values moved by a small relative perturbation (an fp32-sized one for the fp32 validator)."""
