@@ -79,6 +79,20 @@ def test_stream_ties_and_equal_rows():
     check_against_oracle(steps, k, T, what="ties")
 
 
+@pytest.mark.parametrize("k", [128, 512])
+def test_stream_rows_that_grow_step_by_step(k):
+    """every row larger than all rows before it (and ascending inside the row): each append finds its whole row above
+    the stored threshold, the queue and the candidate buffer overflow, and the bound comes from the queue's own values
+    on top of the k seeds the state brought in"""
+    T, n_seq, hidden = 32, 3, 8192
+    n = T * hidden
+    mag = (np.arange(n, dtype=np.uint32) * 0x7F00 // (n + 64)).astype(np.uint16)      # finite bf16 patterns, ascending
+    sign = np.random.default_rng(73).integers(0, 2, size=(n_seq, n)).astype(np.uint16) << 15
+    bits = (mag[None, :] | sign).reshape(n_seq, T, hidden).transpose(1, 0, 2)         # [T, n_seq, hidden]
+    steps = synth.from_bits(np.ascontiguousarray(bits), DEV)
+    check_against_oracle(steps, k, T, what="growing rows")
+
+
 def test_stream_short_chunk_is_reported():
     n_seq, hidden, k = 3, 16, 128
     steps = synth.config5_steps(n_seq, hidden, 4, seed=7200, device=DEV)
