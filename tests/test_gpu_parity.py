@@ -89,6 +89,26 @@ def test_parity_shapes(hidden, tokens, k, n_chunks):
     assert (res["accept"] == 1).all()
 
 
+@pytest.mark.parametrize(
+    "hidden,tokens,k",
+    [
+        (8, 1, 1),         # one vector per chunk
+        (8, 1, 8),         # k = N
+        (16, 2, 5),
+        (264, 32, 128),    # one round plus a ragged tail
+        (1000, 32, 32),    # not a multiple of the round size
+        (1032, 9, 128),    # odd token count, two rounds and a bit
+        (520, 32, 64),     # two rounds and a ragged third
+    ],
+)
+def test_parity_ragged_shapes_in_a_launch_of_several_generations(hidden, tokens, k):
+    """1500 chunks in one launch: more than one generation of workgroups, so the fused kernels with two rounds of
+    loads in flight run (launches of up to 1280 chunks take the three-round instantiation), on the same ragged shapes"""
+    chunks = random_chunks(1500, hidden, tokens, 2000 + hidden + k)
+    res = check_chunks(chunks, k, what="1500 chunks H=%d T=%d" % (hidden, tokens))
+    assert (res["accept"] == 1).all()
+
+
 @pytest.mark.parametrize("law", synth.LAWS)
 def test_parity_every_input_law(law):
     """the value laws of `bench.py --law` (Gaussian, heavy tail, ascending, one magnitude, seven patterns) at a size

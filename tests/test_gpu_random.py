@@ -115,6 +115,34 @@ def test_random_case(seed):
     assert np.array_equal(p_ix.cpu().numpy(), o_proofs) and np.array_equal(s_ix.cpu().numpy(), o_status), what + ": rows"
 
 
+@pytest.mark.parametrize("seed", range(max(10, N_CASES // 4)))
+def test_random_case_in_a_launch_of_several_generations(seed):
+    """the same laws in launches of 1300 to 1700 chunks: past 1280 chunks the fused kernels with two rounds of loads in
+    flight run instead of the three-round instantiation the small cases above take"""
+    rng = np.random.default_rng(33000 + seed)
+    hidden = int(rng.choice([8, 16, 24, 64, 136, 520])) * int(rng.choice([1, 1, 2, 3]))
+    tokens = int(rng.choice([1, 2, 5, 8, 32]))
+    n = hidden * tokens
+    k = int(min(n, rng.choice([1, 2, 7, 32, 100, 128])))
+    n_chunks = int(rng.integers(1300, 1700))
+    bits = random_bits16(rng, n_chunks, n)
+    what = "many chunks: seed %d H=%d T=%d k=%d chunks=%d" % (seed, hidden, tokens, k, n_chunks)
+    print("[case] " + what, flush=True)
+    chunks = synth.from_bits(bits, DEV)
+    o_proofs, o_status, o_idx = orc.build(bits, k, want_topk=True)
+    rec_bits = bits.copy()
+    flip = rng.random(bits.shape) < 0.02
+    rec_bits[flip] ^= np.uint16(1 << int(rng.integers(0, 9)))
+    o_res = orc.verify(rec_bits, o_proofs, k)
+    proofs, status, idx = tl.toploc_build_proofs(chunks, k=k, chunk_tokens=1, want_topk=True)
+    res = tl.toploc_verify_proofs(synth.from_bits(rec_bits, DEV), torch.from_numpy(o_proofs).to(DEV), k=k, chunk_tokens=1)
+    torch.cuda.synchronize()
+    assert np.array_equal(idx.cpu().numpy().view(np.uint32), o_idx), what + ": indices"
+    assert np.array_equal(status.cpu().numpy(), o_status), what + ": status"
+    assert np.array_equal(proofs.cpu().numpy(), o_proofs), what + ": proof bytes"
+    compare(tl.results_numpy(res), o_res, what)
+
+
 @pytest.mark.parametrize("seed", range(max(12, N_CASES // 3)))
 def test_random_case_f32(seed):
     rng = np.random.default_rng(32000 + seed)
