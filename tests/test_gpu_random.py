@@ -134,9 +134,15 @@ def test_random_case_in_a_launch_of_several_generations(seed):
     flip = rng.random(bits.shape) < 0.02
     rec_bits[flip] ^= np.uint16(1 << int(rng.integers(0, 9)))
     o_res = orc.verify(rec_bits, o_proofs, k)
-    proofs, status, idx = tl.toploc_build_proofs(chunks, k=k, chunk_tokens=1, want_topk=True)
-    res = tl.toploc_verify_proofs(synth.from_bits(rec_bits, DEV), torch.from_numpy(o_proofs).to(DEV), k=k, chunk_tokens=1)
-    torch.cuda.synchronize()
+    parts = int(rng.choice([0, 0, 2]))     # 2: the part kernels in a launch of several generations, then the merges
+    try:
+        tl.toploc_set_split(parts)
+        proofs, status, idx = tl.toploc_build_proofs(chunks, k=k, chunk_tokens=1, want_topk=True)
+        res = tl.toploc_verify_proofs(synth.from_bits(rec_bits, DEV), torch.from_numpy(o_proofs).to(DEV), k=k, chunk_tokens=1)
+        torch.cuda.synchronize()
+    finally:
+        tl.toploc_set_split(0)
+    what += " parts=%d" % parts
     assert np.array_equal(idx.cpu().numpy().view(np.uint32), o_idx), what + ": indices"
     assert np.array_equal(status.cpu().numpy(), o_status), what + ": status"
     assert np.array_equal(proofs.cpu().numpy(), o_proofs), what + ": proof bytes"
